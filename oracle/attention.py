@@ -1,0 +1,123 @@
+"""Cache append and attention products as plain sequences of evaluator calls.
+
+Test infrastructure only.  Token rows are "inner-packed" (the paper's section
+2.4): with head dimension d and B = N/d blocks per ciphertext, block b (flat
+slots [b d, (b+1) d)) of a cache ciphertext holds one token's d-vector.
+
+  append          Algorithm 1, steps 2-3 (slot-aware concatenation): the new
+                  row arrives tiled into every block, is masked to block
+                  tau mod B by a plaintext multiplication and added into cache
+                  ciphertext floor(tau / B); tokens are numbered from 0.
+  decode_scores   section 4.3, inner-outer mode: one slot-wise product of the
+                  tiled query with a cache ciphertext, relinearise, then the
+                  folding sum (rotate by 1, 2, 4, ... d/2 and add).  Slot b d
+                  then holds <q, K_b> mod t.
+  decode_context  section 4.3, inner-inner mode with the attention weight of
+                  token b already broadcast over block b by the encryptor:
+                  sum of slot-wise products over the cache ciphertexts (three
+                  components), one relinearisation, then a sum over blocks
+                  (rotate by d, 2d, ... N/4, then swap the two slot rows).
+  prefill_qk      the prompt's Q K^T as m "generalised diagonals" (the paper
+                  names an outer-outer product and gives no procedure; this is
+                  the reading documented in the design notes).
+"""
+import numpy as np
+
+from .client import galois_rot, galois_swap
+
+
+def block_mask_values(n: int, d: int, b: int) -> np.ndarray:
+    v = np.zeros(n, dtype=np.int64)
+    v[b * d:(b + 1) * d] = 1
+    return v
+
+
+def append(orc, cache, tau: int, row_ct, mask_polys, d: int):
+    """cache: list of ciphertexts (grown in place); mask_polys[b] = encode(block mask b)."""
+    B = orc.n // d
+    idx, b = divmod(tau, B)
+    masked = orc.mul_plain(row_ct, mask_polys[b])
+    if idx == len(cache):
+        cache.append(np.zeros_like(masked))
+    cache[idx] = orc.add(cache[idx], masked)
+    return cache
+
+
+def fold_shifts(d: int):
+    sh = 1
+    while sh < d:
+        yield sh
+        sh *= 2
+
+
+def block_shifts(n: int, d: int):
+    sh = d
+    while sh <= n // 4:
+        yield sh
+        sh *= 2
+
+
+def decode_scores(orc, q_ct, k_ct, rlk, gks, d: int, counts=None):
+    x = orc.relin(orc.mul(q_ct, k_ct), rlk)
+    if counts is not None:
+        counts["mul"] = counts.get("mul", 0) + 1
+        counts["relin"] = counts.get("relin", 0) + 1
+    for sh in fold_shifts(d):
+        g = galois_rot(orc.n, sh)
+        x = orc.add(x, orc.rotate(x, g, gks[g]))
+        if counts is not None:
+            counts["rotate"] = counts.get("rotate", 0) + 1
+    return x
+
+
+def decode_context(orc, a_cts, v_cts, rlk, gks, d: int, counts=None):
+    y = None
+    for a_ct, v_ct in zip(a_cts, v_cts):
+        prod3 = orc.mul(a_ct, v_ct)
+        y = prod3 if y is None else orc.add(y, prod3)
+        if counts is not None:
+            counts["mul"] = counts.get("mul", 0) + 1
+    x = orc.relin(y, rlk)
+    if counts is not None:
+        counts["relin"] = counts.get("relin", 0) + 1
+    gs = [galois_rot(orc.n, sh) for sh in block_shifts(orc.n, d)] + [galois_swap(orc.n)]
+    for g in gs:
+        x = orc.add(x, orc.rotate(x, g, gks[g]))
+        if counts is not None:
+            counts["rotate"] = counts.get("rotate", 0) + 1
+    return x
+
+
+def prefill_qk(orc, q_ct, k_ct, rlk, gks, d: int):
+    """All m = N/d generalised diagonals of S = Q K^T for one head.
+
+    Q and K are token-major row-packed (token i in block i).  With H = m/2
+    tokens per slot row, output (sigma, r) holds at slot i*d the entry
+    S[i][j], j = (row_i xor sigma) * H + ((pos_i + r) mod H), i = row_i*H + pos_i.
+    Order of the returned list: sigma-major, r ascending.
+    """
+    n = orc.n
+    m = n // d
+    H = m // 2
+    g_blk, g_swap = galois_rot(n, d), galois_swap(n)
+    rot = [k_ct]
+    for _ in range(1, H):
+        rot.append(orc.rotate(rot[-1], g_blk, gks[g_blk]))
+    out = []
+    for sigma in (0, 1):
+        for r in range(H):
+            kk = rot[r] if sigma == 0 else orc.rotate(rot[r], g_swap, gks[g_swap])
+            x = orc.relin(orc.mul(q_ct, kk), rlk)
+            for sh in fold_shifts(d):
+                g = galois_rot(n, sh)
+                x = orc.add(x, orc.rotate(x, g, gks[g]))
+            out.append(x)
+    return out
+
+
+def required_galois(n: int, d: int):
+    """Galois elements the decode and prefill products use."""
+    gs = [galois_rot(n, sh) for sh in fold_shifts(d)]
+    gs += [galois_rot(n, sh) for sh in block_shifts(n, d)]
+    gs.append(galois_swap(n))
+    return sorted(set(gs))

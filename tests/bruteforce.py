@@ -1,0 +1,124 @@
+"""Brute-force definitions on tiny rings, in Python integers only.
+
+Nothing here uses a transform, a residue number system or the C oracle: ring
+products are the O(N^2) schoolbook negacyclic convolution over the integers,
+roundings are exact integer divisions.  The oracle is pinned against these on
+small N; they are far too slow for anything else.
+"""
+from math import prod
+
+from sympy import isprime
+
+
+def ntt_primes(below: int, two_n: int, count: int):
+    """The `count` largest primes < below that are 1 mod two_n, descending."""
+    c = below - 1
+    c -= (c - 1) % two_n
+    out = []
+    while len(out) < count:
+        if isprime(c):
+            out.append(c)
+        c -= two_n
+    return out
+
+
+def negacyclic(a, b):
+    """a*b in Z[X]/(X^n+1) for integer coefficient lists."""
+    n = len(a)
+    out = [0] * n
+    for i, x in enumerate(a):
+        if x == 0:
+            continue
+        for j, y in enumerate(b):
+            k = i + j
+            if k >= n:
+                out[k - n] -= x * y
+            else:
+                out[k] += x * y
+    return out
+
+
+def centre(x: int, m: int) -> int:
+    x %= m
+    return x - m if x > m // 2 else x
+
+
+def crt(res, mods) -> int:
+    M = prod(mods)
+    x = 0
+    for r, m in zip(res, mods):
+        h = M // m
+        x += int(r) * pow(h % m, -1, m) * h
+    return x % M
+
+
+def round_div(num: int, den: int) -> int:
+    """Nearest integer to num/den (den > 0), halves rounded up."""
+    return (2 * num + den) // (2 * den)
+
+
+def ring_from_rns(rows, mods):
+    """rows[i][n] residues -> list of integers in [0, prod mods)."""
+    n = len(rows[0])
+    return [crt([rows[i][j] for i in range(len(mods))], mods) for j in range(n)]
+
+
+def bf_mul(a2, b2, q, t):
+    """Tensor product scaled by t/Q and rounded; returns [3][k][n] residues."""
+    Q = prod(q)
+    a = [[centre(x, Q) for x in ring_from_rns(c, q)] for c in a2]
+    b = [[centre(x, Q) for x in ring_from_rns(c, q)] for c in b2]
+    e0 = negacyclic(a[0], b[0])
+    e1 = [x + y for x, y in zip(negacyclic(a[0], b[1]), negacyclic(a[1], b[0]))]
+    e2 = negacyclic(a[1], b[1])
+    out = []
+    for e in (e0, e1, e2):
+        d = [round_div(t * x, Q) for x in e]
+        out.append([[x % m for x in d] for m in q])
+    return out
+
+
+def bf_keyswitch(d, ksk, q, p, alpha):
+    """Hybrid key switch of d ([k][n]) with ksk ([dnum][2][k+nsp][n]); returns [2][k][n]."""
+    k, n = len(q), len(d[0])
+    P, Q = prod(p), prod(q)
+    PQ = P * Q
+    qp = list(q) + list(p)
+    dnum = k // alpha
+    acc = [[0] * n, [0] * n]
+    for j in range(dnum):
+        mods = q[j * alpha:(j + 1) * alpha]
+        digit = ring_from_rns(d[j * alpha:(j + 1) * alpha], mods)   # in [0, Q_j)
+        for c in range(2):
+            key = ring_from_rns(ksk[j][c], qp)
+            pr = negacyclic(digit, key)
+            acc[c] = [(x + y) % PQ for x, y in zip(acc[c], pr)]
+    out = []
+    for c in range(2):
+        u = [((x + P // 2) // P) % Q for x in acc[c]]
+        out.append([[x % m for x in u] for m in q])
+    return out
+
+
+def bf_galois(poly, g, m):
+    n = len(poly)
+    out = [0] * n
+    for i, x in enumerate(poly):
+        e = i * g % (2 * n)
+        if e >= n:
+            out[e - n] = (-int(x)) % m
+        else:
+            out[e] = int(x) % m
+    return out
+
+
+def bf_mul_plain(c2, pt, q, t):
+    ptc = [centre(int(x), t) for x in pt]
+    out = []
+    for comp in c2:
+        rows = []
+        for i, m in enumerate(q):
+            pr = negacyclic([int(x) for x in comp[i]], ptc)
+            rows.append([x % m for x in pr])
+        out.append(rows)
+    return out

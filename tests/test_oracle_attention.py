@@ -1,0 +1,114 @@
+"""Pins for the composite operations: decrypted results equal plaintext attention
+arithmetic mod t, and the operation counts are the ones the paper states
+(one slot-wise product per cache ciphertext and log2(d) rotations for the
+decode scores, section 4.3 and its complexity table; B = N/d tokens per cache
+ciphertext, Algorithm 1)."""
+import numpy as np
+
+from oracle import Client, Oracle, attention
+from oracle.client import galois_rot
+from workloads import PRESETS, Stream, attention_activations
+
+from .toy import toy_params
+
+
+def _keys(cl, n, d):
+    return {g: cl.galois_key(g) for g in attention.required_galois(n, d)}
+
+
+def test_append_builds_the_packed_cache():
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 61, orc)
+    n, d, t = prm.n, 64, prm.t
+    B = n // d
+    assert B == 128                                    # Algorithm 1: B = ceil(n / d2)
+    rows = attention_activations(Stream(61, 1), 1, B + 2, d)[0]
+    masks = {b: cl.codec.encode(attention.block_mask_values(n, d, b)) for b in (0, 1, 2, B - 1)}
+    cache = []
+    taus = [0, 1, 2, B - 1, B, B + 1]
+    for tau in taus:
+        row_ct = cl.encrypt_slots(np.tile(rows[tau], B))
+        attention.append(orc, cache, tau, row_ct, masks, d)
+    assert len(cache) == 2                             # token B opens a new ciphertext
+    want0 = np.zeros(n, dtype=np.int64)
+    for tau in (0, 1, 2, B - 1):
+        want0[tau * d:(tau + 1) * d] = rows[tau]
+    want1 = np.zeros(n, dtype=np.int64)
+    for tau in (B, B + 1):
+        want1[(tau - B) * d:(tau - B + 1) * d] = rows[tau]
+    assert np.array_equal(cl.decrypt_slots(cache[0]), want0 % t)
+    assert np.array_equal(cl.decrypt_slots(cache[1]), want1 % t)
+
+
+def test_decode_scores_are_the_dot_products_with_log_d_rotations():
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 62, orc)
+    n, d, t = prm.n, 64, prm.t
+    B = n // d
+    act = attention_activations(Stream(62, 1), 1, B + 1, d)[0]
+    q, K = act[0], act[1:]
+    rlk, gks = cl.relin_key(), _keys(cl, n, d)
+    counts = {}
+    out = attention.decode_scores(orc, cl.encrypt_slots(np.tile(q, B)),
+                                  cl.encrypt_slots(K.reshape(-1)), rlk, gks, d, counts)
+    assert counts == {"mul": 1, "relin": 1, "rotate": 6}       # log2(64) rotations
+    dec = cl.decrypt_slots(out)
+    assert np.array_equal(dec[::d], (K @ q) % t)
+    assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
+
+
+def test_decode_context_is_the_weighted_sum_of_value_rows():
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 63, orc)
+    n, d, t = prm.n, 64, prm.t
+    B = n // d
+    g = Stream(63, 1)
+    V = attention_activations(g, 1, 2 * B, d)[0]
+    a = attention_activations(g, 1, 2 * B, 1)[0, :, 0]
+    rlk, gks = cl.relin_key(), _keys(cl, n, d)
+    a_cts = [cl.encrypt_slots(np.repeat(a[c * B:(c + 1) * B], d)) for c in range(2)]
+    v_cts = [cl.encrypt_slots(V[c * B:(c + 1) * B].reshape(-1)) for c in range(2)]
+    counts = {}
+    out = attention.decode_context(orc, a_cts, v_cts, rlk, gks, d, counts)
+    assert counts == {"mul": 2, "relin": 1, "rotate": 7}
+    dec = cl.decrypt_slots(out)
+    want = (a @ V) % t
+    assert np.array_equal(dec, np.tile(want, B))
+    assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
+
+
+def test_prefill_generalised_diagonals_on_a_small_ring():
+    prm = toy_params(8, 3, 1, 1)
+    orc = Oracle(prm)
+    cl = Client(prm, 64, orc)
+    n, d, t = prm.n, 8, prm.t
+    m = n // d
+    H = m // 2
+    g = Stream(64, 1)
+    Qm = attention_activations(g, 1, m, d)[0]
+    Km = attention_activations(g, 1, m, d)[0]
+    rlk, gks = cl.relin_key(), _keys(cl, n, d)
+    outs = attention.prefill_qk(orc, cl.encrypt_slots(Qm.reshape(-1)),
+                                cl.encrypt_slots(Km.reshape(-1)), rlk, gks, d)
+    assert len(outs) == m
+    S = (Qm @ Km.T) % t
+    seen = np.zeros((m, m), dtype=bool)
+    for idx, ct in enumerate(outs):
+        sigma, r = divmod(idx, H)
+        dec = cl.decrypt_slots(ct)
+        for i in range(m):
+            row, pos = divmod(i, H)
+            j = (row ^ sigma) * H + (pos + r) % H
+            assert dec[i * d] == S[i, j]
+            seen[i, j] = True
+    assert seen.all()
+
+
+def test_galois_elements_needed_by_the_decode_step():
+    n, d = 8192, 64
+    gs = attention.required_galois(n, d)
+    assert len(gs) == 13          # 6 fold shifts + 6 block shifts + row swap
+    assert galois_rot(n, 1) == 3 and 2 * n - 1 in gs
