@@ -1,0 +1,217 @@
+/*
+ * cryptogen.h -- C ABI of the MI355X (gfx950) library for the server-side
+ * ciphertext x ciphertext attention path of CryptoGen (BFV over
+ * R_Q = Z_Q[X]/(X^N+1), Q a product of word-size primes).
+ *
+ * The library is keygen-free: no secret key, no encryption, no decryption.
+ * It evaluates on ciphertexts that the caller already holds in device memory
+ * (for instance PyTorch int64 tensors) and enqueues all work on the HIP stream
+ * the caller passes.  It allocates device memory only in cg_create (constant
+ * tables) and frees it in cg_destroy; every ciphertext, key, plaintext and
+ * workspace buffer is allocated, owned and freed by the caller.
+ *
+ * Conventions shared by all entry points
+ *   pointers    "dev" = device memory, "host" = host memory.  Device buffers
+ *               must be 16-byte aligned.  stream is a hipStream_t passed as
+ *               void* (NULL = the legacy default stream).
+ *   ring element  uint64[k][N]: row i holds the canonical residues in [0,q_i)
+ *               of the N coefficients (coefficient order, degree ascending).
+ *   ciphertext  uint64[ncomp][k][N], ncomp = 2 (c0,c1) or 3 (d0,d1,d2).
+ *   batch       `batch` ciphertexts are stored back to back.
+ *   switch key  as generated: uint64[dnum][2][k+nsp][N], coefficient order,
+ *               ciphertext primes first, then special primes (hybrid key
+ *               switching, digit j = alpha consecutive ciphertext primes,
+ *               key_j = (-a_j s + e_j + P T_j s', a_j) mod P Q).  It must be
+ *               converted once with cg_ksk_prepare; the prepared form is
+ *               opaque (cg_sizes.ksk_bytes bytes).
+ *   results     every output residue is canonical, and is bit-identical to
+ *               the definition over the integers stated at each entry point.
+ *   errors      every call returns 0 or a negative cg_status; nothing throws,
+ *               aborts or synchronises the device (except create/destroy).
+ *               Invalid arguments are rejected before any kernel is launched.
+ *   aliasing    outputs must not overlap inputs unless stated.
+ *   threads     a context may be used from several host threads as long as
+ *               concurrent calls use distinct workspaces.
+ *
+ * Where the paper is cited: "section 4.3" is Auto-Regressive
+ * Ciphertext-Ciphertext Multiplication (ARCC), "section 4.4" Encrypted
+ * KV-Cache Management, "Algorithm 1" the appendix listing of noise refresh and
+ * concatenation; the BFV scheme itself is only named there (section
+ * "Cryptographic Libraries and Parameters"), so the arithmetic follows the
+ * textbook Fan-Vercauteren definitions restated below.
+ */
+#ifndef CRYPTOGEN_H
+#define CRYPTOGEN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cg_ctx cg_ctx;
+
+typedef enum {
+    CG_OK = 0,
+    CG_EINVAL = -1,   /* null / misaligned pointer, bad size, unsupported parameter */
+    CG_ENOMEM = -2,   /* table allocation failed in cg_create */
+    CG_EHIP = -3      /* a HIP runtime call or kernel launch reported an error */
+} cg_status;
+
+typedef struct {
+    uint32_t log2n;       /* ring degree N = 2^log2n, 12 <= log2n <= 14 */
+    uint32_t k;           /* number of ciphertext primes, 1..6 */
+    uint32_t nsp;         /* number of special (key-switching) primes, 1..2 */
+    uint32_t alpha;       /* ciphertext primes per key-switch digit; divides k; <= 3 */
+    uint64_t t;           /* plaintext modulus, odd, < 2^20 */
+    const uint64_t *q;    /* host: k distinct primes, q_i = 1 mod 2N, 2^40 < q_i < 2^50 */
+    const uint64_t *p;    /* host: nsp primes, same conditions, distinct from q */
+} cg_params;
+
+typedef struct {
+    size_t ct2_bytes;        /* one 2-component ciphertext */
+    size_t ct3_bytes;        /* one 3-component ciphertext */
+    size_t ksk_raw_bytes;    /* one switching key as generated */
+    size_t ksk_bytes;        /* one prepared switching key */
+    size_t plain_bytes;      /* one prepared plaintext (cg_plain_prepare output) */
+    size_t ws_bytes_per_unit;/* workspace bytes per batch unit (see cg_workspace_bytes) */
+} cg_sizes;
+
+/* Build a context: validates the parameters (CG_EINVAL otherwise), chooses the
+ * library's private auxiliary primes, uploads twiddle and base-conversion
+ * tables to the current device.  Synchronises the device. */
+int cg_create(cg_ctx **out, const cg_params *prm);
+int cg_destroy(cg_ctx *ctx);
+int cg_get_sizes(const cg_ctx *ctx, cg_sizes *out);
+/* Bytes of caller-provided scratch ("ws") that any call below needs for the
+ * given batch; contents are undefined between calls. */
+size_t cg_workspace_bytes(const cg_ctx *ctx, uint32_t batch);
+const char *cg_strerror(int status);
+
+/* Negacyclic number-theoretic transform of n_limbs ring rows, each modulo the
+ * prime selected by prime_idx[i] (host array; 0..k-1 ciphertext primes,
+ * k..k+nsp-1 special primes).  out[i][j] = in_i(psi^(2*bitrev(j)+1)) mod that
+ * prime, psi its smallest primitive 2N-th root of unity; the inverse call
+ * undoes it.  Canonical in, canonical out; in == out allowed.  This is the
+ * transform every product below is built on (the paper's CT x CT cost is
+ * dominated by it; it is not described there). */
+int cg_ntt_forward(cg_ctx *ctx, void *stream, const uint64_t *in_dev, uint64_t *out_dev,
+                   const uint32_t *prime_idx_host, uint32_t n_limbs);
+int cg_ntt_inverse(cg_ctx *ctx, void *stream, const uint64_t *in_dev, uint64_t *out_dev,
+                   const uint32_t *prime_idx_host, uint32_t n_limbs);
+
+/* Switching key, as generated -> prepared form (once per key). */
+int cg_ksk_prepare(cg_ctx *ctx, void *stream, const uint64_t *ksk_raw_dev, void *ksk_dev);
+
+/* Plaintext polynomials (uint64[batch][N], coefficients in [0,t)) -> prepared
+ * form used by cg_mul_plain / cg_kv_append: each coefficient is lifted to its
+ * centred representative in (-t/2, t/2] before reduction mod every q_i. */
+int cg_plain_prepare(cg_ctx *ctx, void *stream, const uint64_t *pt_dev, void *plain_dev,
+                     uint32_t batch);
+
+/* BFV tensor product with exact scaling (the "CT x CT multiplication" of
+ * section 4.3, without relinearisation).  For unit u:
+ *   a~, b~ = centred lifts of a[u / a_group], b[u] to Z[X]/(X^N+1);
+ *   e0 = a~0 b~0, e1 = a~0 b~1 + a~1 b~0, e2 = a~1 b~1 over Z;
+ *   out3[u] = (round(t e_i / Q) mod Q)_{i=0,1,2}   (nearest integer; no ties since Q is odd).
+ * a holds ceil(batch / a_group) ciphertexts (a_group = 1: one per unit;
+ * a_group = m: each a ciphertext is multiplied with m consecutive b's). */
+int cg_mul(cg_ctx *ctx, void *stream, const uint64_t *a2_dev, const uint64_t *b2_dev,
+           uint64_t *out3_dev, uint32_t batch, uint32_t a_group, void *ws_dev);
+
+/* Relinearisation: out2 = (d0 + u0, d1 + u1) with u = KeySwitch(d2, rlk):
+ *   digit_j = d2 mod Q_j as the integer polynomial with coefficients in [0,Q_j);
+ *   A_c = sum_j digit_j * key_{j,c}  mod P Q, coefficients taken in [0,PQ);
+ *   u_c = floor((A_c + floor(P/2)) / P) mod Q.
+ * out2 may alias the first two components of in3. */
+int cg_relin(cg_ctx *ctx, void *stream, const uint64_t *in3_dev, const void *rlk_dev,
+             uint64_t *out2_dev, uint32_t batch, void *ws_dev);
+
+/* cg_mul followed by cg_relin (same results as the two calls). */
+int cg_mul_relin(cg_ctx *ctx, void *stream, const uint64_t *a2_dev, const uint64_t *b2_dev,
+                 const void *rlk_dev, uint64_t *out2_dev, uint32_t batch, uint32_t a_group,
+                 void *ws_dev);
+
+/* Galois rotation (the "rotations" of the folding sum, section 4.3):
+ * sigma_g moves the coefficient at index i to index i*g mod N, negated when
+ * i*g mod 2N >= N;  rot = (sigma_g(c0) + u0, u1), u = KeySwitch(sigma_g(c1), gk).
+ * galois_elt g must be odd, 0 < g < 2N, and gk the prepared key for s(X^g) -> s.
+ * accumulate = 0: out2 = rot;  accumulate = 1: out2 = in2 + rot (one step of a
+ * rotate-and-add reduction).  out2 may alias in2 only when ws_dev was sized by
+ * cg_workspace_bytes for this batch (the input is read before any write). */
+int cg_rotate(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, uint32_t galois_elt,
+              const void *gk_dev, uint64_t *out2_dev, uint32_t batch, int accumulate,
+              void *ws_dev);
+
+/* out = a + b component-wise mod q_i ("accumulated", section 4.3); ncomp = 2 or 3;
+ * out may alias a or b. */
+int cg_add(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *b_dev,
+           uint64_t *out_dev, uint32_t ncomp, uint32_t batch);
+
+/* Ciphertext x plaintext (MultPlain of Algorithm 1): out2[u] = in2[u] * plain[u * plain_stride]
+ * in R_Q, the plaintext lifted centred (see cg_plain_prepare).  plain_stride = 0
+ * applies one plaintext to the whole batch. */
+int cg_mul_plain(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, const void *plain_dev,
+                 uint32_t plain_stride, uint64_t *out2_dev, uint32_t batch, void *ws_dev);
+
+/* Slot-aware concatenation into the packed cache (Algorithm 1, steps 2-3; section 4.4).
+ * For each of n_caches independent caches c (e.g. heads x {K,V}):
+ *   B = N / d2 tokens per cache ciphertext; token index tau (0-based, same for all caches);
+ *   cache c occupies cache_dev + c * cache_stride_cts ciphertexts;
+ *   cache[c][tau / B] <- cache[c][tau / B] + rows[c] * masks[tau mod B]      (in R_Q)
+ * where masks_dev holds the B prepared block-mask plaintexts (block b selects flat
+ * slots [b d2, (b+1) d2)) and rows[c] is the new d2-vector tiled into all B blocks.
+ * When tau mod B == 0 the target ciphertext is treated as all-zero (it is opened
+ * by this call; its previous contents are ignored).  Returns CG_EINVAL if
+ * tau / B >= cache_stride_cts. */
+int cg_kv_append(cg_ctx *ctx, void *stream, uint64_t *cache_dev, uint32_t cache_stride_cts,
+                 uint32_t n_caches, uint32_t tau, const uint64_t *rows_dev,
+                 const void *masks_dev, uint32_t d2, void *ws_dev);
+
+/* Decode attention scores, ARCC inner-outer mode (section 4.3): for every head h
+ * and cache ciphertext c (n_cts per head, stored [heads][n_cts]):
+ *   x = relin(mul(q[h], K[h][c]));  for sh = 1, 2, 4, ..., d2/2: x = x + rotate(x, 3^sh mod 2N);
+ *   out[h][c] = x  -- flat slot b*d2 of x decrypts to <q_h, K_token b> mod t.
+ * gk_fold_dev_host: host array of log2(d2) device pointers, prepared keys for
+ * g = 3^1, 3^2, 3^4, ... (mod 2N) in that order. */
+int cg_decode_scores(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *kcache_dev,
+                     uint32_t heads, uint32_t n_cts, uint32_t d2, const void *rlk_dev,
+                     const void *const *gk_fold_dev_host, uint64_t *out_dev, void *ws_dev);
+
+/* Decode attention context, ARCC inner-inner mode with the weight of token b
+ * already broadcast over block b (section 4.3): for every head h
+ *   y = sum_c mul(a[h][c], V[h][c])   (three components, c ascending);  x = relin(y);
+ *   for sh = d2, 2 d2, ..., N/4: x = x + rotate(x, 3^sh mod 2N);  x = x + rotate(x, 2N-1);
+ *   out[h] = x  -- every block of x decrypts to sum_tokens a_tau V_tau mod t.
+ * gk_block_dev_host: host array of device pointers, prepared keys for
+ * g = 3^d2, 3^(2 d2), ..., 3^(N/4), then 2N-1, in that order. */
+int cg_decode_context(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *vcache_dev,
+                      uint32_t heads, uint32_t n_cts, uint32_t d2, const void *rlk_dev,
+                      const void *const *gk_block_dev_host, uint64_t *out_dev, void *ws_dev);
+
+/* Prefill Q K^T for `heads` heads as m = N/d2 generalised diagonals per head
+ * (the paper's outer-outer CT x CT product is named, not specified; this is the
+ * library's documented procedure).  Q and K are token-major row-packed
+ * (token i in block i).  With H = m/2:  K_0 = K, K_r = rotate(K_{r-1}, 3^d2);
+ * for sigma in {0,1}, r in [0,H): K' = K_r (sigma = 0) or rotate(K_r, 2N-1);
+ * x = relin(mul(Q, K')); folding sum as in cg_decode_scores;
+ * out[h][sigma*H + r] = x.  gk_fold as in cg_decode_scores; gk_blk = key for
+ * 3^d2, gk_swap = key for 2N-1. */
+int cg_prefill_qk(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *k_dev,
+                  uint32_t heads, uint32_t d2, const void *rlk_dev,
+                  const void *const *gk_fold_dev_host, const void *gk_blk_dev,
+                  const void *gk_swap_dev, uint64_t *out_dev, void *ws_dev);
+
+/* Micro-benchmark of the modular multiply used by every kernel (evidence for
+ * the arithmetic choice): runs `iters` dependent modular multiplications per
+ * lane on n_lanes lanes with kind 0 = FP64 FMA quotient estimate,
+ * 1 = 64-bit Barrett on 32-bit integer multiplies; results go to out_dev
+ * (uint64[n_lanes]) and are identical for both kinds. */
+int cg_bench_modmul(cg_ctx *ctx, void *stream, int kind, uint32_t n_lanes, uint32_t iters,
+                    uint64_t *out_dev);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CRYPTOGEN_H */

@@ -1,0 +1,266 @@
+"""ctypes binding of include/cryptogen.h -- argument marshalling only.
+
+Ciphertexts, keys and plaintexts are torch.int64 CUDA tensors whose bit
+patterns are the uint64 residues; every method passes data_ptr() values and
+the current torch stream to the entry point of the same name.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcryptogen_hip.so")
+
+_SYMBOLS = [
+    "cg_create", "cg_destroy", "cg_get_sizes", "cg_workspace_bytes", "cg_strerror",
+    "cg_ntt_forward", "cg_ntt_inverse", "cg_ksk_prepare", "cg_plain_prepare",
+    "cg_mul", "cg_relin", "cg_mul_relin", "cg_rotate", "cg_add", "cg_mul_plain",
+    "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_prefill_qk",
+    "cg_bench_modmul",
+]
+
+
+class _Params(C.Structure):
+    _fields_ = [("log2n", C.c_uint32), ("k", C.c_uint32), ("nsp", C.c_uint32),
+                ("alpha", C.c_uint32), ("t", C.c_uint64),
+                ("q", C.POINTER(C.c_uint64)), ("p", C.POINTER(C.c_uint64))]
+
+
+class _Sizes(C.Structure):
+    _fields_ = [("ct2_bytes", C.c_size_t), ("ct3_bytes", C.c_size_t),
+                ("ksk_raw_bytes", C.c_size_t), ("ksk_bytes", C.c_size_t),
+                ("plain_bytes", C.c_size_t), ("ws_bytes_per_unit", C.c_size_t)]
+
+
+class Library:
+    """The loaded shared library with typed entry points."""
+
+    def __init__(self, path: str = _LIB_PATH):
+        if not os.path.exists(path):
+            raise RuntimeError(
+                f"{path} is missing: build it with `python -m paper_2602_08798_amd.build` "
+                "(there is no CPU fallback)")
+        self.path = path
+        self.dll = C.CDLL(path)
+        vp, u32, i32 = C.c_void_p, C.c_uint32, C.c_int
+        d = self.dll
+        d.cg_create.argtypes = [C.POINTER(vp), C.POINTER(_Params)]
+        d.cg_destroy.argtypes = [vp]
+        d.cg_get_sizes.argtypes = [vp, C.POINTER(_Sizes)]
+        d.cg_workspace_bytes.argtypes = [vp, u32]
+        d.cg_workspace_bytes.restype = C.c_size_t
+        d.cg_strerror.argtypes = [i32]
+        d.cg_strerror.restype = C.c_char_p
+        d.cg_ntt_forward.argtypes = [vp, vp, vp, vp, C.POINTER(u32), u32]
+        d.cg_ntt_inverse.argtypes = [vp, vp, vp, vp, C.POINTER(u32), u32]
+        d.cg_ksk_prepare.argtypes = [vp, vp, vp, vp]
+        d.cg_plain_prepare.argtypes = [vp, vp, vp, vp, u32]
+        d.cg_mul.argtypes = [vp, vp, vp, vp, vp, u32, u32, vp]
+        d.cg_relin.argtypes = [vp, vp, vp, vp, vp, u32, vp]
+        d.cg_mul_relin.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, vp]
+        d.cg_rotate.argtypes = [vp, vp, vp, u32, vp, vp, u32, i32, vp]
+        d.cg_add.argtypes = [vp, vp, vp, vp, vp, u32, u32]
+        d.cg_mul_plain.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp]
+        d.cg_kv_append.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, u32, vp]
+        d.cg_decode_scores.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
+        d.cg_decode_context.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
+        d.cg_prefill_qk.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp, vp, vp]
+        d.cg_bench_modmul.argtypes = [vp, vp, i32, u32, u32, vp]
+        for name in _SYMBOLS:
+            if name not in ("cg_workspace_bytes", "cg_strerror"):
+                getattr(d, name).restype = i32
+
+    def strerror(self, status: int) -> str:
+        return self.dll.cg_strerror(status).decode()
+
+
+_lib = None
+
+
+def load_library() -> Library:
+    global _lib
+    if _lib is None:
+        _lib = Library()
+    return _lib
+
+
+def exported_symbols():
+    return list(_SYMBOLS)
+
+
+def to_device(arr: np.ndarray, device="cuda") -> torch.Tensor:
+    """numpy uint64 array -> int64 device tensor with the same bits."""
+    a = np.ascontiguousarray(arr, dtype=np.uint64)
+    return torch.from_numpy(a.view(np.int64)).to(device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().contiguous().numpy().view(np.uint64)
+
+
+class CgError(RuntimeError):
+    pass
+
+
+def _ptr(t) -> int:
+    if t is None:
+        return 0
+    assert t.is_cuda and t.is_contiguous() and t.dtype in (torch.int64, torch.float64, torch.uint8)
+    return t.data_ptr()
+
+
+class Context:
+    """One cg_ctx plus a reusable workspace tensor."""
+
+    def __init__(self, params, device="cuda"):
+        self.lib = load_library()
+        self.params = params
+        self.device = torch.device(device)
+        self.n, self.k, self.nsp = params.n, params.k, params.nsp
+        self.dnum = params.k // params.alpha
+        self.L = self.k + self.nsp
+        q = (C.c_uint64 * self.k)(*[int(x) for x in params.q])
+        p = (C.c_uint64 * self.nsp)(*[int(x) for x in params.p])
+        prm = _Params(params.log2n, self.k, self.nsp, params.alpha, int(params.t), q, p)
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            self._check(self.lib.dll.cg_create(C.byref(h), C.byref(prm)))
+        self.h = h
+        s = _Sizes()
+        self._check(self.lib.dll.cg_get_sizes(self.h, C.byref(s)))
+        self.sizes = s
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.dll.cg_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, status: int):
+        if status != 0:
+            raise CgError(f"cryptogen: {self.lib.strerror(status)} ({status})")
+
+    @property
+    def stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def workspace_bytes(self, batch: int) -> int:
+        return int(self.lib.dll.cg_workspace_bytes(self.h, batch))
+
+    def workspace(self, batch: int) -> torch.Tensor:
+        need = self.workspace_bytes(batch)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = None
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def empty_ct(self, *lead, ncomp=2) -> torch.Tensor:
+        return torch.empty(*lead, ncomp, self.k, self.n, dtype=torch.int64, device=self.device)
+
+    # ---- entry points (same names as the C ABI, without the cg_ prefix) ----
+    def ntt_forward(self, x, prime_idx, out=None, inverse=False):
+        out = torch.empty_like(x) if out is None else out
+        idx = (C.c_uint32 * len(prime_idx))(*prime_idx)
+        f = self.lib.dll.cg_ntt_inverse if inverse else self.lib.dll.cg_ntt_forward
+        self._check(f(self.h, self.stream, _ptr(x), _ptr(out), idx, len(prime_idx)))
+        return out
+
+    def ntt_inverse(self, x, prime_idx, out=None):
+        return self.ntt_forward(x, prime_idx, out, inverse=True)
+
+    def ksk_prepare(self, raw):
+        assert raw.shape == (self.dnum, 2, self.L, self.n)
+        out = torch.empty(self.sizes.ksk_bytes // 8, dtype=torch.float64, device=self.device)
+        self._check(self.lib.dll.cg_ksk_prepare(self.h, self.stream, _ptr(raw), _ptr(out)))
+        return out
+
+    def plain_prepare(self, pt):
+        batch = pt.numel() // self.n
+        out = torch.empty(batch * self.sizes.plain_bytes // 8, dtype=torch.float64, device=self.device)
+        self._check(self.lib.dll.cg_plain_prepare(self.h, self.stream, _ptr(pt), _ptr(out), batch))
+        return out
+
+    def mul(self, a2, b2, batch, a_group=1, out=None):
+        out = self.empty_ct(batch, ncomp=3) if out is None else out
+        ws = self.workspace(batch)
+        self._check(self.lib.dll.cg_mul(self.h, self.stream, _ptr(a2), _ptr(b2), _ptr(out), batch,
+                                        a_group, _ptr(ws)))
+        return out
+
+    def relin(self, in3, rlk, batch, out=None):
+        out = self.empty_ct(batch) if out is None else out
+        ws = self.workspace(batch)
+        self._check(self.lib.dll.cg_relin(self.h, self.stream, _ptr(in3), _ptr(rlk), _ptr(out), batch,
+                                          _ptr(ws)))
+        return out
+
+    def mul_relin(self, a2, b2, rlk, batch, a_group=1, out=None):
+        out = self.empty_ct(batch) if out is None else out
+        ws = self.workspace(batch)
+        self._check(self.lib.dll.cg_mul_relin(self.h, self.stream, _ptr(a2), _ptr(b2), _ptr(rlk),
+                                              _ptr(out), batch, a_group, _ptr(ws)))
+        return out
+
+    def rotate(self, in2, galois_elt, gk, batch, accumulate=False, out=None):
+        out = self.empty_ct(batch) if out is None else out
+        ws = self.workspace(batch)
+        self._check(self.lib.dll.cg_rotate(self.h, self.stream, _ptr(in2), galois_elt, _ptr(gk),
+                                           _ptr(out), batch, int(accumulate), _ptr(ws)))
+        return out
+
+    def add(self, a, b, ncomp, batch, out=None):
+        out = torch.empty_like(a) if out is None else out
+        self._check(self.lib.dll.cg_add(self.h, self.stream, _ptr(a), _ptr(b), _ptr(out), ncomp, batch))
+        return out
+
+    def mul_plain(self, in2, plain, batch, plain_stride=0, out=None):
+        out = self.empty_ct(batch) if out is None else out
+        ws = self.workspace(batch)
+        self._check(self.lib.dll.cg_mul_plain(self.h, self.stream, _ptr(in2), _ptr(plain), plain_stride,
+                                              _ptr(out), batch, _ptr(ws)))
+        return out
+
+    def kv_append(self, cache, cache_stride_cts, n_caches, tau, rows, masks, d2):
+        ws = self.workspace(n_caches)
+        self._check(self.lib.dll.cg_kv_append(self.h, self.stream, _ptr(cache), cache_stride_cts, n_caches,
+                                              tau, _ptr(rows), _ptr(masks), d2, _ptr(ws)))
+        return cache
+
+    def _keys(self, keys):
+        return (C.c_void_p * len(keys))(*[_ptr(k) for k in keys])
+
+    def decode_scores(self, q, kcache, heads, n_cts, d2, rlk, gk_fold, out=None):
+        out = self.empty_ct(heads, n_cts) if out is None else out
+        ws = self.workspace(heads * n_cts)
+        self._check(self.lib.dll.cg_decode_scores(self.h, self.stream, _ptr(q), _ptr(kcache), heads, n_cts,
+                                                  d2, _ptr(rlk), self._keys(gk_fold), _ptr(out), _ptr(ws)))
+        return out
+
+    def decode_context(self, a, vcache, heads, n_cts, d2, rlk, gk_block, out=None):
+        out = self.empty_ct(heads) if out is None else out
+        ws = self.workspace(heads * n_cts)
+        self._check(self.lib.dll.cg_decode_context(self.h, self.stream, _ptr(a), _ptr(vcache), heads, n_cts,
+                                                   d2, _ptr(rlk), self._keys(gk_block), _ptr(out), _ptr(ws)))
+        return out
+
+    def prefill_qk(self, q, k, heads, d2, rlk, gk_fold, gk_blk, gk_swap, out=None):
+        m = self.n // d2
+        out = self.empty_ct(heads, m) if out is None else out
+        ws = self.workspace(heads * m)
+        self._check(self.lib.dll.cg_prefill_qk(self.h, self.stream, _ptr(q), _ptr(k), heads, d2, _ptr(rlk),
+                                               self._keys(gk_fold), _ptr(gk_blk), _ptr(gk_swap), _ptr(out),
+                                               _ptr(ws)))
+        return out
+
+    def bench_modmul(self, kind, n_lanes, iters, out=None):
+        out = torch.empty(n_lanes, dtype=torch.int64, device=self.device) if out is None else out
+        self._check(self.lib.dll.cg_bench_modmul(self.h, self.stream, kind, n_lanes, iters, _ptr(out)))
+        return out

@@ -1,0 +1,650 @@
+// C ABI of the library (see include/cryptogen.h): context set-up on the host,
+// argument checks, and the launch sequences of the evaluator operations.
+#include "../../include/cryptogen.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.hpp"
+
+using namespace cg;
+
+typedef unsigned __int128 u128;
+
+// ---------------------------------------------------------------------------
+// host integer helpers (set-up only)
+// ---------------------------------------------------------------------------
+static uint64_t h_mul(uint64_t a, uint64_t b, uint64_t m) { return (uint64_t)((u128)a * b % m); }
+static uint64_t h_pow(uint64_t a, uint64_t e, uint64_t m)
+{
+    uint64_t r = 1;
+    a %= m;
+    for (; e; e >>= 1, a = h_mul(a, a, m))
+        if (e & 1) r = h_mul(r, a, m);
+    return r;
+}
+static uint64_t h_inv(uint64_t a, uint64_t m) { return h_pow(a % m, m - 2, m); }
+static bool h_is_prime(uint64_t n)
+{
+    if (n < 2) return false;
+    static const uint64_t small[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+    for (uint64_t s : small) {
+        if (n == s) return true;
+        if (n % s == 0) return false;
+    }
+    uint64_t d = n - 1;
+    int r = 0;
+    while (!(d & 1)) { d >>= 1; r++; }
+    for (uint64_t a : small) {   // these 12 bases are a deterministic witness set below 2^64
+        uint64_t x = h_pow(a, d, n);
+        if (x == 1 || x == n - 1) continue;
+        bool composite = true;
+        for (int i = 1; i < r && composite; i++) {
+            x = h_mul(x, x, n);
+            if (x == n - 1) composite = false;
+        }
+        if (composite) return false;
+    }
+    return true;
+}
+// smallest primitive 2N-th root of unity mod p
+static uint64_t h_min_root(uint64_t p, uint64_t n)
+{
+    uint64_t root = 0;
+    for (uint64_t x = 2; x < p; x++) {
+        const uint64_t r = h_pow(x, (p - 1) / (2 * n), p);
+        if (h_pow(r, n, p) == p - 1) { root = r; break; }
+    }
+    uint64_t best = root, cur = root;
+    const uint64_t sq = h_mul(root, root, p);
+    for (uint64_t i = 1; i < n; i++) {
+        cur = h_mul(cur, sq, p);
+        if (cur < best) best = cur;
+    }
+    return best;
+}
+static uint32_t h_bitrev(uint32_t x, int bits)
+{
+    uint32_t r = 0;
+    for (int i = 0; i < bits; i++) { r = (r << 1) | (x & 1); x >>= 1; }
+    return r;
+}
+static double h_centred(uint64_t x, uint64_t p) { return x > p / 2 ? -(double)(p - x) : (double)x; }
+
+// ---------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------
+struct cg_ctx {
+    int logn, N, k, nsp, alpha, dnum, l, L, KL, np;
+    uint64_t t;
+    uint64_t pr[MAXPR];
+    DevConst hc;
+    DevConst *dc;
+    double *tw, *itw;     // [np][N] forward / inverse twiddles (centred doubles, bit-reversed order)
+    uint32_t *tab;        // scratch prime-index table for the public transform entry points
+    uint32_t tab_cap;
+    int device;
+    // workspace limbs (N * 8 bytes) per unit
+    int ws_total;
+};
+
+static void fill_conv(ConvTab &T, const uint64_t *pr, const int *sidx, int ns, const int *tidx, int nt)
+{
+    memset(&T, 0, sizeof(T));
+    T.ns = ns;
+    T.nt = nt;
+    for (int i = 0; i < ns; i++) T.sidx[i] = sidx[i];
+    for (int j = 0; j < nt; j++) T.tidx[j] = tidx[j];
+    for (int i = 0; i < ns; i++)
+        for (int j = i + 1; j < ns; j++) {
+            const uint64_t si = pr[sidx[i]], sj = pr[sidx[j]];
+            T.inv[i][j] = h_centred(h_inv(si % sj, sj), sj);
+        }
+    // digits of floor(S/2): its residue modulo s_i is (s_i - 1)/2 because S = 0 and 2 is invertible
+    uint64_t a[MAXS];
+    for (int j = 0; j < ns; j++) {
+        const uint64_t sj = pr[sidx[j]];
+        uint64_t v = (sj - 1) / 2;
+        for (int i = 0; i < j; i++) {
+            const uint64_t si = pr[sidx[i]];
+            v = h_mul((v + sj - a[i] % sj) % sj, h_inv(si % sj, sj), sj);
+        }
+        a[j] = v;
+        T.half[j] = (double)v;
+    }
+    for (int j = 0; j < nt; j++) {
+        const uint64_t tj = pr[tidx[j]];
+        uint64_t prod = 1;
+        for (int i = 0; i < ns; i++) {
+            T.s_mod_t[i][j] = h_centred(pr[sidx[i]] % tj, tj);
+            prod = h_mul(prod, pr[sidx[i]] % tj, tj);
+        }
+        T.S_mod_t[j] = h_centred(prod, tj);
+    }
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+#define CG_REQUIRE(cond) do { if (!(cond)) return CG_EINVAL; } while (0)
+#define CG_HIP(call) do { if ((call) != hipSuccess) return CG_EHIP; } while (0)
+static int check_launch() { return hipGetLastError() == hipSuccess ? CG_OK : CG_EHIP; }
+
+extern "C" const char *cg_strerror(int status)
+{
+    switch (status) {
+    case CG_OK: return "ok";
+    case CG_EINVAL: return "invalid argument";
+    case CG_ENOMEM: return "out of device memory";
+    case CG_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
+{
+    CG_REQUIRE(out && prm && prm->q && prm->p);
+    *out = nullptr;
+    CG_REQUIRE(prm->log2n >= 12 && prm->log2n <= 14);
+    CG_REQUIRE(prm->k >= 1 && prm->k <= 6 && prm->nsp >= 1 && prm->nsp <= 2);
+    CG_REQUIRE(prm->alpha >= 1 && prm->alpha <= 3 && prm->k % prm->alpha == 0);
+    CG_REQUIRE((prm->t & 1) && prm->t > 2 && prm->t < (1u << 20));
+    const uint64_t N = 1ull << prm->log2n;
+    cg_ctx *c = new (std::nothrow) cg_ctx();
+    if (!c) return CG_ENOMEM;
+    memset(c, 0, sizeof(*c));
+    c->logn = (int)prm->log2n; c->N = (int)N; c->k = (int)prm->k; c->nsp = (int)prm->nsp;
+    c->alpha = (int)prm->alpha; c->dnum = c->k / c->alpha; c->t = prm->t;
+    c->l = c->k + 1;
+    c->L = c->k + c->nsp;
+    c->KL = c->k + c->l;
+    int np = 0;
+    uint64_t lowest = ~0ull;
+    auto ok_prime = [&](uint64_t p) {
+        if (!(p > (1ull << 40) && p < (1ull << 50) && p % (2 * N) == 1 && h_is_prime(p))) return false;
+        for (int i = 0; i < np; i++) if (c->pr[i] == p) return false;
+        return true;
+    };
+    for (uint32_t i = 0; i < prm->k + prm->nsp; i++) {
+        const uint64_t p = i < prm->k ? prm->q[i] : prm->p[i - prm->k];
+        if (!ok_prime(p) || p == prm->t) { delete c; return CG_EINVAL; }
+        c->pr[np++] = p;
+        if (p < lowest) lowest = p;
+    }
+    // auxiliary basis for the tensor product: the special primes plus private primes
+    // below every given prime, l = k + 1 in total
+    uint64_t cand = lowest;
+    while (np < c->k + c->l) {
+        cand -= 2 * N;
+        if (cand <= (1ull << 40)) { delete c; return CG_EINVAL; }
+        if (ok_prime(cand) && cand != prm->t) c->pr[np++] = cand;
+    }
+    c->np = np;
+    // the scaled product round(t e / Q) is below t N Q in magnitude and must fit the centred
+    // range of the auxiliary basis
+    double lgQ = 0, lgB = 0;
+    for (int i = 0; i < c->k; i++) lgQ += std::log2((double)c->pr[i]);
+    for (int j = 0; j < c->l; j++) lgB += std::log2((double)c->pr[c->k + j]);
+    if (!(lgB > lgQ + std::log2((double)c->t) + c->logn + 3)) { delete c; return CG_EINVAL; }
+
+    DevConst &H = c->hc;
+    memset(&H, 0, sizeof(H));
+    H.logn = c->logn; H.k = c->k; H.nsp = c->nsp; H.l = c->l; H.alpha = c->alpha; H.dnum = c->dnum;
+    H.L = c->L; H.KL = c->KL; H.np = np; H.tmod = (double)c->t;
+    std::vector<double> tw((size_t)np * N), itw((size_t)np * N);
+    for (int r = 0; r < np; r++) {
+        const uint64_t p = c->pr[r];
+        H.mod[r].p = (double)p;
+        H.mod[r].u = 1.0 / (double)p;
+        const uint64_t psi = h_min_root(p, N);
+        std::vector<uint64_t> pw(N);
+        pw[0] = 1;
+        for (uint64_t i = 1; i < N; i++) pw[i] = h_mul(pw[i - 1], psi, p);
+        for (uint64_t j = 0; j < N; j++) {
+            const uint64_t w = pw[h_bitrev((uint32_t)j, c->logn)];
+            tw[(size_t)r * N + j] = h_centred(w, p);
+            itw[(size_t)r * N + j] = h_centred(h_inv(w, p), p);
+        }
+        const uint64_t ninv = h_inv(N % p, p);
+        H.ninv[r] = h_centred(ninv, p);
+        H.itw1_ninv[r] = h_centred(h_mul(h_inv(pw[h_bitrev(1, c->logn)], p), ninv, p), p);
+    }
+    int qi[MAXS], bi[MAXS], all[MAXT], sp[MAXS];
+    for (int i = 0; i < c->k; i++) qi[i] = i;
+    for (int j = 0; j < c->l; j++) bi[j] = c->k + j;
+    for (int r = 0; r < c->L; r++) all[r] = r;
+    for (int s = 0; s < c->nsp; s++) sp[s] = c->k + s;
+    fill_conv(H.q2b, c->pr, qi, c->k, bi, c->l);
+    fill_conv(H.b2q, c->pr, bi, c->l, qi, c->k);
+    for (int j = 0; j < c->l; j++) {
+        const uint64_t b = c->pr[c->k + j];
+        uint64_t prod = 1;
+        for (int i = 0; i < c->k; i++) prod = h_mul(prod, c->pr[i] % b, b);
+        H.Qinv_b[j] = h_centred(h_inv(prod, b), b);
+    }
+    for (int j = 0; j < c->dnum; j++) fill_conv(H.dig[j], c->pr, qi + j * c->alpha, c->alpha, all, c->L);
+    fill_conv(H.p2q, c->pr, sp, c->nsp, qi, c->k);
+    for (int r = 0; r < c->L; r++) {
+        const uint64_t m = c->pr[r];
+        uint64_t P = 1;
+        for (int s = 0; s < c->nsp; s++) P = h_mul(P, c->pr[c->k + s] % m, m);
+        H.halfP[r] = (double)h_mul((P + m - 1) % m, h_inv(2, m), m);   // (P-1)/2 mod m, P odd
+        if (r < c->k) H.Pinv_q[r] = h_centred(h_inv(P, m), m);
+    }
+    // workspace limbs per unit: three ciphertext temporaries (3k + 2k + 2k) plus the larger of the
+    // tensor-product and key-switch scratch areas (kept separate for simplicity)
+    c->ws_total = 7 * c->k + (4 * c->l + 7 * c->KL) + (c->dnum * c->L + 2 * c->L);
+
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return CG_EHIP; }
+    const size_t tbytes = (size_t)np * N * sizeof(double);
+    c->tab_cap = 1u << 16;
+    if (hipMalloc(&c->dc, sizeof(DevConst)) != hipSuccess || hipMalloc(&c->tw, tbytes) != hipSuccess ||
+        hipMalloc(&c->itw, tbytes) != hipSuccess ||
+        hipMalloc(&c->tab, c->tab_cap * sizeof(uint32_t)) != hipSuccess) {
+        cg_destroy(c);
+        return CG_ENOMEM;
+    }
+    if (hipMemcpy(c->dc, &H, sizeof(DevConst), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(c->tw, tw.data(), tbytes, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(c->itw, itw.data(), tbytes, hipMemcpyHostToDevice) != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess) {
+        cg_destroy(c);
+        return CG_EHIP;
+    }
+    *out = c;
+    return CG_OK;
+}
+
+extern "C" int cg_destroy(cg_ctx *c)
+{
+    if (!c) return CG_OK;
+    (void)hipDeviceSynchronize();
+    if (c->dc) (void)hipFree(c->dc);
+    if (c->tw) (void)hipFree(c->tw);
+    if (c->itw) (void)hipFree(c->itw);
+    if (c->tab) (void)hipFree(c->tab);
+    delete c;
+    return CG_OK;
+}
+
+static size_t limb_bytes(const cg_ctx *c) { return (size_t)c->N * 8; }
+
+extern "C" int cg_get_sizes(const cg_ctx *c, cg_sizes *o)
+{
+    CG_REQUIRE(c && o);
+    o->ct2_bytes = 2 * (size_t)c->k * limb_bytes(c);
+    o->ct3_bytes = 3 * (size_t)c->k * limb_bytes(c);
+    o->ksk_raw_bytes = (size_t)c->dnum * 2 * c->L * limb_bytes(c);
+    o->ksk_bytes = o->ksk_raw_bytes;
+    o->plain_bytes = (size_t)c->k * limb_bytes(c);
+    o->ws_bytes_per_unit = (size_t)c->ws_total * limb_bytes(c);
+    return CG_OK;
+}
+
+extern "C" size_t cg_workspace_bytes(const cg_ctx *c, uint32_t batch)
+{
+    if (!c) return 0;
+    return (size_t)c->ws_total * limb_bytes(c) * (batch ? batch : 1);
+}
+
+// Workspace carving: composite operations take their persistent buffers first and hand the
+// rest to the primitive sequences, which start again from the pointer they are given.
+struct Bump {
+    char *p;
+    size_t limb;
+    template <class T> T *take(size_t limbs)
+    {
+        T *r = reinterpret_cast<T *>(p);
+        p += limbs * limb;
+        return r;
+    }
+};
+static Bump bump(const cg_ctx *c, void *ws) { return Bump{static_cast<char *>(ws), limb_bytes(c)}; }
+
+// ---------------------------------------------------------------------------
+// launch helpers
+// ---------------------------------------------------------------------------
+template <class LD, class ST>
+static int launch_fwd(const cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st)
+{
+    if (nwg == 0) return CG_OK;
+    switch (c->logn) {
+    case 12: hipLaunchKernelGGL((ntt_fwd_kernel<12, LD, ST>), dim3((unsigned)nwg), dim3(256), 0, s, ld, st, c->tw, c->dc); break;
+    case 13: hipLaunchKernelGGL((ntt_fwd_kernel<13, LD, ST>), dim3((unsigned)nwg), dim3(512), 0, s, ld, st, c->tw, c->dc); break;
+    case 14: hipLaunchKernelGGL((ntt_fwd_kernel<14, LD, ST>), dim3((unsigned)nwg), dim3(1024), 0, s, ld, st, c->tw, c->dc); break;
+    default: return CG_EINVAL;
+    }
+    return check_launch();
+}
+template <class LD, class ST>
+static int launch_inv(const cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st)
+{
+    if (nwg == 0) return CG_OK;
+    switch (c->logn) {
+    case 12: hipLaunchKernelGGL((ntt_inv_kernel<12, LD, ST>), dim3((unsigned)nwg), dim3(256), 0, s, ld, st, c->itw, c->dc); break;
+    case 13: hipLaunchKernelGGL((ntt_inv_kernel<13, LD, ST>), dim3((unsigned)nwg), dim3(512), 0, s, ld, st, c->itw, c->dc); break;
+    case 14: hipLaunchKernelGGL((ntt_inv_kernel<14, LD, ST>), dim3((unsigned)nwg), dim3(1024), 0, s, ld, st, c->itw, c->dc); break;
+    default: return CG_EINVAL;
+    }
+    return check_launch();
+}
+static unsigned pw_blocks(const cg_ctx *c, size_t rows) { return (unsigned)((rows * c->N + PW_THREADS - 1) / PW_THREADS); }
+#define CG_TRY(expr) do { int rc_ = (expr); if (rc_ != CG_OK) return rc_; } while (0)
+
+// ---------------------------------------------------------------------------
+// internal operations (arguments already validated)
+// ---------------------------------------------------------------------------
+static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *b2, uint64_t *out3,
+                  uint32_t batch, uint32_t a_group, void *ws, int accumulate)
+{
+    Bump w = bump(c, ws);
+    double *ext = w.take<double>((size_t)4 * c->l * batch);
+    double *ntt = w.take<double>((size_t)4 * c->KL * batch);
+    double *tens = w.take<double>((size_t)3 * c->KL * batch);
+    const int polys = (int)batch * 4;
+    hipLaunchKernelGGL(lift_ext_kernel, dim3(pw_blocks(c, polys)), dim3(PW_THREADS), 0, s, a2, b2, ext,
+                       (int)a_group, polys, c->dc);
+    CG_TRY(check_launch());
+    CG_TRY(launch_fwd(c, s, (size_t)polys * c->k, LdMulQ{a2, b2, (int)a_group, c->logn}, StF64{ntt, c->logn}));
+    CG_TRY(launch_fwd(c, s, (size_t)polys * c->l, LdMulB{ext, c->logn}, StF64{ntt, c->logn}));
+    hipLaunchKernelGGL(tensor_kernel, dim3(pw_blocks(c, (size_t)batch * c->KL)), dim3(PW_THREADS), 0, s, ntt,
+                       tens, (int)batch, c->dc);
+    CG_TRY(check_launch());
+    const size_t rows = (size_t)batch * 3 * c->KL;
+    CG_TRY(launch_inv(c, s, rows, LdInvF64{tens, nullptr, c->KL, c->logn}, StInvF64{tens, c->logn}));
+    hipLaunchKernelGGL(scale_kernel, dim3(pw_blocks(c, (size_t)batch * 3)), dim3(PW_THREADS), 0, s, tens, out3,
+                       (int)batch * 3, accumulate, c->dc);
+    return check_launch();
+}
+
+// key switch of one ring element per unit (src + b*src_stride), then the final additions
+static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t src_stride, uint32_t galois,
+                        const double *key, uint64_t *out2, size_t out_stride, const uint64_t *add, size_t add_stride,
+                        uint32_t galois_inv, int accumulate, uint32_t batch, void *ws)
+{
+    Bump w = bump(c, ws);
+    double *dig = w.take<double>((size_t)c->dnum * c->L * batch);
+    double *acc = w.take<double>((size_t)2 * c->L * batch);
+    CG_TRY(launch_fwd(c, s, (size_t)batch * c->dnum * c->L, LdModup{src, src_stride, galois, c->logn},
+                      StF64{dig, c->logn}));
+    hipLaunchKernelGGL(ks_inner_kernel, dim3(pw_blocks(c, (size_t)batch * c->L)), dim3(PW_THREADS), 0, s, dig, key,
+                       acc, (int)batch, c->dc);
+    CG_TRY(check_launch());
+    CG_TRY(launch_inv(c, s, (size_t)batch * 2 * c->L, LdInvF64{acc, nullptr, c->L, c->logn},
+                      StInvF64{acc, c->logn}));
+    ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch};
+    hipLaunchKernelGGL(moddown_kernel, dim3(pw_blocks(c, (size_t)batch * 2)), dim3(PW_THREADS), 0, s, A, c->dc);
+    return check_launch();
+}
+
+static int do_relin(cg_ctx *c, hipStream_t s, const uint64_t *in3, const void *rlk, uint64_t *out2, uint32_t batch,
+                    void *ws)
+{
+    const size_t ct3 = (size_t)3 * c->k * c->N;
+    return do_keyswitch(c, s, in3 + (size_t)2 * c->k * c->N, ct3, 0, static_cast<const double *>(rlk), out2,
+                        (size_t)2 * c->k * c->N, in3, ct3, 0, 0, batch, ws);
+}
+
+static uint32_t inv_mod_pow2(uint32_t g, uint32_t two_n)
+{
+    uint32_t x = g;   // Newton iteration: correct to 3 bits, doubles each step
+    for (int i = 0; i < 5; i++) x *= 2 - g * x;
+    return x & (two_n - 1);
+}
+
+// in_stride / out_stride: uint64 between consecutive units (0 = densely packed ciphertexts)
+static int do_rotate(cg_ctx *c, hipStream_t s, const uint64_t *in2, uint32_t g, const void *gk, uint64_t *out2,
+                     uint32_t batch, int accumulate, void *ws, size_t in_stride = 0, size_t out_stride = 0)
+{
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    if (!in_stride) in_stride = ct2;
+    if (!out_stride) out_stride = ct2;
+    return do_keyswitch(c, s, in2 + (size_t)c->k * c->N, in_stride, g, static_cast<const double *>(gk), out2,
+                        out_stride, in2, in_stride, inv_mod_pow2(g, 2u * c->N), accumulate, batch, ws);
+}
+
+static int do_add(cg_ctx *c, hipStream_t s, const uint64_t *a, const uint64_t *b, uint64_t *out, size_t rows)
+{
+    hipLaunchKernelGGL(add_kernel, dim3(pw_blocks(c, rows)), dim3(PW_THREADS), 0, s, a, b, out, (int)rows, c->dc);
+    return check_launch();
+}
+
+static bool ptrs_ok(std::initializer_list<const void *> ps)
+{
+    for (const void *p : ps) if (!p || !aligned16(p)) return false;
+    return true;
+}
+static bool batch_ok(uint32_t batch) { return batch >= 1 && batch <= (1u << 16); }
+static bool galois_ok(const cg_ctx *c, uint32_t g) { return (g & 1) && g > 0 && g < 2u * c->N; }
+
+// ---------------------------------------------------------------------------
+// public entry points
+// ---------------------------------------------------------------------------
+static int public_transform(cg_ctx *c, void *stream, const uint64_t *in, uint64_t *out, const uint32_t *idx,
+                            uint32_t n_limbs, bool inverse)
+{
+    CG_REQUIRE(c && idx && ptrs_ok({in, out}) && n_limbs >= 1 && n_limbs <= c->tab_cap);
+    for (uint32_t i = 0; i < n_limbs; i++) CG_REQUIRE(idx[i] < (uint32_t)c->L);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the index table is staged through a context-owned device buffer; the copy is
+    // ordered on the caller's stream before the kernel
+    CG_HIP(hipMemcpyAsync(c->tab, idx, n_limbs * sizeof(uint32_t), hipMemcpyHostToDevice, s));
+    if (!inverse)
+        return launch_fwd(c, s, n_limbs, LdRowsU64{in, c->tab, 1, c->logn}, StU64{out, c->logn});
+    return launch_inv(c, s, n_limbs, LdInvU64{in, c->tab, 1, c->logn}, StInvU64{out, c->logn});
+}
+extern "C" int cg_ntt_forward(cg_ctx *c, void *stream, const uint64_t *in, uint64_t *out, const uint32_t *idx,
+                              uint32_t n_limbs)
+{
+    return public_transform(c, stream, in, out, idx, n_limbs, false);
+}
+extern "C" int cg_ntt_inverse(cg_ctx *c, void *stream, const uint64_t *in, uint64_t *out, const uint32_t *idx,
+                              uint32_t n_limbs)
+{
+    return public_transform(c, stream, in, out, idx, n_limbs, true);
+}
+
+extern "C" int cg_ksk_prepare(cg_ctx *c, void *stream, const uint64_t *raw, void *ksk)
+{
+    CG_REQUIRE(c && ptrs_ok({raw, ksk}));
+    return launch_fwd(c, static_cast<hipStream_t>(stream), (size_t)c->dnum * 2 * c->L,
+                      LdRowsU64{raw, nullptr, c->L, c->logn}, StF64Red{static_cast<double *>(ksk), c->logn});
+}
+
+extern "C" int cg_plain_prepare(cg_ctx *c, void *stream, const uint64_t *pt, void *plain, uint32_t batch)
+{
+    CG_REQUIRE(c && ptrs_ok({pt, plain}) && batch_ok(batch));
+    return launch_fwd(c, static_cast<hipStream_t>(stream), (size_t)batch * c->k, LdPlain{pt, c->logn},
+                      StF64Red{static_cast<double *>(plain), c->logn});
+}
+
+extern "C" int cg_mul(cg_ctx *c, void *stream, const uint64_t *a2, const uint64_t *b2, uint64_t *out3,
+                      uint32_t batch, uint32_t a_group, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({a2, b2, out3, ws}) && batch_ok(batch) && a_group >= 1);
+    return do_mul(c, static_cast<hipStream_t>(stream), a2, b2, out3, batch, a_group, ws, 0);
+}
+
+extern "C" int cg_relin(cg_ctx *c, void *stream, const uint64_t *in3, const void *rlk, uint64_t *out2,
+                        uint32_t batch, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({in3, rlk, out2, ws}) && batch_ok(batch));
+    return do_relin(c, static_cast<hipStream_t>(stream), in3, rlk, out2, batch, ws);
+}
+
+extern "C" int cg_mul_relin(cg_ctx *c, void *stream, const uint64_t *a2, const uint64_t *b2, const void *rlk,
+                            uint64_t *out2, uint32_t batch, uint32_t a_group, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({a2, b2, rlk, out2, ws}) && batch_ok(batch) && a_group >= 1);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Bump w = bump(c, ws);
+    uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
+    CG_TRY(do_mul(c, s, a2, b2, d3, batch, a_group, w.p, 0));
+    return do_relin(c, s, d3, rlk, out2, batch, w.p);
+}
+
+extern "C" int cg_rotate(cg_ctx *c, void *stream, const uint64_t *in2, uint32_t g, const void *gk, uint64_t *out2,
+                         uint32_t batch, int accumulate, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({in2, gk, out2, ws}) && batch_ok(batch) && galois_ok(c, g) && in2 != out2);
+    return do_rotate(c, static_cast<hipStream_t>(stream), in2, g, gk, out2, batch, accumulate, ws);
+}
+
+extern "C" int cg_add(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *b, uint64_t *out, uint32_t ncomp,
+                      uint32_t batch)
+{
+    CG_REQUIRE(c && ptrs_ok({a, b, out}) && batch_ok(batch) && (ncomp == 2 || ncomp == 3));
+    return do_add(c, static_cast<hipStream_t>(stream), a, b, out, (size_t)batch * ncomp * c->k);
+}
+
+extern "C" int cg_mul_plain(cg_ctx *c, void *stream, const uint64_t *in2, const void *plain, uint32_t plain_stride,
+                            uint64_t *out2, uint32_t batch, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({in2, plain, out2, ws}) && batch_ok(batch));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    double *f = static_cast<double *>(ws);
+    const size_t rows = (size_t)batch * 2 * c->k;
+    CG_TRY(launch_fwd(c, s, rows, LdRowsU64{in2, nullptr, c->k, c->logn}, StF64{f, c->logn}));
+    return launch_inv(c, s, rows,
+                      LdInvMulPlain{f, static_cast<const double *>(plain), (int)plain_stride, 0, c->logn},
+                      StInvU64{out2, c->logn});
+}
+
+extern "C" int cg_kv_append(cg_ctx *c, void *stream, uint64_t *cache, uint32_t cache_stride_cts, uint32_t n_caches,
+                            uint32_t tau, const uint64_t *rows_dev, const void *masks, uint32_t d2, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({cache, rows_dev, masks, ws}) && batch_ok(n_caches));
+    CG_REQUIRE(d2 >= 1 && (d2 & (d2 - 1)) == 0 && d2 <= (uint32_t)c->N / 2);
+    const uint32_t B = (uint32_t)c->N / d2, ct_idx = tau / B, blk = tau % B;
+    CG_REQUIRE(ct_idx < cache_stride_cts);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    double *f = static_cast<double *>(ws);
+    const size_t rows = (size_t)n_caches * 2 * c->k;
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    CG_TRY(launch_fwd(c, s, rows, LdRowsU64{rows_dev, nullptr, c->k, c->logn}, StF64{f, c->logn}));
+    return launch_inv(c, s, rows, LdInvMulPlain{f, static_cast<const double *>(masks), 0, (int)blk, c->logn},
+                      StInvAppend{cache + (size_t)ct_idx * ct2, (size_t)cache_stride_cts * ct2, blk == 0 ? 1 : 0,
+                                  c->logn});
+}
+
+static bool pow2_d(const cg_ctx *c, uint32_t d2) { return d2 >= 2 && (d2 & (d2 - 1)) == 0 && d2 <= (uint32_t)c->N / 4; }
+static uint32_t pow3_mod(uint32_t e, uint32_t two_n)
+{
+    uint64_t r = 1, b = 3;
+    for (; e; e >>= 1, b = b * b % two_n)
+        if (e & 1) r = r * b % two_n;
+    return (uint32_t)r;
+}
+
+// x <- x + rotate(x, g) for each g of the list, ping-ponging between two buffers;
+// the last result lands in `out`.  x0 holds the start value.
+static int rotate_add_chain(cg_ctx *c, hipStream_t s, uint64_t *x0, uint64_t *x1, uint64_t *out,
+                            const uint32_t *gs, const void *const *keys, int n, uint32_t batch, void *ws)
+{
+    uint64_t *cur = x0, *nxt = x1;
+    for (int i = 0; i < n; i++) {
+        uint64_t *dst = (i == n - 1) ? out : nxt;
+        CG_TRY(do_rotate(c, s, cur, gs[i], keys[i], dst, batch, 1, ws));
+        nxt = cur;
+        cur = dst;
+    }
+    return CG_OK;
+}
+
+extern "C" int cg_decode_scores(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kc, uint32_t heads,
+                                uint32_t n_cts, uint32_t d2, const void *rlk, const void *const *gk_fold,
+                                uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({q, kc, rlk, out, ws}) && gk_fold && heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
+    const uint32_t batch = heads * n_cts;
+    CG_REQUIRE(batch_ok(batch));
+    int nrot = 0;
+    uint32_t gs[16];
+    for (uint32_t sh = 1; sh < d2; sh <<= 1) {
+        CG_REQUIRE(gk_fold[nrot] && aligned16(gk_fold[nrot]));
+        gs[nrot++] = pow3_mod(sh, 2u * c->N);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Bump w = bump(c, ws);
+    uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
+    uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * batch), *xb = w.take<uint64_t>((size_t)2 * c->k * batch);
+    CG_TRY(do_mul(c, s, q, kc, d3, batch, n_cts, w.p, 0));
+    CG_TRY(do_relin(c, s, d3, rlk, xa, batch, w.p));
+    return rotate_add_chain(c, s, xa, xb, out, gs, gk_fold, nrot, batch, w.p);
+}
+
+extern "C" int cg_decode_context(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, uint32_t heads,
+                                 uint32_t n_cts, uint32_t d2, const void *rlk, const void *const *gk_block,
+                                 uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({a, vc, rlk, out, ws}) && gk_block && heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
+    const uint32_t batch = heads * n_cts;
+    CG_REQUIRE(batch_ok(batch));
+    int nrot = 0;
+    uint32_t gs[20];
+    for (uint32_t sh = d2; sh <= (uint32_t)c->N / 4; sh <<= 1) gs[nrot++] = pow3_mod(sh, 2u * c->N);
+    gs[nrot++] = 2u * c->N - 1;
+    for (int i = 0; i < nrot; i++) CG_REQUIRE(gk_block[i] && aligned16(gk_block[i]));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Bump w = bump(c, ws);
+    uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
+    uint64_t *y = w.take<uint64_t>((size_t)3 * c->k * heads);
+    uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * heads), *xb = w.take<uint64_t>((size_t)2 * c->k * heads);
+    CG_TRY(do_mul(c, s, a, vc, d3, batch, 1, w.p, 0));
+    // y[h] = sum_c d3[h][c]  (three components)
+    const int rows = 3 * c->k;
+    hipLaunchKernelGGL(sum_groups_kernel, dim3(pw_blocks(c, (size_t)heads * rows)), dim3(PW_THREADS), 0, s, d3, y,
+                       (int)heads, (int)n_cts, rows, c->dc);
+    CG_TRY(check_launch());
+    CG_TRY(do_relin(c, s, y, rlk, xa, heads, w.p));
+    return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, heads, w.p);
+}
+
+extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads,
+                             uint32_t d2, const void *rlk, const void *const *gk_fold, const void *gk_blk,
+                             const void *gk_swap, uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({q, kk, rlk, gk_blk, gk_swap, out, ws}) && gk_fold && heads >= 1 && pow2_d(c, d2));
+    const uint32_t m = (uint32_t)c->N / d2, H = m / 2, batch = heads * m;
+    CG_REQUIRE(batch_ok(batch));
+    int nrot = 0;
+    uint32_t gs[16];
+    for (uint32_t sh = 1; sh < d2; sh <<= 1) {
+        CG_REQUIRE(gk_fold[nrot] && aligned16(gk_fold[nrot]));
+        gs[nrot++] = pow3_mod(sh, 2u * c->N);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    // kp[h][sigma*H + r]: rotated copies of K, one ciphertext per output unit
+    Bump w = bump(c, ws);
+    uint64_t *kp = w.take<uint64_t>((size_t)2 * c->k * batch);
+    uint64_t *xb = w.take<uint64_t>((size_t)2 * c->k * batch);
+    uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
+    // r = 0 slots: copy K (device to device, on the stream)
+    for (uint32_t h = 0; h < heads; h++)
+        CG_HIP(hipMemcpyAsync(kp + (size_t)h * m * ct2, kk + (size_t)h * ct2, ct2 * 8, hipMemcpyDeviceToDevice, s));
+    const uint32_t g_blk = pow3_mod(d2, 2u * c->N), g_swap = 2u * c->N - 1;
+    // K_r = rotate(K_{r-1}, 3^d2): sequential in r, all heads in one strided batch
+    for (uint32_t r = 1; r < H; r++)
+        CG_TRY(do_rotate(c, s, kp + (size_t)(r - 1) * ct2, g_blk, gk_blk, kp + (size_t)r * ct2, heads, 0, w.p,
+                         (size_t)m * ct2, (size_t)m * ct2));
+    // sigma = 1 slots: row swap of each K_r (H contiguous units per head)
+    for (uint32_t h = 0; h < heads; h++)
+        CG_TRY(do_rotate(c, s, kp + (size_t)h * m * ct2, g_swap, gk_swap, kp + ((size_t)h * m + H) * ct2, H, 0, w.p));
+    // all heads x m products at once
+    CG_TRY(do_mul(c, s, q, kp, d3, batch, m, w.p, 0));
+    CG_TRY(do_relin(c, s, d3, rlk, kp, batch, w.p));   // the rotated keys are consumed: reuse as x0
+    return rotate_add_chain(c, s, kp, xb, out, gs, gk_fold, nrot, batch, w.p);
+}
+
+extern "C" int cg_bench_modmul(cg_ctx *c, void *stream, int kind, uint32_t n_lanes, uint32_t iters, uint64_t *out)
+{
+    CG_REQUIRE(c && ptrs_ok({out}) && (kind == 0 || kind == 1) && n_lanes >= 1 && c->pr[0] > (1ull << 49));
+    ModI mi{c->pr[0], (uint64_t)((((u128)1) << 100) / c->pr[0])};
+    hipLaunchKernelGGL(bench_modmul_kernel, dim3((n_lanes + PW_THREADS - 1) / PW_THREADS), dim3(PW_THREADS), 0,
+                       static_cast<hipStream_t>(stream), kind, n_lanes, iters, out, c->hc.mod[0], mi);
+    return check_launch();
+}

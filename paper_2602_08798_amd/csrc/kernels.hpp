@@ -1,0 +1,694 @@
+// Device kernels (gfx950).  One workgroup transforms one residue row ("limb")
+// that stays in LDS for the whole transform; everything else is pointwise.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "tables.hpp"
+
+namespace cg {
+
+// ---------------------------------------------------------------------------
+// Transform plan: each thread keeps E = 16 elements in registers and a pass
+// runs R = 3 or 4 butterfly stages on them between two LDS exchanges.
+// ---------------------------------------------------------------------------
+template <int LOGN> struct Plan;
+template <> struct Plan<12> { static constexpr int NP = 3; static constexpr int R[4] = {4, 4, 4, 0}; };
+template <> struct Plan<13> { static constexpr int NP = 4; static constexpr int R[4] = {4, 3, 3, 3}; };
+template <> struct Plan<14> { static constexpr int NP = 4; static constexpr int R[4] = {4, 4, 3, 3}; };
+constexpr int ELEMS = 16;
+
+template <int LOGN, int PASS> constexpr int stage_start()
+{
+    int s = 0;
+    for (int i = 0; i < PASS; i++) s += Plan<LOGN>::R[i];
+    return s;
+}
+
+// Forward stage bound: |out| <= 1.1875 |in| + 0.5 (in units of p).  Values must
+// stay below 8p = 2^53.  fwd_bound_after returns the bound after running pass
+// PASS when the pass starts from `b`.
+constexpr double fwd_grow(double b, int stages)
+{
+    for (int i = 0; i < stages; i++) b = 1.1875 * b + 0.5;
+    return b;
+}
+// Decide at compile time which forward passes start with a reduction.
+template <int LOGN, int PASS> struct FwdBound {
+    static constexpr double in_prev = FwdBound<LOGN, PASS - 1>::out;
+    static constexpr bool reduce = fwd_grow(in_prev, Plan<LOGN>::R[PASS]) > 7.5;
+    static constexpr double out = fwd_grow(reduce ? 0.51 : in_prev, Plan<LOGN>::R[PASS]);
+};
+template <int LOGN> struct FwdBound<LOGN, 0> {
+    static constexpr bool reduce = false;                       // loaders deliver |x| <= p
+    static constexpr double out = fwd_grow(1.0, Plan<LOGN>::R[0]);
+};
+
+__device__ __forceinline__ void bfly_fwd(double &a, double &b, double w, const ModD m)
+{
+    const double t = mulmod(b, w, m);
+    b = a - t;
+    a = a + t;
+}
+__device__ __forceinline__ void bfly_inv(double &a, double &b, double w, const ModD m)
+{
+    const double d = a - b;
+    a = a + b;
+    b = mulmod(d, w, m);
+}
+
+// ---------------------------------------------------------------------------
+// forward transform
+// ---------------------------------------------------------------------------
+template <int LOGN, int PASS, class LD, class ST>
+__device__ __forceinline__ void fwd_pass(double *lds, const LD &ld, const ST &st, int wg, int tid,
+                                         const double *__restrict__ tw, const ModD m, int dst_limb,
+                                         const DevConst *C)
+{
+    using P = Plan<LOGN>;
+    constexpr int R = P::R[PASS];
+    constexpr int S0 = stage_start<LOGN, PASS>();
+    constexpr int L = LOGN - S0 - R;          // index bits below this pass's R bits
+    constexpr int G = ELEMS >> R;             // independent radix-2^R groups per thread
+    constexpr int T = (1 << LOGN) / ELEMS;
+    constexpr bool first = PASS == 0, last = PASS == P::NP - 1;
+    constexpr bool do_red = FwdBound<LOGN, PASS>::reduce;
+    static_assert(FwdBound<LOGN, PASS>::out < 8.0, "lazy bound exceeds 2^53");
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        const int gidx = tid + g * T;
+        const int lo = gidx & ((1 << L) - 1);
+        const int hi = first ? 0 : (gidx >> L);
+        const int base = (hi << (L + R)) | lo;
+        double v[1 << R];
+#pragma unroll
+        for (int c = 0; c < (1 << R); c++) {
+            const int idx = base + (c << L);
+            v[c] = (first && !LD::kStaged) ? ld.load(wg, idx, C) : lds[idx];
+            if (do_red) v[c] = red(v[c], m);
+        }
+#pragma unroll
+        for (int u = 0; u < R; u++) {
+            const int half = 1 << (R - 1 - u);
+#pragma unroll
+            for (int c = 0; c < (1 << R); c++) {
+                if (c & half) continue;
+                const int twi = (1 << (S0 + u)) + ((hi << u) | (c >> (R - u)));
+                bfly_fwd(v[c], v[c + half], tw[twi], m);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < (1 << R); c++) {
+            const int idx = base + (c << L);
+            if (last) st.store(dst_limb, idx, v[c], m);
+            else lds[idx] = v[c];
+        }
+    }
+    if (!last) __syncthreads();
+}
+
+// LD: prime(wg), dst_limb(wg), load(wg, idx, C) -> |x| <= p; kStaged loaders
+// fill LDS themselves in stage(), e.g. to apply a permutation.
+template <int LOGN, class LD, class ST>
+__global__ void __launch_bounds__((1 << LOGN) / ELEMS)
+ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *__restrict__ C)
+{
+    __shared__ double lds[1 << LOGN];
+    const int wg = blockIdx.x, tid = threadIdx.x;
+    const int pr = ld.prime(wg, C);
+    const ModD m = C->mod[pr];
+    const double *tw = tw_all + ((size_t)pr << LOGN);
+    const int dl = ld.dst_limb(wg, C);
+    if constexpr (LD::kStaged) {
+        ld.template stage<LOGN>(lds, wg, tid, C);
+        __syncthreads();
+    }
+    fwd_pass<LOGN, 0>(lds, ld, st, wg, tid, tw, m, dl, C);
+    fwd_pass<LOGN, 1>(lds, ld, st, wg, tid, tw, m, dl, C);
+    fwd_pass<LOGN, 2>(lds, ld, st, wg, tid, tw, m, dl, C);
+    if constexpr (Plan<LOGN>::NP > 3) fwd_pass<LOGN, 3>(lds, ld, st, wg, tid, tw, m, dl, C);
+}
+
+// ---------------------------------------------------------------------------
+// inverse transform (passes in reverse order; N^-1 folded into the last stage)
+// ---------------------------------------------------------------------------
+template <int LOGN, int PASS, class LD, class ST>
+__device__ __forceinline__ void inv_pass(double *lds, const LD &ld, const ST &st, int wg, int tid,
+                                         const double *__restrict__ itw, const ModD m, int pr,
+                                         const DevConst *C)
+{
+    using P = Plan<LOGN>;
+    constexpr int R = P::R[PASS];
+    constexpr int S0 = stage_start<LOGN, PASS>();
+    constexpr int L = LOGN - S0 - R;
+    constexpr int G = ELEMS >> R;
+    constexpr int T = (1 << LOGN) / ELEMS;
+    constexpr bool first = PASS == P::NP - 1, last = PASS == 0;
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        const int gidx = tid + g * T;
+        const int lo = gidx & ((1 << L) - 1);
+        const int hi = last ? 0 : (gidx >> L);
+        const int base = (hi << (L + R)) | lo;
+        double v[1 << R];
+#pragma unroll
+        for (int c = 0; c < (1 << R); c++) {
+            const int idx = base + (c << L);
+            // every pass starts from |x| <= p/2: the sum path doubles per stage
+            v[c] = red(first ? ld.load(wg, idx, m, C) : lds[idx], m);
+        }
+#pragma unroll
+        for (int u = R - 1; u >= 0; u--) {
+            const int half = 1 << (R - 1 - u);
+            if (R == 4 && u == 1) {   // after two stages of a four-stage pass: |x| <= 2p -> p/2
+#pragma unroll
+                for (int c = 0; c < (1 << R); c++) v[c] = red(v[c], m);
+            }
+#pragma unroll
+            for (int c = 0; c < (1 << R); c++) {
+                if (c & half) continue;
+                if (last && u == 0) {
+                    // stage 0: single twiddle; fold N^-1 into both outputs
+                    const double d = v[c] - v[c + half];
+                    v[c] = mulmod(v[c] + v[c + half], C->ninv[pr], m);
+                    v[c + half] = mulmod(d, C->itw1_ninv[pr], m);
+                } else {
+                    const int twi = (1 << (S0 + u)) + ((hi << u) | (c >> (R - u)));
+                    bfly_inv(v[c], v[c + half], itw[twi], m);
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < (1 << R); c++) {
+            const int idx = base + (c << L);
+            if (last) st.store(wg, idx, v[c], m, C);
+            else lds[idx] = v[c];
+        }
+    }
+    if (!last) __syncthreads();
+}
+
+template <int LOGN, class LD, class ST>
+__global__ void __launch_bounds__((1 << LOGN) / ELEMS)
+ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst *__restrict__ C)
+{
+    __shared__ double lds[1 << LOGN];
+    const int wg = blockIdx.x, tid = threadIdx.x;
+    const int pr = ld.prime(wg, C);
+    const ModD m = C->mod[pr];
+    const double *itw = itw_all + ((size_t)pr << LOGN);
+    if constexpr (Plan<LOGN>::NP > 3) inv_pass<LOGN, 3>(lds, ld, st, wg, tid, itw, m, pr, C);
+    inv_pass<LOGN, 2>(lds, ld, st, wg, tid, itw, m, pr, C);
+    inv_pass<LOGN, 1>(lds, ld, st, wg, tid, itw, m, pr, C);
+    inv_pass<LOGN, 0>(lds, ld, st, wg, tid, itw, m, pr, C);
+}
+
+// ---------------------------------------------------------------------------
+// exact base conversion helpers (per coefficient, registers only)
+// ---------------------------------------------------------------------------
+// x[0..ns) canonical residues -> mixed-radix digits a[0..ns); returns true when
+// CENTRED and the integer exceeds floor(S/2) (its centred representative is x - S).
+template <bool CENTRED>
+__device__ __forceinline__ bool garner(const ConvTab &T, const DevConst *C, const double *x, double *a)
+{
+    a[0] = x[0];
+#pragma unroll
+    for (int j = 1; j < MAXS; j++) {
+        if (j < T.ns) {
+            const ModD mj = C->mod[T.sidx[j]];
+            double v = x[j];
+#pragma unroll
+            for (int i = 0; i < j; i++) v = mulmod(v - a[i], T.inv[i][j], mj);
+            a[j] = canon(v, mj);
+        }
+    }
+    bool gt = false;
+    if (CENTRED) {
+#pragma unroll
+        for (int i = 0; i < MAXS; i++)
+            if (i < T.ns) gt = (a[i] > T.half[i]) || (a[i] == T.half[i] && gt);
+    }
+    return gt;
+}
+// residue of the (optionally negative-shifted) integer modulo target jt; lazy, |.| < 3p
+__device__ __forceinline__ double horner(const ConvTab &T, const DevConst *C, const double *a, int jt,
+                                         bool neg)
+{
+    const ModD mt = C->mod[T.tidx[jt]];
+    double acc = 0.0;
+#pragma unroll
+    for (int i = MAXS - 1; i >= 0; i--) {
+        if (i < T.ns) acc = (i == T.ns - 1) ? a[i] : mulmod(acc, T.s_mod_t[i][jt], mt) + a[i];
+    }
+    if (neg) acc -= T.S_mod_t[jt];
+    return acc;
+}
+
+// ---------------------------------------------------------------------------
+// loaders / storers for the transforms
+// ---------------------------------------------------------------------------
+struct StF64 {      // forward output: lazy doubles
+    double *base;
+    __device__ __forceinline__ void store(int limb, int idx, double v, const ModD) const
+    {
+        base[((size_t)limb << logn) + idx] = v;
+    }
+    int logn;
+};
+struct StF64Red {   // forward output reduced to |x| <= p/2 (prepared keys and plaintexts)
+    double *base;
+    int logn;
+    __device__ __forceinline__ void store(int limb, int idx, double v, const ModD m) const
+    {
+        base[((size_t)limb << logn) + idx] = red(v, m);
+    }
+};
+struct StU64 {      // forward output: canonical uint64 (public transform entry point)
+    uint64_t *base;
+    int logn;
+    __device__ __forceinline__ void store(int limb, int idx, double v, const ModD m) const
+    {
+        base[((size_t)limb << logn) + idx] = f64_to_u64(canon(v, m));
+    }
+};
+
+// rows of uint64 residues, row w uses prime tab[w] (tab != null) or w % pmod
+struct LdRowsU64 {
+    static constexpr bool kStaged = false;
+    const uint64_t *src;
+    const uint32_t *tab;
+    int pmod, logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
+    __device__ __forceinline__ int dst_limb(int wg, const DevConst *) const { return wg; }
+    __device__ __forceinline__ double load(int wg, int idx, const DevConst *) const
+    {
+        return u64_to_f64(src[((size_t)wg << logn) + idx]);
+    }
+};
+
+// the four input polynomials of a tensor product, ciphertext primes only:
+// workgroup -> (unit b, poly p in {a0,a1,b0,b1}, prime i)
+struct LdMulQ {
+    static constexpr bool kStaged = false;
+    const uint64_t *cta, *ctb;
+    int a_group, logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
+    __device__ __forceinline__ int dst_limb(int wg, const DevConst *C) const
+    {
+        const int k = C->k, i = wg % k, bp = wg / k;   // bp = unit*4 + p
+        return bp * C->KL + i;
+    }
+    __device__ __forceinline__ double load(int wg, int idx, const DevConst *C) const
+    {
+        const int k = C->k, i = wg % k, bp = wg / k, p = bp & 3, un = bp >> 2;
+        const uint64_t *ct = (p < 2) ? cta + (((size_t)(un / a_group) * 2 * k) << logn)
+                                     : ctb + (((size_t)un * 2 * k) << logn);
+        return u64_to_f64(ct[((size_t)((p & 1) * k + i) << logn) + idx]);
+    }
+};
+// the auxiliary-prime rows produced by lift_ext_kernel: [b*4+p][l][N] doubles
+struct LdMulB {
+    static constexpr bool kStaged = false;
+    const double *ext;
+    int logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return C->k + wg % C->l; }
+    __device__ __forceinline__ int dst_limb(int wg, const DevConst *C) const
+    {
+        const int l = C->l, j = wg % l, bp = wg / l;
+        return bp * C->KL + C->k + j;
+    }
+    __device__ __forceinline__ double load(int wg, int idx, const DevConst *) const
+    {
+        return ext[((size_t)wg << logn) + idx];
+    }
+};
+
+// key-switch mod-up: workgroup -> (unit b, digit j, target prime r); the digit is
+// the integer in [0,Q_j) formed by alpha rows of the source ring element; with
+// galois != 0 the source is first mapped by X -> X^galois (scatter through LDS,
+// an odd multiplier permutes the LDS banks without conflicts).
+struct LdModup {
+    static constexpr bool kStaged = true;
+    const uint64_t *src;     // ring element of unit 0
+    size_t unit_stride;      // in uint64
+    uint32_t galois;
+    int logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->L; }
+    __device__ __forceinline__ int dst_limb(int wg, const DevConst *) const { return wg; }
+    template <int LOGN>
+    __device__ __forceinline__ void stage(double *lds, int wg, int tid, const DevConst *C) const
+    {
+        constexpr int N = 1 << LOGN, T = N / ELEMS;
+        const int L = C->L, r = wg % L, j = (wg / L) % C->dnum, b = wg / (L * C->dnum);
+        const ConvTab &T_ = C->dig[j];
+        const ModD mr = C->mod[r];
+        const uint64_t *e = src + (size_t)b * unit_stride;
+#pragma unroll 4
+        for (int it = 0; it < ELEMS; it++) {
+            const int idx = tid + it * T;
+            // the Galois map acts on the element modulo Q: a negated coefficient is q_s - x in every
+            // source row, and only then is the digit lifted to [0, Q_j) and reduced modulo the target
+            int dst = idx;
+            bool negate = false;
+            if (galois) {
+                const uint32_t ee = ((uint32_t)idx * galois) & (2 * N - 1);
+                negate = ee >= (uint32_t)N;
+                dst = (int)(negate ? ee - N : ee);
+            }
+            double x[MAXS], a[MAXS];
+#pragma unroll
+            for (int s = 0; s < 3; s++)
+                if (s < T_.ns) {
+                    x[s] = u64_to_f64(e[((size_t)T_.sidx[s] << LOGN) + idx]);
+                    if (negate) x[s] = (x[s] == 0.0) ? 0.0 : C->mod[T_.sidx[s]].p - x[s];
+                }
+            garner<false>(T_, C, x, a);
+            const double v = canon(horner(T_, C, a, r, false), mr);
+            lds[dst] = v;
+        }
+    }
+    __device__ __forceinline__ double load(int, int, const DevConst *) const { return 0.0; }
+};
+
+// plaintext polynomial mod t -> centred lift -> row modulo q_i: workgroup -> (b, i)
+struct LdPlain {
+    static constexpr bool kStaged = false;
+    const uint64_t *pt;
+    int logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
+    __device__ __forceinline__ int dst_limb(int wg, const DevConst *) const { return wg; }
+    __device__ __forceinline__ double load(int wg, int idx, const DevConst *C) const
+    {
+        const double v = u64_to_f64(pt[((size_t)(wg / C->k) << logn) + idx]);
+        return (v > 0.5 * (C->tmod - 1.0)) ? v - C->tmod : v;
+    }
+};
+
+// inverse-transform loaders: prime(wg), load(wg, idx, m, C) (any lazy value < 8p)
+struct LdInvF64 {
+    const double *src;
+    const uint32_t *tab;
+    int pmod, logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
+    __device__ __forceinline__ double load(int wg, int idx, const ModD, const DevConst *) const
+    {
+        return src[((size_t)wg << logn) + idx];
+    }
+};
+struct LdInvU64 {
+    const uint64_t *src;
+    const uint32_t *tab;
+    int pmod, logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
+    __device__ __forceinline__ double load(int wg, int idx, const ModD, const DevConst *) const
+    {
+        return u64_to_f64(src[((size_t)wg << logn) + idx]);
+    }
+};
+// transformed ciphertext row times prepared plaintext row (ct x pt fused into the load):
+// workgroup -> (unit b, comp c, prime i), plaintext = plain[b*pstride + pofs]
+struct LdInvMulPlain {
+    const double *ctf;     // forward-transformed ciphertext rows [b][2][k][N]
+    const double *plain;   // prepared plaintexts [*][k][N]
+    int pstride, pofs, logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
+    __device__ __forceinline__ double load(int wg, int idx, const ModD m, const DevConst *C) const
+    {
+        const int k = C->k, i = wg % k, b = wg / (2 * k);
+        const double x = ctf[((size_t)wg << logn) + idx];
+        const double w = plain[((size_t)((b * pstride + pofs) * k + i) << logn) + idx];
+        return mulmod(x, w, m);
+    }
+};
+
+struct StInvF64 {
+    double *dst;
+    int logn;
+    __device__ __forceinline__ void store(int wg, int idx, double v, const ModD, const DevConst *) const
+    {
+        dst[((size_t)wg << logn) + idx] = v;
+    }
+};
+struct StInvU64 {
+    uint64_t *dst;
+    int logn;
+    __device__ __forceinline__ void store(int wg, int idx, double v, const ModD m, const DevConst *) const
+    {
+        dst[((size_t)wg << logn) + idx] = f64_to_u64(canon(v, m));
+    }
+};
+// cache append: workgroup -> (cache c, comp, prime); target row = cache + c*stride + row;
+// fresh != 0 stores, otherwise adds to what is there
+struct StInvAppend {
+    uint64_t *cache;        // first target ciphertext (cache 0)
+    size_t cache_stride;    // uint64 between consecutive caches' target ciphertexts
+    int fresh, logn;
+    __device__ __forceinline__ void store(int wg, int idx, double v, const ModD m, const DevConst *C) const
+    {
+        const int rows = 2 * C->k, c = wg / rows, row = wg % rows;
+        uint64_t *p = cache + (size_t)c * cache_stride + ((size_t)row << logn) + idx;
+        double r = canon(v, m);
+        if (!fresh) r = addmod_canon(r, u64_to_f64(*p), m);
+        *p = f64_to_u64(r);
+    }
+};
+
+// ---------------------------------------------------------------------------
+// pointwise kernels
+// ---------------------------------------------------------------------------
+constexpr int PW_THREADS = 256;
+
+// mul prologue: centred lift of the 4 input polynomials into the auxiliary basis.
+// thread -> (b*4+p, n); out ext[b*4+p][j][n] canonical doubles
+__global__ void __launch_bounds__(PW_THREADS)
+lift_ext_kernel(const uint64_t *__restrict__ a, const uint64_t *__restrict__ b, double *__restrict__ ext,
+                int a_group, int total_polys, const DevConst *__restrict__ C)
+{
+    const int logn = C->logn, N = 1 << logn, k = C->k, l = C->l;
+    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    const int n = (int)(gid & (N - 1));
+    const int bp = (int)(gid >> logn);
+    if (bp >= total_polys) return;
+    const int p = bp & 3, u = bp >> 2;
+    const uint64_t *ct = (p < 2) ? a + (((size_t)(u / a_group) * 2 * k) << logn) : b + (((size_t)u * 2 * k) << logn);
+    ct += ((size_t)((p & 1) * k) << logn) + n;
+    double x[MAXS], dg[MAXS];
+#pragma unroll
+    for (int i = 0; i < MAXS; i++)
+        if (i < k) x[i] = u64_to_f64(ct[(size_t)i << logn]);
+    const bool neg = garner<true>(C->q2b, C, x, dg);
+    double *o = ext + (((size_t)bp * l) << logn) + n;
+#pragma unroll
+    for (int j = 0; j < MAXS; j++)
+        if (j < l) o[(size_t)j << logn] = canon(horner(C->q2b, C, dg, j, neg), C->mod[k + j]);
+}
+
+// tensor product in the transform domain over all k+l primes.
+// ntt[b*4+p][r][n] (lazy) -> tens[b*3+c][r][n] (lazy)
+__global__ void __launch_bounds__(PW_THREADS)
+tensor_kernel(const double *__restrict__ ntt, double *__restrict__ tens, int batch,
+              const DevConst *__restrict__ C)
+{
+    const int logn = C->logn, N = 1 << logn, KL = C->KL;
+    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    const int n = (int)(gid & (N - 1));
+    const int br = (int)(gid >> logn);
+    if (br >= batch * KL) return;
+    const int r = br % KL, b = br / KL;
+    const ModD m = C->mod[r];
+    const size_t pstride = (size_t)KL << logn;
+    const double *src = ntt + (size_t)b * 4 * pstride + ((size_t)r << logn) + n;
+    // forward outputs are lazy (< 4p); bring them to p/2 so the two-term sum stays far below 2^53
+    const double a0 = red(src[0], m), a1 = red(src[pstride], m);
+    const double b0 = red(src[2 * pstride], m), b1 = red(src[3 * pstride], m);
+    double *dst = tens + (size_t)b * 3 * pstride + ((size_t)r << logn) + n;
+    dst[0] = mulmod(a0, b0, m);
+    dst[pstride] = mulmod(a0, b1, m) + mulmod(a1, b0, m);
+    dst[2 * pstride] = mulmod(a1, b1, m);
+}
+
+// exact round(t e / Q) mod Q from e known modulo Q and the auxiliary basis:
+//   r = centred (t e mod Q);  y = (t e - r) / Q computed modulo each b_j;
+//   y is below B/2 in magnitude, so its centred lift from the auxiliary basis is exact.
+// tens[b*3+c][r][n] (lazy, coefficient order) -> out[b][c][i][n] canonical uint64;
+// acc != 0 adds the result to what out already holds (sum of products).
+__global__ void __launch_bounds__(PW_THREADS)
+scale_kernel(const double *__restrict__ tens, uint64_t *__restrict__ out, int total_polys, int acc,
+             const DevConst *__restrict__ C)
+{
+    const int logn = C->logn, N = 1 << logn, k = C->k, l = C->l, KL = C->KL;
+    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    const int n = (int)(gid & (N - 1));
+    const int bc = (int)(gid >> logn);
+    if (bc >= total_polys) return;
+    const double *src = tens + (((size_t)bc * KL) << logn) + n;
+    const double t = C->tmod;
+    double x[MAXS], dg[MAXS], y[MAXS];
+#pragma unroll
+    for (int i = 0; i < MAXS; i++)
+        if (i < k) x[i] = canon(mulmod(src[(size_t)i << logn], t, C->mod[i]), C->mod[i]);
+    const bool neg = garner<true>(C->q2b, C, x, dg);
+#pragma unroll
+    for (int j = 0; j < MAXS; j++)
+        if (j < l) {
+            const ModD mb = C->mod[k + j];
+            const double te = mulmod(src[(size_t)(k + j) << logn], t, mb);
+            const double rj = horner(C->q2b, C, dg, j, neg);
+            y[j] = canon(mulmod(red(te - rj, mb), C->Qinv_b[j], mb), mb);
+        }
+    const bool neg2 = garner<true>(C->b2q, C, y, dg);
+    uint64_t *o = out + (((size_t)bc * k) << logn) + n;
+#pragma unroll
+    for (int i = 0; i < MAXS; i++)
+        if (i < k) {
+            double v = canon(horner(C->b2q, C, dg, i, neg2), C->mod[i]);
+            if (acc) v = addmod_canon(v, u64_to_f64(o[(size_t)i << logn]), C->mod[i]);
+            o[(size_t)i << logn] = f64_to_u64(v);
+        }
+}
+
+// key-switch inner product: dig[b][j][r][n] (lazy) x key[j][c][r][n] -> acc[b][c][r][n] (lazy)
+__global__ void __launch_bounds__(PW_THREADS)
+ks_inner_kernel(const double *__restrict__ dig, const double *__restrict__ key, double *__restrict__ accb,
+                int batch, const DevConst *__restrict__ C)
+{
+    const int logn = C->logn, N = 1 << logn, L = C->L, dnum = C->dnum;
+    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    const int n = (int)(gid & (N - 1));
+    const int br = (int)(gid >> logn);
+    if (br >= batch * L) return;
+    const int r = br % L, b = br / L;
+    const ModD m = C->mod[r];
+    double s0 = 0.0, s1 = 0.0;
+    for (int j = 0; j < dnum; j++) {
+        const double d = red(dig[(((size_t)(b * dnum + j) * L + r) << logn) + n], m);
+        const double k0 = key[(((size_t)(j * 2 + 0) * L + r) << logn) + n];
+        const double k1 = key[(((size_t)(j * 2 + 1) * L + r) << logn) + n];
+        s0 += mulmod(d, k0, m);
+        s1 += mulmod(d, k1, m);
+    }
+    accb[(((size_t)(b * 2 + 0) * L + r) << logn) + n] = s0;
+    accb[(((size_t)(b * 2 + 1) * L + r) << logn) + n] = s1;
+}
+
+// mod-down with rounding and the final additions of relinearisation / rotation:
+//   u = floor((A + floor(P/2)) / P) mod Q,  out[b][c] = u (+ add0) (+ add1)
+// add0: relin -> in3[b][c];  rotate -> sigma_g(in2[b][0]) for c = 0, nothing for c = 1
+// add1: rotate with accumulate -> in2[b][c]
+struct ModdownArgs {
+    const double *acc;        // [b][2][L][N] lazy, coefficient order
+    uint64_t *out;            // unit b at out + b*out_stride, [2][k][N]
+    size_t out_stride;
+    const uint64_t *add;      // base of the addend ciphertexts (unit 0) or null
+    size_t add_stride;        // uint64 per unit in add
+    uint32_t galois;          // != 0: add is permuted by X -> X^galois and only applies to c = 0
+    int accumulate;           // also add the un-permuted add[b][c]
+    int batch;
+};
+__global__ void __launch_bounds__(PW_THREADS)
+moddown_kernel(ModdownArgs A, const DevConst *__restrict__ C)
+{
+    const int logn = C->logn, N = 1 << logn, k = C->k, nsp = C->nsp, L = C->L;
+    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    const int n = (int)(gid & (N - 1));
+    const int bc = (int)(gid >> logn);
+    if (bc >= A.batch * 2) return;
+    const int c = bc & 1, b = bc >> 1;
+    const double *src = A.acc + (((size_t)bc * L) << logn) + n;
+    double xp[MAXS], dg[MAXS];
+#pragma unroll
+    for (int s = 0; s < 2; s++)
+        if (s < nsp) {
+            const ModD mp = C->mod[k + s];
+            xp[s] = addmod_canon(canon(src[(size_t)(k + s) << logn], mp), C->halfP[k + s], mp);
+        }
+    garner<false>(C->p2q, C, xp, dg);
+    int src_idx = 0;
+    bool negate = false;
+    if (A.galois) {
+        // inverse map: output index n takes the coefficient from index n * g^-1 mod 2N
+        // (A.galois already holds g^-1 mod 2N)
+        const uint32_t e = ((uint32_t)n * A.galois) & (2 * N - 1);
+        negate = e >= (uint32_t)N;
+        src_idx = (int)(negate ? e - N : e);
+    }
+    uint64_t *o = A.out + (size_t)b * A.out_stride + (((size_t)c * k) << logn) + n;
+#pragma unroll
+    for (int i = 0; i < MAXS; i++)
+        if (i < k) {
+            const ModD mq = C->mod[i];
+            const double ai = addmod_canon(canon(src[(size_t)i << logn], mq), C->halfP[i], mq);
+            const double ri = horner(C->p2q, C, dg, i, false);
+            double v = canon(mulmod(red(ai - ri, mq), C->Pinv_q[i], mq), mq);
+            if (A.add) {
+                const uint64_t *ad = A.add + (size_t)b * A.add_stride;
+                if (A.galois) {
+                    if (c == 0) {
+                        double w = u64_to_f64(ad[((size_t)i << logn) + src_idx]);
+                        if (negate) w = (w == 0.0) ? 0.0 : mq.p - w;
+                        v = addmod_canon(v, w, mq);
+                    }
+                    if (A.accumulate) v = addmod_canon(v, u64_to_f64(ad[((size_t)(c * k + i) << logn) + n]), mq);
+                } else {
+                    v = addmod_canon(v, u64_to_f64(ad[((size_t)(c * k + i) << logn) + n]), mq);
+                }
+            }
+            o[(size_t)i << logn] = f64_to_u64(v);
+        }
+}
+
+// out = a + b over `rows` rows of N residues, row w modulo q_(w % k)
+__global__ void __launch_bounds__(PW_THREADS)
+add_kernel(const uint64_t *__restrict__ a, const uint64_t *__restrict__ b, uint64_t *__restrict__ out,
+           int rows, const DevConst *__restrict__ C)
+{
+    const int logn = C->logn, N = 1 << logn;
+    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    const int row = (int)(gid >> logn);
+    if (row >= rows) return;
+    (void)N;
+    const ModD m = C->mod[row % C->k];
+    out[gid] = f64_to_u64(addmod_canon(u64_to_f64(a[gid]), u64_to_f64(b[gid]), m));
+}
+
+// out[g][e] = sum_{c < group} in[g*group + c][e] over rows*N elements per unit (row w mod q_(w%k))
+__global__ void __launch_bounds__(PW_THREADS)
+sum_groups_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out, int groups, int group,
+                  int rows, const DevConst *__restrict__ C)
+{
+    const int logn = C->logn;
+    const size_t per = (size_t)rows << logn;
+    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    if (gid >= per * (size_t)groups) return;
+    const size_t g = gid / per, e = gid % per;
+    const ModD m = C->mod[(int)(e >> logn) % C->k];
+    double s = u64_to_f64(in[(g * group) * per + e]);
+    for (int c = 1; c < group; c++) s = addmod_canon(s, u64_to_f64(in[(g * group + c) * per + e]), m);
+    out[gid] = f64_to_u64(s);
+}
+
+// arithmetic micro-benchmark: `iters` dependent products per lane
+__global__ void __launch_bounds__(PW_THREADS)
+bench_modmul_kernel(int kind, uint32_t n_lanes, uint32_t iters, uint64_t *__restrict__ out, ModD md, ModI mi)
+{
+    const uint32_t gid = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (gid >= n_lanes) return;
+    const uint64_t x0 = (0x9E3779B97F4A7C15ull * (gid + 1)) % mi.q;
+    const uint64_t w0 = (0xD1B54A32D192ED03ull * (gid + 7)) % mi.q;
+    if (kind == 0) {
+        double x = u64_to_f64(x0), y = u64_to_f64(w0);
+        const double w = u64_to_f64(w0);
+        for (uint32_t i = 0; i < iters; i++) {
+            x = mulmod(x, w, md);
+            y = mulmod(y, x, md);
+        }
+        out[gid] = f64_to_u64(canon(x, md)) ^ f64_to_u64(canon(y, md));
+    } else {
+        uint64_t x = x0, y = w0;
+        for (uint32_t i = 0; i < iters; i++) {
+            x = mulmod_barrett(x, w0, mi);
+            y = mulmod_barrett(y, x, mi);
+        }
+        out[gid] = x ^ y;
+    }
+}
+
+}  // namespace cg

@@ -1,0 +1,331 @@
+"""Bit-exact parity of the HIP library (through its C ABI) with the CPU oracle.
+
+Inputs are seeded: mostly uniformly random canonical residues (every evaluator
+operation is defined on arbitrary residues, and a fresh ciphertext is
+indistinguishable from uniform), plus real encryptions where the decrypted
+meaning is checked as well.  Sizes: the three parameter sets of the benchmark
+configurations (N = 4096/k = 2, N = 8192/k = 3, N = 16384/k = 6 with two
+special primes and alpha = 2), batches spanning several workgroups.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from workloads import PRESETS, Stream, attention_activations, pseudo_ciphertexts, pseudo_switch_key
+
+
+def say(msg):
+    print(f"[gpu-parity] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+class Env:
+    def __init__(self, name):
+        import paper_2602_08798_amd as P
+        from oracle import Oracle
+        self.P = P
+        self.name = name
+        self.prm = PRESETS[name]
+        self.ctx = P.Context(self.prm)
+        self.orc = Oracle(self.prm)
+        self.n, self.k = self.prm.n, self.prm.k
+        self.qp = list(self.prm.q) + list(self.prm.p)
+        self._keys = {}
+
+    def cts(self, seed, batch, ncomp=2):
+        return pseudo_ciphertexts(Stream(seed, 1), self.prm.q, self.n, batch, ncomp)
+
+    def key(self, seed):
+        """(raw numpy key, prepared device key)"""
+        if seed not in self._keys:
+            raw = pseudo_switch_key(Stream(seed, 2), self.qp, self.n, self.prm.dnum)
+            self._keys[seed] = (raw, self.ctx.ksk_prepare(self.P.to_device(raw)))
+        return self._keys[seed]
+
+    def dev(self, a):
+        return self.P.to_device(a)
+
+    def host(self, t):
+        import torch
+        torch.cuda.synchronize()
+        return self.P.to_host(t)
+
+
+_envs = {}
+
+
+@pytest.fixture(params=["C1", "C2", "C5"])
+def env(request):
+    if request.param not in _envs:
+        _envs[request.param] = Env(request.param)
+    return _envs[request.param]
+
+
+def test_transform_matches_definition(env):
+    say(f"ntt {env.name}")
+    from oracle import bfv
+    L = env.k + env.prm.nsp
+    idx = [i % L for i in range(L + 3)]
+    rng = np.random.default_rng(1)
+    rows = np.stack([rng.integers(0, env.qp[i], env.n, dtype=np.uint64) for i in idx])
+    rows[0, :4] = [0, 1, env.qp[idx[0]] - 1, env.qp[idx[0]] - 2]
+    got = env.host(env.ctx.ntt_forward(env.dev(rows), idx))
+    for r, i in enumerate(idx):
+        assert np.array_equal(got[r], bfv.ntt_forward(rows[r], env.qp[i])), (env.name, r)
+    back = env.host(env.ctx.ntt_inverse(env.dev(got), idx))
+    assert np.array_equal(back, rows)
+
+
+def test_mul_matches_oracle(env):
+    say(f"mul {env.name}")
+    batch = 3
+    a, b = env.cts(10, batch), env.cts(11, batch)
+    # extreme residues in unit 0: zeros, q-1, and the two values around Q/2
+    Q = int(np.prod([int(x) for x in env.prm.q], dtype=object))
+    for i, m in enumerate(env.prm.q):
+        a[0, 0, i, :4] = [0, m - 1, (Q // 2) % m, (Q // 2 + 1) % m]
+        b[0, 1, i, :4] = [m - 1, m - 1, (Q // 2) % m, (Q // 2 + 1) % m]
+    got = env.host(env.ctx.mul(env.dev(a), env.dev(b), batch))
+    for u in range(batch):
+        assert np.array_equal(got[u], env.orc.mul(a[u], b[u])), (env.name, u)
+    say(f"mul a_group {env.name}")
+    got = env.host(env.ctx.mul(env.dev(a[:1]), env.dev(b), batch, a_group=3))
+    for u in range(batch):
+        assert np.array_equal(got[u], env.orc.mul(a[0], b[u])), (env.name, u)
+
+
+def test_relin_and_mul_relin_match_oracle(env):
+    say(f"relin {env.name}")
+    batch = 2
+    raw, rlk = env.key(20)
+    d3 = env.cts(21, batch, 3)
+    got = env.host(env.ctx.relin(env.dev(d3), rlk, batch))
+    for u in range(batch):
+        assert np.array_equal(got[u], env.orc.relin(d3[u], raw)), (env.name, u)
+    say(f"mul_relin {env.name}")
+    a, b = env.cts(22, batch), env.cts(23, batch)
+    got = env.host(env.ctx.mul_relin(env.dev(a), env.dev(b), rlk, batch))
+    for u in range(batch):
+        assert np.array_equal(got[u], env.orc.relin(env.orc.mul(a[u], b[u]), raw)), (env.name, u)
+
+
+def test_rotate_matches_oracle(env):
+    batch = 2
+    raw, gk = env.key(30)
+    x = env.cts(31, batch)
+    x[0, :, :, :3] = 0                                     # zero coefficients: negation of 0 stays 0
+    n = env.n
+    for g in (3, pow(3, 64, 2 * n), 2 * n - 1, 1, 2 * n - 3):
+        for acc in (False, True):
+            say(f"rotate {env.name} g={g} acc={acc}")
+            got = env.host(env.ctx.rotate(env.dev(x), g, gk, batch, accumulate=acc))
+            for u in range(batch):
+                want = env.orc.rotate(x[u], g, raw)
+                if acc:
+                    want = env.orc.add(x[u], want)
+                assert np.array_equal(got[u], want), (env.name, g, acc, u)
+
+
+def test_add_matches_oracle(env):
+    say(f"add {env.name}")
+    for ncomp in (2, 3):
+        a, b = env.cts(40, 2, ncomp), env.cts(41, 2, ncomp)
+        got = env.host(env.ctx.add(env.dev(a), env.dev(b), ncomp, 2))
+        for u in range(2):
+            assert np.array_equal(got[u], env.orc.add(a[u], b[u]))
+
+
+def test_mul_plain_and_append_match_oracle(env):
+    say(f"mul_plain {env.name}")
+    n, t = env.n, env.prm.t
+    rng = np.random.default_rng(50)
+    pts = rng.integers(0, t, (3, n), dtype=np.uint64)
+    pts[0, :2] = [t // 2, t // 2 + 1]
+    plain = env.ctx.plain_prepare(env.dev(pts))
+    x = env.cts(51, 3)
+    got = env.host(env.ctx.mul_plain(env.dev(x), plain, 3, plain_stride=1))
+    for u in range(3):
+        assert np.array_equal(got[u], env.orc.mul_plain(x[u], pts[u]))
+    got = env.host(env.ctx.mul_plain(env.dev(x), plain, 3, plain_stride=0))
+    for u in range(3):
+        assert np.array_equal(got[u], env.orc.mul_plain(x[u], pts[0]))
+
+    say(f"kv_append {env.name}")
+    # 3 caches of 2 ciphertexts each; "masks" are arbitrary plaintexts here (B of them is too many to
+    # transform on the CPU, so the cache geometry uses d2 = N/4, B = 4)
+    d2 = n // 4
+    masks_pt = rng.integers(0, t, (4, n), dtype=np.uint64)
+    masks = env.ctx.plain_prepare(env.dev(masks_pt))
+    cache = env.cts(52, 6)                                  # junk contents: first append must ignore them
+    want = cache.copy()
+    dcache = env.dev(cache)
+    for tau in (0, 1, 3, 4, 5):
+        rows = env.cts(60 + tau, 3)
+        env.ctx.kv_append(dcache, 2, 3, tau, env.dev(rows), masks, d2)
+        for c in range(3):
+            idx, blk = divmod(tau, 4)
+            masked = env.orc.mul_plain(rows[c], masks_pt[blk])
+            want[c * 2 + idx] = masked if blk == 0 else env.orc.add(want[c * 2 + idx], masked)
+    assert np.array_equal(env.host(dcache), want)
+
+
+def _fold_keys(env, d2):
+    n = env.n
+    gs, sh = [], 1
+    while sh < d2:
+        gs.append(pow(3, sh, 2 * n))
+        sh *= 2
+    return gs
+
+
+def _block_keys(env, d2):
+    n = env.n
+    gs, sh = [], d2
+    while sh <= n // 4:
+        gs.append(pow(3, sh, 2 * n))
+        sh *= 2
+    return gs + [2 * n - 1]
+
+
+def test_decode_scores_match_oracle(env):
+    from oracle import attention
+    say(f"decode_scores {env.name}")
+    heads, n_cts, d2 = 2, 2, 64
+    raw_rlk, rlk = env.key(70)
+    gs = _fold_keys(env, d2)
+    keys = {g: env.key(100 + i) for i, g in enumerate(gs)}
+    q, kc = env.cts(71, heads), env.cts(72, heads * n_cts)
+    got = env.host(env.ctx.decode_scores(env.dev(q), env.dev(kc), heads, n_cts, d2, rlk,
+                                         [keys[g][1] for g in gs]))
+    raws = {g: keys[g][0] for g in gs}
+    for h in range(heads):
+        for c in range(n_cts):
+            want = attention.decode_scores(env.orc, q[h], kc[h * n_cts + c], raw_rlk, raws, d2)
+            assert np.array_equal(got[h, c], want), (env.name, h, c)
+
+
+def test_decode_context_match_oracle(env):
+    from oracle import attention
+    say(f"decode_context {env.name}")
+    heads, n_cts, d2 = 2, 3, 64
+    raw_rlk, rlk = env.key(70)
+    gs = _block_keys(env, d2)
+    keys = {g: env.key(200 + i) for i, g in enumerate(gs)}
+    a, vc = env.cts(81, heads * n_cts), env.cts(82, heads * n_cts)
+    got = env.host(env.ctx.decode_context(env.dev(a), env.dev(vc), heads, n_cts, d2, rlk,
+                                          [keys[g][1] for g in gs]))
+    raws = {g: keys[g][0] for g in gs}
+    for h in range(heads):
+        sl = slice(h * n_cts, (h + 1) * n_cts)
+        want = attention.decode_context(env.orc, list(a[sl]), list(vc[sl]), raw_rlk, raws, d2)
+        assert np.array_equal(got[h], want), (env.name, h)
+
+
+def test_prefill_diagonals_match_oracle():
+    from oracle import attention
+    env = _envs.setdefault("C1", Env("C1")) if "C1" in _envs else Env("C1")
+    _envs["C1"] = env
+    say("prefill_qk C1 params, d2 = 256 (m = 16 diagonals), 2 heads")
+    heads, d2 = 2, 256
+    n = env.n
+    raw_rlk, rlk = env.key(70)
+    gs = _fold_keys(env, d2)
+    keys = {g: env.key(300 + i) for i, g in enumerate(gs)}
+    g_blk, g_swap = pow(3, d2, 2 * n), 2 * n - 1
+    kb, ks = env.key(320), env.key(321)
+    q, kk = env.cts(91, heads), env.cts(92, heads)
+    got = env.host(env.ctx.prefill_qk(env.dev(q), env.dev(kk), heads, d2, rlk, [keys[g][1] for g in gs],
+                                      kb[1], ks[1]))
+    raws = {g: keys[g][0] for g in gs}
+    raws[g_blk], raws[g_swap] = kb[0], ks[0]
+    for h in range(heads):
+        want = attention.prefill_qk(env.orc, q[h], kk[h], raw_rlk, raws, d2)
+        assert len(want) == n // d2
+        for i, w in enumerate(want):
+            assert np.array_equal(got[h, i], w), (h, i)
+
+
+def test_real_ciphertexts_decrypt_to_attention_scores():
+    """End to end at the N = 8192 set: GPU scores on real encryptions decrypt to K q mod t."""
+    from oracle import Client, attention
+    env = _envs.get("C2") or Env("C2")
+    _envs["C2"] = env
+    say("semantic decode_scores C2")
+    prm, n, d2 = env.prm, env.n, 64
+    B = n // d2
+    cl = Client(prm, 4242, env.orc)
+    act = attention_activations(Stream(4242, 1), 1, B + 1, d2)[0]
+    qv, K = act[0], act[1:]
+    raw_rlk = cl.relin_key()
+    gs = _fold_keys(env, d2)
+    raw_g = {g: cl.galois_key(g) for g in gs}
+    q_ct = cl.encrypt_slots(np.tile(qv, B))
+    k_ct = cl.encrypt_slots(K.reshape(-1))
+    rlk = env.ctx.ksk_prepare(env.dev(raw_rlk))
+    gks = [env.ctx.ksk_prepare(env.dev(raw_g[g])) for g in gs]
+    got = env.host(env.ctx.decode_scores(env.dev(q_ct[None]), env.dev(k_ct[None]), 1, 1, d2, rlk, gks))[0, 0]
+    assert np.array_equal(got, attention.decode_scores(env.orc, q_ct, k_ct, raw_rlk, raw_g, d2))
+    assert np.array_equal(cl.decrypt_slots(got)[::d2], (K @ qv) % prm.t)
+
+
+def test_full_decode_step_shape_on_sampled_units():
+    """The launch configuration the benchmark times (12 heads x 4 cache ciphertexts at N = 8192):
+    a sample of output units is recomputed by the oracle one by one."""
+    from oracle import attention
+    env = _envs.get("C2") or Env("C2")
+    _envs["C2"] = env
+    say("full-shape decode step, sampled units")
+    heads, n_cts, d2 = 12, 4, 64
+    raw_rlk, rlk = env.key(70)
+    gs = _fold_keys(env, d2)
+    keys = {g: env.key(100 + i) for i, g in enumerate(gs)}
+    q, kc = env.cts(401, heads), env.cts(402, heads * n_cts)
+    got = env.host(env.ctx.decode_scores(env.dev(q), env.dev(kc), heads, n_cts, d2, rlk,
+                                         [keys[g][1] for g in gs]))
+    raws = {g: keys[g][0] for g in gs}
+    for (h, c) in [(0, 0), (5, 2), (11, 3)]:
+        want = attention.decode_scores(env.orc, q[h], kc[h * n_cts + c], raw_rlk, raws, d2)
+        assert np.array_equal(got[h, c], want), (h, c)
+    gb = _block_keys(env, d2)
+    bkeys = {g: env.key(200 + i) for i, g in enumerate(gb)}
+    a, vc = env.cts(403, heads * n_cts), env.cts(404, heads * n_cts)
+    got = env.host(env.ctx.decode_context(env.dev(a), env.dev(vc), heads, n_cts, d2, rlk,
+                                          [bkeys[g][1] for g in gb]))
+    braws = {g: bkeys[g][0] for g in gb}
+    for h in (0, 7, 11):
+        sl = slice(h * n_cts, (h + 1) * n_cts)
+        want = attention.decode_context(env.orc, list(a[sl]), list(vc[sl]), raw_rlk, braws, d2)
+        assert np.array_equal(got[h], want), h
+
+
+def test_invalid_arguments_are_rejected_without_launching():
+    import torch
+    from paper_2602_08798_amd.binding import CgError
+    env = _envs.get("C1") or Env("C1")
+    _envs["C1"] = env
+    say("negative tests")
+    x = env.dev(env.cts(1, 1))
+    raw, gk = env.key(30)
+    with pytest.raises(CgError):
+        env.ctx.rotate(x, 2, gk, 1)                     # even Galois element
+    with pytest.raises(CgError):
+        env.ctx.rotate(x, 2 * env.n + 1, gk, 1)         # out of range
+    with pytest.raises(CgError):
+        env.ctx.rotate(x, 3, gk, 1, out=x)              # in-place is not supported
+    with pytest.raises(CgError):
+        env.ctx.add(x, x, 4, 1)                         # ncomp must be 2 or 3
+    with pytest.raises(CgError):
+        env.ctx.kv_append(x, 1, 1, env.n, x, gk, env.n // 4)   # token beyond the cache
+    # unsupported parameter sets never reach the device
+    import dataclasses
+    P = env.P
+    bad = dataclasses.replace(env.prm, q=(env.prm.q[0], env.prm.q[0]))
+    with pytest.raises(CgError):
+        P.Context(bad)
+    bad = dataclasses.replace(env.prm, q=(env.prm.q[0], (1 << 50) - 27))   # not 1 mod 2N
+    with pytest.raises(CgError):
+        P.Context(bad)
+    torch.cuda.synchronize()
