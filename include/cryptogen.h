@@ -124,7 +124,7 @@ int cg_mul(cg_ctx *ctx, void *stream, const uint64_t *a2_dev, const uint64_t *b2
  *   digit_j = d2 mod Q_j as the integer polynomial with coefficients in [0,Q_j);
  *   A_c = sum_j digit_j * key_{j,c}  mod P Q, coefficients taken in [0,PQ);
  *   u_c = floor((A_c + floor(P/2)) / P) mod Q.
- * out2 may alias the first two components of in3. */
+ * out2 must not overlap in3. */
 int cg_relin(cg_ctx *ctx, void *stream, const uint64_t *in3_dev, const void *rlk_dev,
              uint64_t *out2_dev, uint32_t batch, void *ws_dev);
 
@@ -138,8 +138,8 @@ int cg_mul_relin(cg_ctx *ctx, void *stream, const uint64_t *a2_dev, const uint64
  * i*g mod 2N >= N;  rot = (sigma_g(c0) + u0, u1), u = KeySwitch(sigma_g(c1), gk).
  * galois_elt g must be odd, 0 < g < 2N, and gk the prepared key for s(X^g) -> s.
  * accumulate = 0: out2 = rot;  accumulate = 1: out2 = in2 + rot (one step of a
- * rotate-and-add reduction).  out2 may alias in2 only when ws_dev was sized by
- * cg_workspace_bytes for this batch (the input is read before any write). */
+ * rotate-and-add reduction).  out2 must not overlap in2 (the permuted read of c0
+ * happens while other outputs are written); in2 == out2 is rejected. */
 int cg_rotate(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, uint32_t galois_elt,
               const void *gk_dev, uint64_t *out2_dev, uint32_t batch, int accumulate,
               void *ws_dev);
@@ -170,13 +170,16 @@ int cg_kv_append(cg_ctx *ctx, void *stream, uint64_t *cache_dev, uint32_t cache_
                  const void *masks_dev, uint32_t d2, void *ws_dev);
 
 /* Decode attention scores, ARCC inner-outer mode (section 4.3): for every head h
- * and cache ciphertext c (n_cts per head, stored [heads][n_cts]):
+ * and cache ciphertext c < n_cts (head h's cache starts at ciphertext index
+ * h * cache_stride_cts of kcache_dev, the layout cg_kv_append maintains):
  *   x = relin(mul(q[h], K[h][c]));  for sh = 1, 2, 4, ..., d2/2: x = x + rotate(x, 3^sh mod 2N);
  *   out[h][c] = x  -- flat slot b*d2 of x decrypts to <q_h, K_token b> mod t.
+ * out is dense: [heads][n_cts] ciphertexts.
  * gk_fold_dev_host: host array of log2(d2) device pointers, prepared keys for
  * g = 3^1, 3^2, 3^4, ... (mod 2N) in that order. */
 int cg_decode_scores(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *kcache_dev,
-                     uint32_t heads, uint32_t n_cts, uint32_t d2, const void *rlk_dev,
+                     uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2,
+                     const void *rlk_dev,
                      const void *const *gk_fold_dev_host, uint64_t *out_dev, void *ws_dev);
 
 /* Decode attention context, ARCC inner-inner mode with the weight of token b
@@ -184,10 +187,13 @@ int cg_decode_scores(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uin
  *   y = sum_c mul(a[h][c], V[h][c])   (three components, c ascending);  x = relin(y);
  *   for sh = d2, 2 d2, ..., N/4: x = x + rotate(x, 3^sh mod 2N);  x = x + rotate(x, 2N-1);
  *   out[h] = x  -- every block of x decrypts to sum_tokens a_tau V_tau mod t.
+ * a is dense ([heads][n_cts]); head h's V cache starts at ciphertext index
+ * h * cache_stride_cts of vcache_dev.
  * gk_block_dev_host: host array of device pointers, prepared keys for
  * g = 3^d2, 3^(2 d2), ..., 3^(N/4), then 2N-1, in that order. */
 int cg_decode_context(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *vcache_dev,
-                      uint32_t heads, uint32_t n_cts, uint32_t d2, const void *rlk_dev,
+                      uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2,
+                      const void *rlk_dev,
                       const void *const *gk_block_dev_host, uint64_t *out_dev, void *ws_dev);
 
 /* Prefill Q K^T for `heads` heads as m = N/d2 generalised diagonals per head
@@ -202,6 +208,23 @@ int cg_prefill_qk(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64
                   uint32_t heads, uint32_t d2, const void *rlk_dev,
                   const void *const *gk_fold_dev_host, const void *gk_blk_dev,
                   const void *gk_swap_dev, uint64_t *out_dev, void *ws_dev);
+
+/* Benchmark support: between cg_profile_begin and cg_profile_end every kernel
+ * launch of this context is bracketed by a pair of HIP events on the stream it is
+ * launched on.  cg_profile_end waits for the recorded events and returns, per
+ * kernel class, the number of launches, their summed duration and their summed
+ * algorithmic bytes (distinct inputs read once plus outputs written once).
+ * At most max_launches launches are recorded (later ones run untimed).  Not
+ * thread-safe; do not use around graph capture. */
+typedef struct {
+    uint32_t kernel_id;   /* see cg_kernel_name */
+    uint32_t launches;
+    double total_ms;
+    double algo_bytes;
+} cg_kernel_stat;
+int cg_profile_begin(cg_ctx *ctx, uint32_t max_launches);
+int cg_profile_end(cg_ctx *ctx, cg_kernel_stat *stats_host, uint32_t cap, uint32_t *n_out_host);
+const char *cg_kernel_name(uint32_t kernel_id);
 
 /* Micro-benchmark of the modular multiply used by every kernel (evidence for
  * the arithmetic choice): runs `iters` dependent modular multiplications per

@@ -18,7 +18,7 @@ _SYMBOLS = [
     "cg_ntt_forward", "cg_ntt_inverse", "cg_ksk_prepare", "cg_plain_prepare",
     "cg_mul", "cg_relin", "cg_mul_relin", "cg_rotate", "cg_add", "cg_mul_plain",
     "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_prefill_qk",
-    "cg_bench_modmul",
+    "cg_bench_modmul", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
 ]
 
 
@@ -32,6 +32,11 @@ class _Sizes(C.Structure):
     _fields_ = [("ct2_bytes", C.c_size_t), ("ct3_bytes", C.c_size_t),
                 ("ksk_raw_bytes", C.c_size_t), ("ksk_bytes", C.c_size_t),
                 ("plain_bytes", C.c_size_t), ("ws_bytes_per_unit", C.c_size_t)]
+
+
+class _KernelStat(C.Structure):
+    _fields_ = [("kernel_id", C.c_uint32), ("launches", C.c_uint32),
+                ("total_ms", C.c_double), ("algo_bytes", C.c_double)]
 
 
 class Library:
@@ -64,12 +69,16 @@ class Library:
         d.cg_add.argtypes = [vp, vp, vp, vp, vp, u32, u32]
         d.cg_mul_plain.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp]
         d.cg_kv_append.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, u32, vp]
-        d.cg_decode_scores.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
-        d.cg_decode_context.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
+        d.cg_decode_scores.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
+        d.cg_decode_context.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_prefill_qk.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp, vp, vp]
         d.cg_bench_modmul.argtypes = [vp, vp, i32, u32, u32, vp]
+        d.cg_profile_begin.argtypes = [vp, u32]
+        d.cg_profile_end.argtypes = [vp, C.POINTER(_KernelStat), u32, C.POINTER(u32)]
+        d.cg_kernel_name.argtypes = [u32]
+        d.cg_kernel_name.restype = C.c_char_p
         for name in _SYMBOLS:
-            if name not in ("cg_workspace_bytes", "cg_strerror"):
+            if name not in ("cg_workspace_bytes", "cg_strerror", "cg_kernel_name"):
                 getattr(d, name).restype = i32
 
     def strerror(self, status: int) -> str:
@@ -237,18 +246,20 @@ class Context:
     def _keys(self, keys):
         return (C.c_void_p * len(keys))(*[_ptr(k) for k in keys])
 
-    def decode_scores(self, q, kcache, heads, n_cts, d2, rlk, gk_fold, out=None):
+    def decode_scores(self, q, kcache, heads, n_cts, d2, rlk, gk_fold, out=None, cache_stride_cts=None):
         out = self.empty_ct(heads, n_cts) if out is None else out
         ws = self.workspace(heads * n_cts)
+        stride = n_cts if cache_stride_cts is None else cache_stride_cts
         self._check(self.lib.dll.cg_decode_scores(self.h, self.stream, _ptr(q), _ptr(kcache), heads, n_cts,
-                                                  d2, _ptr(rlk), self._keys(gk_fold), _ptr(out), _ptr(ws)))
+                                                  stride, d2, _ptr(rlk), self._keys(gk_fold), _ptr(out), _ptr(ws)))
         return out
 
-    def decode_context(self, a, vcache, heads, n_cts, d2, rlk, gk_block, out=None):
+    def decode_context(self, a, vcache, heads, n_cts, d2, rlk, gk_block, out=None, cache_stride_cts=None):
         out = self.empty_ct(heads) if out is None else out
         ws = self.workspace(heads * n_cts)
+        stride = n_cts if cache_stride_cts is None else cache_stride_cts
         self._check(self.lib.dll.cg_decode_context(self.h, self.stream, _ptr(a), _ptr(vcache), heads, n_cts,
-                                                   d2, _ptr(rlk), self._keys(gk_block), _ptr(out), _ptr(ws)))
+                                                   stride, d2, _ptr(rlk), self._keys(gk_block), _ptr(out), _ptr(ws)))
         return out
 
     def prefill_qk(self, q, k, heads, d2, rlk, gk_fold, gk_blk, gk_swap, out=None):
@@ -259,6 +270,18 @@ class Context:
                                                self._keys(gk_fold), _ptr(gk_blk), _ptr(gk_swap), _ptr(out),
                                                _ptr(ws)))
         return out
+
+    def profile_begin(self, max_launches=65536):
+        self._check(self.lib.dll.cg_profile_begin(self.h, max_launches))
+
+    def profile_end(self):
+        """-> list of dicts {name, launches, total_ms, algo_bytes} per kernel class."""
+        stats = (_KernelStat * 32)()
+        n = C.c_uint32(0)
+        self._check(self.lib.dll.cg_profile_end(self.h, stats, 32, C.byref(n)))
+        return [dict(name=self.lib.dll.cg_kernel_name(stats[i].kernel_id).decode(),
+                     launches=int(stats[i].launches), total_ms=float(stats[i].total_ms),
+                     algo_bytes=float(stats[i].algo_bytes)) for i in range(n.value)]
 
     def bench_modmul(self, kind, n_lanes, iters, out=None):
         out = torch.empty(n_lanes, dtype=torch.int64, device=self.device) if out is None else out

@@ -91,6 +91,43 @@ struct cg_ctx {
     int device;
     // workspace limbs (N * 8 bytes) per unit
     int ws_total;
+    // optional per-launch timing with HIP events (benchmark support)
+    bool prof_on;
+    uint32_t prof_n, prof_cap;
+    hipEvent_t *prof_ev;      // 2 * prof_cap events
+    uint8_t *prof_id;
+    double *prof_bytes;
+};
+
+// kernel classes for the timing facility
+enum KernelId {
+    KID_LIFT_EXT = 0, KID_FWD_MULQ, KID_FWD_MULB, KID_FWD_MODUP, KID_FWD_ROWS, KID_FWD_PLAIN,
+    KID_TENSOR, KID_INV_F64, KID_INV_U64, KID_INV_MULPLAIN, KID_SCALE, KID_KS_INNER, KID_MODDOWN,
+    KID_ADD, KID_SUM_GROUPS, KID_COUNT
+};
+static const char *const kKernelNames[KID_COUNT] = {
+    "lift_ext", "ntt_fwd<mul,q-rows>", "ntt_fwd<mul,aux-rows>", "ntt_fwd<modup>", "ntt_fwd<rows>",
+    "ntt_fwd<plain>", "tensor", "ntt_inv<f64>", "ntt_inv<u64>", "ntt_inv<mul_plain>", "scale",
+    "ks_inner", "moddown", "add", "sum_groups"};
+
+// Brackets one launch with two events when profiling is on.
+struct ProfScope {
+    cg_ctx *c;
+    hipStream_t s;
+    int slot;
+    ProfScope(cg_ctx *c_, hipStream_t s_, int id, double bytes) : c(c_), s(s_), slot(-1)
+    {
+        if (c->prof_on && c->prof_n < c->prof_cap) {
+            slot = (int)c->prof_n++;
+            c->prof_id[slot] = (uint8_t)id;
+            c->prof_bytes[slot] = bytes;
+            (void)hipEventRecord(c->prof_ev[2 * slot], s);
+        }
+    }
+    ~ProfScope()
+    {
+        if (slot >= 0) (void)hipEventRecord(c->prof_ev[2 * slot + 1], s);
+    }
 };
 
 static void fill_conv(ConvTab &T, const uint64_t *pr, const int *sidx, int ns, const int *tidx, int nt)
@@ -266,6 +303,10 @@ extern "C" int cg_destroy(cg_ctx *c)
     if (c->tw) (void)hipFree(c->tw);
     if (c->itw) (void)hipFree(c->itw);
     if (c->tab) (void)hipFree(c->tab);
+    for (uint32_t i = 0; i < 2 * c->prof_cap; i++) (void)hipEventDestroy(c->prof_ev[i]);
+    delete[] c->prof_ev;
+    delete[] c->prof_id;
+    delete[] c->prof_bytes;
     delete c;
     return CG_OK;
 }
@@ -308,9 +349,10 @@ static Bump bump(const cg_ctx *c, void *ws) { return Bump{static_cast<char *>(ws
 // launch helpers
 // ---------------------------------------------------------------------------
 template <class LD, class ST>
-static int launch_fwd(const cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st)
+static int launch_fwd(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int kid, double bytes)
 {
     if (nwg == 0) return CG_OK;
+    ProfScope ps(c, s, kid, bytes);
     switch (c->logn) {
     case 12: hipLaunchKernelGGL((ntt_fwd_kernel<12, LD, ST>), dim3((unsigned)nwg), dim3(256), 0, s, ld, st, c->tw, c->dc); break;
     case 13: hipLaunchKernelGGL((ntt_fwd_kernel<13, LD, ST>), dim3((unsigned)nwg), dim3(512), 0, s, ld, st, c->tw, c->dc); break;
@@ -320,9 +362,10 @@ static int launch_fwd(const cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st)
     return check_launch();
 }
 template <class LD, class ST>
-static int launch_inv(const cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st)
+static int launch_inv(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int kid, double bytes)
 {
     if (nwg == 0) return CG_OK;
+    ProfScope ps(c, s, kid, bytes);
     switch (c->logn) {
     case 12: hipLaunchKernelGGL((ntt_inv_kernel<12, LD, ST>), dim3((unsigned)nwg), dim3(256), 0, s, ld, st, c->itw, c->dc); break;
     case 13: hipLaunchKernelGGL((ntt_inv_kernel<13, LD, ST>), dim3((unsigned)nwg), dim3(512), 0, s, ld, st, c->itw, c->dc); break;
@@ -337,27 +380,45 @@ static unsigned pw_blocks(const cg_ctx *c, size_t rows) { return (unsigned)((row
 // ---------------------------------------------------------------------------
 // internal operations (arguments already validated)
 // ---------------------------------------------------------------------------
+// one pointwise launch, bracketed by the timing scope
+#define CG_LAUNCH_PW(kid, bytes, kernel, blocks, ...)                                                  \
+    do {                                                                                               \
+        {                                                                                              \
+            ProfScope ps_(c, s, kid, bytes);                                                           \
+            hipLaunchKernelGGL(kernel, dim3(blocks), dim3(PW_THREADS), 0, s, __VA_ARGS__);             \
+        }                                                                                              \
+        CG_TRY(check_launch());                                                                        \
+    } while (0)
+
+// Algorithmic bytes (distinct inputs read once + outputs written once) are attached to every
+// launch for the roofline report; LB = bytes of one residue row.
+// b ciphertext of unit u sits at index (u / b_group) * b_stride + u % b_group (b_group = 0: dense)
 static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *b2, uint64_t *out3,
-                  uint32_t batch, uint32_t a_group, void *ws, int accumulate)
+                  uint32_t batch, uint32_t a_group, void *ws, int accumulate, uint32_t b_group = 0,
+                  uint32_t b_stride = 0)
 {
+    if (!b_group) { b_group = batch; b_stride = batch; }
     Bump w = bump(c, ws);
     double *ext = w.take<double>((size_t)4 * c->l * batch);
     double *ntt = w.take<double>((size_t)4 * c->KL * batch);
     double *tens = w.take<double>((size_t)3 * c->KL * batch);
     const int polys = (int)batch * 4;
-    hipLaunchKernelGGL(lift_ext_kernel, dim3(pw_blocks(c, polys)), dim3(PW_THREADS), 0, s, a2, b2, ext,
-                       (int)a_group, polys, c->dc);
-    CG_TRY(check_launch());
-    CG_TRY(launch_fwd(c, s, (size_t)polys * c->k, LdMulQ{a2, b2, (int)a_group, c->logn}, StF64{ntt, c->logn}));
-    CG_TRY(launch_fwd(c, s, (size_t)polys * c->l, LdMulB{ext, c->logn}, StF64{ntt, c->logn}));
-    hipLaunchKernelGGL(tensor_kernel, dim3(pw_blocks(c, (size_t)batch * c->KL)), dim3(PW_THREADS), 0, s, ntt,
-                       tens, (int)batch, c->dc);
-    CG_TRY(check_launch());
+    const double LB = (double)limb_bytes(c), B = batch;
+    const double in_rows = 2.0 * c->k * ((batch + a_group - 1) / a_group) + 2.0 * c->k * B;
+    CG_LAUNCH_PW(KID_LIFT_EXT, LB * (in_rows + 4.0 * c->l * B), lift_ext_kernel, pw_blocks(c, polys), a2, b2, ext,
+                 (int)a_group, (int)b_group, (int)b_stride, polys, c->dc);
+    CG_TRY(launch_fwd(c, s, (size_t)polys * c->k, LdMulQ{a2, b2, (int)a_group, (int)b_group, (int)b_stride, c->logn}, StF64{ntt, c->logn},
+                      KID_FWD_MULQ, LB * (in_rows + 4.0 * c->k * B)));
+    CG_TRY(launch_fwd(c, s, (size_t)polys * c->l, LdMulB{ext, c->logn}, StF64{ntt, c->logn}, KID_FWD_MULB,
+                      LB * 8.0 * c->l * B));
+    CG_LAUNCH_PW(KID_TENSOR, LB * 7.0 * c->KL * B, tensor_kernel, pw_blocks(c, (size_t)batch * c->KL), ntt, tens,
+                 (int)batch, c->dc);
     const size_t rows = (size_t)batch * 3 * c->KL;
-    CG_TRY(launch_inv(c, s, rows, LdInvF64{tens, nullptr, c->KL, c->logn}, StInvF64{tens, c->logn}));
-    hipLaunchKernelGGL(scale_kernel, dim3(pw_blocks(c, (size_t)batch * 3)), dim3(PW_THREADS), 0, s, tens, out3,
-                       (int)batch * 3, accumulate, c->dc);
-    return check_launch();
+    CG_TRY(launch_inv(c, s, rows, LdInvF64{tens, nullptr, c->KL, c->logn}, StInvF64{tens, c->logn}, KID_INV_F64,
+                      LB * 2.0 * rows));
+    CG_LAUNCH_PW(KID_SCALE, LB * (3.0 * c->KL + 3.0 * c->k * (accumulate ? 2 : 1)) * B, scale_kernel,
+                 pw_blocks(c, (size_t)batch * 3), tens, out3, (int)batch * 3, accumulate, c->dc);
+    return CG_OK;
 }
 
 // key switch of one ring element per unit (src + b*src_stride), then the final additions
@@ -368,16 +429,19 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     Bump w = bump(c, ws);
     double *dig = w.take<double>((size_t)c->dnum * c->L * batch);
     double *acc = w.take<double>((size_t)2 * c->L * batch);
+    const double LB = (double)limb_bytes(c), B = batch;
+    const double dig_rows = (double)c->dnum * c->L;
     CG_TRY(launch_fwd(c, s, (size_t)batch * c->dnum * c->L, LdModup{src, src_stride, galois, c->logn},
-                      StF64{dig, c->logn}));
-    hipLaunchKernelGGL(ks_inner_kernel, dim3(pw_blocks(c, (size_t)batch * c->L)), dim3(PW_THREADS), 0, s, dig, key,
-                       acc, (int)batch, c->dc);
-    CG_TRY(check_launch());
+                      StF64{dig, c->logn}, KID_FWD_MODUP, LB * (c->k + dig_rows) * B));
+    CG_LAUNCH_PW(KID_KS_INNER, LB * ((dig_rows + 2.0 * c->L) * B + 2.0 * dig_rows), ks_inner_kernel,
+                 pw_blocks(c, (size_t)batch * c->L), dig, key, acc, (int)batch, c->dc);
     CG_TRY(launch_inv(c, s, (size_t)batch * 2 * c->L, LdInvF64{acc, nullptr, c->L, c->logn},
-                      StInvF64{acc, c->logn}));
+                      StInvF64{acc, c->logn}, KID_INV_F64, LB * 4.0 * c->L * B));
     ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch};
-    hipLaunchKernelGGL(moddown_kernel, dim3(pw_blocks(c, (size_t)batch * 2)), dim3(PW_THREADS), 0, s, A, c->dc);
-    return check_launch();
+    const double add_rows = !add ? 0.0 : (galois_inv ? c->k + (accumulate ? 2.0 * c->k : 0.0) : 2.0 * c->k);
+    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, moddown_kernel,
+                 pw_blocks(c, (size_t)batch * 2), A, c->dc);
+    return CG_OK;
 }
 
 static int do_relin(cg_ctx *c, hipStream_t s, const uint64_t *in3, const void *rlk, uint64_t *out2, uint32_t batch,
@@ -408,8 +472,9 @@ static int do_rotate(cg_ctx *c, hipStream_t s, const uint64_t *in2, uint32_t g, 
 
 static int do_add(cg_ctx *c, hipStream_t s, const uint64_t *a, const uint64_t *b, uint64_t *out, size_t rows)
 {
-    hipLaunchKernelGGL(add_kernel, dim3(pw_blocks(c, rows)), dim3(PW_THREADS), 0, s, a, b, out, (int)rows, c->dc);
-    return check_launch();
+    CG_LAUNCH_PW(KID_ADD, (double)limb_bytes(c) * 3.0 * rows, add_kernel, pw_blocks(c, rows), a, b, out, (int)rows,
+                 c->dc);
+    return CG_OK;
 }
 
 static bool ptrs_ok(std::initializer_list<const void *> ps)
@@ -433,8 +498,10 @@ static int public_transform(cg_ctx *c, void *stream, const uint64_t *in, uint64_
     // ordered on the caller's stream before the kernel
     CG_HIP(hipMemcpyAsync(c->tab, idx, n_limbs * sizeof(uint32_t), hipMemcpyHostToDevice, s));
     if (!inverse)
-        return launch_fwd(c, s, n_limbs, LdRowsU64{in, c->tab, 1, c->logn}, StU64{out, c->logn});
-    return launch_inv(c, s, n_limbs, LdInvU64{in, c->tab, 1, c->logn}, StInvU64{out, c->logn});
+        return launch_fwd(c, s, n_limbs, LdRowsU64{in, c->tab, 1, c->logn}, StU64{out, c->logn}, KID_FWD_ROWS,
+                          2.0 * limb_bytes(c) * n_limbs);
+    return launch_inv(c, s, n_limbs, LdInvU64{in, c->tab, 1, c->logn}, StInvU64{out, c->logn}, KID_INV_U64,
+                      2.0 * limb_bytes(c) * n_limbs);
 }
 extern "C" int cg_ntt_forward(cg_ctx *c, void *stream, const uint64_t *in, uint64_t *out, const uint32_t *idx,
                               uint32_t n_limbs)
@@ -451,14 +518,16 @@ extern "C" int cg_ksk_prepare(cg_ctx *c, void *stream, const uint64_t *raw, void
 {
     CG_REQUIRE(c && ptrs_ok({raw, ksk}));
     return launch_fwd(c, static_cast<hipStream_t>(stream), (size_t)c->dnum * 2 * c->L,
-                      LdRowsU64{raw, nullptr, c->L, c->logn}, StF64Red{static_cast<double *>(ksk), c->logn});
+                      LdRowsU64{raw, nullptr, c->L, c->logn}, StF64Red{static_cast<double *>(ksk), c->logn},
+                      KID_FWD_ROWS, 4.0 * limb_bytes(c) * c->dnum * c->L);
 }
 
 extern "C" int cg_plain_prepare(cg_ctx *c, void *stream, const uint64_t *pt, void *plain, uint32_t batch)
 {
     CG_REQUIRE(c && ptrs_ok({pt, plain}) && batch_ok(batch));
     return launch_fwd(c, static_cast<hipStream_t>(stream), (size_t)batch * c->k, LdPlain{pt, c->logn},
-                      StF64Red{static_cast<double *>(plain), c->logn});
+                      StF64Red{static_cast<double *>(plain), c->logn}, KID_FWD_PLAIN,
+                      (double)limb_bytes(c) * batch * (1.0 + c->k));
 }
 
 extern "C" int cg_mul(cg_ctx *c, void *stream, const uint64_t *a2, const uint64_t *b2, uint64_t *out3,
@@ -507,10 +576,13 @@ extern "C" int cg_mul_plain(cg_ctx *c, void *stream, const uint64_t *in2, const 
     hipStream_t s = static_cast<hipStream_t>(stream);
     double *f = static_cast<double *>(ws);
     const size_t rows = (size_t)batch * 2 * c->k;
-    CG_TRY(launch_fwd(c, s, rows, LdRowsU64{in2, nullptr, c->k, c->logn}, StF64{f, c->logn}));
+    const double LB = (double)limb_bytes(c);
+    CG_TRY(launch_fwd(c, s, rows, LdRowsU64{in2, nullptr, c->k, c->logn}, StF64{f, c->logn}, KID_FWD_ROWS,
+                      LB * 2.0 * rows));
     return launch_inv(c, s, rows,
                       LdInvMulPlain{f, static_cast<const double *>(plain), (int)plain_stride, 0, c->logn},
-                      StInvU64{out2, c->logn});
+                      StInvU64{out2, c->logn}, KID_INV_MULPLAIN,
+                      LB * (2.0 * rows + c->k * (plain_stride ? (double)batch : 1.0)));
 }
 
 extern "C" int cg_kv_append(cg_ctx *c, void *stream, uint64_t *cache, uint32_t cache_stride_cts, uint32_t n_caches,
@@ -524,10 +596,13 @@ extern "C" int cg_kv_append(cg_ctx *c, void *stream, uint64_t *cache, uint32_t c
     double *f = static_cast<double *>(ws);
     const size_t rows = (size_t)n_caches * 2 * c->k;
     const size_t ct2 = (size_t)2 * c->k * c->N;
-    CG_TRY(launch_fwd(c, s, rows, LdRowsU64{rows_dev, nullptr, c->k, c->logn}, StF64{f, c->logn}));
+    const double LB = (double)limb_bytes(c);
+    CG_TRY(launch_fwd(c, s, rows, LdRowsU64{rows_dev, nullptr, c->k, c->logn}, StF64{f, c->logn}, KID_FWD_ROWS,
+                      LB * 2.0 * rows));
     return launch_inv(c, s, rows, LdInvMulPlain{f, static_cast<const double *>(masks), 0, (int)blk, c->logn},
                       StInvAppend{cache + (size_t)ct_idx * ct2, (size_t)cache_stride_cts * ct2, blk == 0 ? 1 : 0,
-                                  c->logn});
+                                  c->logn},
+                      KID_INV_MULPLAIN, LB * ((blk == 0 ? 2.0 : 3.0) * rows + c->k));
 }
 
 static bool pow2_d(const cg_ctx *c, uint32_t d2) { return d2 >= 2 && (d2 & (d2 - 1)) == 0 && d2 <= (uint32_t)c->N / 4; }
@@ -555,10 +630,11 @@ static int rotate_add_chain(cg_ctx *c, hipStream_t s, uint64_t *x0, uint64_t *x1
 }
 
 extern "C" int cg_decode_scores(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kc, uint32_t heads,
-                                uint32_t n_cts, uint32_t d2, const void *rlk, const void *const *gk_fold,
-                                uint64_t *out, void *ws)
+                                uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
+                                const void *const *gk_fold, uint64_t *out, void *ws)
 {
     CG_REQUIRE(c && ptrs_ok({q, kc, rlk, out, ws}) && gk_fold && heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
+    CG_REQUIRE(cache_stride_cts >= n_cts);
     const uint32_t batch = heads * n_cts;
     CG_REQUIRE(batch_ok(batch));
     int nrot = 0;
@@ -571,16 +647,17 @@ extern "C" int cg_decode_scores(cg_ctx *c, void *stream, const uint64_t *q, cons
     Bump w = bump(c, ws);
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
     uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * batch), *xb = w.take<uint64_t>((size_t)2 * c->k * batch);
-    CG_TRY(do_mul(c, s, q, kc, d3, batch, n_cts, w.p, 0));
+    CG_TRY(do_mul(c, s, q, kc, d3, batch, n_cts, w.p, 0, n_cts, cache_stride_cts));
     CG_TRY(do_relin(c, s, d3, rlk, xa, batch, w.p));
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_fold, nrot, batch, w.p);
 }
 
 extern "C" int cg_decode_context(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, uint32_t heads,
-                                 uint32_t n_cts, uint32_t d2, const void *rlk, const void *const *gk_block,
-                                 uint64_t *out, void *ws)
+                                 uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
+                                 const void *const *gk_block, uint64_t *out, void *ws)
 {
     CG_REQUIRE(c && ptrs_ok({a, vc, rlk, out, ws}) && gk_block && heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
+    CG_REQUIRE(cache_stride_cts >= n_cts);
     const uint32_t batch = heads * n_cts;
     CG_REQUIRE(batch_ok(batch));
     int nrot = 0;
@@ -593,12 +670,11 @@ extern "C" int cg_decode_context(cg_ctx *c, void *stream, const uint64_t *a, con
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
     uint64_t *y = w.take<uint64_t>((size_t)3 * c->k * heads);
     uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * heads), *xb = w.take<uint64_t>((size_t)2 * c->k * heads);
-    CG_TRY(do_mul(c, s, a, vc, d3, batch, 1, w.p, 0));
+    CG_TRY(do_mul(c, s, a, vc, d3, batch, 1, w.p, 0, n_cts, cache_stride_cts));
     // y[h] = sum_c d3[h][c]  (three components)
     const int rows = 3 * c->k;
-    hipLaunchKernelGGL(sum_groups_kernel, dim3(pw_blocks(c, (size_t)heads * rows)), dim3(PW_THREADS), 0, s, d3, y,
-                       (int)heads, (int)n_cts, rows, c->dc);
-    CG_TRY(check_launch());
+    CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), sum_groups_kernel,
+                 pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)n_cts, rows, c->dc);
     CG_TRY(do_relin(c, s, y, rlk, xa, heads, w.p));
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, heads, w.p);
 }
@@ -639,6 +715,52 @@ extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const u
     CG_TRY(do_relin(c, s, d3, rlk, kp, batch, w.p));   // the rotated keys are consumed: reuse as x0
     return rotate_add_chain(c, s, kp, xb, out, gs, gk_fold, nrot, batch, w.p);
 }
+
+extern "C" int cg_profile_begin(cg_ctx *c, uint32_t max_launches)
+{
+    CG_REQUIRE(c && max_launches >= 1 && max_launches <= (1u << 20) && !c->prof_on);
+    if (c->prof_cap < max_launches) {
+        for (uint32_t i = 0; i < 2 * c->prof_cap; i++) (void)hipEventDestroy(c->prof_ev[i]);
+        delete[] c->prof_ev; delete[] c->prof_id; delete[] c->prof_bytes;
+        c->prof_cap = 0;
+        c->prof_ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_launches];
+        c->prof_id = new (std::nothrow) uint8_t[max_launches];
+        c->prof_bytes = new (std::nothrow) double[max_launches];
+        if (!c->prof_ev || !c->prof_id || !c->prof_bytes) return CG_ENOMEM;
+        for (uint32_t i = 0; i < 2 * max_launches; i++) CG_HIP(hipEventCreate(&c->prof_ev[i]));
+        c->prof_cap = max_launches;
+    }
+    c->prof_n = 0;
+    c->prof_on = true;
+    return CG_OK;
+}
+
+extern "C" int cg_profile_end(cg_ctx *c, cg_kernel_stat *stats, uint32_t cap, uint32_t *n_out)
+{
+    CG_REQUIRE(c && stats && n_out && c->prof_on);
+    c->prof_on = false;
+    cg_kernel_stat acc[KID_COUNT];
+    memset(acc, 0, sizeof(acc));
+    for (uint32_t i = 0; i < c->prof_n; i++) {
+        CG_HIP(hipEventSynchronize(c->prof_ev[2 * i + 1]));
+        float ms = 0.f;
+        CG_HIP(hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+        cg_kernel_stat &k = acc[c->prof_id[i]];
+        k.launches++;
+        k.total_ms += ms;
+        k.algo_bytes += c->prof_bytes[i];
+    }
+    uint32_t n = 0;
+    for (int id = 0; id < KID_COUNT; id++)
+        if (acc[id].launches && n < cap) {
+            acc[id].kernel_id = (uint32_t)id;
+            stats[n++] = acc[id];
+        }
+    *n_out = n;
+    return CG_OK;
+}
+
+extern "C" const char *cg_kernel_name(uint32_t id) { return id < KID_COUNT ? kKernelNames[id] : "?"; }
 
 extern "C" int cg_bench_modmul(cg_ctx *c, void *stream, int kind, uint32_t n_lanes, uint32_t iters, uint64_t *out)
 {

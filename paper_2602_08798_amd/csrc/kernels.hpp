@@ -289,7 +289,7 @@ struct LdRowsU64 {
 struct LdMulQ {
     static constexpr bool kStaged = false;
     const uint64_t *cta, *ctb;
-    int a_group, logn;
+    int a_group, b_group, b_stride, logn;   // b ciphertext of unit u: (u / b_group) * b_stride + u % b_group
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *C) const
     {
@@ -300,7 +300,7 @@ struct LdMulQ {
     {
         const int k = C->k, i = wg % k, bp = wg / k, p = bp & 3, un = bp >> 2;
         const uint64_t *ct = (p < 2) ? cta + (((size_t)(un / a_group) * 2 * k) << logn)
-                                     : ctb + (((size_t)un * 2 * k) << logn);
+                                     : ctb + (((size_t)((un / b_group) * b_stride + un % b_group) * 2 * k) << logn);
         return u64_to_f64(ct[((size_t)((p & 1) * k + i) << logn) + idx]);
     }
 };
@@ -460,7 +460,7 @@ constexpr int PW_THREADS = 256;
 // thread -> (b*4+p, n); out ext[b*4+p][j][n] canonical doubles
 __global__ void __launch_bounds__(PW_THREADS)
 lift_ext_kernel(const uint64_t *__restrict__ a, const uint64_t *__restrict__ b, double *__restrict__ ext,
-                int a_group, int total_polys, const DevConst *__restrict__ C)
+                int a_group, int b_group, int b_stride, int total_polys, const DevConst *__restrict__ C)
 {
     const int logn = C->logn, N = 1 << logn, k = C->k, l = C->l;
     const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
@@ -468,7 +468,8 @@ lift_ext_kernel(const uint64_t *__restrict__ a, const uint64_t *__restrict__ b, 
     const int bp = (int)(gid >> logn);
     if (bp >= total_polys) return;
     const int p = bp & 3, u = bp >> 2;
-    const uint64_t *ct = (p < 2) ? a + (((size_t)(u / a_group) * 2 * k) << logn) : b + (((size_t)u * 2 * k) << logn);
+    const uint64_t *ct = (p < 2) ? a + (((size_t)(u / a_group) * 2 * k) << logn)
+                                 : b + (((size_t)((u / b_group) * b_stride + u % b_group) * 2 * k) << logn);
     ct += ((size_t)((p & 1) * k) << logn) + n;
     double x[MAXS], dg[MAXS];
 #pragma unroll
