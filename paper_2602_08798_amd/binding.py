@@ -11,7 +11,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libcryptogen_hip.so")
+_LIB_PATH = os.environ.get("CRYPTOGEN_HIP_LIB", os.path.join(_HERE, "libcryptogen_hip.so"))
 
 _SYMBOLS = [
     "cg_create", "cg_destroy", "cg_get_sizes", "cg_workspace_bytes", "cg_strerror",

@@ -88,7 +88,7 @@ struct cg_ctx {
     double *tw, *itw;     // [np][N] forward / inverse twiddles (centred doubles, bit-reversed order)
     uint32_t *tab;        // scratch prime-index table for the public transform entry points
     uint32_t tab_cap;
-    int device;
+    int device, n_cu;
     // workspace limbs (N * 8 bytes) per unit
     int ws_total;
     // optional per-launch timing with HIP events (benchmark support)
@@ -275,7 +275,12 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
     // tensor-product and key-switch scratch areas (kept separate for simplicity)
     c->ws_total = 7 * c->k + (4 * c->l + 7 * c->KL) + (c->dnum * c->L + 2 * c->L);
 
-    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return CG_EHIP; }
+    if (hipGetDevice(&c->device) != hipSuccess ||
+        hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess ||
+        c->n_cu < 1) {
+        delete c;
+        return CG_EHIP;
+    }
     const size_t tbytes = (size_t)np * N * sizeof(double);
     c->tab_cap = 1u << 16;
     if (hipMalloc(&c->dc, sizeof(DevConst)) != hipSuccess || hipMalloc(&c->tw, tbytes) != hipSuccess ||
@@ -348,15 +353,27 @@ static Bump bump(const cg_ctx *c, void *ws) { return Bump{static_cast<char *>(ws
 // ---------------------------------------------------------------------------
 // launch helpers
 // ---------------------------------------------------------------------------
+// transform kernels are persistent: at most as many workgroups as fit the device at once
+static unsigned ntt_grid(const cg_ctx *c, size_t nwg)
+{
+    const size_t lds_bytes = ((size_t)c->N + c->N / 8) * sizeof(double);
+    size_t per_cu = (160 * 1024) / lds_bytes;
+    const size_t by_threads = 2048 / ((size_t)c->N / ELEMS);
+    if (per_cu > by_threads) per_cu = by_threads;
+    if (per_cu < 1) per_cu = 1;
+    const size_t resident = per_cu * (size_t)c->n_cu;
+    return (unsigned)(nwg < resident ? nwg : resident);
+}
 template <class LD, class ST>
 static int launch_fwd(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int kid, double bytes)
 {
     if (nwg == 0) return CG_OK;
     ProfScope ps(c, s, kid, bytes);
+    const dim3 grid(ntt_grid(c, nwg)), block((unsigned)c->N / ELEMS);
     switch (c->logn) {
-    case 12: hipLaunchKernelGGL((ntt_fwd_kernel<12, LD, ST>), dim3((unsigned)nwg), dim3(256), 0, s, ld, st, c->tw, c->dc); break;
-    case 13: hipLaunchKernelGGL((ntt_fwd_kernel<13, LD, ST>), dim3((unsigned)nwg), dim3(512), 0, s, ld, st, c->tw, c->dc); break;
-    case 14: hipLaunchKernelGGL((ntt_fwd_kernel<14, LD, ST>), dim3((unsigned)nwg), dim3(1024), 0, s, ld, st, c->tw, c->dc); break;
+    case 12: hipLaunchKernelGGL((ntt_fwd_kernel<12, LD, ST>), grid, block, 0, s, ld, st, c->tw, c->dc, (int)nwg); break;
+    case 13: hipLaunchKernelGGL((ntt_fwd_kernel<13, LD, ST>), grid, block, 0, s, ld, st, c->tw, c->dc, (int)nwg); break;
+    case 14: hipLaunchKernelGGL((ntt_fwd_kernel<14, LD, ST>), grid, block, 0, s, ld, st, c->tw, c->dc, (int)nwg); break;
     default: return CG_EINVAL;
     }
     return check_launch();
@@ -366,10 +383,11 @@ static int launch_inv(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int ki
 {
     if (nwg == 0) return CG_OK;
     ProfScope ps(c, s, kid, bytes);
+    const dim3 grid(ntt_grid(c, nwg)), block((unsigned)c->N / ELEMS);
     switch (c->logn) {
-    case 12: hipLaunchKernelGGL((ntt_inv_kernel<12, LD, ST>), dim3((unsigned)nwg), dim3(256), 0, s, ld, st, c->itw, c->dc); break;
-    case 13: hipLaunchKernelGGL((ntt_inv_kernel<13, LD, ST>), dim3((unsigned)nwg), dim3(512), 0, s, ld, st, c->itw, c->dc); break;
-    case 14: hipLaunchKernelGGL((ntt_inv_kernel<14, LD, ST>), dim3((unsigned)nwg), dim3(1024), 0, s, ld, st, c->itw, c->dc); break;
+    case 12: hipLaunchKernelGGL((ntt_inv_kernel<12, LD, ST>), grid, block, 0, s, ld, st, c->itw, c->dc, (int)nwg); break;
+    case 13: hipLaunchKernelGGL((ntt_inv_kernel<13, LD, ST>), grid, block, 0, s, ld, st, c->itw, c->dc, (int)nwg); break;
+    case 14: hipLaunchKernelGGL((ntt_inv_kernel<14, LD, ST>), grid, block, 0, s, ld, st, c->itw, c->dc, (int)nwg); break;
     default: return CG_EINVAL;
     }
     return check_launch();
@@ -431,8 +449,21 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     double *acc = w.take<double>((size_t)2 * c->L * batch);
     const double LB = (double)limb_bytes(c), B = batch;
     const double dig_rows = (double)c->dnum * c->L;
-    CG_TRY(launch_fwd(c, s, (size_t)batch * c->dnum * c->L, LdModup{src, src_stride, galois, c->logn},
-                      StF64{dig, c->logn}, KID_FWD_MODUP, LB * (c->k + dig_rows) * B));
+    const size_t nrows = (size_t)batch * c->dnum * c->L;
+    const double mbytes = LB * (c->k + dig_rows) * B;
+    const StF64 st{dig, c->logn};
+#define CG_MODUP(G, A) launch_fwd(c, s, nrows, LdModup<G, A>{src, src_stride, galois, c->logn}, st, KID_FWD_MODUP, mbytes)
+    int rc;
+    switch (c->alpha * 2 + (galois ? 1 : 0)) {
+    case 2: rc = CG_MODUP(false, 1); break;
+    case 3: rc = CG_MODUP(true, 1); break;
+    case 4: rc = CG_MODUP(false, 2); break;
+    case 5: rc = CG_MODUP(true, 2); break;
+    case 6: rc = CG_MODUP(false, 3); break;
+    default: rc = CG_MODUP(true, 3); break;
+    }
+#undef CG_MODUP
+    CG_TRY(rc);
     CG_LAUNCH_PW(KID_KS_INNER, LB * ((dig_rows + 2.0 * c->L) * B + 2.0 * dig_rows), ks_inner_kernel,
                  pw_blocks(c, (size_t)batch * c->L), dig, key, acc, (int)batch, c->dc);
     CG_TRY(launch_inv(c, s, (size_t)batch * 2 * c->L, LdInvF64{acc, nullptr, c->L, c->logn},

@@ -7,14 +7,19 @@
 namespace cg {
 
 // ---------------------------------------------------------------------------
-// Transform plan: each thread keeps E = 16 elements in registers and a pass
+// Transform plan: each thread keeps ELEMS = 16 elements in registers and a pass
 // runs R = 3 or 4 butterfly stages on them between two LDS exchanges.
 // ---------------------------------------------------------------------------
 template <int LOGN> struct Plan;
+constexpr int ELEMS = 16;
 template <> struct Plan<12> { static constexpr int NP = 3; static constexpr int R[4] = {4, 4, 4, 0}; };
 template <> struct Plan<13> { static constexpr int NP = 4; static constexpr int R[4] = {4, 3, 3, 3}; };
 template <> struct Plan<14> { static constexpr int NP = 4; static constexpr int R[4] = {4, 4, 3, 3}; };
-constexpr int ELEMS = 16;
+// After pass 0 (the only pass that pairs elements owned by different waves) every
+// wave owns one contiguous chunk of 64 * ELEMS = 1024 elements and all later
+// stages stay inside it, so those passes need no workgroup barrier.
+constexpr int CHUNK_LOG = 10;
+static_assert((1 << CHUNK_LOG) == 64 * ELEMS, "chunk = one wave's elements");
 
 template <int LOGN, int PASS> constexpr int stage_start()
 {
@@ -23,9 +28,23 @@ template <int LOGN, int PASS> constexpr int stage_start()
     return s;
 }
 
+// group index of a thread in pass PASS (g-th group of the thread)
+template <int LOGN, int PASS> __device__ __forceinline__ int group_index(int tid, int g)
+{
+    constexpr int R = Plan<LOGN>::R[PASS];
+    if (PASS == 0) return tid + g * ((1 << LOGN) / ELEMS);
+    return ((tid >> 6) << (CHUNK_LOG - R)) + (tid & 63) + 64 * g;
+}
+// compiler-level ordering between LDS writes and reads of the same wave (the LDS pipeline
+// itself executes one wave's operations in order)
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // Forward stage bound: |out| <= 1.1875 |in| + 0.5 (in units of p).  Values must
-// stay below 8p = 2^53.  fwd_bound_after returns the bound after running pass
-// PASS when the pass starts from `b`.
+// stay below 8p = 2^53.
 constexpr double fwd_grow(double b, int stages)
 {
     for (int i = 0; i < stages; i++) b = 1.1875 * b + 0.5;
@@ -56,34 +75,110 @@ __device__ __forceinline__ void bfly_inv(double &a, double &b, double w, const M
 }
 
 // ---------------------------------------------------------------------------
+// twiddles of one pass, fetched into registers ahead of the synchronisation
+// that precedes the pass: slot (g, (1<<u) - 1 + j) holds the factor of stage
+// S0+u for the j-th sub-block of group g
+// ---------------------------------------------------------------------------
+constexpr int TWREGS = 16;
+
+// LDS layout: one pad double after every 8, so that a thread owning 8 (or 16)
+// consecutive elements is 9 doubles away from its neighbour lane and the
+// stride-1 passes are bank-conflict free.  For the index patterns used here
+// (base + (c << L) with the low L bits of base below 2^L) the pad of the sum
+// is the sum of the pads, so the per-element part folds into instruction
+// offsets.
+__device__ __forceinline__ constexpr int pad(int idx) { return idx + (idx >> 3); }
+template <int LOGN> constexpr int lds_doubles() { return (1 << LOGN) + (1 << (LOGN - 3)); }
+
+template <int LOGN, int PASS, bool HI_ZERO>
+__device__ __forceinline__ void load_tw(const double *__restrict__ tw, int tid, double *twr)
+{
+    using P = Plan<LOGN>;
+    constexpr int R = P::R[PASS];
+    constexpr int S0 = stage_start<LOGN, PASS>();
+    constexpr int L = LOGN - S0 - R;
+    constexpr int G = ELEMS >> R;
+    constexpr int PER = (1 << R) - 1;
+    static_assert(G * PER <= TWREGS, "twiddle register file too small");
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        const int hi = HI_ZERO ? 0 : (group_index<LOGN, PASS>(tid, g) >> L);
+#pragma unroll
+        for (int u = 0; u < R; u++)
+#pragma unroll
+            for (int j = 0; j < (1 << u); j++)
+                twr[g * PER + (1 << u) - 1 + j] = tw[(1 << (S0 + u)) + (hi << u) + j];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The transform kernels are persistent: a workgroup walks over rows
+// wg = blockIdx.x, blockIdx.x + gridDim.x, ... and, while it transforms one row,
+// the raw words of its next row are already on their way into registers.
+//
+// Loader interface (LD):
+//   kRaw                       64-bit words fetched per element
+//   kScatter                   forward only: elements are placed into LDS at place(idx) before pass 0
+//   prime(wg, C)               prime index of row wg
+//   dst_limb(wg, C)            forward only: destination row
+//   fetch(wg, idx, C, raw)     issue the loads of element idx (no arithmetic on the loaded words)
+//   finish(raw, wg, idx, m, C) element value, |x| <= p (forward) or < 8p (inverse)
+//
+// Element ownership: CHUNKED = false: element it of a thread is tid + it * T
+// (pass 0); CHUNKED = true: (wave << CHUNK_LOG) + lane + 64 * it (the wave's chunk).
+// Both put consecutive lanes on consecutive addresses.
+// ---------------------------------------------------------------------------
+template <int LOGN, bool CHUNKED, class LD>
+__device__ __forceinline__ void fetch_row(const LD &ld, int wg, int tid, const DevConst *C,
+                                          uint64_t (&raw)[ELEMS][LD::kRaw])
+{
+    constexpr int T = (1 << LOGN) / ELEMS;
+    const int first = CHUNKED ? ((tid >> 6) << CHUNK_LOG) + (tid & 63) : tid;
+#pragma unroll
+    for (int it = 0; it < ELEMS; it++) ld.fetch(wg, first + it * (CHUNKED ? 64 : T), C, raw[it]);
+}
+
+// ---------------------------------------------------------------------------
 // forward transform
 // ---------------------------------------------------------------------------
-template <int LOGN, int PASS, class LD, class ST>
-__device__ __forceinline__ void fwd_pass(double *lds, const LD &ld, const ST &st, int wg, int tid,
-                                         const double *__restrict__ tw, const ModD m, int dst_limb,
-                                         const DevConst *C)
+template <int LOGN, int PASS, bool FROM_REGS, class ST>
+__device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST &st, int tid,
+                                         const double *__restrict__ tw, const double *twr, double *twr_next,
+                                         const ModD m, int dst_limb)
 {
     using P = Plan<LOGN>;
     constexpr int R = P::R[PASS];
     constexpr int S0 = stage_start<LOGN, PASS>();
     constexpr int L = LOGN - S0 - R;          // index bits below this pass's R bits
     constexpr int G = ELEMS >> R;             // independent radix-2^R groups per thread
-    constexpr int T = (1 << LOGN) / ELEMS;
+    constexpr int PER = (1 << R) - 1;
     constexpr bool first = PASS == 0, last = PASS == P::NP - 1;
     constexpr bool do_red = FwdBound<LOGN, PASS>::reduce;
     static_assert(FwdBound<LOGN, PASS>::out < 8.0, "lazy bound exceeds 2^53");
+    static_assert(L >= 3 || L + R >= 3, "pad() additivity needs the group to span 8 elements");
+    static_assert(!FROM_REGS || (first && L + R == LOGN), "register input only for the first pass");
+    static_assert(first || L + R <= CHUNK_LOG, "later passes must stay inside one wave's chunk");
+    double v[G][1 << R];
+    int base[G];
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        const int gidx = tid + g * T;
+        const int gidx = group_index<LOGN, PASS>(tid, g);
         const int lo = gidx & ((1 << L) - 1);
         const int hi = first ? 0 : (gidx >> L);
-        const int base = (hi << (L + R)) | lo;
-        double v[1 << R];
+        base[g] = (hi << (L + R)) | lo;
+        const int pb = pad(base[g]);
 #pragma unroll
         for (int c = 0; c < (1 << R); c++) {
-            const int idx = base + (c << L);
-            v[c] = (first && !LD::kStaged) ? ld.load(wg, idx, C) : lds[idx];
-            if (do_red) v[c] = red(v[c], m);
+            // first pass: element base + (c << L) = tid + (g + c*G) * T is fetched element g + c*G
+            if (FROM_REGS) v[g][c] = in[g + c * G];
+            else v[g][c] = lds[pb + pad(c << L)];
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        if (do_red) {
+#pragma unroll
+            for (int c = 0; c < (1 << R); c++) v[g][c] = red(v[g][c], m);
         }
 #pragma unroll
         for (int u = 0; u < R; u++) {
@@ -91,114 +186,186 @@ __device__ __forceinline__ void fwd_pass(double *lds, const LD &ld, const ST &st
 #pragma unroll
             for (int c = 0; c < (1 << R); c++) {
                 if (c & half) continue;
-                const int twi = (1 << (S0 + u)) + ((hi << u) | (c >> (R - u)));
-                bfly_fwd(v[c], v[c + half], tw[twi], m);
+                bfly_fwd(v[g][c], v[g][c + half], twr[g * PER + (1 << u) - 1 + (c >> (R - u))], m);
             }
         }
-#pragma unroll
-        for (int c = 0; c < (1 << R); c++) {
-            const int idx = base + (c << L);
-            if (last) st.store(dst_limb, idx, v[c], m);
-            else lds[idx] = v[c];
-        }
     }
-    if (!last) __syncthreads();
+    // fetch the next pass's factors while this pass's results drain to LDS
+    if constexpr (!last) load_tw<LOGN, PASS + 1, false>(tw, tid, twr_next);
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        const int pb = pad(base[g]);
+#pragma unroll
+        for (int c = 0; c < (1 << R); c++) lds[pb + pad(c << L)] = v[g][c];
+    }
+    if constexpr (first) __syncthreads();
+    else wave_sync();
+    if constexpr (last) {
+        // results leave through LDS so that consecutive lanes write consecutive addresses; each
+        // wave copies out its own chunk
+        const int cb = ((tid >> 6) << CHUNK_LOG) + (tid & 63);
+        const int pc = pad(cb);
+#pragma unroll
+        for (int it = 0; it < ELEMS; it++) st.store(dst_limb, cb + it * 64, lds[pc + pad(it * 64)], m);
+    }
 }
 
-// LD: prime(wg), dst_limb(wg), load(wg, idx, C) -> |x| <= p; kStaged loaders
-// fill LDS themselves in stage(), e.g. to apply a permutation.
 template <int LOGN, class LD, class ST>
 __global__ void __launch_bounds__((1 << LOGN) / ELEMS)
-ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *__restrict__ C)
+ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *__restrict__ C, int nwg)
 {
-    __shared__ double lds[1 << LOGN];
-    const int wg = blockIdx.x, tid = threadIdx.x;
-    const int pr = ld.prime(wg, C);
-    const ModD m = C->mod[pr];
-    const double *tw = tw_all + ((size_t)pr << LOGN);
-    const int dl = ld.dst_limb(wg, C);
-    if constexpr (LD::kStaged) {
-        ld.template stage<LOGN>(lds, wg, tid, C);
-        __syncthreads();
+    __shared__ double lds[lds_doubles<LOGN>()];
+    constexpr int T = (1 << LOGN) / ELEMS;
+    const int tid = threadIdx.x;
+    int wg = blockIdx.x;
+    uint64_t raw[ELEMS][LD::kRaw];
+    fetch_row<LOGN, false>(ld, wg, tid, C, raw);
+    for (;;) {
+        const int pr = ld.prime(wg, C);
+        const ModD m = C->mod[pr];
+        const double *tw = tw_all + ((size_t)pr << LOGN);
+        const int dl = ld.dst_limb(wg, C);
+        double twa[TWREGS], twb[TWREGS];
+        load_tw<LOGN, 0, true>(tw, tid, twa);
+        double in[ELEMS];
+#pragma unroll
+        for (int it = 0; it < ELEMS; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
+        const int wg_next = wg + (int)gridDim.x;
+        const bool more = wg_next < nwg;
+        if (more) fetch_row<LOGN, false>(ld, wg_next, tid, C, raw);
+        if constexpr (LD::kScatter) {
+#pragma unroll
+            for (int it = 0; it < ELEMS; it++) lds[pad(ld.place(tid + it * T, 1 << LOGN))] = in[it];
+            __syncthreads();
+            fwd_pass<LOGN, 0, false>(lds, in, st, tid, tw, twa, twb, m, dl);
+        } else {
+            fwd_pass<LOGN, 0, true>(lds, in, st, tid, tw, twa, twb, m, dl);
+        }
+        fwd_pass<LOGN, 1, false>(lds, in, st, tid, tw, twb, twa, m, dl);
+        fwd_pass<LOGN, 2, false>(lds, in, st, tid, tw, twa, twb, m, dl);
+        if constexpr (Plan<LOGN>::NP > 3) fwd_pass<LOGN, 3, false>(lds, in, st, tid, tw, twb, twa, m, dl);
+        if (!more) break;
+        wg = wg_next;
+        __syncthreads();   // the copy-out reads of this row precede the next row's LDS writes
     }
-    fwd_pass<LOGN, 0>(lds, ld, st, wg, tid, tw, m, dl, C);
-    fwd_pass<LOGN, 1>(lds, ld, st, wg, tid, tw, m, dl, C);
-    fwd_pass<LOGN, 2>(lds, ld, st, wg, tid, tw, m, dl, C);
-    if constexpr (Plan<LOGN>::NP > 3) fwd_pass<LOGN, 3>(lds, ld, st, wg, tid, tw, m, dl, C);
 }
 
 // ---------------------------------------------------------------------------
 // inverse transform (passes in reverse order; N^-1 folded into the last stage)
 // ---------------------------------------------------------------------------
-template <int LOGN, int PASS, class LD, class ST>
-__device__ __forceinline__ void inv_pass(double *lds, const LD &ld, const ST &st, int wg, int tid,
-                                         const double *__restrict__ itw, const ModD m, int pr,
-                                         const DevConst *C)
+template <int LOGN, int PASS, class ST>
+__device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int tid,
+                                         const double *__restrict__ itw, const double *twr, double *twr_next,
+                                         const ModD m, int pr, const DevConst *C)
 {
     using P = Plan<LOGN>;
     constexpr int R = P::R[PASS];
     constexpr int S0 = stage_start<LOGN, PASS>();
     constexpr int L = LOGN - S0 - R;
     constexpr int G = ELEMS >> R;
-    constexpr int T = (1 << LOGN) / ELEMS;
-    constexpr bool first = PASS == P::NP - 1, last = PASS == 0;
+    constexpr int PER = (1 << R) - 1;
+    constexpr bool last = PASS == 0;
+    static_assert(last || L + R <= CHUNK_LOG, "early passes must stay inside one wave's chunk");
+    double v[G][1 << R];
+    int base[G];
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        const int gidx = tid + g * T;
+        const int gidx = group_index<LOGN, PASS>(tid, g);
         const int lo = gidx & ((1 << L) - 1);
         const int hi = last ? 0 : (gidx >> L);
-        const int base = (hi << (L + R)) | lo;
-        double v[1 << R];
+        base[g] = (hi << (L + R)) | lo;
+        const int pb = pad(base[g]);
 #pragma unroll
-        for (int c = 0; c < (1 << R); c++) {
-            const int idx = base + (c << L);
-            // every pass starts from |x| <= p/2: the sum path doubles per stage
-            v[c] = red(first ? ld.load(wg, idx, m, C) : lds[idx], m);
-        }
+        for (int c = 0; c < (1 << R); c++) v[g][c] = lds[pb + pad(c << L)];
+    }
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        // every pass starts from |x| <= p/2: the sum path doubles per stage
+#pragma unroll
+        for (int c = 0; c < (1 << R); c++) v[g][c] = red(v[g][c], m);
 #pragma unroll
         for (int u = R - 1; u >= 0; u--) {
             const int half = 1 << (R - 1 - u);
             if (R == 4 && u == 1) {   // after two stages of a four-stage pass: |x| <= 2p -> p/2
 #pragma unroll
-                for (int c = 0; c < (1 << R); c++) v[c] = red(v[c], m);
+                for (int c = 0; c < (1 << R); c++) v[g][c] = red(v[g][c], m);
             }
 #pragma unroll
             for (int c = 0; c < (1 << R); c++) {
                 if (c & half) continue;
                 if (last && u == 0) {
                     // stage 0: single twiddle; fold N^-1 into both outputs
-                    const double d = v[c] - v[c + half];
-                    v[c] = mulmod(v[c] + v[c + half], C->ninv[pr], m);
-                    v[c + half] = mulmod(d, C->itw1_ninv[pr], m);
+                    const double d = v[g][c] - v[g][c + half];
+                    v[g][c] = mulmod(v[g][c] + v[g][c + half], C->ninv[pr], m);
+                    v[g][c + half] = mulmod(d, C->itw1_ninv[pr], m);
                 } else {
-                    const int twi = (1 << (S0 + u)) + ((hi << u) | (c >> (R - u)));
-                    bfly_inv(v[c], v[c + half], itw[twi], m);
+                    bfly_inv(v[g][c], v[g][c + half], twr[g * PER + (1 << u) - 1 + (c >> (R - u))], m);
                 }
             }
         }
+    }
+    if constexpr (!last) {
+        if constexpr (PASS == 1) load_tw<LOGN, 0, true>(itw, tid, twr_next);
+        else load_tw<LOGN, PASS - 1, false>(itw, tid, twr_next);
+    }
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        const int pb = pad(base[g]);
 #pragma unroll
         for (int c = 0; c < (1 << R); c++) {
-            const int idx = base + (c << L);
-            if (last) st.store(wg, idx, v[c], m, C);
-            else lds[idx] = v[c];
+            // the last pass pairs elements N/2 apart with consecutive lanes on consecutive
+            // addresses: it stores straight to global memory
+            if (last) st.store(wg, base[g] + (c << L), v[g][c], m, C);
+            else lds[pb + pad(c << L)] = v[g][c];
         }
     }
-    if (!last) __syncthreads();
+    if constexpr (PASS == 1) __syncthreads();   // pass 0 pairs elements of different waves
+    else if constexpr (!last) wave_sync();
 }
 
 template <int LOGN, class LD, class ST>
 __global__ void __launch_bounds__((1 << LOGN) / ELEMS)
-ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst *__restrict__ C)
+ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst *__restrict__ C, int nwg)
 {
-    __shared__ double lds[1 << LOGN];
-    const int wg = blockIdx.x, tid = threadIdx.x;
-    const int pr = ld.prime(wg, C);
-    const ModD m = C->mod[pr];
-    const double *itw = itw_all + ((size_t)pr << LOGN);
-    if constexpr (Plan<LOGN>::NP > 3) inv_pass<LOGN, 3>(lds, ld, st, wg, tid, itw, m, pr, C);
-    inv_pass<LOGN, 2>(lds, ld, st, wg, tid, itw, m, pr, C);
-    inv_pass<LOGN, 1>(lds, ld, st, wg, tid, itw, m, pr, C);
-    inv_pass<LOGN, 0>(lds, ld, st, wg, tid, itw, m, pr, C);
+    __shared__ double lds[lds_doubles<LOGN>()];
+    constexpr int NP = Plan<LOGN>::NP;
+    const int tid = threadIdx.x;
+    int wg = blockIdx.x;
+    uint64_t raw[ELEMS][LD::kRaw];
+    fetch_row<LOGN, true>(ld, wg, tid, C, raw);
+    for (;;) {
+        const int pr = ld.prime(wg, C);
+        const ModD m = C->mod[pr];
+        const double *itw = itw_all + ((size_t)pr << LOGN);
+        double twa[TWREGS], twb[TWREGS];
+        load_tw<LOGN, NP - 1, false>(itw, tid, twa);
+        {
+            // each wave brings in its own chunk (consecutive lanes on consecutive addresses) and
+            // re-reads it from LDS in the stride-1 pattern of the first pass
+            const int cb = ((tid >> 6) << CHUNK_LOG) + (tid & 63);
+            const int pc = pad(cb);
+#pragma unroll
+            for (int it = 0; it < ELEMS; it++)
+                lds[pc + pad(it * 64)] = ld.finish(raw[it], wg, cb + it * 64, m, C);
+        }
+        const int wg_next = wg + (int)gridDim.x;
+        const bool more = wg_next < nwg;
+        if (more) fetch_row<LOGN, true>(ld, wg_next, tid, C, raw);
+        wave_sync();
+        if constexpr (NP > 3) {
+            inv_pass<LOGN, 3>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, 2>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, 1>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, 0>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
+        } else {
+            inv_pass<LOGN, 2>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, 1>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, 0>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+        }
+        if (!more) break;
+        wg = wg_next;
+        __syncthreads();   // pass 0's LDS reads precede the next row's LDS writes
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -270,24 +437,43 @@ struct StU64 {      // forward output: canonical uint64 (public transform entry 
     }
 };
 
+__device__ __forceinline__ uint64_t f64_bits(double x)
+{
+    union { double d; uint64_t u; } v;
+    v.d = x;
+    return v.u;
+}
+__device__ __forceinline__ double bits_f64(uint64_t x)
+{
+    union { double d; uint64_t u; } v;
+    v.u = x;
+    return v.d;
+}
+
 // rows of uint64 residues, row w uses prime tab[w] (tab != null) or w % pmod
 struct LdRowsU64 {
-    static constexpr bool kStaged = false;
+    static constexpr int kRaw = 1;
+    static constexpr bool kScatter = false;
     const uint64_t *src;
     const uint32_t *tab;
     int pmod, logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *) const { return wg; }
-    __device__ __forceinline__ double load(int wg, int idx, const DevConst *) const
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *, uint64_t *raw) const
     {
-        return u64_to_f64(src[((size_t)wg << logn) + idx]);
+        raw[0] = src[((size_t)wg << logn) + idx];
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD, const DevConst *) const
+    {
+        return u64_to_f64(raw[0]);
     }
 };
 
 // the four input polynomials of a tensor product, ciphertext primes only:
-// workgroup -> (unit b, poly p in {a0,a1,b0,b1}, prime i)
+// workgroup -> (unit, poly p in {a0,a1,b0,b1}, prime i)
 struct LdMulQ {
-    static constexpr bool kStaged = false;
+    static constexpr int kRaw = 1;
+    static constexpr bool kScatter = false;
     const uint64_t *cta, *ctb;
     int a_group, b_group, b_stride, logn;   // b ciphertext of unit u: (u / b_group) * b_stride + u % b_group
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
@@ -296,17 +482,22 @@ struct LdMulQ {
         const int k = C->k, i = wg % k, bp = wg / k;   // bp = unit*4 + p
         return bp * C->KL + i;
     }
-    __device__ __forceinline__ double load(int wg, int idx, const DevConst *C) const
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
         const int k = C->k, i = wg % k, bp = wg / k, p = bp & 3, un = bp >> 2;
         const uint64_t *ct = (p < 2) ? cta + (((size_t)(un / a_group) * 2 * k) << logn)
                                      : ctb + (((size_t)((un / b_group) * b_stride + un % b_group) * 2 * k) << logn);
-        return u64_to_f64(ct[((size_t)((p & 1) * k + i) << logn) + idx]);
+        raw[0] = ct[((size_t)((p & 1) * k + i) << logn) + idx];
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD, const DevConst *) const
+    {
+        return u64_to_f64(raw[0]);
     }
 };
-// the auxiliary-prime rows produced by lift_ext_kernel: [b*4+p][l][N] doubles
+// the auxiliary-prime rows produced by lift_ext_kernel: [unit*4+p][l][N] doubles
 struct LdMulB {
-    static constexpr bool kStaged = false;
+    static constexpr int kRaw = 1;
+    static constexpr bool kScatter = false;
     const double *ext;
     int logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return C->k + wg % C->l; }
@@ -315,107 +506,130 @@ struct LdMulB {
         const int l = C->l, j = wg % l, bp = wg / l;
         return bp * C->KL + C->k + j;
     }
-    __device__ __forceinline__ double load(int wg, int idx, const DevConst *) const
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *, uint64_t *raw) const
     {
-        return ext[((size_t)wg << logn) + idx];
+        raw[0] = f64_bits(ext[((size_t)wg << logn) + idx]);
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD, const DevConst *) const
+    {
+        return bits_f64(raw[0]);
     }
 };
 
 // key-switch mod-up: workgroup -> (unit b, digit j, target prime r); the digit is
-// the integer in [0,Q_j) formed by alpha rows of the source ring element; with
-// galois != 0 the source is first mapped by X -> X^galois (scatter through LDS,
-// an odd multiplier permutes the LDS banks without conflicts).
+// the integer in [0,Q_j) formed by ALPHA rows of the source ring element, reduced
+// modulo the target prime.  GALOIS: the source is first mapped by X -> X^galois
+// (scatter through LDS; an odd multiplier permutes the LDS banks without conflicts).
+// The Galois map acts on the element modulo Q: a negated coefficient is q_s - x in
+// every source row, and only then is the digit lifted and reduced.
+template <bool GALOIS, int ALPHA>
 struct LdModup {
-    static constexpr bool kStaged = true;
+    static constexpr int kRaw = ALPHA;
+    static constexpr bool kScatter = GALOIS;
     const uint64_t *src;     // ring element of unit 0
     size_t unit_stride;      // in uint64
     uint32_t galois;
     int logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->L; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *) const { return wg; }
-    template <int LOGN>
-    __device__ __forceinline__ void stage(double *lds, int wg, int tid, const DevConst *C) const
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
-        constexpr int N = 1 << LOGN, T = N / ELEMS;
-        const int L = C->L, r = wg % L, j = (wg / L) % C->dnum, b = wg / (L * C->dnum);
-        const ConvTab &T_ = C->dig[j];
-        const ModD mr = C->mod[r];
-        const uint64_t *e = src + (size_t)b * unit_stride;
-#pragma unroll 4
-        for (int it = 0; it < ELEMS; it++) {
-            const int idx = tid + it * T;
-            // the Galois map acts on the element modulo Q: a negated coefficient is q_s - x in every
-            // source row, and only then is the digit lifted to [0, Q_j) and reduced modulo the target
-            int dst = idx;
-            bool negate = false;
-            if (galois) {
-                const uint32_t ee = ((uint32_t)idx * galois) & (2 * N - 1);
-                negate = ee >= (uint32_t)N;
-                dst = (int)(negate ? ee - N : ee);
-            }
-            double x[MAXS], a[MAXS];
+        const int L = C->L, j = (wg / L) % C->dnum, b = wg / (L * C->dnum);
+        const uint64_t *e = src + (size_t)b * unit_stride + idx;
 #pragma unroll
-            for (int s = 0; s < 3; s++)
-                if (s < T_.ns) {
-                    x[s] = u64_to_f64(e[((size_t)T_.sidx[s] << LOGN) + idx]);
-                    if (negate) x[s] = (x[s] == 0.0) ? 0.0 : C->mod[T_.sidx[s]].p - x[s];
-                }
-            garner<false>(T_, C, x, a);
-            const double v = canon(horner(T_, C, a, r, false), mr);
-            lds[dst] = v;
-        }
+        for (int s = 0; s < ALPHA; s++) raw[s] = e[(size_t)(j * ALPHA + s) << logn];
     }
-    __device__ __forceinline__ double load(int, int, const DevConst *) const { return 0.0; }
+    __device__ __forceinline__ int place(int idx, int n) const
+    {
+        const uint32_t ee = ((uint32_t)idx * galois) & (2u * n - 1);
+        return (int)(ee >= (uint32_t)n ? ee - n : ee);
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int wg, int idx, const ModD mr,
+                                             const DevConst *C) const
+    {
+        const int L = C->L, r = wg % L, j = (wg / L) % C->dnum;
+        bool negate = false;
+        if (GALOIS) negate = (((uint32_t)idx * galois) & ((2u << logn) - 1)) >= (1u << logn);
+        double x[MAXS], a[MAXS];
+#pragma unroll
+        for (int s = 0; s < ALPHA; s++) {
+            x[s] = u64_to_f64(raw[s]);
+            if (negate) x[s] = (x[s] == 0.0) ? 0.0 : C->mod[j * ALPHA + s].p - x[s];
+        }
+        if (ALPHA == 1) return canon(x[0], mr);
+        const ConvTab &T_ = C->dig[j];
+        garner<false>(T_, C, x, a);
+        return canon(horner(T_, C, a, r, false), mr);
+    }
 };
 
 // plaintext polynomial mod t -> centred lift -> row modulo q_i: workgroup -> (b, i)
 struct LdPlain {
-    static constexpr bool kStaged = false;
+    static constexpr int kRaw = 1;
+    static constexpr bool kScatter = false;
     const uint64_t *pt;
     int logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *) const { return wg; }
-    __device__ __forceinline__ double load(int wg, int idx, const DevConst *C) const
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
-        const double v = u64_to_f64(pt[((size_t)(wg / C->k) << logn) + idx]);
+        raw[0] = pt[((size_t)(wg / C->k) << logn) + idx];
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD, const DevConst *C) const
+    {
+        const double v = u64_to_f64(raw[0]);
         return (v > 0.5 * (C->tmod - 1.0)) ? v - C->tmod : v;
     }
 };
 
-// inverse-transform loaders: prime(wg), load(wg, idx, m, C) (any lazy value < 8p)
+// inverse-transform loaders (finish may return any lazy value below 8p)
 struct LdInvF64 {
+    static constexpr int kRaw = 1;
     const double *src;
     const uint32_t *tab;
     int pmod, logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
-    __device__ __forceinline__ double load(int wg, int idx, const ModD, const DevConst *) const
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *, uint64_t *raw) const
     {
-        return src[((size_t)wg << logn) + idx];
+        raw[0] = f64_bits(src[((size_t)wg << logn) + idx]);
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD, const DevConst *) const
+    {
+        return bits_f64(raw[0]);
     }
 };
 struct LdInvU64 {
+    static constexpr int kRaw = 1;
     const uint64_t *src;
     const uint32_t *tab;
     int pmod, logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
-    __device__ __forceinline__ double load(int wg, int idx, const ModD, const DevConst *) const
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *, uint64_t *raw) const
     {
-        return u64_to_f64(src[((size_t)wg << logn) + idx]);
+        raw[0] = src[((size_t)wg << logn) + idx];
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD, const DevConst *) const
+    {
+        return u64_to_f64(raw[0]);
     }
 };
 // transformed ciphertext row times prepared plaintext row (ct x pt fused into the load):
 // workgroup -> (unit b, comp c, prime i), plaintext = plain[b*pstride + pofs]
 struct LdInvMulPlain {
+    static constexpr int kRaw = 2;
     const double *ctf;     // forward-transformed ciphertext rows [b][2][k][N]
     const double *plain;   // prepared plaintexts [*][k][N]
     int pstride, pofs, logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
-    __device__ __forceinline__ double load(int wg, int idx, const ModD m, const DevConst *C) const
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
         const int k = C->k, i = wg % k, b = wg / (2 * k);
-        const double x = ctf[((size_t)wg << logn) + idx];
-        const double w = plain[((size_t)((b * pstride + pofs) * k + i) << logn) + idx];
-        return mulmod(x, w, m);
+        raw[0] = f64_bits(ctf[((size_t)wg << logn) + idx]);
+        raw[1] = f64_bits(plain[((size_t)((b * pstride + pofs) * k + i) << logn) + idx]);
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD m, const DevConst *) const
+    {
+        return mulmod(bits_f64(raw[0]), bits_f64(raw[1]), m);
     }
 };
 
