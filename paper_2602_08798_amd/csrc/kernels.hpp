@@ -35,11 +35,20 @@ template <int LOGN, int PASS> __device__ __forceinline__ int group_index(int tid
     if (PASS == 0) return tid + g * ((1 << LOGN) / ELEMS);
     return ((tid >> 6) << (CHUNK_LOG - R)) + (tid & 63) + 64 * g;
 }
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load (vmcnt(0)), which would drain the next row's prefetch at each
+// barrier; threads of these kernels exchange data through LDS alone.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 // compiler-level ordering between LDS writes and reads of the same wave (the LDS pipeline
 // itself executes one wave's operations in order)
 __device__ __forceinline__ void wave_sync()
 {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
     __builtin_amdgcn_wave_barrier();
 }
 
@@ -198,7 +207,7 @@ __device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST
 #pragma unroll
         for (int c = 0; c < (1 << R); c++) lds[pb + pad(c << L)] = v[g][c];
     }
-    if constexpr (first) __syncthreads();
+    if constexpr (first) lds_barrier();
     else wave_sync();
     if constexpr (last) {
         // results leave through LDS so that consecutive lanes write consecutive addresses; each
@@ -236,7 +245,7 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
         if constexpr (LD::kScatter) {
 #pragma unroll
             for (int it = 0; it < ELEMS; it++) lds[pad(ld.place(tid + it * T, 1 << LOGN))] = in[it];
-            __syncthreads();
+            lds_barrier();
             fwd_pass<LOGN, 0, false>(lds, in, st, tid, tw, twa, twb, m, dl);
         } else {
             fwd_pass<LOGN, 0, true>(lds, in, st, tid, tw, twa, twb, m, dl);
@@ -246,7 +255,7 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
         if constexpr (Plan<LOGN>::NP > 3) fwd_pass<LOGN, 3, false>(lds, in, st, tid, tw, twb, twa, m, dl);
         if (!more) break;
         wg = wg_next;
-        __syncthreads();   // the copy-out reads of this row precede the next row's LDS writes
+        lds_barrier();   // the copy-out reads of this row precede the next row's LDS writes
     }
 }
 
@@ -319,7 +328,7 @@ __device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int 
             else lds[pb + pad(c << L)] = v[g][c];
         }
     }
-    if constexpr (PASS == 1) __syncthreads();   // pass 0 pairs elements of different waves
+    if constexpr (PASS == 1) lds_barrier();   // pass 0 pairs elements of different waves
     else if constexpr (!last) wave_sync();
 }
 
@@ -364,7 +373,7 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
         }
         if (!more) break;
         wg = wg_next;
-        __syncthreads();   // pass 0's LDS reads precede the next row's LDS writes
+        lds_barrier();   // pass 0's LDS reads precede the next row's LDS writes
     }
 }
 
