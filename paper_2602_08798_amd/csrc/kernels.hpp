@@ -111,7 +111,10 @@ __device__ __forceinline__ void load_tw(const double *__restrict__ tw, int tid, 
     static_assert(G * PER <= TWREGS, "twiddle register file too small");
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        const int hi = HI_ZERO ? 0 : (group_index<LOGN, PASS>(tid, g) >> L);
+        int hi = HI_ZERO ? 0 : (group_index<LOGN, PASS>(tid, g) >> L);
+        // with L >= 6 all 64 lanes of a wave share hi: say so, and the factors come in through
+        // the scalar cache instead of one vector load per lane
+        if (!HI_ZERO && PASS > 0 && L >= 6) hi = __builtin_amdgcn_readfirstlane(hi);
 #pragma unroll
         for (int u = 0; u < R; u++)
 #pragma unroll
