@@ -106,7 +106,7 @@ enum KernelId {
     KID_ADD, KID_SUM_GROUPS, KID_COUNT
 };
 static const char *const kKernelNames[KID_COUNT] = {
-    "lift_ext", "ntt_fwd<mul,q-rows>", "ntt_fwd<mul,aux-rows>", "ntt_fwd<modup>", "ntt_fwd<rows>",
+    "(unused)", "ntt_fwd<mul,q-rows>", "ntt_fwd<mul,aux-rows>", "ntt_fwd<modup>", "ntt_fwd<rows>",
     "ntt_fwd<plain>", "tensor", "ntt_inv<f64>", "ntt_inv<u64>", "ntt_inv<mul_plain>", "scale",
     "ks_inner", "moddown", "add", "sum_groups"};
 
@@ -416,26 +416,44 @@ static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *
                   uint32_t b_stride = 0)
 {
     if (!b_group) { b_group = batch; b_stride = batch; }
+    const uint32_t n_a = (batch + a_group - 1) / a_group;
+    const size_t polys = 2 * ((size_t)n_a + batch);
     Bump w = bump(c, ws);
-    double *ext = w.take<double>((size_t)4 * c->l * batch);
-    double *ntt = w.take<double>((size_t)4 * c->KL * batch);
+    double *ntt = w.take<double>(polys * c->KL);
     double *tens = w.take<double>((size_t)3 * c->KL * batch);
-    const int polys = (int)batch * 4;
     const double LB = (double)limb_bytes(c), B = batch;
-    const double in_rows = 2.0 * c->k * ((batch + a_group - 1) / a_group) + 2.0 * c->k * B;
-    CG_LAUNCH_PW(KID_LIFT_EXT, LB * (in_rows + 4.0 * c->l * B), lift_ext_kernel, pw_blocks(c, polys), a2, b2, ext,
-                 (int)a_group, (int)b_group, (int)b_stride, polys, c->dc);
-    CG_TRY(launch_fwd(c, s, (size_t)polys * c->k, LdMulQ{a2, b2, (int)a_group, (int)b_group, (int)b_stride, c->logn}, StF64{ntt, c->logn},
-                      KID_FWD_MULQ, LB * (in_rows + 4.0 * c->k * B)));
-    CG_TRY(launch_fwd(c, s, (size_t)polys * c->l, LdMulB{ext, c->logn}, StF64{ntt, c->logn}, KID_FWD_MULB,
-                      LB * 8.0 * c->l * B));
-    CG_LAUNCH_PW(KID_TENSOR, LB * 7.0 * c->KL * B, tensor_kernel, pw_blocks(c, (size_t)batch * c->KL), ntt, tens,
-                 (int)batch, c->dc);
+    const double in_rows = (double)polys * c->k;
+    const MulSrc src{a2, b2, (int)n_a, (int)b_group, (int)b_stride, c->logn};
+    const StF64 st{ntt, c->logn};
+    CG_TRY(launch_fwd(c, s, polys * c->k, LdMulQ{src}, st, KID_FWD_MULQ, LB * 2.0 * in_rows));
+    const double aux_bytes = LB * (in_rows + (double)polys * c->l);
+    int rc;
+    switch (c->k) {
+    case 1: rc = launch_fwd(c, s, polys * c->l, LdMulAux<1>{src}, st, KID_FWD_MULB, aux_bytes); break;
+    case 2: rc = launch_fwd(c, s, polys * c->l, LdMulAux<2>{src}, st, KID_FWD_MULB, aux_bytes); break;
+    case 3: rc = launch_fwd(c, s, polys * c->l, LdMulAux<3>{src}, st, KID_FWD_MULB, aux_bytes); break;
+    case 4: rc = launch_fwd(c, s, polys * c->l, LdMulAux<4>{src}, st, KID_FWD_MULB, aux_bytes); break;
+    case 5: rc = launch_fwd(c, s, polys * c->l, LdMulAux<5>{src}, st, KID_FWD_MULB, aux_bytes); break;
+    default: rc = launch_fwd(c, s, polys * c->l, LdMulAux<6>{src}, st, KID_FWD_MULB, aux_bytes); break;
+    }
+    CG_TRY(rc);
+    CG_LAUNCH_PW(KID_TENSOR, LB * c->KL * ((double)polys + 3.0 * B), tensor_kernel,
+                 pw_blocks(c, (size_t)batch * c->KL), ntt, tens, (int)batch, (int)a_group, (int)n_a, c->dc);
     const size_t rows = (size_t)batch * 3 * c->KL;
     CG_TRY(launch_inv(c, s, rows, LdInvF64{tens, nullptr, c->KL, c->logn}, StInvF64{tens, c->logn}, KID_INV_F64,
                       LB * 2.0 * rows));
-    CG_LAUNCH_PW(KID_SCALE, LB * (3.0 * c->KL + 3.0 * c->k * (accumulate ? 2 : 1)) * B, scale_kernel,
-                 pw_blocks(c, (size_t)batch * 3), tens, out3, (int)batch * 3, accumulate, c->dc);
+    const double sbytes = LB * (3.0 * c->KL + 3.0 * c->k * (accumulate ? 2 : 1)) * B;
+    const unsigned sblocks = pw_blocks(c, (size_t)batch * 3);
+#define CG_SCALE(K) CG_LAUNCH_PW(KID_SCALE, sbytes, scale_kernel<K>, sblocks, tens, out3, (int)batch * 3, accumulate, c->dc)
+    switch (c->k) {
+    case 1: CG_SCALE(1); break;
+    case 2: CG_SCALE(2); break;
+    case 3: CG_SCALE(3); break;
+    case 4: CG_SCALE(4); break;
+    case 5: CG_SCALE(5); break;
+    default: CG_SCALE(6); break;
+    }
+#undef CG_SCALE
     return CG_OK;
 }
 

@@ -231,8 +231,9 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
     const int tid = threadIdx.x;
     int wg = blockIdx.x;
     uint64_t raw[ELEMS][LD::kRaw];
-    fetch_row<LOGN, false>(ld, wg, tid, C, raw);
+    if (LD::kPrefetch) fetch_row<LOGN, false>(ld, wg, tid, C, raw);
     for (;;) {
+        if (!LD::kPrefetch) fetch_row<LOGN, false>(ld, wg, tid, C, raw);
         const int pr = ld.prime(wg, C);
         const ModD m = C->mod[pr];
         const double *tw = tw_all + ((size_t)pr << LOGN);
@@ -244,7 +245,7 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
         for (int it = 0; it < ELEMS; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
         const int wg_next = wg + (int)gridDim.x;
         const bool more = wg_next < nwg;
-        if (more) fetch_row<LOGN, false>(ld, wg_next, tid, C, raw);
+        if (LD::kPrefetch && more) fetch_row<LOGN, false>(ld, wg_next, tid, C, raw);
         if constexpr (LD::kScatter) {
 #pragma unroll
             for (int it = 0; it < ELEMS; it++) lds[pad(ld.place(tid + it * T, 1 << LOGN))] = in[it];
@@ -344,8 +345,9 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
     const int tid = threadIdx.x;
     int wg = blockIdx.x;
     uint64_t raw[ELEMS][LD::kRaw];
-    fetch_row<LOGN, true>(ld, wg, tid, C, raw);
+    if (LD::kPrefetch) fetch_row<LOGN, true>(ld, wg, tid, C, raw);
     for (;;) {
+        if (!LD::kPrefetch) fetch_row<LOGN, true>(ld, wg, tid, C, raw);
         const int pr = ld.prime(wg, C);
         const ModD m = C->mod[pr];
         const double *itw = itw_all + ((size_t)pr << LOGN);
@@ -362,7 +364,7 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
         }
         const int wg_next = wg + (int)gridDim.x;
         const bool more = wg_next < nwg;
-        if (more) fetch_row<LOGN, true>(ld, wg_next, tid, C, raw);
+        if (LD::kPrefetch && more) fetch_row<LOGN, true>(ld, wg_next, tid, C, raw);
         wave_sync();
         if constexpr (NP > 3) {
             inv_pass<LOGN, 3>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
@@ -421,6 +423,37 @@ __device__ __forceinline__ double horner(const ConvTab &T, const DevConst *C, co
     return acc;
 }
 
+// compile-time-sized variants (source basis of exactly NS primes): fully unrolled, no guards
+template <int NS, bool CENTRED>
+__device__ __forceinline__ bool garner_t(const ConvTab &T, const DevConst *C, const double (&x)[NS], double (&a)[NS])
+{
+    a[0] = x[0];
+#pragma unroll
+    for (int j = 1; j < NS; j++) {
+        const ModD mj = C->mod[T.sidx[j]];
+        double v = x[j];
+#pragma unroll
+        for (int i = 0; i < j; i++) v = mulmod(v - a[i], T.inv[i][j], mj);
+        a[j] = canon(v, mj);
+    }
+    bool gt = false;
+    if (CENTRED) {
+#pragma unroll
+        for (int i = 0; i < NS; i++) gt = (a[i] > T.half[i]) || (a[i] == T.half[i] && gt);
+    }
+    return gt;
+}
+template <int NS>
+__device__ __forceinline__ double horner_t(const ConvTab &T, const DevConst *C, const double (&a)[NS], int jt, bool neg)
+{
+    const ModD mt = C->mod[T.tidx[jt]];
+    double acc = a[NS - 1];
+#pragma unroll
+    for (int i = NS - 2; i >= 0; i--) acc = mulmod(acc, T.s_mod_t[i][jt], mt) + a[i];
+    if (neg) acc -= T.S_mod_t[jt];
+    return acc;
+}
+
 // ---------------------------------------------------------------------------
 // loaders / storers for the transforms
 // ---------------------------------------------------------------------------
@@ -465,6 +498,7 @@ __device__ __forceinline__ double bits_f64(uint64_t x)
 // rows of uint64 residues, row w uses prime tab[w] (tab != null) or w % pmod
 struct LdRowsU64 {
     static constexpr int kRaw = 1;
+    static constexpr bool kPrefetch = true;
     static constexpr bool kScatter = false;
     const uint64_t *src;
     const uint32_t *tab;
@@ -481,50 +515,71 @@ struct LdRowsU64 {
     }
 };
 
-// the four input polynomials of a tensor product, ciphertext primes only:
-// workgroup -> (unit, poly p in {a0,a1,b0,b1}, prime i)
-struct LdMulQ {
-    static constexpr int kRaw = 1;
-    static constexpr bool kScatter = false;
+// Inputs of a batch of tensor products.  The source ciphertexts are the n_a "a" operands followed
+// by the `batch` "b" operands; polynomial pp = 2 * ciphertext + component.  Every polynomial is
+// transformed once over the k ciphertext primes (LdMulQ) and the l auxiliary primes (LdMulAux) into
+// ntt[pp][k+l][N]; an a operand shared by several products is transformed once.
+struct MulSrc {
     const uint64_t *cta, *ctb;
-    int a_group, b_group, b_stride, logn;   // b ciphertext of unit u: (u / b_group) * b_stride + u % b_group
+    int n_a, b_group, b_stride, logn;   // b ciphertext of unit u: (u / b_group) * b_stride + u % b_group
+    __device__ __forceinline__ const uint64_t *poly(int pp, int k) const
+    {
+        const int ct = pp >> 1, comp = pp & 1;
+        const uint64_t *base;
+        if (ct < n_a) base = cta + (((size_t)ct * 2 * k) << logn);
+        else {
+            const int u = ct - n_a;
+            base = ctb + (((size_t)((u / b_group) * b_stride + u % b_group) * 2 * k) << logn);
+        }
+        return base + (((size_t)comp * k) << logn);
+    }
+};
+struct LdMulQ {     // workgroup -> (pp, ciphertext prime i)
+    static constexpr int kRaw = 1;
+    static constexpr bool kPrefetch = true;
+    static constexpr bool kScatter = false;
+    MulSrc src;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *C) const
     {
-        const int k = C->k, i = wg % k, bp = wg / k;   // bp = unit*4 + p
-        return bp * C->KL + i;
+        return (wg / C->k) * C->KL + wg % C->k;
     }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
-        const int k = C->k, i = wg % k, bp = wg / k, p = bp & 3, un = bp >> 2;
-        const uint64_t *ct = (p < 2) ? cta + (((size_t)(un / a_group) * 2 * k) << logn)
-                                     : ctb + (((size_t)((un / b_group) * b_stride + un % b_group) * 2 * k) << logn);
-        raw[0] = ct[((size_t)((p & 1) * k + i) << logn) + idx];
+        const int k = C->k;
+        raw[0] = src.poly(wg / k, k)[((size_t)(wg % k) << src.logn) + idx];
     }
     __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD, const DevConst *) const
     {
         return u64_to_f64(raw[0]);
     }
 };
-// the auxiliary-prime rows produced by lift_ext_kernel: [unit*4+p][l][N] doubles
-struct LdMulB {
-    static constexpr int kRaw = 1;
+// workgroup -> (pp, auxiliary prime j): the centred integer lift of each coefficient (exact, via
+// mixed-radix digits of its K residues) reduced modulo the auxiliary prime
+template <int K>
+struct LdMulAux {
+    static constexpr int kRaw = K;
+    static constexpr bool kPrefetch = (K <= 2);   // more words per element would cost occupancy
     static constexpr bool kScatter = false;
-    const double *ext;
-    int logn;
+    MulSrc src;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return C->k + wg % C->l; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *C) const
     {
-        const int l = C->l, j = wg % l, bp = wg / l;
-        return bp * C->KL + C->k + j;
+        return (wg / C->l) * C->KL + C->k + wg % C->l;
     }
-    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *, uint64_t *raw) const
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
-        raw[0] = f64_bits(ext[((size_t)wg << logn) + idx]);
+        const uint64_t *p = src.poly(wg / C->l, K) + idx;
+#pragma unroll
+        for (int i = 0; i < K; i++) raw[i] = p[(size_t)i << src.logn];
     }
-    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD, const DevConst *) const
+    __device__ __forceinline__ double finish(const uint64_t *raw, int wg, int, const ModD mb, const DevConst *C) const
     {
-        return bits_f64(raw[0]);
+        double x[K], dg[K];
+#pragma unroll
+        for (int i = 0; i < K; i++) x[i] = u64_to_f64(raw[i]);
+        const bool neg = garner_t<K, true>(C->q2b, C, x, dg);
+        return canon(horner_t<K>(C->q2b, C, dg, wg % C->l, neg), mb);
     }
 };
 
@@ -537,6 +592,7 @@ struct LdMulB {
 template <bool GALOIS, int ALPHA>
 struct LdModup {
     static constexpr int kRaw = ALPHA;
+    static constexpr bool kPrefetch = true;
     static constexpr bool kScatter = GALOIS;
     const uint64_t *src;     // ring element of unit 0
     size_t unit_stride;      // in uint64
@@ -578,6 +634,7 @@ struct LdModup {
 // plaintext polynomial mod t -> centred lift -> row modulo q_i: workgroup -> (b, i)
 struct LdPlain {
     static constexpr int kRaw = 1;
+    static constexpr bool kPrefetch = true;
     static constexpr bool kScatter = false;
     const uint64_t *pt;
     int logn;
@@ -597,6 +654,7 @@ struct LdPlain {
 // inverse-transform loaders (finish may return any lazy value below 8p)
 struct LdInvF64 {
     static constexpr int kRaw = 1;
+    static constexpr bool kPrefetch = true;
     const double *src;
     const uint32_t *tab;
     int pmod, logn;
@@ -612,6 +670,7 @@ struct LdInvF64 {
 };
 struct LdInvU64 {
     static constexpr int kRaw = 1;
+    static constexpr bool kPrefetch = true;
     const uint64_t *src;
     const uint32_t *tab;
     int pmod, logn;
@@ -629,6 +688,7 @@ struct LdInvU64 {
 // workgroup -> (unit b, comp c, prime i), plaintext = plain[b*pstride + pofs]
 struct LdInvMulPlain {
     static constexpr int kRaw = 2;
+    static constexpr bool kPrefetch = true;
     const double *ctf;     // forward-transformed ciphertext rows [b][2][k][N]
     const double *plain;   // prepared plaintexts [*][k][N]
     int pstride, pofs, logn;
@@ -682,36 +742,11 @@ struct StInvAppend {
 // ---------------------------------------------------------------------------
 constexpr int PW_THREADS = 256;
 
-// mul prologue: centred lift of the 4 input polynomials into the auxiliary basis.
-// thread -> (b*4+p, n); out ext[b*4+p][j][n] canonical doubles
+// tensor product in the transform domain over all k+l primes:
+// ntt[pp][r][n] (lazy) -> tens[u*3+c][r][n] (lazy); a polys of unit u: pp = 2*(u / a_group) + {0,1},
+// b polys: pp = 2*(n_a + u) + {0,1}
 __global__ void __launch_bounds__(PW_THREADS)
-lift_ext_kernel(const uint64_t *__restrict__ a, const uint64_t *__restrict__ b, double *__restrict__ ext,
-                int a_group, int b_group, int b_stride, int total_polys, const DevConst *__restrict__ C)
-{
-    const int logn = C->logn, N = 1 << logn, k = C->k, l = C->l;
-    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
-    const int n = (int)(gid & (N - 1));
-    const int bp = (int)(gid >> logn);
-    if (bp >= total_polys) return;
-    const int p = bp & 3, u = bp >> 2;
-    const uint64_t *ct = (p < 2) ? a + (((size_t)(u / a_group) * 2 * k) << logn)
-                                 : b + (((size_t)((u / b_group) * b_stride + u % b_group) * 2 * k) << logn);
-    ct += ((size_t)((p & 1) * k) << logn) + n;
-    double x[MAXS], dg[MAXS];
-#pragma unroll
-    for (int i = 0; i < MAXS; i++)
-        if (i < k) x[i] = u64_to_f64(ct[(size_t)i << logn]);
-    const bool neg = garner<true>(C->q2b, C, x, dg);
-    double *o = ext + (((size_t)bp * l) << logn) + n;
-#pragma unroll
-    for (int j = 0; j < MAXS; j++)
-        if (j < l) o[(size_t)j << logn] = canon(horner(C->q2b, C, dg, j, neg), C->mod[k + j]);
-}
-
-// tensor product in the transform domain over all k+l primes.
-// ntt[b*4+p][r][n] (lazy) -> tens[b*3+c][r][n] (lazy)
-__global__ void __launch_bounds__(PW_THREADS)
-tensor_kernel(const double *__restrict__ ntt, double *__restrict__ tens, int batch,
+tensor_kernel(const double *__restrict__ ntt, double *__restrict__ tens, int batch, int a_group, int n_a,
               const DevConst *__restrict__ C)
 {
     const int logn = C->logn, N = 1 << logn, KL = C->KL;
@@ -719,14 +754,15 @@ tensor_kernel(const double *__restrict__ ntt, double *__restrict__ tens, int bat
     const int n = (int)(gid & (N - 1));
     const int br = (int)(gid >> logn);
     if (br >= batch * KL) return;
-    const int r = br % KL, b = br / KL;
+    const int r = br % KL, u = br / KL;
     const ModD m = C->mod[r];
     const size_t pstride = (size_t)KL << logn;
-    const double *src = ntt + (size_t)b * 4 * pstride + ((size_t)r << logn) + n;
+    const double *sa = ntt + (size_t)(2 * (u / a_group)) * pstride + ((size_t)r << logn) + n;
+    const double *sb = ntt + (size_t)(2 * (n_a + u)) * pstride + ((size_t)r << logn) + n;
     // forward outputs are lazy (< 4p); bring them to p/2 so the two-term sum stays far below 2^53
-    const double a0 = red(src[0], m), a1 = red(src[pstride], m);
-    const double b0 = red(src[2 * pstride], m), b1 = red(src[3 * pstride], m);
-    double *dst = tens + (size_t)b * 3 * pstride + ((size_t)r << logn) + n;
+    const double a0 = red(sa[0], m), a1 = red(sa[pstride], m);
+    const double b0 = red(sb[0], m), b1 = red(sb[pstride], m);
+    double *dst = tens + (size_t)u * 3 * pstride + ((size_t)r << logn) + n;
     dst[0] = mulmod(a0, b0, m);
     dst[pstride] = mulmod(a0, b1, m) + mulmod(a1, b0, m);
     dst[2 * pstride] = mulmod(a1, b1, m);
@@ -737,39 +773,41 @@ tensor_kernel(const double *__restrict__ ntt, double *__restrict__ tens, int bat
 //   y is below B/2 in magnitude, so its centred lift from the auxiliary basis is exact.
 // tens[b*3+c][r][n] (lazy, coefficient order) -> out[b][c][i][n] canonical uint64;
 // acc != 0 adds the result to what out already holds (sum of products).
+template <int K>
 __global__ void __launch_bounds__(PW_THREADS)
 scale_kernel(const double *__restrict__ tens, uint64_t *__restrict__ out, int total_polys, int acc,
              const DevConst *__restrict__ C)
 {
-    const int logn = C->logn, N = 1 << logn, k = C->k, l = C->l, KL = C->KL;
+    constexpr int L = K + 1;
+    const int logn = C->logn, N = 1 << logn;
     const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
     const int n = (int)(gid & (N - 1));
     const int bc = (int)(gid >> logn);
     if (bc >= total_polys) return;
-    const double *src = tens + (((size_t)bc * KL) << logn) + n;
+    const double *src = tens + (((size_t)bc * (K + L)) << logn) + n;
     const double t = C->tmod;
-    double x[MAXS], dg[MAXS], y[MAXS];
+    double e[K + L];
 #pragma unroll
-    for (int i = 0; i < MAXS; i++)
-        if (i < k) x[i] = canon(mulmod(src[(size_t)i << logn], t, C->mod[i]), C->mod[i]);
-    const bool neg = garner<true>(C->q2b, C, x, dg);
+    for (int i = 0; i < K + L; i++) e[i] = src[(size_t)i << logn];
+    double x[K], dq[K], y[L], db[L];
 #pragma unroll
-    for (int j = 0; j < MAXS; j++)
-        if (j < l) {
-            const ModD mb = C->mod[k + j];
-            const double te = mulmod(src[(size_t)(k + j) << logn], t, mb);
-            const double rj = horner(C->q2b, C, dg, j, neg);
-            y[j] = canon(mulmod(red(te - rj, mb), C->Qinv_b[j], mb), mb);
-        }
-    const bool neg2 = garner<true>(C->b2q, C, y, dg);
-    uint64_t *o = out + (((size_t)bc * k) << logn) + n;
+    for (int i = 0; i < K; i++) x[i] = canon(mulmod(e[i], t, C->mod[i]), C->mod[i]);
+    const bool neg = garner_t<K, true>(C->q2b, C, x, dq);
 #pragma unroll
-    for (int i = 0; i < MAXS; i++)
-        if (i < k) {
-            double v = canon(horner(C->b2q, C, dg, i, neg2), C->mod[i]);
-            if (acc) v = addmod_canon(v, u64_to_f64(o[(size_t)i << logn]), C->mod[i]);
-            o[(size_t)i << logn] = f64_to_u64(v);
-        }
+    for (int j = 0; j < L; j++) {
+        const ModD mb = C->mod[K + j];
+        const double te = mulmod(e[K + j], t, mb);
+        const double rj = horner_t<K>(C->q2b, C, dq, j, neg);
+        y[j] = canon(mulmod(red(te - rj, mb), C->Qinv_b[j], mb), mb);
+    }
+    const bool neg2 = garner_t<L, true>(C->b2q, C, y, db);
+    uint64_t *o = out + (((size_t)bc * K) << logn) + n;
+#pragma unroll
+    for (int i = 0; i < K; i++) {
+        double v = canon(horner_t<L>(C->b2q, C, db, i, neg2), C->mod[i]);
+        if (acc) v = addmod_canon(v, u64_to_f64(o[(size_t)i << logn]), C->mod[i]);
+        o[(size_t)i << logn] = f64_to_u64(v);
+    }
 }
 
 // key-switch inner product: dig[b][j][r][n] (lazy) x key[j][c][r][n] -> acc[b][c][r][n] (lazy)
