@@ -101,14 +101,14 @@ struct cg_ctx {
 
 // kernel classes for the timing facility
 enum KernelId {
-    KID_LIFT_EXT = 0, KID_FWD_MULQ, KID_FWD_MULB, KID_FWD_MODUP, KID_FWD_ROWS, KID_FWD_PLAIN,
-    KID_TENSOR, KID_INV_F64, KID_INV_U64, KID_INV_MULPLAIN, KID_SCALE, KID_KS_INNER, KID_MODDOWN,
+    KID_FWD_MULQ = 0, KID_FWD_MULB, KID_FWD_MODUP, KID_FWD_ROWS, KID_FWD_PLAIN,
+    KID_TENSOR, KID_INV_F64, KID_INV_U64, KID_INV_MULPLAIN, KID_SCALE, KID_INV_KSINNER, KID_MODDOWN,
     KID_ADD, KID_SUM_GROUPS, KID_COUNT
 };
 static const char *const kKernelNames[KID_COUNT] = {
-    "(unused)", "ntt_fwd<mul,q-rows>", "ntt_fwd<mul,aux-rows>", "ntt_fwd<modup>", "ntt_fwd<rows>",
+    "ntt_fwd<mul,q-rows>", "ntt_fwd<mul,aux-rows>", "ntt_fwd<modup>", "ntt_fwd<rows>",
     "ntt_fwd<plain>", "tensor", "ntt_inv<f64>", "ntt_inv<u64>", "ntt_inv<mul_plain>", "scale",
-    "ks_inner", "moddown", "add", "sum_groups"};
+    "ntt_inv<ks_inner>", "moddown", "add", "sum_groups"};
 
 // Brackets one launch with two events when profiling is on.
 struct ProfScope {
@@ -482,10 +482,21 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     }
 #undef CG_MODUP
     CG_TRY(rc);
-    CG_LAUNCH_PW(KID_KS_INNER, LB * ((dig_rows + 2.0 * c->L) * B + 2.0 * dig_rows), ks_inner_kernel,
-                 pw_blocks(c, (size_t)batch * c->L), dig, key, acc, (int)batch, c->dc);
-    CG_TRY(launch_inv(c, s, (size_t)batch * 2 * c->L, LdInvF64{acc, nullptr, c->L, c->logn},
-                      StInvF64{acc, c->logn}, KID_INV_F64, LB * 4.0 * c->L * B));
+    // inner product with the key fused into the inverse transform's load
+    const size_t irows = (size_t)batch * 2 * c->L;
+    const double ibytes = LB * ((dig_rows + 2.0 * c->L) * B + 2.0 * dig_rows);
+    const StInvF64 ist{acc, c->logn};
+#define CG_KSI(D) launch_inv(c, s, irows, LdInvKsInner<D>{dig, key, c->logn}, ist, KID_INV_KSINNER, ibytes)
+    switch (c->dnum) {
+    case 1: rc = CG_KSI(1); break;
+    case 2: rc = CG_KSI(2); break;
+    case 3: rc = CG_KSI(3); break;
+    case 4: rc = CG_KSI(4); break;
+    case 5: rc = CG_KSI(5); break;
+    default: rc = CG_KSI(6); break;
+    }
+#undef CG_KSI
+    CG_TRY(rc);
     ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch};
     const double add_rows = !add ? 0.0 : (galois_inv ? c->k + (accumulate ? 2.0 * c->k : 0.0) : 2.0 * c->k);
     CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, moddown_kernel,

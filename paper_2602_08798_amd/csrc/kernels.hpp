@@ -150,6 +150,25 @@ __device__ __forceinline__ void fetch_row(const LD &ld, int wg, int tid, const D
     for (int it = 0; it < ELEMS; it++) ld.fetch(wg, first + it * (CHUNKED ? 64 : T), C, raw[it]);
 }
 
+// Loaders that do not prefetch fetch and finish a row in slices, so that at most about 32 raw
+// words are live per thread however many words an element needs.
+template <int LOGN, bool CHUNKED, class LD, class F>
+__device__ __forceinline__ void load_row_now(const LD &ld, int wg, int tid, const ModD m, const DevConst *C, F &&sink)
+{
+    constexpr int T = (1 << LOGN) / ELEMS;
+    constexpr int CH = LD::kRaw <= 2 ? ELEMS : (LD::kRaw <= 4 ? 8 : 4);
+    const int first = CHUNKED ? ((tid >> 6) << CHUNK_LOG) + (tid & 63) : tid;
+    constexpr int step = CHUNKED ? 64 : T;
+#pragma unroll
+    for (int c0 = 0; c0 < ELEMS; c0 += CH) {
+        uint64_t rw[CH][LD::kRaw];
+#pragma unroll
+        for (int i = 0; i < CH; i++) ld.fetch(wg, first + (c0 + i) * step, C, rw[i]);
+#pragma unroll
+        for (int i = 0; i < CH; i++) sink(c0 + i, ld.finish(rw[i], wg, first + (c0 + i) * step, m, C));
+    }
+}
+
 // ---------------------------------------------------------------------------
 // forward transform
 // ---------------------------------------------------------------------------
@@ -230,10 +249,9 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
     constexpr int T = (1 << LOGN) / ELEMS;
     const int tid = threadIdx.x;
     int wg = blockIdx.x;
-    uint64_t raw[ELEMS][LD::kRaw];
-    if (LD::kPrefetch) fetch_row<LOGN, false>(ld, wg, tid, C, raw);
+    uint64_t raw[LD::kPrefetch ? ELEMS : 1][LD::kRaw];
+    if constexpr (LD::kPrefetch) fetch_row<LOGN, false>(ld, wg, tid, C, raw);
     for (;;) {
-        if (!LD::kPrefetch) fetch_row<LOGN, false>(ld, wg, tid, C, raw);
         const int pr = ld.prime(wg, C);
         const ModD m = C->mod[pr];
         const double *tw = tw_all + ((size_t)pr << LOGN);
@@ -241,11 +259,15 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
         double twa[TWREGS], twb[TWREGS];
         load_tw<LOGN, 0, true>(tw, tid, twa);
         double in[ELEMS];
-#pragma unroll
-        for (int it = 0; it < ELEMS; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
         const int wg_next = wg + (int)gridDim.x;
         const bool more = wg_next < nwg;
-        if (LD::kPrefetch && more) fetch_row<LOGN, false>(ld, wg_next, tid, C, raw);
+        if constexpr (LD::kPrefetch) {
+#pragma unroll
+            for (int it = 0; it < ELEMS; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
+            if (more) fetch_row<LOGN, false>(ld, wg_next, tid, C, raw);
+        } else {
+            load_row_now<LOGN, false>(ld, wg, tid, m, C, [&](int it, double v) { in[it] = v; });
+        }
         if constexpr (LD::kScatter) {
 #pragma unroll
             for (int it = 0; it < ELEMS; it++) lds[pad(ld.place(tid + it * T, 1 << LOGN))] = in[it];
@@ -344,10 +366,9 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
     constexpr int NP = Plan<LOGN>::NP;
     const int tid = threadIdx.x;
     int wg = blockIdx.x;
-    uint64_t raw[ELEMS][LD::kRaw];
-    if (LD::kPrefetch) fetch_row<LOGN, true>(ld, wg, tid, C, raw);
+    uint64_t raw[LD::kPrefetch ? ELEMS : 1][LD::kRaw];
+    if constexpr (LD::kPrefetch) fetch_row<LOGN, true>(ld, wg, tid, C, raw);
     for (;;) {
-        if (!LD::kPrefetch) fetch_row<LOGN, true>(ld, wg, tid, C, raw);
         const int pr = ld.prime(wg, C);
         const ModD m = C->mod[pr];
         const double *itw = itw_all + ((size_t)pr << LOGN);
@@ -358,13 +379,19 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
             // re-reads it from LDS in the stride-1 pattern of the first pass
             const int cb = ((tid >> 6) << CHUNK_LOG) + (tid & 63);
             const int pc = pad(cb);
+            if constexpr (LD::kPrefetch) {
 #pragma unroll
-            for (int it = 0; it < ELEMS; it++)
-                lds[pc + pad(it * 64)] = ld.finish(raw[it], wg, cb + it * 64, m, C);
+                for (int it = 0; it < ELEMS; it++)
+                    lds[pc + pad(it * 64)] = ld.finish(raw[it], wg, cb + it * 64, m, C);
+            } else {
+                load_row_now<LOGN, true>(ld, wg, tid, m, C, [&](int it, double v) { lds[pc + pad(it * 64)] = v; });
+            }
         }
         const int wg_next = wg + (int)gridDim.x;
         const bool more = wg_next < nwg;
-        if (LD::kPrefetch && more) fetch_row<LOGN, true>(ld, wg_next, tid, C, raw);
+        if constexpr (LD::kPrefetch) {
+            if (more) fetch_row<LOGN, true>(ld, wg_next, tid, C, raw);
+        }
         wave_sync();
         if constexpr (NP > 3) {
             inv_pass<LOGN, 3>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
@@ -559,7 +586,7 @@ struct LdMulQ {     // workgroup -> (pp, ciphertext prime i)
 template <int K>
 struct LdMulAux {
     static constexpr int kRaw = K;
-    static constexpr bool kPrefetch = (K <= 2);   // more words per element would cost occupancy
+    static constexpr bool kPrefetch = false;   // K words per element: fetched in slices instead
     static constexpr bool kScatter = false;
     MulSrc src;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return C->k + wg % C->l; }
@@ -684,6 +711,34 @@ struct LdInvU64 {
         return u64_to_f64(raw[0]);
     }
 };
+// key-switch inner product fused into the load: workgroup -> (unit b, component c, prime r),
+// element = sum_j digit_j[b][r] * key[j][c][r] (both in transform order)
+template <int DNUM>
+struct LdInvKsInner {
+    static constexpr int kRaw = 2 * DNUM;
+    static constexpr bool kPrefetch = false;
+    const double *dig;   // [b][DNUM][L][N] lazy
+    const double *key;   // [DNUM][2][L][N] reduced
+    int logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->L; }
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
+    {
+        const int L = C->L, r = wg % L, c = (wg / L) & 1, b = wg / (2 * L);
+#pragma unroll
+        for (int j = 0; j < DNUM; j++) {
+            raw[2 * j] = f64_bits(dig[(((size_t)(b * DNUM + j) * L + r) << logn) + idx]);
+            raw[2 * j + 1] = f64_bits(key[(((size_t)(j * 2 + c) * L + r) << logn) + idx]);
+        }
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD m, const DevConst *) const
+    {
+        double s = 0.0;
+#pragma unroll
+        for (int j = 0; j < DNUM; j++) s += mulmod(red(bits_f64(raw[2 * j]), m), bits_f64(raw[2 * j + 1]), m);
+        return s;
+    }
+};
+
 // transformed ciphertext row times prepared plaintext row (ct x pt fused into the load):
 // workgroup -> (unit b, comp c, prime i), plaintext = plain[b*pstride + pofs]
 struct LdInvMulPlain {
@@ -808,30 +863,6 @@ scale_kernel(const double *__restrict__ tens, uint64_t *__restrict__ out, int to
         if (acc) v = addmod_canon(v, u64_to_f64(o[(size_t)i << logn]), C->mod[i]);
         o[(size_t)i << logn] = f64_to_u64(v);
     }
-}
-
-// key-switch inner product: dig[b][j][r][n] (lazy) x key[j][c][r][n] -> acc[b][c][r][n] (lazy)
-__global__ void __launch_bounds__(PW_THREADS)
-ks_inner_kernel(const double *__restrict__ dig, const double *__restrict__ key, double *__restrict__ accb,
-                int batch, const DevConst *__restrict__ C)
-{
-    const int logn = C->logn, N = 1 << logn, L = C->L, dnum = C->dnum;
-    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
-    const int n = (int)(gid & (N - 1));
-    const int br = (int)(gid >> logn);
-    if (br >= batch * L) return;
-    const int r = br % L, b = br / L;
-    const ModD m = C->mod[r];
-    double s0 = 0.0, s1 = 0.0;
-    for (int j = 0; j < dnum; j++) {
-        const double d = red(dig[(((size_t)(b * dnum + j) * L + r) << logn) + n], m);
-        const double k0 = key[(((size_t)(j * 2 + 0) * L + r) << logn) + n];
-        const double k1 = key[(((size_t)(j * 2 + 1) * L + r) << logn) + n];
-        s0 += mulmod(d, k0, m);
-        s1 += mulmod(d, k1, m);
-    }
-    accb[(((size_t)(b * 2 + 0) * L + r) << logn) + n] = s0;
-    accb[(((size_t)(b * 2 + 1) * L + r) << logn) + n] = s1;
 }
 
 // mod-down with rounding and the final additions of relinearisation / rotation:
