@@ -159,6 +159,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the mult+relin/sec loops (used when profiling the step alone)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by head with no "
@@ -199,23 +201,28 @@ def main():
                 "algo_bytes_per_launch": dom_stat["algo_bytes"] / dom_stat["launches"],
                 "avg_launch_us": dom["avg_us"]}
 
-    # secondary metric: ct-ct mult+relin per second at N = 8192, batch 48
-    H, C = ws.heads, ws.n_cts
-    out2 = ws.ctx.empty_ct(H * C)
-    b_dense = ws.cache[:H * C]
-    mr = lambda: ws.ctx.mul_relin(ws.a, b_dense, ws.rlk, H * C, out=out2)
-    mr()
-    mr_ms = timed(torch, mr, max(5, args.steps))
+    secondary = None
+    if not args.no_secondary:
+        # secondary metric: ct-ct mult+relin per second at N = 8192, batch 48
+        H, C = ws.heads, ws.n_cts
+        out2 = ws.ctx.empty_ct(H * C)
+        b_dense = ws.cache[:H * C]
+        mr = lambda: ws.ctx.mul_relin(ws.a, b_dense, ws.rlk, H * C, out=out2)
+        mr()
+        mr_ms = timed(torch, mr, max(5, args.steps))
 
-    # same metric at a batch large enough to keep every compute unit busy for several rows
-    big = 8 * H * C
-    a_big = ws.a.repeat(8, 1, 1, 1)
-    b_big = b_dense.repeat(8, 1, 1, 1)
-    out_big = ws.ctx.empty_ct(big)
-    mrb = lambda: ws.ctx.mul_relin(a_big, b_big, ws.rlk, big, out=out_big)
-    mrb()
-    mrb_ms = timed(torch, mrb, 5)
-    del a_big, b_big, out_big
+        # same metric at a batch large enough to keep every compute unit busy for several rows
+        big = 8 * H * C
+        a_big = ws.a.repeat(8, 1, 1, 1)
+        b_big = b_dense.repeat(8, 1, 1, 1)
+        out_big = ws.ctx.empty_ct(big)
+        mrb = lambda: ws.ctx.mul_relin(a_big, b_big, ws.rlk, big, out=out_big)
+        mrb()
+        mrb_ms = timed(torch, mrb, 5)
+        del a_big, b_big, out_big
+        secondary = {"metric": "ct-ct mult+relin/sec at N=8192", "value": round(H * C / (mr_ms * 1e-3), 1),
+                     "unit": "1/s", "batch": H * C,
+                     "value_at_batch_%d" % big: round(big / (mrb_ms * 1e-3), 1)}
 
     result = {
         "metric": "encrypted decode-step ms/token at 512 ctx",
@@ -227,9 +234,7 @@ def main():
         "config": {"workload": "C4: decode step, 12 heads x d=64, 512-token encrypted KV cache, N=8192, "
                                "3+1 primes < 2^50, t=65537", "ops_per_step": ws.op_counts(),
                    "derived_12_layers_ms_per_token": round(12 * ms, 3)},
-        "secondary": {"metric": "ct-ct mult+relin/sec at N=8192", "value": round(H * C / (mr_ms * 1e-3), 1),
-                      "unit": "1/s", "batch": H * C,
-                      "value_at_batch_%d" % big: round(big / (mrb_ms * 1e-3), 1)},
+        "secondary": secondary,
         "roofline": roofline,
         "kernels": kernels,
     }
