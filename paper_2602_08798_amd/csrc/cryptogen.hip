@@ -89,6 +89,7 @@ struct cg_ctx {
     uint32_t *tab;        // scratch prime-index table for the public transform entry points
     uint32_t tab_cap;
     int device, n_cu;
+    int elems;            // elements per thread in the transform kernels (8 or 16)
     // workspace limbs (N * 8 bytes) per unit
     int ws_total;
     // optional per-launch timing with HIP events (benchmark support)
@@ -196,6 +197,7 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
     c->logn = (int)prm->log2n; c->N = (int)N; c->k = (int)prm->k; c->nsp = (int)prm->nsp;
     c->alpha = (int)prm->alpha; c->dnum = c->k / c->alpha; c->t = prm->t;
     c->l = c->k + 1;
+    c->elems = c->logn <= 13 ? 8 : 16;   // 1024 threads per row at N >= 8192, 512 at N = 4096
     c->L = c->k + c->nsp;
     c->KL = c->k + c->l;
     int np = 0;
@@ -353,29 +355,42 @@ static Bump bump(const cg_ctx *c, void *ws) { return Bump{static_cast<char *>(ws
 // ---------------------------------------------------------------------------
 // launch helpers
 // ---------------------------------------------------------------------------
-// transform kernels are persistent: at most as many workgroups as fit the device at once
-static unsigned ntt_grid(const cg_ctx *c, size_t nwg)
+// Transform kernels are persistent: the grid is at most the number of workgroups that are
+// resident at once (what the runtime reports for this instantiation's registers and LDS), so
+// that every workgroup starts immediately and walks over its rows with the next row prefetched.
+template <class K>
+static unsigned ntt_grid(const cg_ctx *c, size_t nwg, K kernel, int threads)
 {
-    const size_t lds_bytes = ((size_t)c->N + c->N / 8) * sizeof(double);
-    size_t per_cu = (160 * 1024) / lds_bytes;
-    const size_t by_threads = 2048 / ((size_t)c->N / ELEMS);
-    if (per_cu > by_threads) per_cu = by_threads;
-    if (per_cu < 1) per_cu = 1;
-    const size_t resident = per_cu * (size_t)c->n_cu;
+    static int per_cu = 0;   // one value per kernel instantiation
+    if (per_cu == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, 0) != hipSuccess || n < 1) n = 1;
+        per_cu = n;
+    }
+    const size_t resident = (size_t)per_cu * (size_t)c->n_cu;
     return (unsigned)(nwg < resident ? nwg : resident);
 }
+// elements per thread for this context's transforms
+static int ntt_elems(const cg_ctx *c) { return c->elems; }
+
 template <class LD, class ST>
 static int launch_fwd(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int kid, double bytes)
 {
     if (nwg == 0) return CG_OK;
     ProfScope ps(c, s, kid, bytes);
-    const dim3 grid(ntt_grid(c, nwg)), block((unsigned)c->N / ELEMS);
-    switch (c->logn) {
-    case 12: hipLaunchKernelGGL((ntt_fwd_kernel<12, LD, ST>), grid, block, 0, s, ld, st, c->tw, c->dc, (int)nwg); break;
-    case 13: hipLaunchKernelGGL((ntt_fwd_kernel<13, LD, ST>), grid, block, 0, s, ld, st, c->tw, c->dc, (int)nwg); break;
-    case 14: hipLaunchKernelGGL((ntt_fwd_kernel<14, LD, ST>), grid, block, 0, s, ld, st, c->tw, c->dc, (int)nwg); break;
+    const int e = ntt_elems(c);
+    const int threads = c->N / e;
+#define CG_FWD(LG, EL)                                                                                      \
+    hipLaunchKernelGGL((ntt_fwd_kernel<LG, EL, LD, ST>),                                                    \
+                       dim3(ntt_grid(c, nwg, ntt_fwd_kernel<LG, EL, LD, ST>, threads)), dim3(threads), 0, s, \
+                       ld, st, c->tw, c->dc, (int)nwg)
+    switch (c->logn * 100 + e) {
+    case 1416: CG_FWD(14, 16); break;
+    case 1208: CG_FWD(12, 8); break;
+    case 1308: CG_FWD(13, 8); break;
     default: return CG_EINVAL;
     }
+#undef CG_FWD
     return check_launch();
 }
 template <class LD, class ST>
@@ -383,13 +398,19 @@ static int launch_inv(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int ki
 {
     if (nwg == 0) return CG_OK;
     ProfScope ps(c, s, kid, bytes);
-    const dim3 grid(ntt_grid(c, nwg)), block((unsigned)c->N / ELEMS);
-    switch (c->logn) {
-    case 12: hipLaunchKernelGGL((ntt_inv_kernel<12, LD, ST>), grid, block, 0, s, ld, st, c->itw, c->dc, (int)nwg); break;
-    case 13: hipLaunchKernelGGL((ntt_inv_kernel<13, LD, ST>), grid, block, 0, s, ld, st, c->itw, c->dc, (int)nwg); break;
-    case 14: hipLaunchKernelGGL((ntt_inv_kernel<14, LD, ST>), grid, block, 0, s, ld, st, c->itw, c->dc, (int)nwg); break;
+    const int e = ntt_elems(c);
+    const int threads = c->N / e;
+#define CG_INV(LG, EL)                                                                                      \
+    hipLaunchKernelGGL((ntt_inv_kernel<LG, EL, LD, ST>),                                                    \
+                       dim3(ntt_grid(c, nwg, ntt_inv_kernel<LG, EL, LD, ST>, threads)), dim3(threads), 0, s, \
+                       ld, st, c->itw, c->dc, (int)nwg)
+    switch (c->logn * 100 + e) {
+    case 1416: CG_INV(14, 16); break;
+    case 1208: CG_INV(12, 8); break;
+    case 1308: CG_INV(13, 8); break;
     default: return CG_EINVAL;
     }
+#undef CG_INV
     return check_launch();
 }
 static unsigned pw_blocks(const cg_ctx *c, size_t rows) { return (unsigned)((rows * c->N + PW_THREADS - 1) / PW_THREADS); }

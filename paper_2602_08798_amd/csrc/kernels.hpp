@@ -7,33 +7,36 @@
 namespace cg {
 
 // ---------------------------------------------------------------------------
-// Transform plan: each thread keeps ELEMS = 16 elements in registers and a pass
-// runs R = 3 or 4 butterfly stages on them between two LDS exchanges.
+// Transform plan.  A row of N = 2^LOGN residues is transformed by one workgroup
+// of N / E threads; each thread keeps E elements in registers and a pass runs
+// R butterfly stages on them between two LDS exchanges.  The first NC passes pair
+// elements owned by different waves (workgroup barrier); after them every wave
+// owns one contiguous chunk of 64 * E elements and all remaining stages stay
+// inside it, so those passes only need wave-level ordering.
+//   E = 8 (N <= 8192) puts 16 waves on a row of 8192 and measured a few per cent faster than
+//   E = 16 on the decode step; E = 16 is the only choice at N = 16384 (1024 threads).
 // ---------------------------------------------------------------------------
-template <int LOGN> struct Plan;
-constexpr int ELEMS = 16;
-template <> struct Plan<12> { static constexpr int NP = 3; static constexpr int R[4] = {4, 4, 4, 0}; };
-template <> struct Plan<13> { static constexpr int NP = 4; static constexpr int R[4] = {4, 3, 3, 3}; };
-template <> struct Plan<14> { static constexpr int NP = 4; static constexpr int R[4] = {4, 4, 3, 3}; };
-// After pass 0 (the only pass that pairs elements owned by different waves) every
-// wave owns one contiguous chunk of 64 * ELEMS = 1024 elements and all later
-// stages stay inside it, so those passes need no workgroup barrier.
-constexpr int CHUNK_LOG = 10;
-static_assert((1 << CHUNK_LOG) == 64 * ELEMS, "chunk = one wave's elements");
+template <int LOGN, int E> struct Plan;
+template <> struct Plan<14, 16> { static constexpr int NP = 4, NC = 1; static constexpr int R[5] = {4, 4, 3, 3, 0}; };
+template <> struct Plan<12, 8> { static constexpr int NP = 4, NC = 1; static constexpr int R[5] = {3, 3, 3, 3, 0}; };
+template <> struct Plan<13, 8> { static constexpr int NP = 5, NC = 2; static constexpr int R[5] = {3, 3, 3, 3, 1}; };
 
-template <int LOGN, int PASS> constexpr int stage_start()
+constexpr int ilog2c(int x) { return x <= 1 ? 0 : 1 + ilog2c(x / 2); }
+template <int E> constexpr int chunk_log() { return 6 + ilog2c(E); }
+
+template <int LOGN, int E, int PASS> constexpr int stage_start()
 {
     int s = 0;
-    for (int i = 0; i < PASS; i++) s += Plan<LOGN>::R[i];
+    for (int i = 0; i < PASS; i++) s += Plan<LOGN, E>::R[i];
     return s;
 }
 
 // group index of a thread in pass PASS (g-th group of the thread)
-template <int LOGN, int PASS> __device__ __forceinline__ int group_index(int tid, int g)
+template <int LOGN, int E, int PASS> __device__ __forceinline__ int group_index(int tid, int g)
 {
-    constexpr int R = Plan<LOGN>::R[PASS];
-    if (PASS == 0) return tid + g * ((1 << LOGN) / ELEMS);
-    return ((tid >> 6) << (CHUNK_LOG - R)) + (tid & 63) + 64 * g;
+    constexpr int R = Plan<LOGN, E>::R[PASS];
+    if (PASS < Plan<LOGN, E>::NC) return tid + g * ((1 << LOGN) / E);
+    return ((tid >> 6) << (chunk_log<E>() - R)) + (tid & 63) + 64 * g;
 }
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
 // outstanding global load (vmcnt(0)), which would drain the next row's prefetch at each
@@ -60,14 +63,14 @@ constexpr double fwd_grow(double b, int stages)
     return b;
 }
 // Decide at compile time which forward passes start with a reduction.
-template <int LOGN, int PASS> struct FwdBound {
-    static constexpr double in_prev = FwdBound<LOGN, PASS - 1>::out;
-    static constexpr bool reduce = fwd_grow(in_prev, Plan<LOGN>::R[PASS]) > 7.5;
-    static constexpr double out = fwd_grow(reduce ? 0.51 : in_prev, Plan<LOGN>::R[PASS]);
+template <int LOGN, int E, int PASS> struct FwdBound {
+    static constexpr double in_prev = FwdBound<LOGN, E, PASS - 1>::out;
+    static constexpr bool reduce = fwd_grow(in_prev, Plan<LOGN, E>::R[PASS]) > 7.5;
+    static constexpr double out = fwd_grow(reduce ? 0.51 : in_prev, Plan<LOGN, E>::R[PASS]);
 };
-template <int LOGN> struct FwdBound<LOGN, 0> {
+template <int LOGN, int E> struct FwdBound<LOGN, E, 0> {
     static constexpr bool reduce = false;                       // loaders deliver |x| <= p
-    static constexpr double out = fwd_grow(1.0, Plan<LOGN>::R[0]);
+    static constexpr double out = fwd_grow(1.0, Plan<LOGN, E>::R[0]);
 };
 
 __device__ __forceinline__ void bfly_fwd(double &a, double &b, double w, const ModD m)
@@ -93,25 +96,26 @@ constexpr int TWREGS = 16;
 // LDS layout: one pad double after every 8, so that a thread owning 8 (or 16)
 // consecutive elements is 9 doubles away from its neighbour lane and the
 // stride-1 passes are bank-conflict free.  For the index patterns used here
-// (base + (c << L) with the low L bits of base below 2^L) the pad of the sum
-// is the sum of the pads, so the per-element part folds into instruction
-// offsets.
+// (base + (c << L), base = (hi << (L+R)) | lo with lo < 2^L) the pad of the sum
+// is the sum of the pads -- with L >= 3 the element part is a multiple of 8,
+// otherwise it never carries out of the group's aligned span -- so the
+// per-element part folds into instruction offsets.
 __device__ __forceinline__ constexpr int pad(int idx) { return idx + (idx >> 3); }
 template <int LOGN> constexpr int lds_doubles() { return (1 << LOGN) + (1 << (LOGN - 3)); }
 
-template <int LOGN, int PASS, bool HI_ZERO>
+template <int LOGN, int E, int PASS, bool HI_ZERO>
 __device__ __forceinline__ void load_tw(const double *__restrict__ tw, int tid, double *twr)
 {
-    using P = Plan<LOGN>;
+    using P = Plan<LOGN, E>;
     constexpr int R = P::R[PASS];
-    constexpr int S0 = stage_start<LOGN, PASS>();
+    constexpr int S0 = stage_start<LOGN, E, PASS>();
     constexpr int L = LOGN - S0 - R;
-    constexpr int G = ELEMS >> R;
+    constexpr int G = E >> R;
     constexpr int PER = (1 << R) - 1;
     static_assert(G * PER <= TWREGS, "twiddle register file too small");
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        int hi = HI_ZERO ? 0 : (group_index<LOGN, PASS>(tid, g) >> L);
+        int hi = HI_ZERO ? 0 : (group_index<LOGN, E, PASS>(tid, g) >> L);
         // with L >= 6 all 64 lanes of a wave share hi: say so, and the factors come in through
         // the scalar cache instead of one vector load per lane
         if (!HI_ZERO && PASS > 0 && L >= 6) hi = __builtin_amdgcn_readfirstlane(hi);
@@ -130,6 +134,7 @@ __device__ __forceinline__ void load_tw(const double *__restrict__ tw, int tid, 
 //
 // Loader interface (LD):
 //   kRaw                       64-bit words fetched per element
+//   kPrefetch                  fetch the next row during the current one (else fetch in slices at use)
 //   kScatter                   forward only: elements are placed into LDS at place(idx) before pass 0
 //   prime(wg, C)               prime index of row wg
 //   dst_limb(wg, C)            forward only: destination row
@@ -137,30 +142,31 @@ __device__ __forceinline__ void load_tw(const double *__restrict__ tw, int tid, 
 //   finish(raw, wg, idx, m, C) element value, |x| <= p (forward) or < 8p (inverse)
 //
 // Element ownership: CHUNKED = false: element it of a thread is tid + it * T
-// (pass 0); CHUNKED = true: (wave << CHUNK_LOG) + lane + 64 * it (the wave's chunk).
+// (pass 0); CHUNKED = true: (wave << chunk_log) + lane + 64 * it (the wave's chunk).
 // Both put consecutive lanes on consecutive addresses.
 // ---------------------------------------------------------------------------
-template <int LOGN, bool CHUNKED, class LD>
+template <int LOGN, int E, bool CHUNKED, class LD>
 __device__ __forceinline__ void fetch_row(const LD &ld, int wg, int tid, const DevConst *C,
-                                          uint64_t (&raw)[ELEMS][LD::kRaw])
+                                          uint64_t (&raw)[E][LD::kRaw])
 {
-    constexpr int T = (1 << LOGN) / ELEMS;
-    const int first = CHUNKED ? ((tid >> 6) << CHUNK_LOG) + (tid & 63) : tid;
+    constexpr int T = (1 << LOGN) / E;
+    const int first = CHUNKED ? ((tid >> 6) << chunk_log<E>()) + (tid & 63) : tid;
 #pragma unroll
-    for (int it = 0; it < ELEMS; it++) ld.fetch(wg, first + it * (CHUNKED ? 64 : T), C, raw[it]);
+    for (int it = 0; it < E; it++) ld.fetch(wg, first + it * (CHUNKED ? 64 : T), C, raw[it]);
 }
 
 // Loaders that do not prefetch fetch and finish a row in slices, so that at most about 32 raw
 // words are live per thread however many words an element needs.
-template <int LOGN, bool CHUNKED, class LD, class F>
+template <int LOGN, int E, bool CHUNKED, class LD, class F>
 __device__ __forceinline__ void load_row_now(const LD &ld, int wg, int tid, const ModD m, const DevConst *C, F &&sink)
 {
-    constexpr int T = (1 << LOGN) / ELEMS;
-    constexpr int CH = LD::kRaw <= 2 ? ELEMS : (LD::kRaw <= 4 ? 8 : 4);
-    const int first = CHUNKED ? ((tid >> 6) << CHUNK_LOG) + (tid & 63) : tid;
+    constexpr int T = (1 << LOGN) / E;
+    constexpr int CH0 = LD::kRaw <= 2 ? 16 : (LD::kRaw <= 4 ? 8 : 4);
+    constexpr int CH = CH0 < E ? CH0 : E;
+    const int first = CHUNKED ? ((tid >> 6) << chunk_log<E>()) + (tid & 63) : tid;
     constexpr int step = CHUNKED ? 64 : T;
 #pragma unroll
-    for (int c0 = 0; c0 < ELEMS; c0 += CH) {
+    for (int c0 = 0; c0 < E; c0 += CH) {
         uint64_t rw[CH][LD::kRaw];
 #pragma unroll
         for (int i = 0; i < CH; i++) ld.fetch(wg, first + (c0 + i) * step, C, rw[i]);
@@ -172,28 +178,29 @@ __device__ __forceinline__ void load_row_now(const LD &ld, int wg, int tid, cons
 // ---------------------------------------------------------------------------
 // forward transform
 // ---------------------------------------------------------------------------
-template <int LOGN, int PASS, bool FROM_REGS, class ST>
+template <int LOGN, int E, int PASS, bool FROM_REGS, class ST>
 __device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST &st, int tid,
                                          const double *__restrict__ tw, const double *twr, double *twr_next,
                                          const ModD m, int dst_limb)
 {
-    using P = Plan<LOGN>;
+    using P = Plan<LOGN, E>;
     constexpr int R = P::R[PASS];
-    constexpr int S0 = stage_start<LOGN, PASS>();
+    constexpr int S0 = stage_start<LOGN, E, PASS>();
     constexpr int L = LOGN - S0 - R;          // index bits below this pass's R bits
-    constexpr int G = ELEMS >> R;             // independent radix-2^R groups per thread
+    constexpr int G = E >> R;                 // independent radix-2^R groups per thread
     constexpr int PER = (1 << R) - 1;
     constexpr bool first = PASS == 0, last = PASS == P::NP - 1;
-    constexpr bool do_red = FwdBound<LOGN, PASS>::reduce;
-    static_assert(FwdBound<LOGN, PASS>::out < 8.0, "lazy bound exceeds 2^53");
-    static_assert(L >= 3 || L + R >= 3, "pad() additivity needs the group to span 8 elements");
+    constexpr bool cross = PASS < P::NC;      // pairs elements owned by different waves
+    constexpr bool do_red = FwdBound<LOGN, E, PASS>::reduce;
+    static_assert(FwdBound<LOGN, E, PASS>::out < 8.0, "lazy bound exceeds 2^53");
     static_assert(!FROM_REGS || (first && L + R == LOGN), "register input only for the first pass");
-    static_assert(first || L + R <= CHUNK_LOG, "later passes must stay inside one wave's chunk");
+    static_assert(cross || L + R <= chunk_log<E>(), "wave-local passes must stay inside one chunk");
+    static_assert(!last || !cross, "the last pass must be wave-local (chunk-wise copy-out)");
     double v[G][1 << R];
     int base[G];
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        const int gidx = group_index<LOGN, PASS>(tid, g);
+        const int gidx = group_index<LOGN, E, PASS>(tid, g);
         const int lo = gidx & ((1 << L) - 1);
         const int hi = first ? 0 : (gidx >> L);
         base[g] = (hi << (L + R)) | lo;
@@ -222,63 +229,65 @@ __device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST
         }
     }
     // fetch the next pass's factors while this pass's results drain to LDS
-    if constexpr (!last) load_tw<LOGN, PASS + 1, false>(tw, tid, twr_next);
+    if constexpr (!last) load_tw<LOGN, E, PASS + 1, false>(tw, tid, twr_next);
 #pragma unroll
     for (int g = 0; g < G; g++) {
         const int pb = pad(base[g]);
 #pragma unroll
         for (int c = 0; c < (1 << R); c++) lds[pb + pad(c << L)] = v[g][c];
     }
-    if constexpr (first) lds_barrier();
+    if constexpr (cross) lds_barrier();
     else wave_sync();
     if constexpr (last) {
         // results leave through LDS so that consecutive lanes write consecutive addresses; each
         // wave copies out its own chunk
-        const int cb = ((tid >> 6) << CHUNK_LOG) + (tid & 63);
+        const int cb = ((tid >> 6) << chunk_log<E>()) + (tid & 63);
         const int pc = pad(cb);
 #pragma unroll
-        for (int it = 0; it < ELEMS; it++) st.store(dst_limb, cb + it * 64, lds[pc + pad(it * 64)], m);
+        for (int it = 0; it < E; it++) st.store(dst_limb, cb + it * 64, lds[pc + pad(it * 64)], m);
     }
 }
 
-template <int LOGN, class LD, class ST>
-__global__ void __launch_bounds__((1 << LOGN) / ELEMS)
+template <int LOGN, int E, class LD, class ST>
+__global__ void __launch_bounds__((1 << LOGN) / E)
 ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *__restrict__ C, int nwg)
 {
     __shared__ double lds[lds_doubles<LOGN>()];
-    constexpr int T = (1 << LOGN) / ELEMS;
+    constexpr int T = (1 << LOGN) / E;
+    constexpr int NP = Plan<LOGN, E>::NP;
     const int tid = threadIdx.x;
     int wg = blockIdx.x;
-    uint64_t raw[LD::kPrefetch ? ELEMS : 1][LD::kRaw];
-    if constexpr (LD::kPrefetch) fetch_row<LOGN, false>(ld, wg, tid, C, raw);
+    uint64_t raw[LD::kPrefetch ? E : 1][LD::kRaw];
+    if constexpr (LD::kPrefetch) fetch_row<LOGN, E, false>(ld, wg, tid, C, raw);
     for (;;) {
         const int pr = ld.prime(wg, C);
         const ModD m = C->mod[pr];
         const double *tw = tw_all + ((size_t)pr << LOGN);
         const int dl = ld.dst_limb(wg, C);
         double twa[TWREGS], twb[TWREGS];
-        load_tw<LOGN, 0, true>(tw, tid, twa);
-        double in[ELEMS];
+        load_tw<LOGN, E, 0, true>(tw, tid, twa);
+        double in[E];
         const int wg_next = wg + (int)gridDim.x;
         const bool more = wg_next < nwg;
         if constexpr (LD::kPrefetch) {
 #pragma unroll
-            for (int it = 0; it < ELEMS; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
-            if (more) fetch_row<LOGN, false>(ld, wg_next, tid, C, raw);
+            for (int it = 0; it < E; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
+            if (more) fetch_row<LOGN, E, false>(ld, wg_next, tid, C, raw);
         } else {
-            load_row_now<LOGN, false>(ld, wg, tid, m, C, [&](int it, double v) { in[it] = v; });
+            load_row_now<LOGN, E, false>(ld, wg, tid, m, C, [&](int it, double v) { in[it] = v; });
         }
         if constexpr (LD::kScatter) {
 #pragma unroll
-            for (int it = 0; it < ELEMS; it++) lds[pad(ld.place(tid + it * T, 1 << LOGN))] = in[it];
+            for (int it = 0; it < E; it++) lds[pad(ld.place(tid + it * T, 1 << LOGN))] = in[it];
             lds_barrier();
-            fwd_pass<LOGN, 0, false>(lds, in, st, tid, tw, twa, twb, m, dl);
+            fwd_pass<LOGN, E, 0, false>(lds, in, st, tid, tw, twa, twb, m, dl);
         } else {
-            fwd_pass<LOGN, 0, true>(lds, in, st, tid, tw, twa, twb, m, dl);
+            fwd_pass<LOGN, E, 0, true>(lds, in, st, tid, tw, twa, twb, m, dl);
         }
-        fwd_pass<LOGN, 1, false>(lds, in, st, tid, tw, twb, twa, m, dl);
-        fwd_pass<LOGN, 2, false>(lds, in, st, tid, tw, twa, twb, m, dl);
-        if constexpr (Plan<LOGN>::NP > 3) fwd_pass<LOGN, 3, false>(lds, in, st, tid, tw, twb, twa, m, dl);
+        fwd_pass<LOGN, E, 1, false>(lds, in, st, tid, tw, twb, twa, m, dl);
+        fwd_pass<LOGN, E, 2, false>(lds, in, st, tid, tw, twa, twb, m, dl);
+        if constexpr (NP > 3) fwd_pass<LOGN, E, 3, false>(lds, in, st, tid, tw, twb, twa, m, dl);
+        if constexpr (NP > 4) fwd_pass<LOGN, E, 4, false>(lds, in, st, tid, tw, twa, twb, m, dl);
         if (!more) break;
         wg = wg_next;
         lds_barrier();   // the copy-out reads of this row precede the next row's LDS writes
@@ -288,24 +297,25 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
 // ---------------------------------------------------------------------------
 // inverse transform (passes in reverse order; N^-1 folded into the last stage)
 // ---------------------------------------------------------------------------
-template <int LOGN, int PASS, class ST>
+template <int LOGN, int E, int PASS, class ST>
 __device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int tid,
                                          const double *__restrict__ itw, const double *twr, double *twr_next,
                                          const ModD m, int pr, const DevConst *C)
 {
-    using P = Plan<LOGN>;
+    using P = Plan<LOGN, E>;
     constexpr int R = P::R[PASS];
-    constexpr int S0 = stage_start<LOGN, PASS>();
+    constexpr int S0 = stage_start<LOGN, E, PASS>();
     constexpr int L = LOGN - S0 - R;
-    constexpr int G = ELEMS >> R;
+    constexpr int G = E >> R;
     constexpr int PER = (1 << R) - 1;
     constexpr bool last = PASS == 0;
-    static_assert(last || L + R <= CHUNK_LOG, "early passes must stay inside one wave's chunk");
+    constexpr bool cross = PASS < P::NC;
+    static_assert(cross || L + R <= chunk_log<E>(), "wave-local passes must stay inside one chunk");
     double v[G][1 << R];
     int base[G];
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        const int gidx = group_index<LOGN, PASS>(tid, g);
+        const int gidx = group_index<LOGN, E, PASS>(tid, g);
         const int lo = gidx & ((1 << L) - 1);
         const int hi = last ? 0 : (gidx >> L);
         base[g] = (hi << (L + R)) | lo;
@@ -340,8 +350,8 @@ __device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int 
         }
     }
     if constexpr (!last) {
-        if constexpr (PASS == 1) load_tw<LOGN, 0, true>(itw, tid, twr_next);
-        else load_tw<LOGN, PASS - 1, false>(itw, tid, twr_next);
+        if constexpr (PASS == 1) load_tw<LOGN, E, 0, true>(itw, tid, twr_next);
+        else load_tw<LOGN, E, PASS - 1, false>(itw, tid, twr_next);
     }
 #pragma unroll
     for (int g = 0; g < G; g++) {
@@ -354,54 +364,64 @@ __device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int 
             else lds[pb + pad(c << L)] = v[g][c];
         }
     }
-    if constexpr (PASS == 1) lds_barrier();   // pass 0 pairs elements of different waves
-    else if constexpr (!last) wave_sync();
+    if constexpr (!last) {
+        if constexpr (PASS - 1 < P::NC) lds_barrier();   // the next pass reads other waves' elements
+        else wave_sync();
+    }
 }
 
-template <int LOGN, class LD, class ST>
-__global__ void __launch_bounds__((1 << LOGN) / ELEMS)
+template <int LOGN, int E, class LD, class ST>
+__global__ void __launch_bounds__((1 << LOGN) / E)
 ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst *__restrict__ C, int nwg)
 {
     __shared__ double lds[lds_doubles<LOGN>()];
-    constexpr int NP = Plan<LOGN>::NP;
+    constexpr int NP = Plan<LOGN, E>::NP;
+    static_assert(NP - 1 >= Plan<LOGN, E>::NC, "the first inverse pass must be wave-local");
     const int tid = threadIdx.x;
     int wg = blockIdx.x;
-    uint64_t raw[LD::kPrefetch ? ELEMS : 1][LD::kRaw];
-    if constexpr (LD::kPrefetch) fetch_row<LOGN, true>(ld, wg, tid, C, raw);
+    uint64_t raw[LD::kPrefetch ? E : 1][LD::kRaw];
+    if constexpr (LD::kPrefetch) fetch_row<LOGN, E, true>(ld, wg, tid, C, raw);
     for (;;) {
         const int pr = ld.prime(wg, C);
         const ModD m = C->mod[pr];
         const double *itw = itw_all + ((size_t)pr << LOGN);
         double twa[TWREGS], twb[TWREGS];
-        load_tw<LOGN, NP - 1, false>(itw, tid, twa);
+        load_tw<LOGN, E, NP - 1, false>(itw, tid, twa);
         {
             // each wave brings in its own chunk (consecutive lanes on consecutive addresses) and
             // re-reads it from LDS in the stride-1 pattern of the first pass
-            const int cb = ((tid >> 6) << CHUNK_LOG) + (tid & 63);
+            const int cb = ((tid >> 6) << chunk_log<E>()) + (tid & 63);
             const int pc = pad(cb);
             if constexpr (LD::kPrefetch) {
 #pragma unroll
-                for (int it = 0; it < ELEMS; it++)
+                for (int it = 0; it < E; it++)
                     lds[pc + pad(it * 64)] = ld.finish(raw[it], wg, cb + it * 64, m, C);
             } else {
-                load_row_now<LOGN, true>(ld, wg, tid, m, C, [&](int it, double v) { lds[pc + pad(it * 64)] = v; });
+                load_row_now<LOGN, E, true>(ld, wg, tid, m, C, [&](int it, double v) { lds[pc + pad(it * 64)] = v; });
             }
         }
         const int wg_next = wg + (int)gridDim.x;
         const bool more = wg_next < nwg;
         if constexpr (LD::kPrefetch) {
-            if (more) fetch_row<LOGN, true>(ld, wg_next, tid, C, raw);
+            if (more) fetch_row<LOGN, E, true>(ld, wg_next, tid, C, raw);
         }
         wave_sync();
-        if constexpr (NP > 3) {
-            inv_pass<LOGN, 3>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
-            inv_pass<LOGN, 2>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
-            inv_pass<LOGN, 1>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
-            inv_pass<LOGN, 0>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
+        // passes NP-1 ... 0; the twiddle buffers alternate
+        if constexpr (NP == 5) {
+            inv_pass<LOGN, E, 4>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 3>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, E, 2>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 1>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, E, 0>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+        } else if constexpr (NP == 4) {
+            inv_pass<LOGN, E, 3>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 2>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, E, 1>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 0>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
         } else {
-            inv_pass<LOGN, 2>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
-            inv_pass<LOGN, 1>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
-            inv_pass<LOGN, 0>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 2>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 1>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, E, 0>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
         }
         if (!more) break;
         wg = wg_next;
