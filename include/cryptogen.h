@@ -196,6 +196,20 @@ int cg_decode_context(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const ui
                       const void *rlk_dev,
                       const void *const *gk_block_dev_host, uint64_t *out_dev, void *ws_dev);
 
+/* Decode attention scores against an outer-packed cache segment (one ciphertext per feature
+ * column: kcols[h][j] holds K[tau][j] in flat slot tau), ARCC inner-inner mode (section 4.3 and
+ * its figure on masking and rotating a scalar).  q[h] is the query tiled with period d2.  For
+ * every head h and feature j < d2:
+ *   x_j = q[h] * mask_j           (ct x pt; mask_j = prepared plaintext selecting slots = j mod d2)
+ *   for sh = 1, 2, 4, ..., d2/2:  x_j = x_j + rotate(x_j, 3^sh mod 2N)      -> every slot holds q_j
+ *   y = y + mul(x_j, kcols[h][j])                                 (three components, j ascending)
+ * out[h] = relin(y)  -- flat slot tau decrypts to <q_h, K_tau> mod t.
+ * masks_dev: d2 prepared plaintexts (cg_plain_prepare) in order j = 0..d2-1; gk_fold as in
+ * cg_decode_scores; the workspace must be sized for heads * d2 units. */
+int cg_decode_scores_outer(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *kcols_dev,
+                           uint32_t heads, uint32_t d2, const void *masks_dev, const void *rlk_dev,
+                           const void *const *gk_fold_dev_host, uint64_t *out_dev, void *ws_dev);
+
 /* Prefill Q K^T for `heads` heads as m = N/d2 generalised diagonals per head
  * (the paper's outer-outer CT x CT product is named, not specified; this is the
  * library's documented procedure).  Q and K are token-major row-packed

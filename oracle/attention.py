@@ -17,6 +17,9 @@ slots [b d, (b+1) d)) of a cache ciphertext holds one token's d-vector.
                   sum of slot-wise products over the cache ciphertexts (three
                   components), one relinearisation, then a sum over blocks
                   (rotate by d, 2d, ... N/4, then swap the two slot rows).
+  decode_scores_outer  section 4.3, inner-inner mode: scores against an outer-packed
+                  (column-per-ciphertext) cache segment; each query feature is masked,
+                  broadcast by rotations and multiplied with its column ciphertext.
   prefill_qk      the prompt's Q K^T as m "generalised diagonals" (the paper
                   names an outer-outer product and gives no procedure; this is
                   the reading documented in the design notes).
@@ -86,6 +89,35 @@ def decode_context(orc, a_cts, v_cts, rlk, gks, d: int, counts=None):
         if counts is not None:
             counts["rotate"] = counts.get("rotate", 0) + 1
     return x
+
+
+def residue_mask_values(n: int, d: int, j: int) -> np.ndarray:
+    """1 on the flat slots congruent to j modulo d, else 0."""
+    v = np.zeros(n, dtype=np.int64)
+    v[j::d] = 1
+    return v
+
+
+def decode_scores_outer(orc, q_ct, k_cols, mask_polys, rlk, gks, d: int, counts=None):
+    """Section 4.3, inner-inner mode against an outer-packed cache segment.
+
+    k_cols[j] holds feature j of every cached token (token tau in flat slot tau); q_ct holds the
+    query tiled with period d.  Each feature of the query is isolated by a plaintext mask,
+    broadcast to every slot by the folding rotations, multiplied with its column ciphertext,
+    and the three-component products are summed before one relinearisation."""
+    y = None
+    for j in range(d):
+        x = orc.mul_plain(q_ct, mask_polys[j])
+        for sh in fold_shifts(d):
+            g = galois_rot(orc.n, sh)
+            x = orc.add(x, orc.rotate(x, g, gks[g]))
+            if counts is not None:
+                counts["rotate"] = counts.get("rotate", 0) + 1
+        prod3 = orc.mul(x, k_cols[j])
+        y = prod3 if y is None else orc.add(y, prod3)
+        if counts is not None:
+            counts["mul"] = counts.get("mul", 0) + 1
+    return orc.relin(y, rlk)
 
 
 def prefill_qk(orc, q_ct, k_ct, rlk, gks, d: int):

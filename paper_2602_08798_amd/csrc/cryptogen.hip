@@ -661,7 +661,7 @@ extern "C" int cg_mul_plain(cg_ctx *c, void *stream, const uint64_t *in2, const 
     CG_TRY(launch_fwd(c, s, rows, LdRowsU64{in2, nullptr, c->k, c->logn}, StF64{f, c->logn}, KID_FWD_ROWS,
                       LB * 2.0 * rows));
     return launch_inv(c, s, rows,
-                      LdInvMulPlain{f, static_cast<const double *>(plain), (int)plain_stride, 0, c->logn},
+                      LdInvMulPlain{f, static_cast<const double *>(plain), 1, 1 << 30, (int)plain_stride, 0, c->logn},
                       StInvU64{out2, c->logn}, KID_INV_MULPLAIN,
                       LB * (2.0 * rows + c->k * (plain_stride ? (double)batch : 1.0)));
 }
@@ -680,7 +680,7 @@ extern "C" int cg_kv_append(cg_ctx *c, void *stream, uint64_t *cache, uint32_t c
     const double LB = (double)limb_bytes(c);
     CG_TRY(launch_fwd(c, s, rows, LdRowsU64{rows_dev, nullptr, c->k, c->logn}, StF64{f, c->logn}, KID_FWD_ROWS,
                       LB * 2.0 * rows));
-    return launch_inv(c, s, rows, LdInvMulPlain{f, static_cast<const double *>(masks), 0, (int)blk, c->logn},
+    return launch_inv(c, s, rows, LdInvMulPlain{f, static_cast<const double *>(masks), 1, 1 << 30, 0, (int)blk, c->logn},
                       StInvAppend{cache + (size_t)ct_idx * ct2, (size_t)cache_stride_cts * ct2, blk == 0 ? 1 : 0,
                                   c->logn},
                       KID_INV_MULPLAIN, LB * ((blk == 0 ? 2.0 : 3.0) * rows + c->k));
@@ -758,6 +758,44 @@ extern "C" int cg_decode_context(cg_ctx *c, void *stream, const uint64_t *a, con
                  pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)n_cts, rows, c->dc);
     CG_TRY(do_relin(c, s, y, rlk, xa, heads, w.p));
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, heads, w.p);
+}
+
+extern "C" int cg_decode_scores_outer(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kcols,
+                                      uint32_t heads, uint32_t d2, const void *masks, const void *rlk,
+                                      const void *const *gk_fold, uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({q, kcols, masks, rlk, out, ws}) && gk_fold && heads >= 1 && pow2_d(c, d2));
+    const uint32_t batch = heads * d2;
+    CG_REQUIRE(batch_ok(batch));
+    int nrot = 0;
+    uint32_t gs[16];
+    for (uint32_t sh = 1; sh < d2; sh <<= 1) {
+        CG_REQUIRE(gk_fold[nrot] && aligned16(gk_fold[nrot]));
+        gs[nrot++] = pow3_mod(sh, 2u * c->N);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const double LB = (double)limb_bytes(c);
+    Bump w = bump(c, ws);
+    uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * batch), *xb = w.take<uint64_t>((size_t)2 * c->k * batch);
+    uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
+    uint64_t *y = w.take<uint64_t>((size_t)3 * c->k * heads);
+    // x[h][j] = q[h] * mask_j: one forward transform per query row, the mask product rides on the
+    // inverse transform's load
+    double *f = reinterpret_cast<double *>(d3);   // free until the products are formed
+    const size_t qrows = (size_t)heads * 2 * c->k, xrows = (size_t)batch * 2 * c->k;
+    CG_TRY(launch_fwd(c, s, qrows, LdRowsU64{q, nullptr, c->k, c->logn}, StF64{f, c->logn}, KID_FWD_ROWS,
+                      LB * 2.0 * qrows));
+    CG_TRY(launch_inv(c, s, xrows,
+                      LdInvMulPlain{f, static_cast<const double *>(masks), (int)d2, (int)d2, 1, 0, c->logn},
+                      StInvU64{xa, c->logn}, KID_INV_MULPLAIN, LB * (qrows + (double)d2 * c->k + xrows)));
+    // broadcast q_j to every slot: log2(d2) rotate-and-add steps; the last one lands in xb or xa
+    uint64_t *bc = (nrot & 1) ? xb : xa;
+    if (nrot) CG_TRY(rotate_add_chain(c, s, xa, xb, bc, gs, gk_fold, nrot, batch, w.p));
+    CG_TRY(do_mul(c, s, bc, kcols, d3, batch, 1, w.p, 0));
+    const int rows = 3 * c->k;
+    CG_LAUNCH_PW(KID_SUM_GROUPS, LB * rows * (batch + heads), sum_groups_kernel, pw_blocks(c, (size_t)heads * rows),
+                 d3, y, (int)heads, (int)d2, rows, c->dc);
+    return do_relin(c, s, y, rlk, out, heads, w.p);
 }
 
 extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads,

@@ -760,19 +760,20 @@ struct LdInvKsInner {
 };
 
 // transformed ciphertext row times prepared plaintext row (ct x pt fused into the load):
-// workgroup -> (unit b, comp c, prime i), plaintext = plain[b*pstride + pofs]
+// workgroup -> (unit b, comp c, prime i); ciphertext = ctf[b / ct_group], plaintext =
+// plain[(b % p_mod) * pstride + pofs]
 struct LdInvMulPlain {
     static constexpr int kRaw = 2;
     static constexpr bool kPrefetch = true;
-    const double *ctf;     // forward-transformed ciphertext rows [b][2][k][N]
+    const double *ctf;     // forward-transformed ciphertext rows [*][2][k][N]
     const double *plain;   // prepared plaintexts [*][k][N]
-    int pstride, pofs, logn;
+    int ct_group, p_mod, pstride, pofs, logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
-        const int k = C->k, i = wg % k, b = wg / (2 * k);
-        raw[0] = f64_bits(ctf[((size_t)wg << logn) + idx]);
-        raw[1] = f64_bits(plain[((size_t)((b * pstride + pofs) * k + i) << logn) + idx]);
+        const int k = C->k, i = wg % k, c = (wg / k) & 1, b = wg / (2 * k);
+        raw[0] = f64_bits(ctf[((size_t)(((b / ct_group) * 2 + c) * k + i) << logn) + idx]);
+        raw[1] = f64_bits(plain[((size_t)(((b % p_mod) * pstride + pofs) * k + i) << logn) + idx]);
     }
     __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD m, const DevConst *) const
     {

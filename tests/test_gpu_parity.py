@@ -329,3 +329,24 @@ def test_invalid_arguments_are_rejected_without_launching():
     with pytest.raises(CgError):
         P.Context(bad)
     torch.cuda.synchronize()
+
+
+def test_decode_scores_outer_match_oracle(env):
+    from oracle import attention
+    heads, d2 = 2, 8
+    say(f"decode_scores_outer {env.name} d2={d2}")
+    n, t = env.n, env.prm.t
+    raw_rlk, rlk = env.key(70)
+    gs = _fold_keys(env, d2)
+    keys = {g: env.key(100 + i) for i, g in enumerate(gs)}
+    rng = np.random.default_rng(77)
+    masks_pt = rng.integers(0, t, (d2, n), dtype=np.uint64)      # arbitrary plaintexts stand in for the masks
+    masks = env.ctx.plain_prepare(env.dev(masks_pt))
+    q, cols = env.cts(501, heads), env.cts(502, heads * d2)
+    got = env.host(env.ctx.decode_scores_outer(env.dev(q), env.dev(cols), heads, d2, masks, rlk,
+                                               [keys[g][1] for g in gs]))
+    raws = {g: keys[g][0] for g in gs}
+    for h in range(heads):
+        want = attention.decode_scores_outer(env.orc, q[h], list(cols[h * d2:(h + 1) * d2]), list(masks_pt),
+                                             raw_rlk, raws, d2)
+        assert np.array_equal(got[h], want), (env.name, h)

@@ -112,3 +112,29 @@ def test_galois_elements_needed_by_the_decode_step():
     gs = attention.required_galois(n, d)
     assert len(gs) == 13          # 6 fold shifts + 6 block shifts + row swap
     assert galois_rot(n, 1) == 3 and 2 * n - 1 in gs
+
+
+def test_scores_against_an_outer_packed_segment_are_the_dot_products():
+    """Inner-inner mode on a small ring: column ciphertexts, masked and broadcast query features."""
+    prm = toy_params(8, 3, 1, 1)
+    orc = Oracle(prm)
+    cl = Client(prm, 65, orc)
+    n, d, t = prm.n, 8, prm.t
+    m = 40                                              # cached tokens (any number up to n)
+    g = Stream(65, 1)
+    K = attention_activations(g, 1, m, d)[0]
+    q = attention_activations(g, 1, 1, d)[0, 0]
+    rlk, gks = cl.relin_key(), _keys(cl, n, d)
+    cols = []
+    for j in range(d):
+        v = np.zeros(n, dtype=np.int64)
+        v[:m] = K[:, j]
+        cols.append(cl.encrypt_slots(v))
+    masks = [cl.codec.encode(attention.residue_mask_values(n, d, j)) for j in range(d)]
+    counts = {}
+    out = attention.decode_scores_outer(orc, cl.encrypt_slots(np.tile(q, n // d)), cols, masks, rlk, gks, d, counts)
+    assert counts == {"mul": d, "rotate": d * 3}        # log2(8) rotations per feature
+    dec = cl.decrypt_slots(out)
+    assert np.array_equal(dec[:m], (K @ q) % t)
+    assert not dec[m:].any()
+    assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 10
