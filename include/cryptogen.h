@@ -210,6 +210,18 @@ int cg_decode_scores_outer(cg_ctx *ctx, void *stream, const uint64_t *q_dev, con
                            uint32_t heads, uint32_t d2, const void *masks_dev, const void *rlk_dev,
                            const void *const *gk_fold_dev_host, uint64_t *out_dev, void *ws_dev);
 
+/* Decode attention context against an outer-packed value segment (vcols[h][j] holds V[tau][j] in
+ * flat slot tau), ARCC inner-outer mode (section 4.3): a[h] holds the weight a_tau in flat slot tau.
+ * For every head h and feature j < d2:
+ *   x = relin(mul(a[h], vcols[h][j]));
+ *   for sh = 1, 2, 4, ..., N/4: x = x + rotate(x, 3^sh mod 2N);  x = x + rotate(x, 2N-1);
+ *   out[h][j] = x  -- every slot decrypts to o_j = sum_tau a_tau V[tau][j] mod t.
+ * gk_all_dev_host: prepared keys for g = 3^1, 3^2, 3^4, ..., 3^(N/4), then 2N-1 (log2(N/2) + 1 keys).
+ * d2 may be any positive column count; the workspace must be sized for heads * d2 units. */
+int cg_decode_context_outer(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *vcols_dev,
+                            uint32_t heads, uint32_t d2, const void *rlk_dev,
+                            const void *const *gk_all_dev_host, uint64_t *out_dev, void *ws_dev);
+
 /* Prefill Q K^T for `heads` heads as m = N/d2 generalised diagonals per head
  * (the paper's outer-outer CT x CT product is named, not specified; this is the
  * library's documented procedure).  Q and K are token-major row-packed

@@ -120,6 +120,28 @@ def decode_scores_outer(orc, q_ct, k_cols, mask_polys, rlk, gks, d: int, counts=
     return orc.relin(y, rlk)
 
 
+def all_slot_shifts(n: int):
+    sh = 1
+    while sh <= n // 4:
+        yield sh
+        sh *= 2
+
+
+def decode_context_outer(orc, a_ct, v_cols, rlk, gks):
+    """Section 4.3, inner-outer mode on an outer-packed value segment: one slot-wise product of
+    the weight ciphertext (a_tau in flat slot tau) with each column ciphertext, relinearise,
+    then a folding sum over all slots (rotate by 1, 2, ..., N/4, then swap the rows)."""
+    n = orc.n
+    gs = [galois_rot(n, sh) for sh in all_slot_shifts(n)] + [galois_swap(n)]
+    outs = []
+    for v_ct in v_cols:
+        x = orc.relin(orc.mul(a_ct, v_ct), rlk)
+        for g in gs:
+            x = orc.add(x, orc.rotate(x, g, gks[g]))
+        outs.append(x)
+    return outs
+
+
 def prefill_qk(orc, q_ct, k_ct, rlk, gks, d: int):
     """All m = N/d generalised diagonals of S = Q K^T for one head.
 

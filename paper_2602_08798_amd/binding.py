@@ -17,7 +17,7 @@ _SYMBOLS = [
     "cg_create", "cg_destroy", "cg_get_sizes", "cg_workspace_bytes", "cg_strerror",
     "cg_ntt_forward", "cg_ntt_inverse", "cg_ksk_prepare", "cg_plain_prepare",
     "cg_mul", "cg_relin", "cg_mul_relin", "cg_rotate", "cg_add", "cg_mul_plain",
-    "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_decode_scores_outer", "cg_prefill_qk",
+    "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_decode_scores_outer", "cg_decode_context_outer", "cg_prefill_qk",
     "cg_bench_modmul", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
 ]
 
@@ -72,6 +72,7 @@ class Library:
         d.cg_decode_scores.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_decode_context.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_decode_scores_outer.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, C.POINTER(vp), vp, vp]
+        d.cg_decode_context_outer.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_prefill_qk.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp, vp, vp]
         d.cg_bench_modmul.argtypes = [vp, vp, i32, u32, u32, vp]
         d.cg_profile_begin.argtypes = [vp, u32]
@@ -269,6 +270,13 @@ class Context:
         self._check(self.lib.dll.cg_decode_scores_outer(self.h, self.stream, _ptr(q), _ptr(kcols), heads, d2,
                                                         _ptr(masks), _ptr(rlk), self._keys(gk_fold), _ptr(out),
                                                         _ptr(ws)))
+        return out
+
+    def decode_context_outer(self, a, vcols, heads, d2, rlk, gk_all, out=None):
+        out = self.empty_ct(heads, d2) if out is None else out
+        ws = self.workspace(heads * d2)
+        self._check(self.lib.dll.cg_decode_context_outer(self.h, self.stream, _ptr(a), _ptr(vcols), heads, d2,
+                                                         _ptr(rlk), self._keys(gk_all), _ptr(out), _ptr(ws)))
         return out
 
     def prefill_qk(self, q, k, heads, d2, rlk, gk_fold, gk_blk, gk_swap, out=None):

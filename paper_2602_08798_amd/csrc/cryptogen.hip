@@ -798,6 +798,27 @@ extern "C" int cg_decode_scores_outer(cg_ctx *c, void *stream, const uint64_t *q
     return do_relin(c, s, y, rlk, out, heads, w.p);
 }
 
+extern "C" int cg_decode_context_outer(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vcols,
+                                       uint32_t heads, uint32_t d2, const void *rlk, const void *const *gk_all,
+                                       uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({a, vcols, rlk, out, ws}) && gk_all && heads >= 1 && d2 >= 1);
+    const uint32_t batch = heads * d2;
+    CG_REQUIRE(batch_ok(batch));
+    int nrot = 0;
+    uint32_t gs[20];
+    for (uint32_t sh = 1; sh <= (uint32_t)c->N / 4; sh <<= 1) gs[nrot++] = pow3_mod(sh, 2u * c->N);
+    gs[nrot++] = 2u * c->N - 1;
+    for (int i = 0; i < nrot; i++) CG_REQUIRE(gk_all[i] && aligned16(gk_all[i]));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Bump w = bump(c, ws);
+    uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
+    uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * batch), *xb = w.take<uint64_t>((size_t)2 * c->k * batch);
+    CG_TRY(do_mul(c, s, a, vcols, d3, batch, d2, w.p, 0));
+    CG_TRY(do_relin(c, s, d3, rlk, xa, batch, w.p));
+    return rotate_add_chain(c, s, xa, xb, out, gs, gk_all, nrot, batch, w.p);
+}
+
 extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads,
                              uint32_t d2, const void *rlk, const void *const *gk_fold, const void *gk_blk,
                              const void *gk_swap, uint64_t *out, void *ws)

@@ -350,3 +350,25 @@ def test_decode_scores_outer_match_oracle(env):
         want = attention.decode_scores_outer(env.orc, q[h], list(cols[h * d2:(h + 1) * d2]), list(masks_pt),
                                              raw_rlk, raws, d2)
         assert np.array_equal(got[h], want), (env.name, h)
+
+
+def test_decode_context_outer_match_oracle(env):
+    from oracle import attention
+    heads, d2 = 2, 3
+    say(f"decode_context_outer {env.name} columns={d2}")
+    n = env.n
+    raw_rlk, rlk = env.key(70)
+    gs, sh = [], 1
+    while sh <= n // 4:
+        gs.append(pow(3, sh, 2 * n))
+        sh *= 2
+    gs.append(2 * n - 1)
+    keys = {g: env.key(600 + i) for i, g in enumerate(gs)}
+    a, cols = env.cts(601, heads), env.cts(602, heads * d2)
+    got = env.host(env.ctx.decode_context_outer(env.dev(a), env.dev(cols), heads, d2, rlk,
+                                                [keys[g][1] for g in gs]))
+    raws = {g: keys[g][0] for g in gs}
+    for h in range(heads):
+        want = attention.decode_context_outer(env.orc, a[h], list(cols[h * d2:(h + 1) * d2]), raw_rlk, raws)
+        for j in range(d2):
+            assert np.array_equal(got[h, j], want[j]), (env.name, h, j)

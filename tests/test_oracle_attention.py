@@ -138,3 +138,28 @@ def test_scores_against_an_outer_packed_segment_are_the_dot_products():
     assert np.array_equal(dec[:m], (K @ q) % t)
     assert not dec[m:].any()
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 10
+
+
+def test_context_against_an_outer_packed_segment_is_the_weighted_sum():
+    prm = toy_params(8, 3, 1, 1)
+    orc = Oracle(prm)
+    cl = Client(prm, 66, orc)
+    n, d, t = prm.n, 4, prm.t
+    m = 50
+    g = Stream(66, 1)
+    V = attention_activations(g, 1, m, d)[0]
+    a = attention_activations(g, 1, m, 1)[0, :, 0]
+    rlk = cl.relin_key()
+    gals = [galois_rot(n, sh) for sh in attention.all_slot_shifts(n)] + [2 * n - 1]
+    gks = {g_: cl.galois_key(g_) for g_ in gals}
+    cols = []
+    for j in range(d):
+        v = np.zeros(n, dtype=np.int64)
+        v[:m] = V[:, j]
+        cols.append(cl.encrypt_slots(v))
+    av = np.zeros(n, dtype=np.int64)
+    av[:m] = a
+    outs = attention.decode_context_outer(orc, cl.encrypt_slots(av), cols, rlk, gks)
+    want = (a @ V) % t
+    for j in range(d):
+        assert np.array_equal(cl.decrypt_slots(outs[j]), np.full(n, want[j]))
