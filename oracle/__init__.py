@@ -10,9 +10,12 @@ import this package.  It shares nothing with the HIP library.  Contents:
                     decryption (the party that holds the secret key).
   attention         the cache append and the decode / prefill attention
                     products as plain sequences of evaluator operations.
+  run_configs       the five benchmark configurations end to end (used to write the
+                    digests under tests/golden/ and by the CPU baseline).
 """
 from .bfv import Oracle, load_library
 from .client import Client
 from . import attention
+from . import run_configs
 
-__all__ = ["Oracle", "Client", "attention", "load_library"]
+__all__ = ["Oracle", "Client", "attention", "run_configs", "load_library"]

@@ -1,0 +1,91 @@
+"""The five benchmark configurations evaluated by the oracle (test infrastructure only).
+
+Each function takes the seeded inputs of workloads.configs and returns {name: ciphertext array}
+for every output unit, in the order and with the operation sequence the library documents."""
+import numpy as np
+
+from . import attention
+
+
+def run_c1(orc, inp):
+    return {f"pair{u}": orc.relin(orc.mul(inp["a"][u], inp["b"][u]), inp["rlk"]) for u in range(len(inp["a"]))}
+
+
+def _decode_step(orc, st, q, a, cache, rows, tau, n_cts, out, tag=""):
+    """Append at token tau, then scores and context over n_cts cache ciphertexts per head.
+    `cache` is modified in place (numpy array [2*heads*stride] of ciphertexts)."""
+    H, S, B, d2 = st["heads"], st["stride"], st["B"], st["d2"]
+    idx, blk = divmod(tau, B)
+    for c in range(2 * H):
+        masked = orc.mul_plain(rows[c], st["masks"][blk])
+        tgt = c * S + idx
+        cache[tgt] = masked if blk == 0 else orc.add(cache[tgt], masked)
+        out[f"{tag}cache{c}"] = cache[tgt].copy()
+    fold = {g: st["gk"][g] for g in st["fold"]}
+    block = {g: st["gk"][g] for g in st["block"]}
+    for h in range(H):
+        for c in range(n_cts):
+            out[f"{tag}score{h}_{c}"] = attention.decode_scores(orc, q[h], cache[h * S + c], st["rlk"], fold, d2)
+        v0 = (H + h) * S
+        out[f"{tag}context{h}"] = attention.decode_context(orc, list(a[h * n_cts:(h + 1) * n_cts]),
+                                                          list(cache[v0:v0 + n_cts]), st["rlk"], block, d2)
+
+
+def run_c2(orc, st):
+    """Decode scores of one head against its one cache ciphertext."""
+    fold = {g: st["gk"][g] for g in st["fold"]}
+    return {"score0_0": attention.decode_scores(orc, st["q"][0], st["cache"][0], st["rlk"], fold, st["d2"])}
+
+
+def run_c4(orc, st):
+    """Scores and context over the 512 cached tokens, then the append of token 512 (which opens the
+    fifth ciphertext of every cache and therefore does not feed this step's products)."""
+    out = {}
+    cache = st["cache"].copy()
+    H, S, C, d2 = st["heads"], st["stride"], st["n_cts"], st["d2"]
+    fold = {g: st["gk"][g] for g in st["fold"]}
+    block = {g: st["gk"][g] for g in st["block"]}
+    for h in range(H):
+        for c in range(C):
+            out[f"score{h}_{c}"] = attention.decode_scores(orc, st["q"][h], cache[h * S + c], st["rlk"], fold, d2)
+        v0 = (H + h) * S
+        out[f"context{h}"] = attention.decode_context(orc, list(st["a"][h * C:(h + 1) * C]),
+                                                      list(cache[v0:v0 + C]), st["rlk"], block, d2)
+    idx, blk = divmod(st["tau"], st["B"])
+    for c in range(2 * H):
+        masked = orc.mul_plain(st["rows"][c], st["masks"][blk])
+        out[f"cache{c}"] = masked if blk == 0 else orc.add(cache[c * S + idx], masked)
+    return out
+
+
+def run_c3(orc, st, heads=None, progress=None):
+    """Build every K and V cache ciphertext from its 128 row ciphertexts, then Q K^T per head."""
+    H, m, d2 = st["heads"], st["m"], st["d2"]
+    heads = range(H) if heads is None else heads
+    out = {}
+    caches = {}
+    for c in [h for h in heads] + [H + h for h in heads]:
+        acc = None
+        for tau in range(m):
+            masked = orc.mul_plain(st["rows"][tau][c], st["masks"][tau])
+            acc = masked if acc is None else orc.add(acc, masked)
+        caches[c] = acc
+        out[f"cache{c}"] = acc
+    for h in heads:
+        diag = attention.prefill_qk(orc, st["q"][h], caches[h], st["rlk"], st["gk"], d2)
+        for i, x in enumerate(diag):
+            out[f"qk{h}_{i}"] = x
+        if progress:
+            progress(f"C3 head {h} done")
+    return out
+
+
+def run_c5(orc, st, steps):
+    """`steps` successive decode steps with cache growth (append first, then attend over the cache
+    including the new token's ciphertext)."""
+    out = {}
+    cache = st["cache"].copy()
+    for i in range(steps):
+        si = st["step_inputs"](i)
+        _decode_step(orc, st, si["q"], si["a"], cache, si["rows"], 512 + i, si["n_cts"], out, tag=f"s{i}_")
+    return out

@@ -1,0 +1,58 @@
+"""Writes tests/golden/digests_<config>.json: SHA-256 of every output ciphertext of the five
+benchmark configurations as computed by the CPU oracle (and by nothing else).
+
+    python -m tests.golden.make_digests C1 C2 C4        (about a minute)
+    python -m tests.golden.make_digests C3              (all 12 heads: tens of minutes)
+    python -m tests.golden.make_digests C5              (first 4 of the 64 steps: several minutes)
+
+The GPU tests recompute the same units with the HIP library from the same seeded inputs
+(workloads.configs) and compare digests, i.e. every residue of every output, bit for bit.
+"""
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+from oracle import Oracle, run_configs
+from workloads import configs
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+C5_STEPS = 4
+
+
+def digest(arr) -> str:
+    return hashlib.sha256(np.ascontiguousarray(arr, dtype="<u8").tobytes()).hexdigest()
+
+
+def main(names):
+    for name in names:
+        t0 = time.time()
+        if name == "C1":
+            inp = configs.c1_inputs(); out = run_configs.run_c1(Oracle(inp["prm"]), inp); note = "16 mult+relin pairs"
+        elif name == "C2":
+            inp = configs.c2_inputs(); out = run_configs.run_c2(Oracle(inp["prm"]), inp); note = "decode scores, 1 head x 1 ciphertext"
+        elif name == "C4":
+            inp = configs.c4_inputs(); out = run_configs.run_c4(Oracle(inp["prm"]), inp); note = "full decode step, 12 heads, 512-token cache"
+        elif name == "C3":
+            inp = configs.c3_inputs()
+            out = run_configs.run_c3(Oracle(inp["prm"]), inp, progress=lambda m: print(m, f"{time.time() - t0:.0f}s", flush=True))
+            note = "prefill: 3072 appends, then 12 x 128 generalised diagonals of Q K^T"
+        elif name == "C5":
+            inp = configs.c5_inputs(); out = run_configs.run_c5(Oracle(inp["prm"]), inp, C5_STEPS)
+            note = f"first {C5_STEPS} of 64 decode steps with cache growth, 16 heads, N = 16384"
+        else:
+            raise SystemExit(f"unknown configuration {name}")
+        doc = {"config": name, "what": note, "source": "oracle/ only (tests/golden/make_digests.py)",
+               "hash": "sha256 of the little-endian uint64 residues of each output ciphertext",
+               "digests": {k: digest(v) for k, v in out.items()}}
+        path = os.path.join(HERE, f"digests_{name}.json")
+        with open(path, "w") as f:
+            json.dump(doc, f, indent=0, sort_keys=True)
+        print(f"{name}: {len(out)} outputs, {time.time() - t0:.1f} s -> {path}", flush=True)
+
+
+if __name__ == "__main__":
+    main(sys.argv[1:] or ["C1", "C2", "C4"])

@@ -13,7 +13,9 @@ from .synth import (Stream, ternary_secret, gaussian_error, uniform_residues,
                     slot_values, attention_activations, pseudo_ciphertexts,
                     pseudo_switch_key, WORKLOADS, Workload)
 
-__all__ = ["ParamSet", "PRESETS", "get_params", "Stream", "ternary_secret",
+from . import configs
+
+__all__ = ["configs", "ParamSet", "PRESETS", "get_params", "Stream", "ternary_secret",
            "gaussian_error", "uniform_residues", "slot_values",
            "attention_activations", "pseudo_ciphertexts", "pseudo_switch_key",
            "WORKLOADS", "Workload"]
