@@ -59,6 +59,14 @@ class DecodeStep:
         torch.cuda.synchronize()
 
     def step(self):
+        """One call: the three branches run side by side on the library's streams."""
+        self.ctx.decode_step(self.q, self.a, self.cache, self.heads, self.n_cts, self.stride, self.d2, self.tau,
+                             self.rows, self.masks, self.rlk, [self.gk[g] for g in self.g_fold],
+                             [self.gk[g] for g in self.g_block], scores=self.scores, context=self.context)
+
+    def step_serial(self):
+        """The same work as three calls in sequence (used for per-kernel timing: a kernel's
+        duration only describes the kernel when it has the device to itself)."""
         c, H, C = self.ctx, self.heads, self.n_cts
         c.decode_scores(self.q, self.kcache, H, C, self.d2, self.rlk, [self.gk[g] for g in self.g_fold],
                         out=self.scores, cache_stride_cts=self.stride)
@@ -131,6 +139,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial", action="store_true",
+                    help="time the three calls in sequence instead of the one-call step (profiling runs)")
     ap.add_argument("--no-secondary", action="store_true",
                     help="skip the mult+relin/sec loops (used when profiling the step alone)")
     args = ap.parse_args()
@@ -144,14 +154,17 @@ def main():
         sys.exit(1)
 
     ws = DecodeStep()
+    step = ws.step_serial if args.serial else ws.step
     for _ in range(args.warmup):
-        ws.step()
-    ms = timed(torch, ws.step, args.steps)
+        step()
+    ms = timed(torch, step, args.steps)
+    ms_serial = ms if args.serial else timed(torch, ws.step_serial, args.steps)
 
-    # second, identical pass with the library's event bracketing for per-kernel figures
+    # second pass over the same work, one call after the other, with the library's event
+    # bracketing for per-kernel figures
     ws.ctx.profile_begin(200 * args.steps)
     for _ in range(args.steps):
-        ws.step()
+        ws.step_serial()
     stats = ws.ctx.profile_end()
     kernels = []
     for s in stats:
@@ -205,7 +218,10 @@ def main():
         "data": "synthetic",
         "config": {"workload": "C4: decode step, 12 heads x d=64, 512-token encrypted KV cache, N=8192, "
                                "3+1 primes < 2^50, t=65537", "ops_per_step": ws.op_counts(),
-                   "derived_12_layers_ms_per_token": round(12 * ms, 3)},
+                   "derived_12_layers_ms_per_token": round(12 * ms, 3),
+                   "launch": "three calls in sequence" if args.serial else
+                             "cg_decode_step: scores, context and append side by side on three streams",
+                   "ms_per_step_three_calls_in_sequence": round(ms_serial, 4)},
         "secondary": secondary,
         "roofline": roofline,
         "kernels": kernels,

@@ -196,6 +196,26 @@ int cg_decode_context(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const ui
                       const void *rlk_dev,
                       const void *const *gk_block_dev_host, uint64_t *out_dev, void *ws_dev);
 
+/* One decode step of one layer over the encrypted cache (Algorithm 1 steps 2-3 followed by the
+ * two products of section 4.3): equivalent to
+ *   cg_kv_append(cache, cache_stride_cts, 2*heads, tau, rows, masks, d2);
+ *   cg_decode_scores (q, K caches, heads, n_cts, ...) -> scores_dev  [heads][n_cts];
+ *   cg_decode_context(a, V caches, heads, n_cts, ...) -> context_dev [heads];
+ * with cache_dev holding the heads K caches followed by the heads V caches (each
+ * cache_stride_cts ciphertexts) and rows_dev the new K rows followed by the new V rows.
+ * The appended ciphertext is visible to the products when tau / (N/d2) < n_cts.
+ * Independent branches run side by side on two internal streams (default priority) that
+ * fork from and join back into `stream`, so the call is ordered on `stream` like any other;
+ * results are bit-identical to the three calls in sequence.  A context runs one such call
+ * at a time.  ws_dev: cg_decode_step_workspace_bytes(ctx, heads, n_cts) bytes. */
+size_t cg_decode_step_workspace_bytes(const cg_ctx *ctx, uint32_t heads, uint32_t n_cts);
+int cg_decode_step(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *a_dev,
+                   uint64_t *cache_dev, uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts,
+                   uint32_t d2, uint32_t tau, const uint64_t *rows_dev, const void *masks_dev,
+                   const void *rlk_dev, const void *const *gk_fold_dev_host,
+                   const void *const *gk_block_dev_host, uint64_t *scores_dev, uint64_t *context_dev,
+                   void *ws_dev);
+
 /* Decode attention scores against an outer-packed cache segment (one ciphertext per feature
  * column: kcols[h][j] holds K[tau][j] in flat slot tau), ARCC inner-inner mode (section 4.3 and
  * its figure on masking and rotating a scalar).  q[h] is the query tiled with period d2.  For

@@ -18,6 +18,7 @@ _SYMBOLS = [
     "cg_ntt_forward", "cg_ntt_inverse", "cg_ksk_prepare", "cg_plain_prepare",
     "cg_mul", "cg_relin", "cg_mul_relin", "cg_rotate", "cg_add", "cg_mul_plain",
     "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_decode_scores_outer", "cg_decode_context_outer", "cg_prefill_qk",
+    "cg_decode_step", "cg_decode_step_workspace_bytes",
     "cg_bench_modmul", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
 ]
 
@@ -74,13 +75,17 @@ class Library:
         d.cg_decode_scores_outer.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, C.POINTER(vp), vp, vp]
         d.cg_decode_context_outer.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_prefill_qk.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp, vp, vp]
+        d.cg_decode_step.argtypes = [vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp, vp, C.POINTER(vp),
+                                     C.POINTER(vp), vp, vp, vp]
+        d.cg_decode_step_workspace_bytes.argtypes = [vp, u32, u32]
+        d.cg_decode_step_workspace_bytes.restype = C.c_size_t
         d.cg_bench_modmul.argtypes = [vp, vp, i32, u32, u32, vp]
         d.cg_profile_begin.argtypes = [vp, u32]
         d.cg_profile_end.argtypes = [vp, C.POINTER(_KernelStat), u32, C.POINTER(u32)]
         d.cg_kernel_name.argtypes = [u32]
         d.cg_kernel_name.restype = C.c_char_p
         for name in _SYMBOLS:
-            if name not in ("cg_workspace_bytes", "cg_strerror", "cg_kernel_name"):
+            if name not in ("cg_workspace_bytes", "cg_decode_step_workspace_bytes", "cg_strerror", "cg_kernel_name"):
                 getattr(d, name).restype = i32
 
     def strerror(self, status: int) -> str:
@@ -143,6 +148,7 @@ class Context:
         self._check(self.lib.dll.cg_get_sizes(self.h, C.byref(s)))
         self.sizes = s
         self._ws = None
+        self._ws_step = None
 
     def close(self):
         if getattr(self, "h", None):
@@ -263,6 +269,22 @@ class Context:
         self._check(self.lib.dll.cg_decode_context(self.h, self.stream, _ptr(a), _ptr(vcache), heads, n_cts,
                                                    stride, d2, _ptr(rlk), self._keys(gk_block), _ptr(out), _ptr(ws)))
         return out
+
+    def decode_step(self, q, a, cache, heads, n_cts, cache_stride_cts, d2, tau, rows, masks, rlk, gk_fold,
+                    gk_block, scores=None, context=None):
+        scores = self.empty_ct(heads, n_cts) if scores is None else scores
+        context = self.empty_ct(heads) if context is None else context
+        need = int(self.lib.dll.cg_decode_step_workspace_bytes(self.h, heads, n_cts))
+        if need == 0:
+            raise CgError("cryptogen: invalid decode-step shape")
+        if self._ws_step is None or self._ws_step.numel() < need:
+            self._ws_step = None
+            self._ws_step = torch.empty(need, dtype=torch.uint8, device=self.device)
+        self._check(self.lib.dll.cg_decode_step(
+            self.h, self.stream, _ptr(q), _ptr(a), _ptr(cache), heads, n_cts, cache_stride_cts, d2, tau,
+            _ptr(rows), _ptr(masks), _ptr(rlk), self._keys(gk_fold), self._keys(gk_block), _ptr(scores),
+            _ptr(context), _ptr(self._ws_step)))
+        return scores, context
 
     def decode_scores_outer(self, q, kcols, heads, d2, masks, rlk, gk_fold, out=None):
         out = self.empty_ct(heads) if out is None else out

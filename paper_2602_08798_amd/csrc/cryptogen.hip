@@ -89,9 +89,13 @@ struct cg_ctx {
     uint32_t *tab;        // scratch prime-index table for the public transform entry points
     uint32_t tab_cap;
     int device, n_cu;
-    int elems;            // elements per thread in the transform kernels (8 or 16)
+    int elems, elems_fwd; // elements per thread in the inverse / forward transform kernels (8 or 16)
     // workspace limbs (N * 8 bytes) per unit
     int ws_total;
+    // two side streams (default priority) and fork/join events for entry points that run
+    // independent branches side by side
+    hipStream_t side[2];
+    hipEvent_t ev_fork, ev_join[2];
     // optional per-launch timing with HIP events (benchmark support)
     bool prof_on;
     uint32_t prof_n, prof_cap;
@@ -197,7 +201,8 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
     c->logn = (int)prm->log2n; c->N = (int)N; c->k = (int)prm->k; c->nsp = (int)prm->nsp;
     c->alpha = (int)prm->alpha; c->dnum = c->k / c->alpha; c->t = prm->t;
     c->l = c->k + 1;
-    c->elems = c->logn <= 13 ? 8 : 16;   // 1024 threads per row at N >= 8192, 512 at N = 4096
+    c->elems = c->logn <= 13 ? 8 : 16;              // 1024 threads per row at N >= 8192, 512 at N = 4096
+    c->elems_fwd = c->logn == 13 ? 16 : c->elems;   // two 512-thread workgroups per compute unit at N = 8192
     c->L = c->k + c->nsp;
     c->KL = c->k + c->l;
     int np = 0;
@@ -298,6 +303,14 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
         cg_destroy(c);
         return CG_EHIP;
     }
+    bool ok = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 2 && ok; i++)
+        ok = hipStreamCreateWithFlags(&c->side[i], hipStreamNonBlocking) == hipSuccess &&
+             hipEventCreateWithFlags(&c->ev_join[i], hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+        cg_destroy(c);
+        return CG_EHIP;
+    }
     *out = c;
     return CG_OK;
 }
@@ -306,6 +319,11 @@ extern "C" int cg_destroy(cg_ctx *c)
 {
     if (!c) return CG_OK;
     (void)hipDeviceSynchronize();
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    for (int i = 0; i < 2; i++) {
+        if (c->ev_join[i]) (void)hipEventDestroy(c->ev_join[i]);
+        if (c->side[i]) (void)hipStreamDestroy(c->side[i]);
+    }
     if (c->dc) (void)hipFree(c->dc);
     if (c->tw) (void)hipFree(c->tw);
     if (c->itw) (void)hipFree(c->itw);
@@ -358,13 +376,13 @@ static Bump bump(const cg_ctx *c, void *ws) { return Bump{static_cast<char *>(ws
 // Transform kernels are persistent: the grid is at most the number of workgroups that are
 // resident at once (what the runtime reports for this instantiation's registers and LDS), so
 // that every workgroup starts immediately and walks over its rows with the next row prefetched.
-template <class K>
-static unsigned ntt_grid(const cg_ctx *c, size_t nwg, K kernel, int threads)
+template <auto KERNEL>
+static unsigned ntt_grid(const cg_ctx *c, size_t nwg, int threads)
 {
-    static int per_cu = 0;   // one value per kernel instantiation
+    static int per_cu = 0;   // one value per kernel instantiation (the kernel is a template argument)
     if (per_cu == 0) {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, 0) != hipSuccess || n < 1) n = 1;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, KERNEL, threads, 0) != hipSuccess || n < 1) n = 1;
         per_cu = n;
     }
     const size_t resident = (size_t)per_cu * (size_t)c->n_cu;
@@ -378,16 +396,17 @@ static int launch_fwd(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int ki
 {
     if (nwg == 0) return CG_OK;
     ProfScope ps(c, s, kid, bytes);
-    const int e = ntt_elems(c);
+    const int e = c->elems_fwd;
     const int threads = c->N / e;
 #define CG_FWD(LG, EL)                                                                                      \
     hipLaunchKernelGGL((ntt_fwd_kernel<LG, EL, LD, ST>),                                                    \
-                       dim3(ntt_grid(c, nwg, ntt_fwd_kernel<LG, EL, LD, ST>, threads)), dim3(threads), 0, s, \
+                       dim3(ntt_grid<ntt_fwd_kernel<LG, EL, LD, ST>>(c, nwg, threads)), dim3(threads), 0, s, \
                        ld, st, c->tw, c->dc, (int)nwg)
     switch (c->logn * 100 + e) {
     case 1416: CG_FWD(14, 16); break;
     case 1208: CG_FWD(12, 8); break;
     case 1308: CG_FWD(13, 8); break;
+    case 1316: CG_FWD(13, 16); break;
     default: return CG_EINVAL;
     }
 #undef CG_FWD
@@ -402,12 +421,13 @@ static int launch_inv(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int ki
     const int threads = c->N / e;
 #define CG_INV(LG, EL)                                                                                      \
     hipLaunchKernelGGL((ntt_inv_kernel<LG, EL, LD, ST>),                                                    \
-                       dim3(ntt_grid(c, nwg, ntt_inv_kernel<LG, EL, LD, ST>, threads)), dim3(threads), 0, s, \
+                       dim3(ntt_grid<ntt_inv_kernel<LG, EL, LD, ST>>(c, nwg, threads)), dim3(threads), 0, s, \
                        ld, st, c->itw, c->dc, (int)nwg)
     switch (c->logn * 100 + e) {
     case 1416: CG_INV(14, 16); break;
     case 1208: CG_INV(12, 8); break;
     case 1308: CG_INV(13, 8); break;
+    case 1316: CG_INV(13, 16); break;
     default: return CG_EINVAL;
     }
 #undef CG_INV
@@ -758,6 +778,51 @@ extern "C" int cg_decode_context(cg_ctx *c, void *stream, const uint64_t *a, con
                  pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)n_cts, rows, c->dc);
     CG_TRY(do_relin(c, s, y, rlk, xa, heads, w.p));
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, heads, w.p);
+}
+
+extern "C" size_t cg_decode_step_workspace_bytes(const cg_ctx *c, uint32_t heads, uint32_t n_cts)
+{
+    if (!c || !heads || !n_cts || (uint64_t)heads * n_cts > (1u << 16)) return 0;
+    return 2 * cg_workspace_bytes(c, heads * n_cts) + cg_workspace_bytes(c, 2 * heads);
+}
+
+extern "C" int cg_decode_step(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *a, uint64_t *cache,
+                              uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, uint32_t tau,
+                              const uint64_t *rows, const void *masks, const void *rlk, const void *const *gk_fold,
+                              const void *const *gk_block, uint64_t *scores, uint64_t *context, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({q, a, cache, rows, masks, rlk, scores, context, ws}) && gk_fold && gk_block);
+    CG_REQUIRE(heads >= 1 && n_cts >= 1 && batch_ok(heads * n_cts) && pow2_d(c, d2) && cache_stride_cts >= n_cts);
+    CG_REQUIRE(tau / ((uint32_t)c->N / d2) < cache_stride_cts);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    uint64_t *vcache = cache + (size_t)heads * cache_stride_cts * ct2;
+    char *ws_scores = static_cast<char *>(ws);
+    char *ws_context = ws_scores + cg_workspace_bytes(c, heads * n_cts);
+    char *ws_append = ws_context + cg_workspace_bytes(c, heads * n_cts);
+    // The appended ciphertext is read by this step's products only when it lies inside the first
+    // n_cts: then the append goes first on the caller's stream; otherwise it is a third branch.
+    const bool append_first = tau / ((uint32_t)c->N / d2) < n_cts;
+    if (append_first)
+        CG_TRY(cg_kv_append(c, s, cache, cache_stride_cts, 2 * heads, tau, rows, masks, d2, ws_append));
+    CG_HIP(hipEventRecord(c->ev_fork, s));
+    CG_HIP(hipStreamWaitEvent(c->side[0], c->ev_fork, 0));
+    if (!append_first) CG_HIP(hipStreamWaitEvent(c->side[1], c->ev_fork, 0));
+    // Branches are always joined, also after a failed launch, so that the caller's stream never
+    // runs ahead of work this call started.
+    int rc = cg_decode_scores(c, s, q, cache, heads, n_cts, cache_stride_cts, d2, rlk, gk_fold, scores, ws_scores);
+    const int rc1 = cg_decode_context(c, c->side[0], a, vcache, heads, n_cts, cache_stride_cts, d2, rlk, gk_block,
+                                      context, ws_context);
+    if (rc == CG_OK) rc = rc1;
+    if (!append_first) {
+        const int rc2 = cg_kv_append(c, c->side[1], cache, cache_stride_cts, 2 * heads, tau, rows, masks, d2, ws_append);
+        if (rc == CG_OK) rc = rc2;
+    }
+    for (int i = 0; i < (append_first ? 1 : 2); i++) {
+        CG_HIP(hipEventRecord(c->ev_join[i], c->side[i]));
+        CG_HIP(hipStreamWaitEvent(s, c->ev_join[i], 0));
+    }
+    return rc;
 }
 
 extern "C" int cg_decode_scores_outer(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kcols,

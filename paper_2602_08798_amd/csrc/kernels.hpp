@@ -13,13 +13,21 @@ namespace cg {
 // elements owned by different waves (workgroup barrier); after them every wave
 // owns one contiguous chunk of 64 * E elements and all remaining stages stay
 // inside it, so those passes only need wave-level ordering.
-//   E = 8 (N <= 8192) puts 16 waves on a row of 8192 and measured a few per cent faster than
-//   E = 16 on the decode step; E = 16 is the only choice at N = 16384 (1024 threads).
+//   N = 8192: forward kernels run E = 16 (512 threads, registers capped at 128 so that two
+//   workgroups share a compute unit and cover each other's loads; no register prefetch), which
+//   measured 5-10 % faster than E = 8; the inverse kernels keep E = 8 (their fused loaders spill
+//   at 128 registers).  E = 16 is the only choice at N = 16384 (1024 threads).
 // ---------------------------------------------------------------------------
 template <int LOGN, int E> struct Plan;
 template <> struct Plan<14, 16> { static constexpr int NP = 4, NC = 1; static constexpr int R[5] = {4, 4, 3, 3, 0}; };
 template <> struct Plan<12, 8> { static constexpr int NP = 4, NC = 1; static constexpr int R[5] = {3, 3, 3, 3, 0}; };
 template <> struct Plan<13, 8> { static constexpr int NP = 5, NC = 2; static constexpr int R[5] = {3, 3, 3, 3, 1}; };
+template <> struct Plan<13, 16> { static constexpr int NP = 4, NC = 1; static constexpr int R[5] = {4, 3, 3, 3, 0}; };
+// waves per SIMD the register allocation must leave room for: the workgroup's own, or, for rows of
+// 8192 on 512 threads, twice that, so that two workgroups share a compute unit (2 x 72 KiB of LDS)
+// with two workgroups on a compute unit each covers the other's load latency: no register prefetch
+template <int LOGN, int E> constexpr bool prefetch_rows() { return !(LOGN == 13 && E == 16); }
+template <int LOGN, int E> constexpr int min_waves() { return (LOGN == 13 && E == 16) ? 4 : ((1 << LOGN) / E) / 256; }
 
 constexpr int ilog2c(int x) { return x <= 1 ? 0 : 1 + ilog2c(x / 2); }
 template <int E> constexpr int chunk_log() { return 6 + ilog2c(E); }
@@ -249,16 +257,17 @@ __device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST
 }
 
 template <int LOGN, int E, class LD, class ST>
-__global__ void __launch_bounds__((1 << LOGN) / E)
+__global__ void __launch_bounds__((1 << LOGN) / E, (min_waves<LOGN, E>()))
 ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *__restrict__ C, int nwg)
 {
     __shared__ double lds[lds_doubles<LOGN>()];
+    constexpr bool PF = LD::kPrefetch && prefetch_rows<LOGN, E>();
     constexpr int T = (1 << LOGN) / E;
     constexpr int NP = Plan<LOGN, E>::NP;
     const int tid = threadIdx.x;
     int wg = blockIdx.x;
-    uint64_t raw[LD::kPrefetch ? E : 1][LD::kRaw];
-    if constexpr (LD::kPrefetch) fetch_row<LOGN, E, false>(ld, wg, tid, C, raw);
+    uint64_t raw[PF ? E : 1][LD::kRaw];
+    if constexpr (PF) fetch_row<LOGN, E, false>(ld, wg, tid, C, raw);
     for (;;) {
         const int pr = ld.prime(wg, C);
         const ModD m = C->mod[pr];
@@ -269,7 +278,7 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
         double in[E];
         const int wg_next = wg + (int)gridDim.x;
         const bool more = wg_next < nwg;
-        if constexpr (LD::kPrefetch) {
+        if constexpr (PF) {
 #pragma unroll
             for (int it = 0; it < E; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
             if (more) fetch_row<LOGN, E, false>(ld, wg_next, tid, C, raw);
@@ -371,16 +380,17 @@ __device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int 
 }
 
 template <int LOGN, int E, class LD, class ST>
-__global__ void __launch_bounds__((1 << LOGN) / E)
+__global__ void __launch_bounds__((1 << LOGN) / E, (min_waves<LOGN, E>()))
 ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst *__restrict__ C, int nwg)
 {
     __shared__ double lds[lds_doubles<LOGN>()];
+    constexpr bool PF = LD::kPrefetch && prefetch_rows<LOGN, E>();
     constexpr int NP = Plan<LOGN, E>::NP;
     static_assert(NP - 1 >= Plan<LOGN, E>::NC, "the first inverse pass must be wave-local");
     const int tid = threadIdx.x;
     int wg = blockIdx.x;
-    uint64_t raw[LD::kPrefetch ? E : 1][LD::kRaw];
-    if constexpr (LD::kPrefetch) fetch_row<LOGN, E, true>(ld, wg, tid, C, raw);
+    uint64_t raw[PF ? E : 1][LD::kRaw];
+    if constexpr (PF) fetch_row<LOGN, E, true>(ld, wg, tid, C, raw);
     for (;;) {
         const int pr = ld.prime(wg, C);
         const ModD m = C->mod[pr];
@@ -392,7 +402,7 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
             // re-reads it from LDS in the stride-1 pattern of the first pass
             const int cb = ((tid >> 6) << chunk_log<E>()) + (tid & 63);
             const int pc = pad(cb);
-            if constexpr (LD::kPrefetch) {
+            if constexpr (PF) {
 #pragma unroll
                 for (int it = 0; it < E; it++)
                     lds[pc + pad(it * 64)] = ld.finish(raw[it], wg, cb + it * 64, m, C);
@@ -402,7 +412,7 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
         }
         const int wg_next = wg + (int)gridDim.x;
         const bool more = wg_next < nwg;
-        if constexpr (LD::kPrefetch) {
+        if constexpr (PF) {
             if (more) fetch_row<LOGN, E, true>(ld, wg_next, tid, C, raw);
         }
         wave_sync();
