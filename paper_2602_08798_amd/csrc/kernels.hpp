@@ -136,6 +136,23 @@ __device__ __forceinline__ void load_tw(const double *__restrict__ tw, int tid, 
 }
 
 // ---------------------------------------------------------------------------
+// Workgroups are handed to the 8 XCDs round-robin (physical index p runs on XCD p % 8), each
+// with its own L2.  Rows that read the same operand are neighbours in logical order, in groups
+// of S (the loader's share()); this bijection on [0, nwg) gives every XCD whole groups, so the
+// operand comes from HBM once and from that XCD's L2 afterwards: within each full block of 8*S
+// physical indices, XCD x takes the logical rows block*8S + x*S ... + S-1.  (Grids are multiples
+// of 8 whenever a workgroup walks over more than one row.)
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int xcd_row(int p, int nwg, int S)
+{
+    const int blk = 8 * S;
+    const int full = nwg - nwg % blk;
+    if (S == 1 || p >= full) return p;
+    const int b = p / blk, w = p - b * blk;
+    return b * blk + (w & 7) * S + (w >> 3);
+}
+
+// ---------------------------------------------------------------------------
 // The transform kernels are persistent: a workgroup walks over rows
 // wg = blockIdx.x, blockIdx.x + gridDim.x, ... and, while it transforms one row,
 // the raw words of its next row are already on their way into registers.
@@ -265,7 +282,9 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
     constexpr int T = (1 << LOGN) / E;
     constexpr int NP = Plan<LOGN, E>::NP;
     const int tid = threadIdx.x;
-    int wg = blockIdx.x;
+    const int S = ld.share(C);
+    int p = blockIdx.x;
+    int wg = xcd_row(p, nwg, S);
     uint64_t raw[PF ? E : 1][LD::kRaw];
     if constexpr (PF) fetch_row<LOGN, E, false>(ld, wg, tid, C, raw);
     for (;;) {
@@ -276,8 +295,9 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
         double twa[TWREGS], twb[TWREGS];
         load_tw<LOGN, E, 0, true>(tw, tid, twa);
         double in[E];
-        const int wg_next = wg + (int)gridDim.x;
-        const bool more = wg_next < nwg;
+        p += (int)gridDim.x;
+        const bool more = p < nwg;
+        const int wg_next = more ? xcd_row(p, nwg, S) : 0;
         if constexpr (PF) {
 #pragma unroll
             for (int it = 0; it < E; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
@@ -388,7 +408,9 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
     constexpr int NP = Plan<LOGN, E>::NP;
     static_assert(NP - 1 >= Plan<LOGN, E>::NC, "the first inverse pass must be wave-local");
     const int tid = threadIdx.x;
-    int wg = blockIdx.x;
+    const int S = ld.share(C);
+    int p = blockIdx.x;
+    int wg = xcd_row(p, nwg, S);
     uint64_t raw[PF ? E : 1][LD::kRaw];
     if constexpr (PF) fetch_row<LOGN, E, true>(ld, wg, tid, C, raw);
     for (;;) {
@@ -410,28 +432,30 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
                 load_row_now<LOGN, E, true>(ld, wg, tid, m, C, [&](int it, double v) { lds[pc + pad(it * 64)] = v; });
             }
         }
-        const int wg_next = wg + (int)gridDim.x;
-        const bool more = wg_next < nwg;
+        p += (int)gridDim.x;
+        const bool more = p < nwg;
+        const int wg_next = more ? xcd_row(p, nwg, S) : 0;
+        const int orow = ld.out_row(wg, C);
         if constexpr (PF) {
             if (more) fetch_row<LOGN, E, true>(ld, wg_next, tid, C, raw);
         }
         wave_sync();
         // passes NP-1 ... 0; the twiddle buffers alternate
         if constexpr (NP == 5) {
-            inv_pass<LOGN, E, 4>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
-            inv_pass<LOGN, E, 3>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
-            inv_pass<LOGN, E, 2>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
-            inv_pass<LOGN, E, 1>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
-            inv_pass<LOGN, E, 0>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 4>(lds, st, orow, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 3>(lds, st, orow, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, E, 2>(lds, st, orow, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 1>(lds, st, orow, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, E, 0>(lds, st, orow, tid, itw, twa, twb, m, pr, C);
         } else if constexpr (NP == 4) {
-            inv_pass<LOGN, E, 3>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
-            inv_pass<LOGN, E, 2>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
-            inv_pass<LOGN, E, 1>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
-            inv_pass<LOGN, E, 0>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, E, 3>(lds, st, orow, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 2>(lds, st, orow, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, E, 1>(lds, st, orow, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 0>(lds, st, orow, tid, itw, twb, twa, m, pr, C);
         } else {
-            inv_pass<LOGN, E, 2>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
-            inv_pass<LOGN, E, 1>(lds, st, wg, tid, itw, twb, twa, m, pr, C);
-            inv_pass<LOGN, E, 0>(lds, st, wg, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 2>(lds, st, orow, tid, itw, twa, twb, m, pr, C);
+            inv_pass<LOGN, E, 1>(lds, st, orow, tid, itw, twb, twa, m, pr, C);
+            inv_pass<LOGN, E, 0>(lds, st, orow, tid, itw, twa, twb, m, pr, C);
         }
         if (!more) break;
         wg = wg_next;
@@ -561,6 +585,7 @@ struct LdRowsU64 {
     const uint32_t *tab;
     int pmod, logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 1; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *) const { return wg; }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *, uint64_t *raw) const
     {
@@ -597,6 +622,7 @@ struct LdMulQ {     // workgroup -> (pp, ciphertext prime i)
     static constexpr bool kScatter = false;
     MulSrc src;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 1; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *C) const
     {
         return (wg / C->k) * C->KL + wg % C->k;
@@ -620,6 +646,7 @@ struct LdMulAux {
     static constexpr bool kScatter = false;
     MulSrc src;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return C->k + wg % C->l; }
+    __device__ __forceinline__ int share(const DevConst *C) const { return C->l; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *C) const
     {
         return (wg / C->l) * C->KL + C->k + wg % C->l;
@@ -656,6 +683,7 @@ struct LdModup {
     uint32_t galois;
     int logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->L; }
+    __device__ __forceinline__ int share(const DevConst *C) const { return C->L; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *) const { return wg; }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
@@ -696,6 +724,7 @@ struct LdPlain {
     const uint64_t *pt;
     int logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 1; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *) const { return wg; }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
@@ -716,6 +745,8 @@ struct LdInvF64 {
     const uint32_t *tab;
     int pmod, logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 1; }
+    __device__ __forceinline__ int out_row(int wg, const DevConst *) const { return wg; }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *, uint64_t *raw) const
     {
         raw[0] = f64_bits(src[((size_t)wg << logn) + idx]);
@@ -732,6 +763,8 @@ struct LdInvU64 {
     const uint32_t *tab;
     int pmod, logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 1; }
+    __device__ __forceinline__ int out_row(int wg, const DevConst *) const { return wg; }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *, uint64_t *raw) const
     {
         raw[0] = src[((size_t)wg << logn) + idx];
@@ -741,8 +774,9 @@ struct LdInvU64 {
         return u64_to_f64(raw[0]);
     }
 };
-// key-switch inner product fused into the load: workgroup -> (unit b, component c, prime r),
-// element = sum_j digit_j[b][r] * key[j][c][r] (both in transform order)
+// key-switch inner product fused into the load: workgroup -> (unit b, prime r, component c), the
+// component running fastest so that the two rows reading the same digits are neighbours;
+// element = sum_j digit_j[b][r] * key[j][c][r] (both in transform order); result row [b][c][r]
 template <int DNUM>
 struct LdInvKsInner {
     static constexpr int kRaw = 2 * DNUM;
@@ -750,10 +784,16 @@ struct LdInvKsInner {
     const double *dig;   // [b][DNUM][L][N] lazy
     const double *key;   // [DNUM][2][L][N] reduced
     int logn;
-    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->L; }
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return (wg >> 1) % C->L; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 2; }
+    __device__ __forceinline__ int out_row(int wg, const DevConst *C) const
+    {
+        const int L = C->L, r = (wg >> 1) % L, b = wg / (2 * L);
+        return (b * 2 + (wg & 1)) * L + r;
+    }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
-        const int L = C->L, r = wg % L, c = (wg / L) & 1, b = wg / (2 * L);
+        const int L = C->L, r = (wg >> 1) % L, c = wg & 1, b = wg / (2 * L);
 #pragma unroll
         for (int j = 0; j < DNUM; j++) {
             raw[2 * j] = f64_bits(dig[(((size_t)(b * DNUM + j) * L + r) << logn) + idx]);
@@ -779,6 +819,8 @@ struct LdInvMulPlain {
     const double *plain;   // prepared plaintexts [*][k][N]
     int ct_group, p_mod, pstride, pofs, logn;
     __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 1; }
+    __device__ __forceinline__ int out_row(int wg, const DevConst *) const { return wg; }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
         const int k = C->k, i = wg % k, c = (wg / k) & 1, b = wg / (2 * k);
