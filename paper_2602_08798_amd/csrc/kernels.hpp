@@ -802,9 +802,14 @@ struct LdInvKsInner {
     }
     __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD m, const DevConst *) const
     {
+        // digits are lazy (|x| <= 7.5 p), keys reduced: each product is below 1.91 p, so up to four
+        // of them sum to less than 8 p without reducing the digits first
         double s = 0.0;
 #pragma unroll
-        for (int j = 0; j < DNUM; j++) s += mulmod(red(bits_f64(raw[2 * j]), m), bits_f64(raw[2 * j + 1]), m);
+        for (int j = 0; j < DNUM; j++) {
+            const double d = bits_f64(raw[2 * j]);
+            s += mulmod(DNUM <= 4 ? d : red(d, m), bits_f64(raw[2 * j + 1]), m);
+        }
         return s;
     }
 };
