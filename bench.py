@@ -8,11 +8,14 @@ for one generated token (GPT-2-small shape: 12 heads x d = 64, N = 8192, three
     context  a . V    over 12 x 4 cache ciphertexts (48 mul, 12 relin, 7 rotate-and-add each)
     append   the new K and V rows into 24 caches at token 512 (opens ciphertext 5)
 Inputs are seeded uniform residues (stand-ins for ciphertexts and keys; see
-workloads.synth) already resident in HBM when the timed region starts.
+workloads.synth) already resident in HBM when the timed region starts.  The
+timed step is one cg_decode_step call (the three parts side by side on three
+streams); --serial times them as three calls in sequence instead.
 
 Prints ONE JSON line.  `roofline` is for the kernel class with the largest
-share of the step, timed with HIP events by the library itself in a second,
-identical pass; `cpu_baseline` times the CPU oracle on a bounded sample of the
+share of the step, timed with HIP events by the library itself in a further
+pass over the same work issued as three calls in sequence (so that each
+kernel has the device to itself while it is timed); `cpu_baseline` times the CPU oracle on a bounded sample of the
 same workload (and checks the GPU results against it bit for bit).
 """
 import argparse
