@@ -255,6 +255,33 @@ int cg_prefill_qk(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64
                   const void *const *gk_fold_dev_host, const void *gk_blk_dev,
                   const void *gk_swap_dev, uint64_t *out_dev, void *ws_dev);
 
+/* Prefill context O = A V for every head (the softmax-times-values product of the prompt,
+ * section 4.1 "outer-outer"; the paper gives no procedure -- this is the product over the same
+ * generalised diagonals as cg_prefill_qk).  v_dev: [heads] token-major ciphertexts (token i in
+ * block i, the layout cg_kv_append builds); a_dev: [heads][m] ciphertexts, m = N/d2, unit
+ * (sigma, r) = sigma*H + r (H = m/2) holding A[i][j(i,sigma,r)] in all d2 slots of block i, with
+ * j as in cg_prefill_qk.  Computes, per head, the rotated copies V_(sigma,r) exactly as
+ * cg_prefill_qk does for K, y = sum over units of mul(a[h][u], V_u) (three components, u
+ * ascending), out[h] = relin(y): block i of out[h] decrypts to sum_j A[i][j] V[j][:] mod t.
+ * gk_blk / gk_swap: prepared keys for 3^d2 and 2N-1. */
+int cg_prefill_av(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *v_dev,
+                  uint32_t heads, uint32_t d2, const void *rlk_dev, const void *gk_blk_dev,
+                  const void *gk_swap_dev, uint64_t *out_dev, void *ws_dev);
+
+/* Compaction of the m score ciphertexts of cg_prefill_qk, whose useful values sit in slot 0 of
+ * every block (a step the score hand-over to the non-linear protocol needs; not described in
+ * the paper).  Units come in groups of w = min(d2, H) consecutive diagonals; every unit is
+ * multiplied by mask0 (prepared plaintext selecting slot 0 of each block) and the group is
+ * summed with diagonal r' of the group shifted right by r' slots, as a pairwise tree: at
+ * level l = 0, 1, ..., log2(w)-1:  y[j 2^(l+1)] += rotate(y[j 2^(l+1) + 2^l], 3^(N/2 - 2^l)).
+ * out_dev: [heads * m / w] ciphertexts; slot i*d2 + r' of group output g holds the useful
+ * value of diagonal g*w + r' for token i.  x_dev is not modified.
+ * gk_right_dev_host: host array of log2(w) device pointers, prepared keys for
+ * g = 3^(N/2 - 1), 3^(N/2 - 2), 3^(N/2 - 4), ... (mod 2N) in that order. */
+int cg_prefill_repack(cg_ctx *ctx, void *stream, const uint64_t *x_dev, uint32_t heads, uint32_t d2,
+                      const void *mask0_dev, const void *const *gk_right_dev_host, uint64_t *out_dev,
+                      void *ws_dev);
+
 /* Benchmark support: between cg_profile_begin and cg_profile_end every kernel
  * launch of this context is bracketed by a pair of HIP events on the stream it is
  * launched on.  cg_profile_end waits for the recorded events and returns, per

@@ -23,6 +23,10 @@ slots [b d, (b+1) d)) of a cache ciphertext holds one token's d-vector.
   prefill_qk      the prompt's Q K^T as m "generalised diagonals" (the paper
                   names an outer-outer product and gives no procedure; this is
                   the reading documented in the design notes).
+  prefill_av      the prompt's A V over the same diagonals: the weights arrive
+                  one ciphertext per diagonal, broadcast over each token's block.
+  prefill_repack  compaction of the score ciphertexts (useful values in slot 0 of
+                  each block) into ciphertexts with d useful values per block.
 """
 import numpy as np
 
@@ -167,6 +171,57 @@ def prefill_qk(orc, q_ct, k_ct, rlk, gks, d: int):
                 x = orc.add(x, orc.rotate(x, g, gks[g]))
             out.append(x)
     return out
+
+
+def rotated_copies(orc, ct, gks, d: int):
+    """[sigma*H + r] -> ct rotated left by r blocks (sequentially, one key), row-swapped for sigma = 1."""
+    n = orc.n
+    H = n // d // 2
+    g_blk, g_swap = galois_rot(n, d), galois_swap(n)
+    rot = [ct]
+    for _ in range(1, H):
+        rot.append(orc.rotate(rot[-1], g_blk, gks[g_blk]))
+    return rot + [orc.rotate(x, g_swap, gks[g_swap]) for x in rot]
+
+
+def prefill_av(orc, a_cts, v_ct, rlk, gks, d: int):
+    """O = A V for one head.  a_cts[sigma*H + r] holds A[i][j(i, sigma, r)] in every slot of block i
+    (j as in prefill_qk); v_ct is token-major.  Sum of the m slot-wise products (three components,
+    unit order ascending), one relinearisation: block i of the result holds sum_j A[i][j] V[j][:]."""
+    vs = rotated_copies(orc, v_ct, gks, d)
+    y = orc.mul(a_cts[0], vs[0])
+    for u in range(1, len(vs)):
+        y = orc.add(y, orc.mul(a_cts[u], vs[u]))
+    return orc.relin(y, rlk)
+
+
+def slot0_mask_values(n: int, d: int) -> np.ndarray:
+    v = np.zeros(n, dtype=np.int64)
+    v[::d] = 1
+    return v
+
+
+def right_shifts(w: int):
+    sh = 1
+    while sh < w:
+        yield sh
+        sh *= 2
+
+
+def prefill_repack(orc, x_cts, mask0_poly, gks, d: int):
+    """x_cts: the m score ciphertexts of one head (unit order of prefill_qk).  Groups of
+    w = min(d, H) consecutive units; each unit is masked to slot 0 of every block, then a pairwise
+    tree adds unit r' of the group shifted right by r' slots: at level l,
+    y[j 2^(l+1)] += rotate_right(y[j 2^(l+1) + 2^l], 2^l).  Returns the m / w group sums."""
+    n = orc.n
+    H = n // d // 2
+    w = min(d, H)
+    y = [orc.mul_plain(x, mask0_poly) for x in x_cts]
+    for sh in right_shifts(w):
+        g = galois_rot(n, n // 2 - sh)
+        for j in range(0, len(y), 2 * sh):
+            y[j] = orc.add(y[j], orc.rotate(y[j + sh], g, gks[g]))
+    return [y[j] for j in range(0, len(y), w)]
 
 
 def required_galois(n: int, d: int):

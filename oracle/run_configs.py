@@ -59,7 +59,8 @@ def run_c4(orc, st):
 
 
 def run_c3(orc, st, heads=None, progress=None):
-    """Build every K and V cache ciphertext from its 128 row ciphertexts, then Q K^T per head."""
+    """Build every K and V cache ciphertext from its 128 row ciphertexts, then per head: Q K^T,
+    the compaction of its score ciphertexts, and A V."""
     H, m, d2 = st["heads"], st["m"], st["d2"]
     heads = range(H) if heads is None else heads
     out = {}
@@ -75,6 +76,12 @@ def run_c3(orc, st, heads=None, progress=None):
         diag = attention.prefill_qk(orc, st["q"][h], caches[h], st["rlk"], st["gk"], d2)
         for i, x in enumerate(diag):
             out[f"qk{h}_{i}"] = x
+        # the scores compacted for hand-over, and the context from the (stand-in) weights
+        gkr = dict(st["gk_right"])
+        for i, x in enumerate(attention.prefill_repack(orc, diag, st["mask0"], gkr, d2)):
+            out[f"packed{h}_{i}"] = x
+        out[f"av{h}"] = attention.prefill_av(orc, list(st["a"][h * m:(h + 1) * m]), caches[H + h], st["rlk"],
+                                             st["gk"], d2)
         if progress:
             progress(f"C3 head {h} done")
     return out

@@ -18,7 +18,7 @@ _SYMBOLS = [
     "cg_ntt_forward", "cg_ntt_inverse", "cg_ksk_prepare", "cg_plain_prepare",
     "cg_mul", "cg_relin", "cg_mul_relin", "cg_rotate", "cg_add", "cg_mul_plain",
     "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_decode_scores_outer", "cg_decode_context_outer", "cg_prefill_qk",
-    "cg_decode_step", "cg_decode_step_workspace_bytes",
+    "cg_decode_step", "cg_decode_step_workspace_bytes", "cg_prefill_av", "cg_prefill_repack",
     "cg_bench_modmul", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
 ]
 
@@ -75,6 +75,8 @@ class Library:
         d.cg_decode_scores_outer.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, C.POINTER(vp), vp, vp]
         d.cg_decode_context_outer.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_prefill_qk.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp, vp, vp]
+        d.cg_prefill_av.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp, vp, vp]
+        d.cg_prefill_repack.argtypes = [vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_decode_step.argtypes = [vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp, vp, C.POINTER(vp),
                                      C.POINTER(vp), vp, vp, vp]
         d.cg_decode_step_workspace_bytes.argtypes = [vp, u32, u32]
@@ -308,6 +310,22 @@ class Context:
         self._check(self.lib.dll.cg_prefill_qk(self.h, self.stream, _ptr(q), _ptr(k), heads, d2, _ptr(rlk),
                                                self._keys(gk_fold), _ptr(gk_blk), _ptr(gk_swap), _ptr(out),
                                                _ptr(ws)))
+        return out
+
+    def prefill_av(self, a, v, heads, d2, rlk, gk_blk, gk_swap, out=None):
+        out = self.empty_ct(heads) if out is None else out
+        ws = self.workspace(heads * (self.n // d2))
+        self._check(self.lib.dll.cg_prefill_av(self.h, self.stream, _ptr(a), _ptr(v), heads, d2, _ptr(rlk),
+                                               _ptr(gk_blk), _ptr(gk_swap), _ptr(out), _ptr(ws)))
+        return out
+
+    def prefill_repack(self, x, heads, d2, mask0, gk_right, out=None):
+        m = self.n // d2
+        w = min(d2, m // 2)
+        out = self.empty_ct(heads * m // w) if out is None else out
+        ws = self.workspace(heads * m)
+        self._check(self.lib.dll.cg_prefill_repack(self.h, self.stream, _ptr(x), heads, d2, _ptr(mask0),
+                                                   self._keys(gk_right), _ptr(out), _ptr(ws)))
         return out
 
     def profile_begin(self, max_launches=65536):

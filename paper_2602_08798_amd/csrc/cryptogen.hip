@@ -501,8 +501,10 @@ static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *
 // key switch of one ring element per unit (src + b*src_stride), then the final additions
 static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t src_stride, uint32_t galois,
                         const double *key, uint64_t *out2, size_t out_stride, const uint64_t *add, size_t add_stride,
-                        uint32_t galois_inv, int accumulate, uint32_t batch, void *ws)
+                        uint32_t galois_inv, int accumulate, uint32_t batch, void *ws,
+                        const uint64_t *acc_add = nullptr, size_t acc_stride = 0)
 {
+    if (!acc_add) { acc_add = add; acc_stride = add_stride; }
     Bump w = bump(c, ws);
     double *dig = w.take<double>((size_t)c->dnum * c->L * batch);
     double *acc = w.take<double>((size_t)2 * c->L * batch);
@@ -538,7 +540,7 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     }
 #undef CG_KSI
     CG_TRY(rc);
-    ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch};
+    ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch, acc_add, acc_stride};
     const double add_rows = !add ? 0.0 : (galois_inv ? c->k + (accumulate ? 2.0 * c->k : 0.0) : 2.0 * c->k);
     CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, moddown_kernel,
                  pw_blocks(c, (size_t)batch * 2), A, c->dc);
@@ -561,14 +563,18 @@ static uint32_t inv_mod_pow2(uint32_t g, uint32_t two_n)
 }
 
 // in_stride / out_stride: uint64 between consecutive units (0 = densely packed ciphertexts)
+// out2 = rotate(in2, g) (accumulate = 0), in2 + rotate(in2, g) (accumulate = 1, acc_add null) or
+// acc_add + rotate(in2, g) (accumulate = 1, acc_add given; out2 may be acc_add itself)
 static int do_rotate(cg_ctx *c, hipStream_t s, const uint64_t *in2, uint32_t g, const void *gk, uint64_t *out2,
-                     uint32_t batch, int accumulate, void *ws, size_t in_stride = 0, size_t out_stride = 0)
+                     uint32_t batch, int accumulate, void *ws, size_t in_stride = 0, size_t out_stride = 0,
+                     const uint64_t *acc_add = nullptr, size_t acc_stride = 0)
 {
     const size_t ct2 = (size_t)2 * c->k * c->N;
     if (!in_stride) in_stride = ct2;
     if (!out_stride) out_stride = ct2;
     return do_keyswitch(c, s, in2 + (size_t)c->k * c->N, in_stride, g, static_cast<const double *>(gk), out2,
-                        out_stride, in2, in_stride, inv_mod_pow2(g, 2u * c->N), accumulate, batch, ws);
+                        out_stride, in2, in_stride, inv_mod_pow2(g, 2u * c->N), accumulate, batch, ws, acc_add,
+                        acc_stride);
 }
 
 static int do_add(cg_ctx *c, hipStream_t s, const uint64_t *a, const uint64_t *b, uint64_t *out, size_t rows)
@@ -884,12 +890,30 @@ extern "C" int cg_decode_context_outer(cg_ctx *c, void *stream, const uint64_t *
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_all, nrot, batch, w.p);
 }
 
+// kp[h][sigma*H + r] (m = 2H units per head): r = 0 copies of the source, K_r = rotate(K_{r-1}, 3^d2)
+// sequentially for all heads at once, then the row-swapped copies (sigma = 1)
+static int rotated_copies(cg_ctx *c, hipStream_t s, const uint64_t *src, uint32_t heads, uint32_t d2,
+                          const void *gk_blk, const void *gk_swap, uint64_t *kp, void *ws)
+{
+    const uint32_t m = (uint32_t)c->N / d2, H = m / 2;
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    for (uint32_t h = 0; h < heads; h++)
+        CG_HIP(hipMemcpyAsync(kp + (size_t)h * m * ct2, src + (size_t)h * ct2, ct2 * 8, hipMemcpyDeviceToDevice, s));
+    const uint32_t g_blk = pow3_mod(d2, 2u * c->N), g_swap = 2u * c->N - 1;
+    for (uint32_t r = 1; r < H; r++)
+        CG_TRY(do_rotate(c, s, kp + (size_t)(r - 1) * ct2, g_blk, gk_blk, kp + (size_t)r * ct2, heads, 0, ws,
+                         (size_t)m * ct2, (size_t)m * ct2));
+    for (uint32_t h = 0; h < heads; h++)
+        CG_TRY(do_rotate(c, s, kp + (size_t)h * m * ct2, g_swap, gk_swap, kp + ((size_t)h * m + H) * ct2, H, 0, ws));
+    return CG_OK;
+}
+
 extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads,
                              uint32_t d2, const void *rlk, const void *const *gk_fold, const void *gk_blk,
                              const void *gk_swap, uint64_t *out, void *ws)
 {
     CG_REQUIRE(c && ptrs_ok({q, kk, rlk, gk_blk, gk_swap, out, ws}) && gk_fold && heads >= 1 && pow2_d(c, d2));
-    const uint32_t m = (uint32_t)c->N / d2, H = m / 2, batch = heads * m;
+    const uint32_t m = (uint32_t)c->N / d2, batch = heads * m;
     CG_REQUIRE(batch_ok(batch));
     int nrot = 0;
     uint32_t gs[16];
@@ -898,27 +922,75 @@ extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const u
         gs[nrot++] = pow3_mod(sh, 2u * c->N);
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const size_t ct2 = (size_t)2 * c->k * c->N;
     // kp[h][sigma*H + r]: rotated copies of K, one ciphertext per output unit
     Bump w = bump(c, ws);
     uint64_t *kp = w.take<uint64_t>((size_t)2 * c->k * batch);
     uint64_t *xb = w.take<uint64_t>((size_t)2 * c->k * batch);
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
-    // r = 0 slots: copy K (device to device, on the stream)
-    for (uint32_t h = 0; h < heads; h++)
-        CG_HIP(hipMemcpyAsync(kp + (size_t)h * m * ct2, kk + (size_t)h * ct2, ct2 * 8, hipMemcpyDeviceToDevice, s));
-    const uint32_t g_blk = pow3_mod(d2, 2u * c->N), g_swap = 2u * c->N - 1;
-    // K_r = rotate(K_{r-1}, 3^d2): sequential in r, all heads in one strided batch
-    for (uint32_t r = 1; r < H; r++)
-        CG_TRY(do_rotate(c, s, kp + (size_t)(r - 1) * ct2, g_blk, gk_blk, kp + (size_t)r * ct2, heads, 0, w.p,
-                         (size_t)m * ct2, (size_t)m * ct2));
-    // sigma = 1 slots: row swap of each K_r (H contiguous units per head)
-    for (uint32_t h = 0; h < heads; h++)
-        CG_TRY(do_rotate(c, s, kp + (size_t)h * m * ct2, g_swap, gk_swap, kp + ((size_t)h * m + H) * ct2, H, 0, w.p));
+    CG_TRY(rotated_copies(c, s, kk, heads, d2, gk_blk, gk_swap, kp, w.p));
     // all heads x m products at once
     CG_TRY(do_mul(c, s, q, kp, d3, batch, m, w.p, 0));
     CG_TRY(do_relin(c, s, d3, rlk, kp, batch, w.p));   // the rotated keys are consumed: reuse as x0
     return rotate_add_chain(c, s, kp, xb, out, gs, gk_fold, nrot, batch, w.p);
+}
+
+extern "C" int cg_prefill_av(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *v, uint32_t heads,
+                             uint32_t d2, const void *rlk, const void *gk_blk, const void *gk_swap, uint64_t *out,
+                             void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({a, v, rlk, gk_blk, gk_swap, out, ws}) && heads >= 1 && pow2_d(c, d2));
+    const uint32_t m = (uint32_t)c->N / d2, batch = heads * m;
+    CG_REQUIRE(batch_ok(batch));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Bump w = bump(c, ws);
+    uint64_t *vp = w.take<uint64_t>((size_t)2 * c->k * batch);
+    uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
+    uint64_t *y = w.take<uint64_t>((size_t)3 * c->k * heads);
+    CG_TRY(rotated_copies(c, s, v, heads, d2, gk_blk, gk_swap, vp, w.p));
+    CG_TRY(do_mul(c, s, a, vp, d3, batch, 1, w.p, 0));
+    const int rows = 3 * c->k;
+    CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), sum_groups_kernel,
+                 pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)m, rows, c->dc);
+    return do_relin(c, s, y, rlk, out, heads, w.p);
+}
+
+extern "C" int cg_prefill_repack(cg_ctx *c, void *stream, const uint64_t *x, uint32_t heads, uint32_t d2,
+                                 const void *mask0, const void *const *gk_right, uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({x, mask0, out, ws}) && gk_right && heads >= 1 && pow2_d(c, d2));
+    const uint32_t m = (uint32_t)c->N / d2, H = m / 2, batch = heads * m;
+    CG_REQUIRE(batch_ok(batch));
+    const uint32_t wdt = H < d2 ? H : d2;        // diagonals packed into one output
+    const uint32_t n_out = batch / wdt;
+    int levels = 0;
+    for (uint32_t sh = 1; sh < wdt; sh <<= 1) {
+        CG_REQUIRE(gk_right[levels] && aligned16(gk_right[levels]));
+        levels++;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    const double LB = (double)limb_bytes(c);
+    Bump w = bump(c, ws);
+    uint64_t *y = w.take<uint64_t>((size_t)2 * c->k * batch);
+    double *f = w.take<double>((size_t)2 * c->k * batch);
+    // y[u] = x[u] * mask0 (keeps slot 0 of every block)
+    const size_t rows = (size_t)batch * 2 * c->k;
+    CG_TRY(launch_fwd(c, s, rows, LdRowsU64{x, nullptr, c->k, c->logn}, StF64{f, c->logn}, KID_FWD_ROWS,
+                      LB * 2.0 * rows));
+    CG_TRY(launch_inv(c, s, rows, LdInvMulPlain{f, static_cast<const double *>(mask0), 1, 1 << 30, 0, 0, c->logn},
+                      StInvU64{y, c->logn}, KID_INV_MULPLAIN, LB * (2.0 * rows + c->k)));
+    // pairwise tree inside every group of wdt consecutive units: at level l (shift 2^l)
+    // y[j 2^(l+1)] += rotate_right(y[j 2^(l+1) + 2^l], 2^l); rotate right by sh = Galois 3^(N/2 - sh)
+    for (int l = 0; l < levels; l++) {
+        const uint32_t sh = 1u << l;
+        const size_t stride = (size_t)2 * sh * ct2;
+        CG_TRY(do_rotate(c, s, y + (size_t)sh * ct2, pow3_mod((uint32_t)c->N / 2 - sh, 2u * c->N), gk_right[l], y,
+                         batch / (2 * sh), 1, w.p, stride, stride, y, stride));
+    }
+    // gather the group leaders
+    for (uint32_t o = 0; o < n_out; o++)
+        CG_HIP(hipMemcpyAsync(out + (size_t)o * ct2, y + (size_t)o * wdt * ct2, ct2 * 8, hipMemcpyDeviceToDevice, s));
+    return CG_OK;
 }
 
 extern "C" int cg_profile_begin(cg_ctx *c, uint32_t max_launches)

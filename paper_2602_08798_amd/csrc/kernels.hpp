@@ -946,7 +946,7 @@ scale_kernel(const double *__restrict__ tens, uint64_t *__restrict__ out, int to
 // mod-down with rounding and the final additions of relinearisation / rotation:
 //   u = floor((A + floor(P/2)) / P) mod Q,  out[b][c] = u (+ add0) (+ add1)
 // add0: relin -> in3[b][c];  rotate -> sigma_g(in2[b][0]) for c = 0, nothing for c = 1
-// add1: rotate with accumulate -> in2[b][c]
+// add1: rotate with accumulate -> acc_add[b][c] (the rotated ciphertext itself, or another one)
 struct ModdownArgs {
     const double *acc;        // [b][2][L][N] lazy, coefficient order
     uint64_t *out;            // unit b at out + b*out_stride, [2][k][N]
@@ -954,8 +954,10 @@ struct ModdownArgs {
     const uint64_t *add;      // base of the addend ciphertexts (unit 0) or null
     size_t add_stride;        // uint64 per unit in add
     uint32_t galois;          // != 0: add is permuted by X -> X^galois and only applies to c = 0
-    int accumulate;           // also add the un-permuted add[b][c]
+    int accumulate;           // also add the un-permuted acc_add[b][c]
     int batch;
+    const uint64_t *acc_add;  // base of the ciphertexts added un-permuted (accumulate)
+    size_t acc_stride;
 };
 __global__ void __launch_bounds__(PW_THREADS)
 moddown_kernel(ModdownArgs A, const DevConst *__restrict__ C)
@@ -1000,7 +1002,10 @@ moddown_kernel(ModdownArgs A, const DevConst *__restrict__ C)
                         if (negate) w = (w == 0.0) ? 0.0 : mq.p - w;
                         v = addmod_canon(v, w, mq);
                     }
-                    if (A.accumulate) v = addmod_canon(v, u64_to_f64(ad[((size_t)(c * k + i) << logn) + n]), mq);
+                    if (A.accumulate) {
+                        const uint64_t *aa = A.acc_add + (size_t)b * A.acc_stride;
+                        v = addmod_canon(v, u64_to_f64(aa[((size_t)(c * k + i) << logn) + n]), mq);
+                    }
                 } else {
                     v = addmod_canon(v, u64_to_f64(ad[((size_t)(c * k + i) << logn) + n]), mq);
                 }

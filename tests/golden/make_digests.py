@@ -39,7 +39,7 @@ def main(names):
         elif name == "C3":
             inp = configs.c3_inputs()
             out = run_configs.run_c3(Oracle(inp["prm"]), inp, progress=lambda m: print(m, f"{time.time() - t0:.0f}s", flush=True))
-            note = "prefill: 3072 appends, then 12 x 128 generalised diagonals of Q K^T"
+            note = "prefill: 3072 appends, 12 x 128 generalised diagonals of Q K^T, their compaction (12 x 2), A V (12)"
         elif name == "C5":
             inp = configs.c5_inputs(); out = run_configs.run_c5(Oracle(inp["prm"]), inp, C5_STEPS)
             note = f"first {C5_STEPS} of 64 decode steps with cache growth, 16 heads, N = 16384"

@@ -105,7 +105,7 @@ def test_c4_full_decode_step_every_output():
     compare(got, want, "C4")
 
 
-def test_c3_prefill_appends_and_all_diagonals():
+def test_c3_prefill_appends_diagonals_compaction_and_context():
     say("C3")
     st, want = configs.c3_inputs(), load("C3")
     g = Gpu(st["prm"])
@@ -117,11 +117,19 @@ def test_c3_prefill_appends_and_all_diagonals():
     gk = {gal: g.key(k) for gal, k in st["gk"].items()}
     out = g.ctx.prefill_qk(g.dev(st["q"]), cache[:H], H, d2, g.key(st["rlk"]), [gk[x] for x in st["fold"]],
                            gk[st["g_blk"]], gk[st["g_swap"]])
-    cache_h, out = g.host(cache), g.host(out)
+    gkr = [g.key(st["gk_right"][x]) for x in st["right"]]
+    mask0 = g.ctx.plain_prepare(g.dev(st["mask0"][None, :]))
+    packed = g.ctx.prefill_repack(out, H, d2, mask0, gkr)
+    av = g.ctx.prefill_av(g.dev(st["a"]), cache[H:], H, d2, g.key(st["rlk"]), gk[st["g_blk"]], gk[st["g_swap"]])
+    cache_h, out, packed, av = g.host(cache), g.host(out), g.host(packed), g.host(av)
     got = {f"cache{c}": digest(cache_h[c]) for c in range(2 * H)}
+    per_head = packed.shape[0] // H
     for h in range(H):
         for i in range(m):
             got[f"qk{h}_{i}"] = digest(out[h, i])
+        for i in range(per_head):
+            got[f"packed{h}_{i}"] = digest(packed[h * per_head + i])
+        got[f"av{h}"] = digest(av[h])
     compare(got, want, "C3")
 
 

@@ -372,3 +372,53 @@ def test_decode_context_outer_match_oracle(env):
         want = attention.decode_context_outer(env.orc, a[h], list(cols[h * d2:(h + 1) * d2]), raw_rlk, raws)
         for j in range(d2):
             assert np.array_equal(got[h, j], want[j]), (env.name, h, j)
+
+
+@pytest.mark.parametrize("name,heads,d2", [("C1", 2, 256), ("C2", 2, 512)])
+def test_prefill_context_match_oracle(name, heads, d2):
+    from oracle import attention
+    env = _envs.get(name) or Env(name)
+    _envs[name] = env
+    n = env.n
+    m = n // d2
+    say(f"prefill_av {name}, d2 = {d2} (m = {m} units per head), {heads} heads")
+    raw_rlk, rlk = env.key(70)
+    g_blk, g_swap = pow(3, d2, 2 * n), 2 * n - 1
+    kb, ks = env.key(320), env.key(321)
+    a, v = env.cts(93, heads * m), env.cts(94, heads)
+    got = env.host(env.ctx.prefill_av(env.dev(a), env.dev(v), heads, d2, rlk, kb[1], ks[1]))
+    raws = {g_blk: kb[0], g_swap: ks[0]}
+    for h in range(heads):
+        want = attention.prefill_av(env.orc, list(a[h * m:(h + 1) * m]), v[h], raw_rlk, raws, d2)
+        assert np.array_equal(got[h], want), (name, h)
+
+
+@pytest.mark.parametrize("name,heads,d2", [("C1", 2, 256), ("C2", 1, 512), ("C1", 1, 16)])
+def test_prefill_repack_match_oracle(name, heads, d2):
+    """Groups of min(d2, H) score ciphertexts are compacted; the inputs stay untouched.  The third case
+    has more diagonals per slot row (H = 128) than slots per block (16): eight groups per row."""
+    from oracle import attention
+    env = _envs.get(name) or Env(name)
+    _envs[name] = env
+    n, t = env.n, env.prm.t
+    m = n // d2
+    w = min(d2, m // 2)
+    say(f"prefill_repack {name}, d2 = {d2}: {heads} x {m} units in groups of {w}")
+    shifts = list(attention.right_shifts(w))
+    gs = [pow(3, n // 2 - sh, 2 * n) for sh in shifts]
+    keys = [env.key(400 + i) for i in range(len(gs))]
+    mask_pt = attention.slot0_mask_values(n, d2).astype(np.uint64)
+    # an arbitrary plaintext exercises the same path as the encoded mask, which is not sparse either
+    rng = np.random.default_rng(95)
+    mask_pt = (mask_pt + rng.integers(0, t, n, dtype=np.uint64)) % t
+    mask0 = env.ctx.plain_prepare(env.dev(mask_pt[None, :]))
+    x = env.cts(96, heads * m)
+    dx = env.dev(x)
+    got = env.host(env.ctx.prefill_repack(dx, heads, d2, mask0, [k[1] for k in keys]))
+    assert np.array_equal(env.host(dx), x)
+    raws = {g: k[0] for g, k in zip(gs, keys)}
+    assert got.shape[0] == heads * m // w
+    for h in range(heads):
+        want = attention.prefill_repack(env.orc, list(x[h * m:(h + 1) * m]), mask_pt, raws, d2)
+        for i, wv in enumerate(want):
+            assert np.array_equal(got[h * (m // w) + i], wv), (name, h, i)

@@ -163,3 +163,71 @@ def test_context_against_an_outer_packed_segment_is_the_weighted_sum():
     want = (a @ V) % t
     for j in range(d):
         assert np.array_equal(cl.decrypt_slots(outs[j]), np.full(n, want[j]))
+
+
+def _diag_col(i, sigma, r, H):
+    row, pos = divmod(i, H)
+    return (row ^ sigma) * H + (pos + r) % H
+
+
+def test_prefill_context_is_the_matrix_product_on_a_small_ring():
+    """O = A V over the generalised diagonals: block i of the result is row i of A V mod t."""
+    prm = toy_params(8, 3, 1, 1)
+    orc = Oracle(prm)
+    cl = Client(prm, 66, orc)
+    n, d, t = prm.n, 8, prm.t
+    m = n // d
+    H = m // 2
+    g = Stream(66, 1)
+    Vm = attention_activations(g, 1, m, d)[0]
+    Am = attention_activations(g, 1, m, m)[0]
+    rlk, gks = cl.relin_key(), _keys(cl, n, d)
+    a_cts = []
+    for u in range(m):
+        sigma, r = divmod(u, H)
+        slots = np.zeros(n, dtype=np.int64)
+        for i in range(m):
+            slots[i * d:(i + 1) * d] = Am[i, _diag_col(i, sigma, r, H)]
+        a_cts.append(cl.encrypt_slots(slots))
+    out = attention.prefill_av(orc, a_cts, cl.encrypt_slots(Vm.reshape(-1)), rlk, gks, d)
+    dec = cl.decrypt_slots(out).reshape(m, d)
+    assert np.array_equal(dec, (Am @ Vm) % t)
+
+
+def _repack_case(log2n, d, seed):
+    prm = toy_params(log2n, 3, 1, 1)
+    orc = Oracle(prm)
+    cl = Client(prm, seed, orc)
+    n, t = prm.n, prm.t
+    m = n // d
+    H = m // 2
+    w = min(d, H)
+    g = Stream(seed, 1)
+    Qm = attention_activations(g, 1, m, d)[0]
+    Km = attention_activations(g, 1, m, d)[0]
+    rlk, gks = cl.relin_key(), _keys(cl, n, d)
+    for sh in attention.right_shifts(w):
+        gr = galois_rot(n, n // 2 - sh)
+        gks[gr] = cl.galois_key(gr)
+    xs = attention.prefill_qk(orc, cl.encrypt_slots(Qm.reshape(-1)), cl.encrypt_slots(Km.reshape(-1)), rlk, gks, d)
+    mask0 = cl.codec.encode(attention.slot0_mask_values(n, d))
+    packed = attention.prefill_repack(orc, xs, mask0, gks, d)
+    assert len(packed) == m // w
+    S = (Qm @ Km.T) % t
+    for gi, ct in enumerate(packed):
+        dec = cl.decrypt_slots(ct)
+        for i in range(m):
+            for rp in range(d):
+                if rp < w:
+                    sigma, r = divmod(gi * w + rp, H)
+                    assert dec[i * d + rp] == S[i, _diag_col(i, sigma, r, H)], (gi, i, rp)
+                else:
+                    assert dec[i * d + rp] == 0
+
+
+def test_score_repacking_compacts_d_diagonals_per_ciphertext():
+    _repack_case(8, 8, 67)      # H = 16 > d = 8: two groups per slot row
+
+
+def test_score_repacking_when_a_slot_row_has_fewer_diagonals_than_slots_per_block():
+    _repack_case(7, 16, 68)     # m = 8, H = 4 < d = 16: one group of 4 per slot row

@@ -80,13 +80,22 @@ def c3_inputs(heads: int = 12, d2: int = 64):
     s, m = w.seed, prm.n // d2
     fold = fold_galois(prm.n, d2)
     g_blk, g_swap = pow(3, d2, 2 * prm.n), 2 * prm.n - 1
+    right, sh = [], 1
+    while sh < min(d2, m // 2):                      # right shifts by 1, 2, 4, ... slots
+        right.append(pow(3, prm.n // 2 - sh, 2 * prm.n))
+        sh *= 2
     return {"prm": prm, "heads": heads, "d2": d2, "m": m,
             "q": pseudo_ciphertexts(Stream(s, 1), prm.q, prm.n, heads),
             # rows[tau][cache]: caches = K of head 0..heads-1, then V of head 0..heads-1
             "rows": pseudo_ciphertexts(Stream(s, 4), prm.q, prm.n, m * 2 * heads).reshape(
                 m, 2 * heads, 2, prm.k, prm.n),
             "masks": _masks(prm, s, m), "fold": fold, "g_blk": g_blk, "g_swap": g_swap,
-            "rlk": _keys(prm, s, 5, ["rlk"])["rlk"], "gk": _keys(prm, s, 6, fold + [g_blk, g_swap])}
+            "rlk": _keys(prm, s, 5, ["rlk"])["rlk"], "gk": _keys(prm, s, 6, fold + [g_blk, g_swap]),
+            # the rest of the prompt's attention: compaction of the scores, then A V with the weights
+            # arriving as one ciphertext per (head, diagonal) (stand-ins for re-encrypted softmax output)
+            "right": right, "gk_right": _keys(prm, s, 8, right),
+            "mask0": np.random.default_rng(s + 1).integers(0, prm.t, prm.n, dtype=np.uint64),
+            "a": pseudo_ciphertexts(Stream(s, 7), prm.q, prm.n, heads * m)}
 
 
 def c5_inputs(heads: int = 16, d2: int = 64, steps: int = 64):
