@@ -59,13 +59,22 @@ class DecodeStep:
         self.scores = ctx.empty_ct(H, C)
         self.context = ctx.empty_ct(H)
         ctx.workspace(H * C)
+        # the cache's transformed copy (what earlier steps leave behind): every ciphertext the products read
+        self.ext = ctx.empty_ext(2 * H * self.stride)
+        ctx.cache_extend(self.cache, 2 * H, C, self.stride, self.ext)
         torch.cuda.synchronize()
 
-    def step(self):
-        """One call: the three branches run side by side on the library's streams."""
+    def step(self, transformed_cache=False):
+        """One call: the three branches run side by side on the library's streams.  With the
+        transformed copy of the cache the products skip the lift and forward transforms of the
+        cache operands, and the step refreshes the copy of the ciphertext it appended to."""
         self.ctx.decode_step(self.q, self.a, self.cache, self.heads, self.n_cts, self.stride, self.d2, self.tau,
                              self.rows, self.masks, self.rlk, [self.gk[g] for g in self.g_fold],
-                             [self.gk[g] for g in self.g_block], scores=self.scores, context=self.context)
+                             [self.gk[g] for g in self.g_block], scores=self.scores, context=self.context,
+                             cache_ext=self.ext if transformed_cache else None)
+
+    def step_transformed_cache(self):
+        self.step(transformed_cache=True)
 
     def step_serial(self):
         """The same work as three calls in sequence (used for per-kernel timing: a kernel's
@@ -162,6 +171,7 @@ def main():
         step()
     ms = timed(torch, step, args.steps)
     ms_serial = ms if args.serial else timed(torch, ws.step_serial, args.steps)
+    ms_ext = timed(torch, ws.step_transformed_cache, args.steps)
 
     # second pass over the same work, one call after the other, with the library's event
     # bracketing for per-kernel figures
@@ -224,6 +234,7 @@ def main():
                    "derived_12_layers_ms_per_token": round(12 * ms, 3),
                    "launch": "three calls in sequence" if args.serial else
                              "cg_decode_step: scores, context and append side by side on three streams",
+                   "ms_per_step_with_transformed_cache_copy": round(ms_ext, 4),
                    "ms_per_step_three_calls_in_sequence": round(ms_serial, 4)},
         "secondary": secondary,
         "roofline": roofline,

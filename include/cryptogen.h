@@ -76,6 +76,7 @@ typedef struct {
     size_t ksk_bytes;        /* one prepared switching key */
     size_t plain_bytes;      /* one prepared plaintext (cg_plain_prepare output) */
     size_t ws_bytes_per_unit;/* workspace bytes per batch unit (see cg_workspace_bytes) */
+    size_t ct_ext_bytes;     /* one ciphertext in transformed form (cg_cache_extend output) */
 } cg_sizes;
 
 /* Build a context: validates the parameters (CG_EINVAL otherwise), chooses the
@@ -215,6 +216,35 @@ int cg_decode_step(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint6
                    const void *rlk_dev, const void *const *gk_fold_dev_host,
                    const void *const *gk_block_dev_host, uint64_t *scores_dev, uint64_t *context_dev,
                    void *ws_dev);
+
+/* The cache kept in transformed form (an optimisation of the decode scan that leaves every
+ * result bit-identical): a ciphertext that is multiplied in many steps -- every cache
+ * ciphertext is -- need not be lifted to the extended basis and transformed again each time.
+ * cg_cache_extend writes, for ciphertext (g, i), g < n_groups, i < group_len, at index
+ * g * group_stride_cts + i of cts_dev, its transformed form (opaque, cg_sizes.ct_ext_bytes
+ * bytes) at the same index of ext_dev.  cg_decode_scores_ext / cg_decode_context_ext are
+ * cg_decode_scores / cg_decode_context reading that form (same cache geometry, indices in
+ * units of transformed ciphertexts).  cg_decode_step_ext is cg_decode_step with the
+ * transformed copy of the whole cache ([2*heads][cache_stride_cts], K caches first) beside
+ * it: the products read the copy, and after the append the copy of the ciphertext each
+ * cache received is refreshed (the untransformed cache stays authoritative and is what the
+ * append updates).  The copy must be up to date for every ciphertext the products read. */
+int cg_cache_extend(cg_ctx *ctx, void *stream, const uint64_t *cts_dev, uint32_t n_groups,
+                    uint32_t group_len, uint32_t group_stride_cts, void *ext_dev);
+int cg_decode_scores_ext(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const void *kext_dev,
+                         uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2,
+                         const void *rlk_dev, const void *const *gk_fold_dev_host, uint64_t *out_dev,
+                         void *ws_dev);
+int cg_decode_context_ext(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const void *vext_dev,
+                          uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2,
+                          const void *rlk_dev, const void *const *gk_block_dev_host, uint64_t *out_dev,
+                          void *ws_dev);
+int cg_decode_step_ext(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *a_dev,
+                       uint64_t *cache_dev, void *cache_ext_dev, uint32_t heads, uint32_t n_cts,
+                       uint32_t cache_stride_cts, uint32_t d2, uint32_t tau, const uint64_t *rows_dev,
+                       const void *masks_dev, const void *rlk_dev, const void *const *gk_fold_dev_host,
+                       const void *const *gk_block_dev_host, uint64_t *scores_dev, uint64_t *context_dev,
+                       void *ws_dev);
 
 /* Decode attention scores against an outer-packed cache segment (one ciphertext per feature
  * column: kcols[h][j] holds K[tau][j] in flat slot tau), ARCC inner-inner mode (section 4.3 and

@@ -19,6 +19,7 @@ _SYMBOLS = [
     "cg_mul", "cg_relin", "cg_mul_relin", "cg_rotate", "cg_add", "cg_mul_plain",
     "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_decode_scores_outer", "cg_decode_context_outer", "cg_prefill_qk",
     "cg_decode_step", "cg_decode_step_workspace_bytes", "cg_prefill_av", "cg_prefill_repack",
+    "cg_cache_extend", "cg_decode_scores_ext", "cg_decode_context_ext", "cg_decode_step_ext",
     "cg_bench_modmul", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
 ]
 
@@ -32,7 +33,7 @@ class _Params(C.Structure):
 class _Sizes(C.Structure):
     _fields_ = [("ct2_bytes", C.c_size_t), ("ct3_bytes", C.c_size_t),
                 ("ksk_raw_bytes", C.c_size_t), ("ksk_bytes", C.c_size_t),
-                ("plain_bytes", C.c_size_t), ("ws_bytes_per_unit", C.c_size_t)]
+                ("plain_bytes", C.c_size_t), ("ws_bytes_per_unit", C.c_size_t), ("ct_ext_bytes", C.c_size_t)]
 
 
 class _KernelStat(C.Structure):
@@ -75,6 +76,11 @@ class Library:
         d.cg_decode_scores_outer.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, C.POINTER(vp), vp, vp]
         d.cg_decode_context_outer.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_prefill_qk.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp, vp, vp]
+        d.cg_cache_extend.argtypes = [vp, vp, vp, u32, u32, u32, vp]
+        d.cg_decode_scores_ext.argtypes = d.cg_decode_scores.argtypes
+        d.cg_decode_context_ext.argtypes = d.cg_decode_context.argtypes
+        d.cg_decode_step_ext.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp, vp, C.POINTER(vp),
+                                         C.POINTER(vp), vp, vp, vp]
         d.cg_prefill_av.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp, vp, vp]
         d.cg_prefill_repack.argtypes = [vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_decode_step.argtypes = [vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp, vp, C.POINTER(vp),
@@ -272,8 +278,33 @@ class Context:
                                                    stride, d2, _ptr(rlk), self._keys(gk_block), _ptr(out), _ptr(ws)))
         return out
 
+    def empty_ext(self, n_cts) -> torch.Tensor:
+        """Room for n_cts ciphertexts in transformed form (cache_extend output)."""
+        return torch.empty(n_cts, int(self.sizes.ct_ext_bytes) // 8, dtype=torch.float64, device=self.device)
+
+    def cache_extend(self, cts, n_groups, group_len, group_stride_cts, ext):
+        self._check(self.lib.dll.cg_cache_extend(self.h, self.stream, _ptr(cts), n_groups, group_len,
+                                                 group_stride_cts, _ptr(ext)))
+        return ext
+
+    def decode_scores_ext(self, q, kext, heads, n_cts, d2, rlk, gk_fold, out=None, cache_stride_cts=None):
+        out = self.empty_ct(heads, n_cts) if out is None else out
+        ws = self.workspace(heads * n_cts)
+        stride = n_cts if cache_stride_cts is None else cache_stride_cts
+        self._check(self.lib.dll.cg_decode_scores_ext(self.h, self.stream, _ptr(q), _ptr(kext), heads, n_cts, stride,
+                                                      d2, _ptr(rlk), self._keys(gk_fold), _ptr(out), _ptr(ws)))
+        return out
+
+    def decode_context_ext(self, a, vext, heads, n_cts, d2, rlk, gk_block, out=None, cache_stride_cts=None):
+        out = self.empty_ct(heads) if out is None else out
+        ws = self.workspace(heads * n_cts)
+        stride = n_cts if cache_stride_cts is None else cache_stride_cts
+        self._check(self.lib.dll.cg_decode_context_ext(self.h, self.stream, _ptr(a), _ptr(vext), heads, n_cts, stride,
+                                                       d2, _ptr(rlk), self._keys(gk_block), _ptr(out), _ptr(ws)))
+        return out
+
     def decode_step(self, q, a, cache, heads, n_cts, cache_stride_cts, d2, tau, rows, masks, rlk, gk_fold,
-                    gk_block, scores=None, context=None):
+                    gk_block, scores=None, context=None, cache_ext=None):
         scores = self.empty_ct(heads, n_cts) if scores is None else scores
         context = self.empty_ct(heads) if context is None else context
         need = int(self.lib.dll.cg_decode_step_workspace_bytes(self.h, heads, n_cts))
@@ -282,10 +313,16 @@ class Context:
         if self._ws_step is None or self._ws_step.numel() < need:
             self._ws_step = None
             self._ws_step = torch.empty(need, dtype=torch.uint8, device=self.device)
-        self._check(self.lib.dll.cg_decode_step(
-            self.h, self.stream, _ptr(q), _ptr(a), _ptr(cache), heads, n_cts, cache_stride_cts, d2, tau,
-            _ptr(rows), _ptr(masks), _ptr(rlk), self._keys(gk_fold), self._keys(gk_block), _ptr(scores),
-            _ptr(context), _ptr(self._ws_step)))
+        if cache_ext is None:
+            self._check(self.lib.dll.cg_decode_step(
+                self.h, self.stream, _ptr(q), _ptr(a), _ptr(cache), heads, n_cts, cache_stride_cts, d2, tau,
+                _ptr(rows), _ptr(masks), _ptr(rlk), self._keys(gk_fold), self._keys(gk_block), _ptr(scores),
+                _ptr(context), _ptr(self._ws_step)))
+        else:
+            self._check(self.lib.dll.cg_decode_step_ext(
+                self.h, self.stream, _ptr(q), _ptr(a), _ptr(cache), _ptr(cache_ext), heads, n_cts, cache_stride_cts,
+                d2, tau, _ptr(rows), _ptr(masks), _ptr(rlk), self._keys(gk_fold), self._keys(gk_block),
+                _ptr(scores), _ptr(context), _ptr(self._ws_step)))
         return scores, context
 
     def decode_scores_outer(self, q, kcols, heads, d2, masks, rlk, gk_fold, out=None):

@@ -347,6 +347,7 @@ extern "C" int cg_get_sizes(const cg_ctx *c, cg_sizes *o)
     o->ksk_bytes = o->ksk_raw_bytes;
     o->plain_bytes = (size_t)c->k * limb_bytes(c);
     o->ws_bytes_per_unit = (size_t)c->ws_total * limb_bytes(c);
+    o->ct_ext_bytes = 2 * (size_t)c->KL * limb_bytes(c);
     return CG_OK;
 }
 
@@ -449,37 +450,46 @@ static unsigned pw_blocks(const cg_ctx *c, size_t rows) { return (unsigned)((row
         CG_TRY(check_launch());                                                                        \
     } while (0)
 
+// Every polynomial named by src -> its transform over the k ciphertext primes and the l auxiliary
+// primes (centred lift), rows dst[poly][k+l][N], lazy.
+static int transform_ext(cg_ctx *c, hipStream_t s, const MulSrc &src, size_t polys, double *dst)
+{
+    const double LB = (double)limb_bytes(c);
+    const double in_rows = (double)polys * c->k;
+    const StF64 st{dst, c->logn};
+    CG_TRY(launch_fwd(c, s, polys * c->k, LdMulQ{src}, st, KID_FWD_MULQ, LB * 2.0 * in_rows));
+    const double aux_bytes = LB * (in_rows + (double)polys * c->l);
+    switch (c->k) {
+    case 1: return launch_fwd(c, s, polys * c->l, LdMulAux<1>{src}, st, KID_FWD_MULB, aux_bytes);
+    case 2: return launch_fwd(c, s, polys * c->l, LdMulAux<2>{src}, st, KID_FWD_MULB, aux_bytes);
+    case 3: return launch_fwd(c, s, polys * c->l, LdMulAux<3>{src}, st, KID_FWD_MULB, aux_bytes);
+    case 4: return launch_fwd(c, s, polys * c->l, LdMulAux<4>{src}, st, KID_FWD_MULB, aux_bytes);
+    case 5: return launch_fwd(c, s, polys * c->l, LdMulAux<5>{src}, st, KID_FWD_MULB, aux_bytes);
+    default: return launch_fwd(c, s, polys * c->l, LdMulAux<6>{src}, st, KID_FWD_MULB, aux_bytes);
+    }
+}
+
 // Algorithmic bytes (distinct inputs read once + outputs written once) are attached to every
 // launch for the roofline report; LB = bytes of one residue row.
 // b ciphertext of unit u sits at index (u / b_group) * b_stride + u % b_group (b_group = 0: dense)
 static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *b2, uint64_t *out3,
                   uint32_t batch, uint32_t a_group, void *ws, int accumulate, uint32_t b_group = 0,
-                  uint32_t b_stride = 0)
+                  uint32_t b_stride = 0, const double *b_ext = nullptr)
 {
+    // b_ext: the b operands are already in transformed extended-basis form (cg_cache_extend);
+    // only the a operands are transformed here
     if (!b_group) { b_group = batch; b_stride = batch; }
     const uint32_t n_a = (batch + a_group - 1) / a_group;
-    const size_t polys = 2 * ((size_t)n_a + batch);
+    const size_t polys = 2 * ((size_t)n_a + (b_ext ? 0 : batch));
     Bump w = bump(c, ws);
     double *ntt = w.take<double>(polys * c->KL);
     double *tens = w.take<double>((size_t)3 * c->KL * batch);
     const double LB = (double)limb_bytes(c), B = batch;
-    const double in_rows = (double)polys * c->k;
-    const MulSrc src{a2, b2, (int)n_a, (int)b_group, (int)b_stride, c->logn};
-    const StF64 st{ntt, c->logn};
-    CG_TRY(launch_fwd(c, s, polys * c->k, LdMulQ{src}, st, KID_FWD_MULQ, LB * 2.0 * in_rows));
-    const double aux_bytes = LB * (in_rows + (double)polys * c->l);
-    int rc;
-    switch (c->k) {
-    case 1: rc = launch_fwd(c, s, polys * c->l, LdMulAux<1>{src}, st, KID_FWD_MULB, aux_bytes); break;
-    case 2: rc = launch_fwd(c, s, polys * c->l, LdMulAux<2>{src}, st, KID_FWD_MULB, aux_bytes); break;
-    case 3: rc = launch_fwd(c, s, polys * c->l, LdMulAux<3>{src}, st, KID_FWD_MULB, aux_bytes); break;
-    case 4: rc = launch_fwd(c, s, polys * c->l, LdMulAux<4>{src}, st, KID_FWD_MULB, aux_bytes); break;
-    case 5: rc = launch_fwd(c, s, polys * c->l, LdMulAux<5>{src}, st, KID_FWD_MULB, aux_bytes); break;
-    default: rc = launch_fwd(c, s, polys * c->l, LdMulAux<6>{src}, st, KID_FWD_MULB, aux_bytes); break;
-    }
-    CG_TRY(rc);
-    CG_LAUNCH_PW(KID_TENSOR, LB * c->KL * ((double)polys + 3.0 * B), tensor_kernel,
-                 pw_blocks(c, (size_t)batch * c->KL), ntt, tens, (int)batch, (int)a_group, (int)n_a, c->dc);
+    const MulSrc src{a2, b2, (int)n_a, (int)b_group, (int)b_stride, c->logn, 0};
+    CG_TRY(transform_ext(c, s, src, polys, ntt));
+    CG_LAUNCH_PW(KID_TENSOR, LB * c->KL * (2.0 * ((double)n_a + B) + 3.0 * B), tensor_kernel,
+                 pw_blocks(c, (size_t)batch * c->KL), ntt, tens, (int)batch, (int)a_group, (int)n_a, b_ext,
+                 (int)b_group, (int)b_stride, c->dc);
     const size_t rows = (size_t)batch * 3 * c->KL;
     CG_TRY(launch_inv(c, s, rows, LdInvF64{tens, nullptr, c->KL, c->logn}, StInvF64{tens, c->logn}, KID_INV_F64,
                       LB * 2.0 * rows));
@@ -736,11 +746,13 @@ static int rotate_add_chain(cg_ctx *c, hipStream_t s, uint64_t *x0, uint64_t *x1
     return CG_OK;
 }
 
-extern "C" int cg_decode_scores(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kc, uint32_t heads,
-                                uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
-                                const void *const *gk_fold, uint64_t *out, void *ws)
+// kext != null: the cache in transformed form (kc is then not read)
+static int scores_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kc, const double *kext,
+                       uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
+                       const void *const *gk_fold, uint64_t *out, void *ws)
 {
-    CG_REQUIRE(c && ptrs_ok({q, kc, rlk, out, ws}) && gk_fold && heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
+    CG_REQUIRE(c && ptrs_ok({q, kext ? (const void *)kext : (const void *)kc, rlk, out, ws}) && gk_fold &&
+               heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
     CG_REQUIRE(cache_stride_cts >= n_cts);
     const uint32_t batch = heads * n_cts;
     CG_REQUIRE(batch_ok(batch));
@@ -754,16 +766,31 @@ extern "C" int cg_decode_scores(cg_ctx *c, void *stream, const uint64_t *q, cons
     Bump w = bump(c, ws);
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
     uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * batch), *xb = w.take<uint64_t>((size_t)2 * c->k * batch);
-    CG_TRY(do_mul(c, s, q, kc, d3, batch, n_cts, w.p, 0, n_cts, cache_stride_cts));
+    CG_TRY(do_mul(c, s, q, kc, d3, batch, n_cts, w.p, 0, n_cts, cache_stride_cts, kext));
     CG_TRY(do_relin(c, s, d3, rlk, xa, batch, w.p));
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_fold, nrot, batch, w.p);
 }
-
-extern "C" int cg_decode_context(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, uint32_t heads,
-                                 uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
-                                 const void *const *gk_block, uint64_t *out, void *ws)
+extern "C" int cg_decode_scores(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kc, uint32_t heads,
+                                uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
+                                const void *const *gk_fold, uint64_t *out, void *ws)
 {
-    CG_REQUIRE(c && ptrs_ok({a, vc, rlk, out, ws}) && gk_block && heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
+    return scores_impl(c, stream, q, kc, nullptr, heads, n_cts, cache_stride_cts, d2, rlk, gk_fold, out, ws);
+}
+extern "C" int cg_decode_scores_ext(cg_ctx *c, void *stream, const uint64_t *q, const void *kext, uint32_t heads,
+                                    uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
+                                    const void *const *gk_fold, uint64_t *out, void *ws)
+{
+    CG_REQUIRE(kext);
+    return scores_impl(c, stream, q, nullptr, static_cast<const double *>(kext), heads, n_cts, cache_stride_cts, d2,
+                       rlk, gk_fold, out, ws);
+}
+
+static int context_impl(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, const double *vext,
+                        uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
+                        const void *const *gk_block, uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({a, vext ? (const void *)vext : (const void *)vc, rlk, out, ws}) && gk_block &&
+               heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
     CG_REQUIRE(cache_stride_cts >= n_cts);
     const uint32_t batch = heads * n_cts;
     CG_REQUIRE(batch_ok(batch));
@@ -777,13 +804,37 @@ extern "C" int cg_decode_context(cg_ctx *c, void *stream, const uint64_t *a, con
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
     uint64_t *y = w.take<uint64_t>((size_t)3 * c->k * heads);
     uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * heads), *xb = w.take<uint64_t>((size_t)2 * c->k * heads);
-    CG_TRY(do_mul(c, s, a, vc, d3, batch, 1, w.p, 0, n_cts, cache_stride_cts));
+    CG_TRY(do_mul(c, s, a, vc, d3, batch, 1, w.p, 0, n_cts, cache_stride_cts, vext));
     // y[h] = sum_c d3[h][c]  (three components)
     const int rows = 3 * c->k;
     CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), sum_groups_kernel,
                  pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)n_cts, rows, c->dc);
     CG_TRY(do_relin(c, s, y, rlk, xa, heads, w.p));
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, heads, w.p);
+}
+extern "C" int cg_decode_context(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, uint32_t heads,
+                                 uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
+                                 const void *const *gk_block, uint64_t *out, void *ws)
+{
+    return context_impl(c, stream, a, vc, nullptr, heads, n_cts, cache_stride_cts, d2, rlk, gk_block, out, ws);
+}
+extern "C" int cg_decode_context_ext(cg_ctx *c, void *stream, const uint64_t *a, const void *vext, uint32_t heads,
+                                     uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
+                                     const void *const *gk_block, uint64_t *out, void *ws)
+{
+    CG_REQUIRE(vext);
+    return context_impl(c, stream, a, nullptr, static_cast<const double *>(vext), heads, n_cts, cache_stride_cts, d2,
+                        rlk, gk_block, out, ws);
+}
+
+extern "C" int cg_cache_extend(cg_ctx *c, void *stream, const uint64_t *cts, uint32_t n_groups, uint32_t group_len,
+                               uint32_t group_stride_cts, void *ext)
+{
+    CG_REQUIRE(c && ptrs_ok({cts, ext}) && n_groups >= 1 && group_len >= 1 && group_stride_cts >= group_len);
+    CG_REQUIRE((uint64_t)n_groups * group_len <= (1u << 16));
+    const MulSrc src{nullptr, cts, 0, (int)group_len, (int)group_stride_cts, c->logn, 1};
+    return transform_ext(c, static_cast<hipStream_t>(stream), src, (size_t)2 * n_groups * group_len,
+                         static_cast<double *>(ext));
 }
 
 extern "C" size_t cg_decode_step_workspace_bytes(const cg_ctx *c, uint32_t heads, uint32_t n_cts)
@@ -792,10 +843,12 @@ extern "C" size_t cg_decode_step_workspace_bytes(const cg_ctx *c, uint32_t heads
     return 2 * cg_workspace_bytes(c, heads * n_cts) + cg_workspace_bytes(c, 2 * heads);
 }
 
-extern "C" int cg_decode_step(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *a, uint64_t *cache,
-                              uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, uint32_t tau,
-                              const uint64_t *rows, const void *masks, const void *rlk, const void *const *gk_fold,
-                              const void *const *gk_block, uint64_t *scores, uint64_t *context, void *ws)
+// ext != null: the cache's transformed copy is read by the products and brought up to date for
+// the appended ciphertext of every cache
+static int step_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *a, uint64_t *cache, double *ext,
+                     uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, uint32_t tau,
+                     const uint64_t *rows, const void *masks, const void *rlk, const void *const *gk_fold,
+                     const void *const *gk_block, uint64_t *scores, uint64_t *context, void *ws)
 {
     CG_REQUIRE(c && ptrs_ok({q, a, cache, rows, masks, rlk, scores, context, ws}) && gk_fold && gk_block);
     CG_REQUIRE(heads >= 1 && n_cts >= 1 && batch_ok(heads * n_cts) && pow2_d(c, d2) && cache_stride_cts >= n_cts);
@@ -806,22 +859,31 @@ extern "C" int cg_decode_step(cg_ctx *c, void *stream, const uint64_t *q, const 
     char *ws_scores = static_cast<char *>(ws);
     char *ws_context = ws_scores + cg_workspace_bytes(c, heads * n_cts);
     char *ws_append = ws_context + cg_workspace_bytes(c, heads * n_cts);
+    const size_t ext_ct = (size_t)2 * c->KL * c->N;          // doubles per transformed ciphertext
+    const uint32_t app_idx = tau / ((uint32_t)c->N / d2);
+    const double *kext = ext, *vext = ext ? ext + (size_t)heads * cache_stride_cts * ext_ct : nullptr;
+    // append, then (with a transformed copy) re-transform the ciphertext every cache just received
+    auto append = [&](hipStream_t st) -> int {
+        CG_TRY(cg_kv_append(c, st, cache, cache_stride_cts, 2 * heads, tau, rows, masks, d2, ws_append));
+        if (!ext) return CG_OK;
+        return cg_cache_extend(c, st, cache + (size_t)app_idx * ct2, 2 * heads, 1, cache_stride_cts,
+                               ext + (size_t)app_idx * ext_ct);
+    };
     // The appended ciphertext is read by this step's products only when it lies inside the first
     // n_cts: then the append goes first on the caller's stream; otherwise it is a third branch.
     const bool append_first = tau / ((uint32_t)c->N / d2) < n_cts;
-    if (append_first)
-        CG_TRY(cg_kv_append(c, s, cache, cache_stride_cts, 2 * heads, tau, rows, masks, d2, ws_append));
+    if (append_first) CG_TRY(append(s));
     CG_HIP(hipEventRecord(c->ev_fork, s));
     CG_HIP(hipStreamWaitEvent(c->side[0], c->ev_fork, 0));
     if (!append_first) CG_HIP(hipStreamWaitEvent(c->side[1], c->ev_fork, 0));
     // Branches are always joined, also after a failed launch, so that the caller's stream never
     // runs ahead of work this call started.
-    int rc = cg_decode_scores(c, s, q, cache, heads, n_cts, cache_stride_cts, d2, rlk, gk_fold, scores, ws_scores);
-    const int rc1 = cg_decode_context(c, c->side[0], a, vcache, heads, n_cts, cache_stride_cts, d2, rlk, gk_block,
-                                      context, ws_context);
+    int rc = scores_impl(c, s, q, cache, kext, heads, n_cts, cache_stride_cts, d2, rlk, gk_fold, scores, ws_scores);
+    const int rc1 = context_impl(c, c->side[0], a, vcache, vext, heads, n_cts, cache_stride_cts, d2, rlk, gk_block,
+                                 context, ws_context);
     if (rc == CG_OK) rc = rc1;
     if (!append_first) {
-        const int rc2 = cg_kv_append(c, c->side[1], cache, cache_stride_cts, 2 * heads, tau, rows, masks, d2, ws_append);
+        const int rc2 = append(c->side[1]);
         if (rc == CG_OK) rc = rc2;
     }
     for (int i = 0; i < (append_first ? 1 : 2); i++) {
@@ -829,6 +891,25 @@ extern "C" int cg_decode_step(cg_ctx *c, void *stream, const uint64_t *q, const 
         CG_HIP(hipStreamWaitEvent(s, c->ev_join[i], 0));
     }
     return rc;
+}
+
+extern "C" int cg_decode_step(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *a, uint64_t *cache,
+                              uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, uint32_t tau,
+                              const uint64_t *rows, const void *masks, const void *rlk, const void *const *gk_fold,
+                              const void *const *gk_block, uint64_t *scores, uint64_t *context, void *ws)
+{
+    return step_impl(c, stream, q, a, cache, nullptr, heads, n_cts, cache_stride_cts, d2, tau, rows, masks, rlk, gk_fold,
+                     gk_block, scores, context, ws);
+}
+extern "C" int cg_decode_step_ext(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *a, uint64_t *cache,
+                                  void *cache_ext, uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts,
+                                  uint32_t d2, uint32_t tau, const uint64_t *rows, const void *masks, const void *rlk,
+                                  const void *const *gk_fold, const void *const *gk_block, uint64_t *scores,
+                                  uint64_t *context, void *ws)
+{
+    CG_REQUIRE(cache_ext && aligned16(cache_ext));
+    return step_impl(c, stream, q, a, cache, static_cast<double *>(cache_ext), heads, n_cts, cache_stride_cts, d2, tau,
+                     rows, masks, rlk, gk_fold, gk_block, scores, context, ws);
 }
 
 extern "C" int cg_decode_scores_outer(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kcols,

@@ -604,6 +604,13 @@ struct LdRowsU64 {
 struct MulSrc {
     const uint64_t *cta, *ctb;
     int n_a, b_group, b_stride, logn;   // b ciphertext of unit u: (u / b_group) * b_stride + u % b_group
+    int dst_strided;                    // transformed rows land at the source's (strided) ciphertext index
+    __device__ __forceinline__ int dst_poly(int pp) const
+    {
+        if (!dst_strided) return pp;
+        const int u = (pp >> 1) - n_a;
+        return 2 * ((u / b_group) * b_stride + u % b_group) + (pp & 1);
+    }
     __device__ __forceinline__ const uint64_t *poly(int pp, int k) const
     {
         const int ct = pp >> 1, comp = pp & 1;
@@ -625,7 +632,7 @@ struct LdMulQ {     // workgroup -> (pp, ciphertext prime i)
     __device__ __forceinline__ int share(const DevConst *) const { return 1; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *C) const
     {
-        return (wg / C->k) * C->KL + wg % C->k;
+        return src.dst_poly(wg / C->k) * C->KL + wg % C->k;
     }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
@@ -649,7 +656,7 @@ struct LdMulAux {
     __device__ __forceinline__ int share(const DevConst *C) const { return C->l; }
     __device__ __forceinline__ int dst_limb(int wg, const DevConst *C) const
     {
-        return (wg / C->l) * C->KL + C->k + wg % C->l;
+        return src.dst_poly(wg / C->l) * C->KL + C->k + wg % C->l;
     }
     __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
     {
@@ -877,10 +884,11 @@ constexpr int PW_THREADS = 256;
 
 // tensor product in the transform domain over all k+l primes:
 // ntt[pp][r][n] (lazy) -> tens[u*3+c][r][n] (lazy); a polys of unit u: pp = 2*(u / a_group) + {0,1},
-// b polys: pp = 2*(n_a + u) + {0,1}
+// b polys: pp = 2*(n_a + u) + {0,1}, or, with bext given, the transformed ciphertext
+// bext[(u / b_group) * b_stride + u % b_group] ([2][k+l][N] each)
 __global__ void __launch_bounds__(PW_THREADS)
 tensor_kernel(const double *__restrict__ ntt, double *__restrict__ tens, int batch, int a_group, int n_a,
-              const DevConst *__restrict__ C)
+              const double *__restrict__ bext, int b_group, int b_stride, const DevConst *__restrict__ C)
 {
     const int logn = C->logn, N = 1 << logn, KL = C->KL;
     const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
@@ -891,7 +899,8 @@ tensor_kernel(const double *__restrict__ ntt, double *__restrict__ tens, int bat
     const ModD m = C->mod[r];
     const size_t pstride = (size_t)KL << logn;
     const double *sa = ntt + (size_t)(2 * (u / a_group)) * pstride + ((size_t)r << logn) + n;
-    const double *sb = ntt + (size_t)(2 * (n_a + u)) * pstride + ((size_t)r << logn) + n;
+    const double *sb = (bext ? bext + (size_t)(2 * ((u / b_group) * b_stride + u % b_group)) * pstride
+                             : ntt + (size_t)(2 * (n_a + u)) * pstride) + ((size_t)r << logn) + n;
     // forward outputs are lazy (< 4p); bring them to p/2 so the two-term sum stays far below 2^53
     const double a0 = red(sa[0], m), a1 = red(sa[pstride], m);
     const double b0 = red(sb[0], m), b1 = red(sb[pstride], m);

@@ -160,20 +160,26 @@ def test_c5_scaled_decode_steps_with_cache_growth():
     compare(got, want, "C5")
 
 
-def test_c4_decode_step_entry_point_three_branches():
+@pytest.mark.parametrize("transformed_cache", [False, True])
+def test_c4_decode_step_entry_point_three_branches(transformed_cache):
     """The one-call step (append of token 512 opens ciphertext 5, so all three branches run
-    side by side) against the same digests."""
-    say("C4 decode_step")
+    side by side) against the same digests; also with the cache's transformed copy beside it."""
+    say(f"C4 decode_step transformed_cache={transformed_cache}")
     st, want = configs.c4_inputs(), load("C4")
     g = Gpu(st["prm"])
     d = _decode_state(g, st)
     H, C, S, d2 = st["heads"], st["n_cts"], st["stride"], st["d2"]
     cache = g.dev(st["cache"])
     q, a, rows = g.dev(st["q"]), g.dev(st["a"]), g.dev(st["rows"])
+    ext = None
+    if transformed_cache:
+        ext = g.ctx.empty_ext(2 * H * S)
+        ext.fill_(float("nan"))
+        g.ctx.cache_extend(cache, 2 * H, C, S, ext)      # the ciphertexts the products read
     for rep in range(2):    # the second call reuses streams, events and workspace
         cache.copy_(g.dev(st["cache"]))
         scores, context = g.ctx.decode_step(q, a, cache, H, C, S, d2, st["tau"], rows, d["masks"], d["rlk"],
-                                            d["fold"], d["block"])
+                                            d["fold"], d["block"], cache_ext=ext)
         scores, context, cache_h = g.host(scores), g.host(context), g.host(cache)
         got = {}
         for h in range(H):
@@ -186,23 +192,31 @@ def test_c4_decode_step_entry_point_three_branches():
         compare(got, want, f"C4 decode_step call {rep}")
 
 
-def test_c5_decode_step_entry_point_append_feeds_products():
+@pytest.mark.parametrize("transformed_cache", [False, True])
+def test_c5_decode_step_entry_point_append_feeds_products(transformed_cache):
     """The one-call step where the appended ciphertext is read by the products (append first,
-    then two branches), over successive steps with cache growth."""
+    then two branches), over successive steps with cache growth; with a transformed copy of
+    the cache, the copy of the growing ciphertext has to be refreshed by every step."""
     from tests.golden.make_digests import C5_STEPS
-    say("C5 decode_step")
+    say(f"C5 decode_step transformed_cache={transformed_cache}")
     st, want = configs.c5_inputs(), load("C5")
     g = Gpu(st["prm"])
     d = _decode_state(g, st)
     H, S, d2, B = st["heads"], st["stride"], st["d2"], st["B"]
     cache = g.dev(st["cache"])
+    ext = None
+    if transformed_cache:
+        ext = g.ctx.empty_ext(2 * H * S)
+        ext.fill_(float("nan"))
+        g.ctx.cache_extend(cache, 2 * H, 512 // B, S, ext)   # the full ciphertexts; the growing one is refreshed per step
     got = {}
     for i in range(C5_STEPS):
         si = st["step_inputs"](i)
         tau, C = 512 + i, si["n_cts"]
         assert tau // B < C
         scores, context = g.ctx.decode_step(g.dev(si["q"]), g.dev(si["a"]), cache, H, C, S, d2, tau,
-                                            g.dev(si["rows"]), d["masks"], d["rlk"], d["fold"], d["block"])
+                                            g.dev(si["rows"]), d["masks"], d["rlk"], d["fold"], d["block"],
+                                            cache_ext=ext)
         scores, context, cache_h = g.host(scores), g.host(context), g.host(cache)
         idx = tau // B
         for c in range(2 * H):

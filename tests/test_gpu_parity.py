@@ -200,11 +200,22 @@ def test_decode_scores_match_oracle(env):
     q, kc = env.cts(71, heads), env.cts(72, heads * n_cts)
     got = env.host(env.ctx.decode_scores(env.dev(q), env.dev(kc), heads, n_cts, d2, rlk,
                                          [keys[g][1] for g in gs]))
+    # the same call reading the cache in transformed form (strided: one spare ciphertext per head)
+    stride = n_cts + 1
+    spaced = np.zeros((heads * stride,) + kc.shape[1:], dtype=kc.dtype)
+    for h in range(heads):
+        spaced[h * stride:h * stride + n_cts] = kc[h * n_cts:(h + 1) * n_cts]
+    ext = env.ctx.empty_ext(heads * stride)
+    ext.fill_(float("nan"))                              # entries that are not extended must not be read
+    env.ctx.cache_extend(env.dev(spaced), heads, n_cts, stride, ext)
+    got_ext = env.host(env.ctx.decode_scores_ext(env.dev(q), ext, heads, n_cts, d2, rlk, [keys[g][1] for g in gs],
+                                                 cache_stride_cts=stride))
     raws = {g: keys[g][0] for g in gs}
     for h in range(heads):
         for c in range(n_cts):
             want = attention.decode_scores(env.orc, q[h], kc[h * n_cts + c], raw_rlk, raws, d2)
             assert np.array_equal(got[h, c], want), (env.name, h, c)
+            assert np.array_equal(got_ext[h, c], want), (env.name, h, c, "transformed cache")
 
 
 def test_decode_context_match_oracle(env):
@@ -217,11 +228,14 @@ def test_decode_context_match_oracle(env):
     a, vc = env.cts(81, heads * n_cts), env.cts(82, heads * n_cts)
     got = env.host(env.ctx.decode_context(env.dev(a), env.dev(vc), heads, n_cts, d2, rlk,
                                           [keys[g][1] for g in gs]))
+    ext = env.ctx.cache_extend(env.dev(vc), heads, n_cts, n_cts, env.ctx.empty_ext(heads * n_cts))
+    got_ext = env.host(env.ctx.decode_context_ext(env.dev(a), ext, heads, n_cts, d2, rlk, [keys[g][1] for g in gs]))
     raws = {g: keys[g][0] for g in gs}
     for h in range(heads):
         sl = slice(h * n_cts, (h + 1) * n_cts)
         want = attention.decode_context(env.orc, list(a[sl]), list(vc[sl]), raw_rlk, raws, d2)
         assert np.array_equal(got[h], want), (env.name, h)
+        assert np.array_equal(got_ext[h], want), (env.name, h, "transformed cache")
 
 
 def test_prefill_diagonals_match_oracle():
