@@ -31,7 +31,9 @@
  *               Invalid arguments are rejected before any kernel is launched.
  *   aliasing    outputs must not overlap inputs unless stated.
  *   threads     a context may be used from several host threads as long as
- *               concurrent calls use distinct workspaces.
+ *               concurrent calls use distinct workspaces; cg_decode_step and
+ *               cg_decode_step_ext use streams and events owned by the context,
+ *               so a context runs one of them at a time.
  *
  * Where the paper is cited: "section 4.3" is Auto-Regressive
  * Ciphertext-Ciphertext Multiplication (ARCC), "section 4.4" Encrypted
