@@ -436,3 +436,86 @@ def test_prefill_repack_match_oracle(name, heads, d2):
         want = attention.prefill_repack(env.orc, list(x[h * m:(h + 1) * m]), mask_pt, raws, d2)
         for i, wv in enumerate(want):
             assert np.array_equal(got[h * (m // w) + i], wv), (name, h, i)
+
+
+def test_invalid_arguments_of_the_step_and_prompt_entry_points():
+    import torch
+    from paper_2602_08798_amd.binding import CgError
+    env = _envs.get("C1") or Env("C1")
+    _envs["C1"] = env
+    say("negative tests, composite entry points")
+    n, d2 = env.n, 64
+    B = n // d2
+    heads, n_cts, stride = 1, 1, 2
+    x = env.dev(env.cts(1, 2 * heads * stride))
+    q = env.dev(env.cts(2, heads))
+    rows = env.dev(env.cts(3, 2 * heads))
+    raw, key = env.key(30)
+    fold = [key] * 6
+    block = [key] * (len(_block_keys(env, d2)))
+    masks = env.ctx.plain_prepare(env.dev(np.zeros((B, n), dtype=np.uint64)))
+    step = lambda **kw: env.ctx.decode_step(q, q, x, heads, kw.get("n_cts", n_cts), kw.get("stride", stride),
+                                            kw.get("d2", d2), kw.get("tau", 0), rows, masks, key, fold, block)
+    before = env.host(x).copy()
+    with pytest.raises(CgError):
+        step(tau=stride * B)                             # token beyond the last cache ciphertext
+    with pytest.raises(CgError):
+        step(n_cts=3)                                    # more ciphertexts than a cache holds
+    with pytest.raises(CgError):
+        step(d2=48)                                      # block size must be a power of two
+    with pytest.raises(CgError):
+        env.ctx.decode_step(q, q, x, 1 << 15, 4, 4, d2, 0, rows, masks, key, fold, block)   # batch too large
+    with pytest.raises(CgError):
+        env.ctx.cache_extend(x, 2, 3, 2, env.ctx.empty_ext(4))      # group longer than its stride
+    with pytest.raises(CgError):
+        env.ctx.prefill_av(x, q, 1, 48, key, key, key)
+    with pytest.raises(CgError):
+        env.ctx.prefill_repack(x, 1, n // 2, masks, [key])     # d2 above N/4
+    assert np.array_equal(env.host(x), before)           # nothing was launched on the cache
+    torch.cuda.synchronize()
+
+
+def test_decode_step_edge_shapes_match_oracle():
+    """One head and one cache ciphertext; tokens at the first and the last block of a ciphertext; the
+    smallest head dimension the fold accepts (d2 = 2: a single fold rotation, log2(N/4) block rotations)
+    and the largest (d2 = N/4: two blocks per slot row)."""
+    from oracle import attention
+    env = _envs.get("C1") or Env("C1")
+    _envs["C1"] = env
+    n = env.n
+    raw_rlk, rlk = env.key(70)
+    for d2, taus in ((2, (0, n // 2 - 1)), (n // 4, (0, 3, 4))):
+        B = n // d2
+        say(f"decode_step edge shapes C1, d2 = {d2}, tokens {taus}")
+        gs_f, gs_b = _fold_keys(env, d2), _block_keys(env, d2)
+        kf = {g: env.key(500 + i) for i, g in enumerate(gs_f)}
+        kb = {g: env.key(520 + i) for i, g in enumerate(gs_b)}
+        rng = np.random.default_rng(7 + d2)
+        # only the masks the tokens use are prepared (B can be thousands)
+        blocks = sorted({t % B for t in taus})
+        masks_pt = np.zeros((max(blocks) + 1, n), dtype=np.uint64)
+        for b in blocks:
+            masks_pt[b] = rng.integers(0, env.prm.t, n, dtype=np.uint64)
+        masks = env.ctx.plain_prepare(env.dev(masks_pt))
+        heads, stride = 1, 2
+        cache = env.cts(600 + d2, 2 * heads * stride)
+        want_cache = cache.copy()
+        dcache = env.dev(cache)
+        for tau in taus:
+            idx, blk = divmod(tau, B)
+            n_cts = idx + 1                              # the appended ciphertext is read by the products
+            q, a, rows = env.cts(610 + tau, heads), env.cts(620 + tau, heads * n_cts), env.cts(630 + tau, 2 * heads)
+            scores, context = env.ctx.decode_step(env.dev(q), env.dev(a), dcache, heads, n_cts, stride, d2, tau,
+                                                  env.dev(rows), masks, rlk, [kf[g][1] for g in gs_f],
+                                                  [kb[g][1] for g in gs_b])
+            for c in range(2 * heads):
+                masked = env.orc.mul_plain(rows[c], masks_pt[blk])
+                want_cache[c * stride + idx] = masked if blk == 0 else env.orc.add(want_cache[c * stride + idx], masked)
+            assert np.array_equal(env.host(dcache), want_cache), (d2, tau)
+            scores, context = env.host(scores), env.host(context)
+            for c in range(n_cts):
+                w = attention.decode_scores(env.orc, q[0], want_cache[c], raw_rlk, {g: kf[g][0] for g in gs_f}, d2)
+                assert np.array_equal(scores[0, c], w), (d2, tau, c)
+            w = attention.decode_context(env.orc, list(a), list(want_cache[stride:stride + n_cts]), raw_rlk,
+                                         {g: kb[g][0] for g in gs_b}, d2)
+            assert np.array_equal(context[0], w), (d2, tau)
