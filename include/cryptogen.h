@@ -33,7 +33,8 @@
  *   threads     a context may be used from several host threads as long as
  *               concurrent calls use distinct workspaces; cg_decode_step and
  *               cg_decode_step_ext use streams and events owned by the context,
- *               so a context runs one of them at a time.
+ *               and cg_ntt_forward / cg_ntt_inverse an index table owned by it,
+ *               so a context runs one of each of these at a time.
  *
  * Where the paper is cited: "section 4.3" is Auto-Regressive
  * Ciphertext-Ciphertext Multiplication (ARCC), "section 4.4" Encrypted
