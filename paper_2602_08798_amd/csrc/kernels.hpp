@@ -972,7 +972,10 @@ __global__ void __launch_bounds__(PW_THREADS)
 moddown_kernel(ModdownArgs A, const DevConst *__restrict__ C)
 {
     const int logn = C->logn, N = 1 << logn, k = C->k, nsp = C->nsp, L = C->L;
-    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    // the N / PW_THREADS blocks of one (unit, component) run on one XCD: the permuted reads of a
+    // c0 row touch all of its cache lines, which that XCD's L2 then fetches once instead of once
+    // per XCD
+    const size_t gid = (size_t)xcd_row((int)blockIdx.x, (int)gridDim.x, N / PW_THREADS) * PW_THREADS + threadIdx.x;
     const int n = (int)(gid & (N - 1));
     const int bc = (int)(gid >> logn);
     if (bc >= A.batch * 2) return;
