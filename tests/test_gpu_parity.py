@@ -519,3 +519,23 @@ def test_decode_step_edge_shapes_match_oracle():
             w = attention.decode_context(env.orc, list(a), list(want_cache[stride:stride + n_cts]), raw_rlk,
                                          {g: kb[g][0] for g in gs_b}, d2)
             assert np.array_equal(context[0], w), (d2, tau)
+
+
+@pytest.mark.parametrize("batch", [5, 9, 23])
+def test_rotate_and_mul_relin_at_ragged_batches(batch):
+    """Batches whose row and block counts are not multiples of the XCD-aware launch orders' period
+    (full periods are permuted, the ragged tail is not): every unit still gets its own result."""
+    env = _envs.get("C1") or Env("C1")
+    _envs["C1"] = env
+    say(f"ragged batch {batch} C1")
+    n = env.n
+    raw, key = env.key(30)
+    x = env.cts(700 + batch, batch)
+    g = pow(3, 5, 2 * n)
+    got = env.host(env.ctx.rotate(env.dev(x), g, key, batch, accumulate=True))
+    for u in range(batch):
+        assert np.array_equal(got[u], env.orc.add(x[u], env.orc.rotate(x[u], g, raw))), (batch, u)
+    y = env.cts(800 + batch, batch)
+    got = env.host(env.ctx.mul_relin(env.dev(x), env.dev(y), key, batch))
+    for u in range(batch):
+        assert np.array_equal(got[u], env.orc.relin(env.orc.mul(x[u], y[u]), raw)), (batch, u)
