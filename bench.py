@@ -229,10 +229,11 @@ def main():
         "value": round(ms, 4), "unit": "ms/token (one layer: 12 heads, CT x CT path)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64 (exact integer residues < 2^50 carried in FP64 registers; u64 at the ABI)",
+        "dtype": "f64",
         "data": "synthetic",
         "config": {"workload": "C4: decode step, 12 heads x d=64, 512-token encrypted KV cache, N=8192, "
                                "3+1 primes < 2^50, t=65537", "ops_per_step": ws.op_counts(),
+                   "arithmetic": "exact integer residues < 2^50 carried in FP64 registers; uint64 at the ABI",
                    "derived_12_layers_ms_per_token": round(12 * ms, 3),
                    "launch": "three calls in sequence" if args.serial else
                              "cg_decode_step_ext: scores, context and append side by side on three streams; the "
