@@ -23,10 +23,13 @@ template <> struct Plan<14, 16> { static constexpr int NP = 4, NC = 1; static co
 template <> struct Plan<12, 8> { static constexpr int NP = 4, NC = 1; static constexpr int R[5] = {3, 3, 3, 3, 0}; };
 template <> struct Plan<13, 8> { static constexpr int NP = 5, NC = 2; static constexpr int R[5] = {3, 3, 3, 3, 1}; };
 template <> struct Plan<13, 16> { static constexpr int NP = 4, NC = 1; static constexpr int R[5] = {4, 3, 3, 3, 0}; };
+// The next row is prefetched into registers where that helps: not with two workgroups on a compute
+// unit (each covers the other's load latency), and not at N = 16384, where the prefetched words
+// push the 128-register budget of a 1024-thread workgroup into spilling (measured: C5 step
+// 4.58 -> 4.29 ms without).
+template <int LOGN, int E> constexpr bool prefetch_rows() { return LOGN <= 12 || (LOGN == 13 && E == 8); }
 // waves per SIMD the register allocation must leave room for: the workgroup's own, or, for rows of
 // 8192 on 512 threads, twice that, so that two workgroups share a compute unit (2 x 72 KiB of LDS)
-// with two workgroups on a compute unit each covers the other's load latency: no register prefetch
-template <int LOGN, int E> constexpr bool prefetch_rows() { return !(LOGN == 13 && E == 16); }
 template <int LOGN, int E> constexpr int min_waves() { return (LOGN == 13 && E == 16) ? 4 : ((1 << LOGN) / E) / 256; }
 
 constexpr int ilog2c(int x) { return x <= 1 ? 0 : 1 + ilog2c(x / 2); }
