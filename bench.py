@@ -104,6 +104,33 @@ def timed(torch, fn, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def c5_step_ms(torch, P, steps):
+    """The scaled configuration (16 heads, N = 16384, 6+2 primes): first of its 64 decode steps, where
+    the appended ciphertext is among those the products read."""
+    from workloads import configs
+    st = configs.c5_inputs()
+    ctx = P.Context(st["prm"])
+    H, S, d2 = st["heads"], st["stride"], st["d2"]
+    dev = P.to_device
+    cache = dev(st["cache"])
+    masks = ctx.plain_prepare(dev(st["masks"]))
+    rlk = ctx.ksk_prepare(dev(st["rlk"]))
+    gk = {g: ctx.ksk_prepare(dev(k)) for g, k in st["gk"].items()}
+    fold, block = [gk[g] for g in st["fold"]], [gk[g] for g in st["block"]]
+    si = st["step_inputs"](0)
+    C = si["n_cts"]
+    q, a, rows = dev(si["q"]), dev(si["a"]), dev(si["rows"])
+    scores, context = ctx.empty_ct(H, C), ctx.empty_ct(H)
+    step = lambda: ctx.decode_step(q, a, cache, H, C, S, d2, 512, rows, masks, rlk, fold, block,
+                                   scores=scores, context=context)
+    for _ in range(3):
+        step()
+    ms = timed(torch, step, steps)
+    ctx.close()
+    return {"metric": "C5 scaled decode step ms/token (one layer: 16 heads, N=16384, 6+2 primes, step 0 of 64)",
+            "value": round(ms, 4), "unit": "ms"}
+
+
 def cpu_baseline(ws: DecodeStep, budget_units=(2, 1, 2)):
     """Time the oracle on a sample of the step and compare the GPU outputs of those units."""
     from oracle import Oracle, attention
@@ -222,7 +249,8 @@ def main():
         del a_big, b_big, out_big
         secondary = {"metric": "ct-ct mult+relin/sec at N=8192", "value": round(H * C / (mr_ms * 1e-3), 1),
                      "unit": "1/s", "batch": H * C,
-                     "value_at_batch_%d" % big: round(big / (mrb_ms * 1e-3), 1)}
+                     "value_at_batch_%d" % big: round(big / (mrb_ms * 1e-3), 1),
+                     "scaled_config": c5_step_ms(torch, ws.P, 10)}
 
     result = {
         "metric": "encrypted decode-step ms/token at 512 ctx",
