@@ -17,8 +17,9 @@ steps maintain, this step refreshing the copy of the ciphertexts it appends to);
 Prints ONE JSON line.  `roofline` is for the kernel class with the largest
 share of the step, timed with HIP events by the library itself in a further
 pass over the same work issued as three calls in sequence (so that each
-kernel has the device to itself while it is timed); `cpu_baseline` times the CPU oracle on a bounded sample of the
-same workload (and checks the GPU results against it bit for bit).
+kernel has the device to itself while it is timed); `cpu_baseline` times the
+CPU oracle on the whole step of the same workload (a few seconds on the host's
+cores) and checks every output ciphertext of the GPU step against it.
 """
 import argparse
 import json
