@@ -3,6 +3,7 @@
     python -m paper_2602_08798_amd.microbench modmul   FP64-FMA vs 32-bit-integer Barrett modular multiply
     python -m paper_2602_08798_amd.microbench ntt      forward/inverse transform throughput vs number of rows
     python -m paper_2602_08798_amd.microbench copy     plain device copy of known size (counter calibration)
+    python -m paper_2602_08798_amd.microbench c5curve  the scaled configuration: per-step time over its 64 decode steps
 
 Kernel durations printed by `ntt` include the host-side staging of the prime-index table that the
 public transform entry point performs; use `rocprofv3 --kernel-trace` around it for kernel-only times.
@@ -70,6 +71,38 @@ def copy(mib=256):
     print(f"copy of {mib} MiB (read {mib} MiB + write {mib} MiB): {us:.1f} us  {2 * n * 8 / us / 1e3:.0f} GB/s")
 
 
+def c5curve(steps=64):
+    """16 heads, N = 16384, cache growing from token 512 to 575 (the third ciphertext of every cache
+    fills up; the number of ciphertexts read stays at 3, so the curve is flat by construction)."""
+    import time
+    from workloads import configs
+    from .binding import to_device
+    st = configs.c5_inputs()
+    ctx = Context(st["prm"])
+    H, S, d2 = st["heads"], st["stride"], st["d2"]
+    cache = to_device(st["cache"])
+    masks = ctx.plain_prepare(to_device(st["masks"]))
+    rlk = ctx.ksk_prepare(to_device(st["rlk"]))
+    gk = {g: ctx.ksk_prepare(to_device(k)) for g, k in st["gk"].items()}
+    fold, block = [gk[g] for g in st["fold"]], [gk[g] for g in st["block"]]
+    times = []
+    for i in range(steps):
+        si = st["step_inputs"](i)
+        C = si["n_cts"]
+        q, a, rows = to_device(si["q"]), to_device(si["a"]), to_device(si["rows"])
+        scores, context = ctx.empty_ct(H, C), ctx.empty_ct(H)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.decode_step(q, a, cache, H, C, S, d2, 512 + i, rows, masks, rlk, fold, block, scores=scores,
+                        context=context)
+        torch.cuda.synchronize()
+        times.append((time.perf_counter() - t0) * 1e3)
+        print(f"step {i:2d} token {512 + i} ciphertexts read per cache {C}: {times[-1]:.3f} ms", flush=True)
+    warm = times[2:]
+    print(f"steps 2..{steps - 1}: mean {sum(warm) / len(warm):.3f} ms, min {min(warm):.3f}, max {max(warm):.3f} "
+          f"(single launches, host-timed with a synchronisation per step)")
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "modmul"
-    {"modmul": modmul, "ntt": ntt, "copy": copy}[what]()
+    {"modmul": modmul, "ntt": ntt, "copy": copy, "c5curve": c5curve}[what]()
