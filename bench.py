@@ -172,7 +172,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by head with no "
-              "collectives; see DESIGN.md); rerun with --gpus 1", file=sys.stderr)
+              "collectives: heads are independent and keys replicated); rerun with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
