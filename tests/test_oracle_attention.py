@@ -231,3 +231,39 @@ def test_score_repacking_compacts_d_diagonals_per_ciphertext():
 
 def test_score_repacking_when_a_slot_row_has_fewer_diagonals_than_slots_per_block():
     _repack_case(7, 16, 68)     # m = 8, H = 4 < d = 16: one group of 4 per slot row
+
+
+def test_a_whole_decode_step_attends_over_the_cache_including_the_new_token():
+    """The step as the configurations run it (append first, then scores and context over the cache):
+    on a small ring with real encryptions the new token's key and value take part in both products."""
+    from oracle import run_configs
+    prm = toy_params(8, 3, 1, 1)
+    orc = Oracle(prm)
+    cl = Client(prm, 69, orc)
+    n, d, t = prm.n, 8, prm.t
+    B = n // d
+    heads, stride, tau = 1, 2, 5                         # five tokens cached, token 5 arrives
+    g = Stream(69, 1)
+    K = attention_activations(g, 1, tau + 1, d)[0]
+    V = attention_activations(g, 1, tau + 1, d)[0]
+    q = attention_activations(g, 1, 1, d)[0, 0]
+    a = attention_activations(g, 1, tau + 1, 1)[0, :, 0]
+    packed = lambda M: np.concatenate([M[:tau].reshape(-1), np.zeros(n - tau * d, dtype=np.int64)])
+    zero = np.zeros_like(cl.encrypt_slots(np.zeros(n, dtype=np.int64)))
+    cache = np.stack([cl.encrypt_slots(packed(K)), zero, cl.encrypt_slots(packed(V)), zero])
+    fold = [galois_rot(n, sh) for sh in attention.fold_shifts(d)]
+    block = [galois_rot(n, sh) for sh in attention.block_shifts(n, d)] + [2 * n - 1]
+    st = {"heads": heads, "stride": stride, "B": B, "d2": d, "fold": fold, "block": block,
+          "masks": {b: cl.codec.encode(attention.block_mask_values(n, d, b)) for b in (tau,)},
+          "rlk": cl.relin_key(), "gk": {x: cl.galois_key(x) for x in fold + block}}
+    weights = np.zeros(n, dtype=np.int64)
+    weights[:(tau + 1) * d] = np.repeat(a, d)
+    out = {}
+    run_configs._decode_step(orc, st, [cl.encrypt_slots(np.tile(q, B))], [cl.encrypt_slots(weights)], cache,
+                             [cl.encrypt_slots(np.tile(K[tau], B)), cl.encrypt_slots(np.tile(V[tau], B))],
+                             tau, 1, out)
+    scores = cl.decrypt_slots(out["score0_0"])
+    assert np.array_equal(scores[:(tau + 1) * d:d], (K @ q) % t)          # six dot products, the new token's last
+    assert np.array_equal(cl.decrypt_slots(out["context0"])[:d], (a @ V) % t)
+    grown = cl.decrypt_slots(out["cache0"])
+    assert np.array_equal(grown[tau * d:(tau + 1) * d], K[tau] % t)
