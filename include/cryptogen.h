@@ -153,6 +153,14 @@ int cg_rotate(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, uint32_t galoi
 int cg_add(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *b_dev,
            uint64_t *out_dev, uint32_t ncomp, uint32_t batch);
 
+/* Ciphertext +- plaintext (the server's two moves of the lazy noise refresh, Algorithm 1 step 1:
+ * the share cache - r goes to the client, r is added back to what returns):
+ *   out2[u] = (c0 +- floor(Q/t) * pt[u mod n_plain], c1),  pt coefficients in [0,t),
+ * floor(Q/t) being the scale at which an encryption carries its plaintext.  negative != 0
+ * subtracts.  pt_dev: uint64[n_plain][N] plaintext polynomials (not prepared); out2 may alias in2. */
+int cg_add_plain(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, const uint64_t *pt_dev,
+                 uint32_t n_plain, int negative, uint64_t *out2_dev, uint32_t batch);
+
 /* Ciphertext x plaintext (MultPlain of Algorithm 1): out2[u] = in2[u] * plain[u * plain_stride]
  * in R_Q, the plaintext lifted centred (see cg_plain_prepare).  plain_stride = 0
  * applies one plaintext to the whole batch. */

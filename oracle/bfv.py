@@ -43,6 +43,7 @@ def load_library():
     lib.orc_galois_poly.argtypes = [C.c_void_p, _U64P, C.c_uint64, _U64P]
     lib.orc_rotate.argtypes = [C.c_void_p, _U64P, C.c_uint64, _U64P, _U64P]
     lib.orc_mul_plain.argtypes = [C.c_void_p, _U64P, _U64P, _U64P]
+    lib.orc_add_plain.argtypes = [C.c_void_p, _U64P, _U64P, C.c_int, _U64P]
     lib.orc_test_crt.restype = C.c_int
     lib.orc_test_crt.argtypes = [_U64P, C.c_int, _U64P, _U32P, C.c_int]
     lib.orc_test_divmod.restype = C.c_int
@@ -229,6 +230,15 @@ class Oracle:
         in2, gk = self._ct(in2, 2), self._key(gk)
         out = np.empty_like(in2)
         self.lib.orc_rotate(self.ctx, _p(in2), g, _p(gk), _p(out))
+        return out
+
+    def add_plain(self, in2, pt, negative=False):
+        """(c0 +- floor(Q/t) pt, c1): Algorithm 1 step 1, the server's masking and unmasking."""
+        in2 = self._ct(in2, 2)
+        pt = _u64(pt)
+        assert pt.shape == (self.n,)
+        out = np.empty_like(in2)
+        self.lib.orc_add_plain(self.ctx, _p(in2), _p(pt), 1 if negative else 0, _p(out))
         return out
 
     def mul_plain(self, in2, pt):

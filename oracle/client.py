@@ -187,6 +187,11 @@ class Client:
             worst = max(worst, abs(r))
         return log2(Q / 2) - log2(worst)
 
+    def refresh(self, share_ct) -> np.ndarray:
+        """The client's part of the lazy noise refresh (Algorithm 1 step 1): decrypt the masked
+        share and encrypt it afresh."""
+        return self.encrypt_poly(self.decrypt_poly(share_ct))
+
     # -- switching keys ------------------------------------------------------
     def switch_key(self, s_prime) -> np.ndarray:
         """Key that moves a component under s_prime to the key s."""

@@ -709,6 +709,26 @@ void orc_mul_plain(const orc_ctx *c, const u64 *in2, const u64 *pt, u64 *out2)
     free(lifted);
 }
 
+/* ciphertext +- plaintext: (c0 +- floor(Q/t) * pt, c1), pt coefficients in [0,t); the quotient
+ * floor(Q/t) is taken over the integers (long division of Q by t) and then reduced modulo each q_i */
+void orc_add_plain(const orc_ctx *c, const u64 *in2, const u64 *pt, int negative, u64 *out2)
+{
+    const int N = c->N, k = c->k;
+    bn tt, delta, rem;
+    tt.n = 1; tt.w[0] = (u32)c->t; bn_norm(&tt);
+    if (c->t >> 32) { tt.n = 2; tt.w[1] = (u32)(c->t >> 32); }
+    bn_divmod(&delta, &rem, &c->cQ.M, &tt);
+    for (int i = 0; i < k; i++) {
+        const u64 m = c->q[i], d = bn_mod_u64(&delta, m);
+        for (int n = 0; n < N; n++) {
+            const size_t o = (size_t)i * N + n;
+            const u64 x = mulmod(d, pt[n] % c->t, m);
+            out2[o] = negative ? submod(in2[o], x, m) : addmod(in2[o], x, m);
+            out2[(size_t)k * N + o] = in2[(size_t)k * N + o];
+        }
+    }
+}
+
 /* ------------------------------------------------------------------ */
 /* hooks used only by the pin tests and the host-side client            */
 /* ------------------------------------------------------------------ */

@@ -16,7 +16,7 @@ _LIB_PATH = os.environ.get("CRYPTOGEN_HIP_LIB", os.path.join(_HERE, "libcryptoge
 _SYMBOLS = [
     "cg_create", "cg_destroy", "cg_get_sizes", "cg_workspace_bytes", "cg_strerror",
     "cg_ntt_forward", "cg_ntt_inverse", "cg_ksk_prepare", "cg_plain_prepare",
-    "cg_mul", "cg_relin", "cg_mul_relin", "cg_rotate", "cg_add", "cg_mul_plain",
+    "cg_mul", "cg_relin", "cg_mul_relin", "cg_rotate", "cg_add", "cg_mul_plain", "cg_add_plain",
     "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_decode_scores_outer", "cg_decode_context_outer", "cg_prefill_qk",
     "cg_decode_step", "cg_decode_step_workspace_bytes", "cg_prefill_av", "cg_prefill_repack",
     "cg_cache_extend", "cg_decode_scores_ext", "cg_decode_context_ext", "cg_decode_step_ext",
@@ -69,6 +69,7 @@ class Library:
         d.cg_mul_relin.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, vp]
         d.cg_rotate.argtypes = [vp, vp, vp, u32, vp, vp, u32, i32, vp]
         d.cg_add.argtypes = [vp, vp, vp, vp, vp, u32, u32]
+        d.cg_add_plain.argtypes = [vp, vp, vp, vp, u32, i32, vp, u32]
         d.cg_mul_plain.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp]
         d.cg_kv_append.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, u32, vp]
         d.cg_decode_scores.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
@@ -244,6 +245,13 @@ class Context:
     def add(self, a, b, ncomp, batch, out=None):
         out = torch.empty_like(a) if out is None else out
         self._check(self.lib.dll.cg_add(self.h, self.stream, _ptr(a), _ptr(b), _ptr(out), ncomp, batch))
+        return out
+
+    def add_plain(self, in2, pt, batch, negative=False, out=None):
+        """pt: uint64 tensor [n_plain][N] of plaintext polynomials (coefficients in [0, t))."""
+        out = torch.empty_like(in2) if out is None else out
+        self._check(self.lib.dll.cg_add_plain(self.h, self.stream, _ptr(in2), _ptr(pt), pt.shape[0],
+                                              1 if negative else 0, _ptr(out), batch))
         return out
 
     def mul_plain(self, in2, plain, batch, plain_stride=0, out=None):

@@ -278,6 +278,16 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
         H.halfP[r] = (double)h_mul((P + m - 1) % m, h_inv(2, m), m);   // (P-1)/2 mod m, P odd
         if (r < c->k) H.Pinv_q[r] = h_centred(h_inv(P, m), m);
     }
+    {
+        // floor(Q/t) = (Q - (Q mod t)) / t, and Q = 0 modulo q_i: floor(Q/t) = -(Q mod t) t^-1 (mod q_i)
+        uint64_t q_mod_t = 1;
+        for (int j = 0; j < c->k; j++) q_mod_t = h_mul(q_mod_t, c->pr[j] % c->t, c->t);
+        for (int i = 0; i < c->k; i++) {
+            const uint64_t m = c->pr[i];
+            const uint64_t d = h_mul(m - q_mod_t % m, h_inv(c->t % m, m), m);
+            H.delta_q[i] = h_centred(d % m, m);
+        }
+    }
     // workspace limbs per unit: three ciphertext temporaries (3k + 2k + 2k) plus the larger of the
     // tensor-product and key-switch scratch areas (kept separate for simplicity)
     c->ws_total = 7 * c->k + (4 * c->l + 7 * c->KL) + (c->dnum * c->L + 2 * c->L);
@@ -684,6 +694,17 @@ extern "C" int cg_add(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t
 {
     CG_REQUIRE(c && ptrs_ok({a, b, out}) && batch_ok(batch) && (ncomp == 2 || ncomp == 3));
     return do_add(c, static_cast<hipStream_t>(stream), a, b, out, (size_t)batch * ncomp * c->k);
+}
+
+extern "C" int cg_add_plain(cg_ctx *c, void *stream, const uint64_t *in2, const uint64_t *pt, uint32_t n_plain,
+                            int negative, uint64_t *out2, uint32_t batch)
+{
+    CG_REQUIRE(c && ptrs_ok({in2, pt, out2}) && batch_ok(batch) && n_plain >= 1 && n_plain <= batch);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t rows = (size_t)batch * 2 * c->k;
+    CG_LAUNCH_PW(KID_ADD, (double)limb_bytes(c) * (2.0 * rows + n_plain), add_plain_kernel, pw_blocks(c, rows), in2, pt,
+                 out2, (int)batch, (int)n_plain, negative ? 1 : 0, c->dc);
+    return CG_OK;
 }
 
 extern "C" int cg_mul_plain(cg_ctx *c, void *stream, const uint64_t *in2, const void *plain, uint32_t plain_stride,

@@ -1043,6 +1043,27 @@ add_kernel(const uint64_t *__restrict__ a, const uint64_t *__restrict__ b, uint6
     out[gid] = f64_to_u64(addmod_canon(u64_to_f64(a[gid]), u64_to_f64(b[gid]), m));
 }
 
+// out[b] = in[b] + sign * floor(Q/t) * pt  (the plaintext enters component 0 only; component 1 is
+// copied): rows = batch * 2 * k, pt[(b % p_mod)][N] coefficients in [0, t)
+__global__ void __launch_bounds__(PW_THREADS)
+add_plain_kernel(const uint64_t *__restrict__ in, const uint64_t *__restrict__ pt, uint64_t *__restrict__ out,
+                 int batch, int p_mod, int negative, const DevConst *__restrict__ C)
+{
+    const int logn = C->logn, N = 1 << logn, k = C->k;
+    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    const int n = (int)(gid & (N - 1));
+    const int row = (int)(gid >> logn);
+    if (row >= batch * 2 * k) return;
+    const int i = row % k, c = (row / k) & 1, b = row / (2 * k);
+    double v = u64_to_f64(in[gid]);
+    if (c == 0) {
+        const ModD m = C->mod[i];
+        const double d = canon(mulmod(u64_to_f64(pt[((size_t)(b % p_mod) << logn) + n]), C->delta_q[i], m), m);
+        v = negative ? (v >= d ? v - d : v - d + m.p) : addmod_canon(v, d, m);
+    }
+    out[gid] = f64_to_u64(v);
+}
+
 // out[g][e] = sum_{c < group} in[g*group + c][e] over rows*N elements per unit (row w mod q_(w%k))
 __global__ void __launch_bounds__(PW_THREADS)
 sum_groups_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out, int groups, int group,

@@ -43,6 +43,7 @@ struct DevConst {
     ConvTab p2q;              // special primes -> Q, non-centred
     double halfP[MAXT];       // floor(P/2) mod each of the k+nsp primes (canonical)
     double Pinv_q[MAXS];      // P^-1 mod q_i (centred)
+    double delta_q[MAXS];     // floor(Q/t) mod q_i (centred): the scale of a plaintext inside a ciphertext
 };
 
 }  // namespace cg

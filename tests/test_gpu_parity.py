@@ -138,6 +138,27 @@ def test_add_matches_oracle(env):
             assert np.array_equal(got[u], env.orc.add(a[u], b[u]))
 
 
+def test_add_plain_matches_oracle(env):
+    """Masking and unmasking of the lazy noise refresh: one plaintext for the whole batch or one per
+    ciphertext, both signs, also in place."""
+    say(f"add_plain {env.name}")
+    n, t = env.n, env.prm.t
+    rng = np.random.default_rng(40)
+    pts = rng.integers(0, t, (3, n), dtype=np.uint64)
+    pts[0, :3] = [0, t - 1, t // 2]
+    x = env.cts(41, 3)
+    for negative in (False, True):
+        got = env.host(env.ctx.add_plain(env.dev(x), env.dev(pts), 3, negative=negative))
+        one = env.host(env.ctx.add_plain(env.dev(x), env.dev(pts[:1]), 3, negative=negative))
+        for u in range(3):
+            assert np.array_equal(got[u], env.orc.add_plain(x[u], pts[u], negative)), (env.name, negative, u)
+            assert np.array_equal(one[u], env.orc.add_plain(x[u], pts[0], negative)), (env.name, negative, u)
+    dx = env.dev(x)
+    env.ctx.add_plain(dx, env.dev(pts), 3, negative=True, out=dx)
+    env.ctx.add_plain(dx, env.dev(pts), 3, out=dx)
+    assert np.array_equal(env.host(dx), x)
+
+
 def test_mul_plain_and_append_match_oracle(env):
     say(f"mul_plain {env.name}")
     n, t = env.n, env.prm.t

@@ -267,3 +267,55 @@ def test_a_whole_decode_step_attends_over_the_cache_including_the_new_token():
     assert np.array_equal(cl.decrypt_slots(out["context0"])[:d], (a @ V) % t)
     grown = cl.decrypt_slots(out["cache0"])
     assert np.array_equal(grown[tau * d:(tau + 1) * d], K[tau] % t)
+
+
+def test_lazy_noise_refresh_restores_the_budget_and_keeps_the_cache():
+    """Algorithm 1 step 1 emulated end to end on the C2 parameters: a cache ciphertext that has taken
+    many appends is masked by the server (ciphertext - r), refreshed by the client (decrypt, encrypt),
+    unmasked (+ r): same contents, the noise budget of a fresh ciphertext.  The client never sees the
+    cache (only cache - r), and a step after the refresh still attends correctly."""
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 70, orc)
+    n, d, t = prm.n, 64, prm.t
+    B = n // d
+    g = Stream(70, 1)
+    rows = attention_activations(g, 1, 6, d)[0]
+    masks = {b: cl.codec.encode(attention.block_mask_values(n, d, b)) for b in range(6)}
+    cache = []
+    for tau in range(5):
+        attention.append(orc, cache, tau, cl.encrypt_slots(np.tile(rows[tau], B)), masks, d)
+    contents = cl.decrypt_poly(cache[0])
+    worn = cl.noise_budget_bits(cache[0], contents)
+    fresh = cl.noise_budget_bits(cl.encrypt_poly(contents), contents)
+    assert worn < fresh - 20                            # each append costs a plaintext product
+
+    r = np.random.default_rng(70).integers(0, t, n, dtype=np.uint64)       # the server's random mask
+    share = orc.add_plain(cache[0], r, negative=True)
+    seen_by_client = cl.decrypt_poly(share)
+    assert np.array_equal(seen_by_client, (contents.astype(np.int64) - r.astype(np.int64)) % t)
+    refreshed = orc.add_plain(cl.refresh(share), r)
+    assert np.array_equal(cl.decrypt_poly(refreshed), contents)
+    assert cl.noise_budget_bits(refreshed, contents) > fresh - 2
+
+    cache[0] = refreshed
+    attention.append(orc, cache, 5, cl.encrypt_slots(np.tile(rows[5], B)), masks, d)
+    want = np.zeros(n, dtype=np.int64)
+    want[:6 * d] = rows.reshape(-1)
+    assert np.array_equal(cl.decrypt_slots(cache[0]), want % t)
+
+
+def test_add_plain_is_addition_of_plaintexts_under_encryption():
+    prm = toy_params(7, 2, 1, 1)
+    orc = Oracle(prm)
+    cl = Client(prm, 71, orc)
+    rng = np.random.default_rng(71)
+    a = rng.integers(0, prm.t, prm.n, dtype=np.uint64)
+    b = rng.integers(0, prm.t, prm.n, dtype=np.uint64)
+    ct = cl.encrypt_poly(a)
+    assert np.array_equal(cl.decrypt_poly(orc.add_plain(ct, b)), (a + b) % prm.t)
+    assert np.array_equal(cl.decrypt_poly(orc.add_plain(ct, b, negative=True)), (a + prm.t - b) % prm.t)
+    # against the key-free encryption of b: ct + trivial(b) is the same ciphertext, bit for bit
+    assert np.array_equal(orc.add_plain(ct, b), orc.add(ct, cl.trivial(b)))
+    back = orc.add_plain(orc.add_plain(ct, b, negative=True), b)
+    assert np.array_equal(back, ct)
