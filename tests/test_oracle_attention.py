@@ -319,3 +319,32 @@ def test_add_plain_is_addition_of_plaintexts_under_encryption():
     assert np.array_equal(orc.add_plain(ct, b), orc.add(ct, cl.trivial(b)))
     back = orc.add_plain(orc.add_plain(ct, b, negative=True), b)
     assert np.array_equal(back, ct)
+
+
+def test_a_full_cache_ciphertext_stays_far_from_the_refresh_threshold():
+    """Multi-step noise: 128 appends fill one cache ciphertext at the C2 parameters; its budget falls by
+    a few bits only (the noise of the masked rows adds up like a random walk), and the scores computed
+    against it still decrypt with tens of bits to spare -- the lazy refresh is rarely due, as the paper
+    reports (its overhead stays below one per cent up to 512 tokens)."""
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 72, orc)
+    n, d, t = prm.n, 64, prm.t
+    B = n // d
+    g = Stream(72, 1)
+    K = attention_activations(g, 1, B, d)[0]
+    q = attention_activations(g, 1, 1, d)[0, 0]
+    cache = []
+    budgets = {}
+    for tau in range(B):
+        mask = cl.codec.encode(attention.block_mask_values(n, d, tau))
+        attention.append(orc, cache, tau, cl.encrypt_slots(np.tile(K[tau], B)), {tau: mask}, d)
+        if tau in (0, B - 1):
+            budgets[tau] = cl.noise_budget_bits(cache[0], cl.decrypt_poly(cache[0]))
+    assert len(cache) == 1
+    assert np.array_equal(cl.decrypt_slots(cache[0]), K.reshape(-1) % t)
+    assert budgets[0] - 6 < budgets[B - 1] < budgets[0]
+    rlk, gks = cl.relin_key(), _keys(cl, n, d)
+    out = attention.decode_scores(orc, cl.encrypt_slots(np.tile(q, B)), cache[0], rlk, gks, d)
+    assert np.array_equal(cl.decrypt_slots(out)[::d], (K @ q) % t)
+    assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
