@@ -4,6 +4,7 @@
     python -m paper_2602_08798_amd.microbench ntt      forward/inverse transform throughput vs number of rows
     python -m paper_2602_08798_amd.microbench copy     plain device copy of known size (counter calibration)
     python -m paper_2602_08798_amd.microbench c5curve  the scaled configuration: per-step time over its 64 decode steps
+    python -m paper_2602_08798_amd.microbench prefill  the prompt configuration: appends, Q K^T, score compaction, A V
 
 Kernel durations printed by `ntt` include the host-side staging of the prime-index table that the
 public transform entry point performs; use `rocprofv3 --kernel-trace` around it for kernel-only times.
@@ -103,6 +104,55 @@ def c5curve(steps=64):
           f"(single launches, host-timed with a synchronisation per step)")
 
 
+def prefill():
+    """12 heads, 128 prompt tokens, N = 8192: the four parts of the prompt's attention, each timed as a
+    whole (host clock around three repetitions, inputs resident)."""
+    import time
+    from workloads import configs
+    from .binding import to_device as dev
+    st = configs.c3_inputs()
+    ctx = Context(st["prm"])
+    H, m, d2 = st["heads"], st["m"], st["d2"]
+    masks = ctx.plain_prepare(dev(st["masks"]))
+    rows = [dev(st["rows"][tau]) for tau in range(m)]
+    key = lambda k: ctx.ksk_prepare(dev(k))
+    gk = {g: key(k) for g, k in st["gk"].items()}
+    rlk, gkr = key(st["rlk"]), [key(st["gk_right"][x]) for x in st["right"]]
+    mask0 = ctx.plain_prepare(dev(st["mask0"][None, :]))
+    q, a = dev(st["q"]), dev(st["a"])
+    cache, out = ctx.empty_ct(2 * H), ctx.empty_ct(H, m)
+
+    def timed(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    def appends():
+        for tau in range(m):
+            ctx.kv_append(cache, 1, 2 * H, tau, rows[tau], masks, d2)
+
+    fold = [gk[x] for x in st["fold"]]
+    parts = [
+        (f"{2 * H * m} appends ({m} calls of {2 * H} caches)", appends),
+        (f"Q K^T: {H} heads x {m} diagonals", lambda: ctx.prefill_qk(q, cache[:H], H, d2, rlk, fold, gk[st["g_blk"]],
+                                                                      gk[st["g_swap"]], out=out)),
+        (f"score compaction: {H * m} -> {H * m // min(d2, m // 2)} ciphertexts",
+         lambda: ctx.prefill_repack(out, H, d2, mask0, gkr)),
+        (f"A V: {H} heads x {m} products", lambda: ctx.prefill_av(a, cache[H:], H, d2, rlk, gk[st["g_blk"]],
+                                                                  gk[st["g_swap"]])),
+    ]
+    total = 0.0
+    for name, fn in parts:
+        ms = timed(fn)
+        total += ms
+        print(f"{name:58s} {ms:8.2f} ms", flush=True)
+    print(f"{'prompt attention of one layer':58s} {total:8.2f} ms")
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "modmul"
-    {"modmul": modmul, "ntt": ntt, "copy": copy, "c5curve": c5curve}[what]()
+    {"modmul": modmul, "ntt": ntt, "copy": copy, "c5curve": c5curve, "prefill": prefill}[what]()
