@@ -105,6 +105,28 @@ def timed(torch, fn, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def transform_rate(torch, ws, rows=16384, reps=5):
+    """The transform kernel in its throughput regime: cg_ntt_forward over `rows` residue rows of
+    N = 8192 (uint64 in, uint64 out: 2 x 64 KiB of algorithmic traffic per row), kernel time from
+    the library's HIP-event bracketing."""
+    prm = ws.prm
+    L = prm.k + prm.nsp
+    idx = [i % L for i in range(rows)]
+    x = torch.randint(0, 1 << 49, (rows, prm.n), dtype=torch.int64, device="cuda")
+    y = torch.empty_like(x)
+    ws.ctx.ntt_forward(x, idx, out=y)
+    torch.cuda.synchronize()
+    ws.ctx.profile_begin(reps + 1)
+    for _ in range(reps):
+        ws.ctx.ntt_forward(x, idx, out=y)
+    st = [s for s in ws.ctx.profile_end() if s["name"] == "ntt_fwd<rows>"][0]
+    ms = st["total_ms"] / st["launches"]
+    gbs = rows * prm.n * 16 / (ms * 1e-3) / 1e9
+    return {"metric": "negacyclic NTT rows/s at N=8192 (%d rows per launch, kernel time)" % rows,
+            "value": round(rows / (ms * 1e-3), 1), "unit": "1/s", "avg_launch_us": round(ms * 1e3, 1),
+            "algo_GBps": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+
 def c5_step_ms(torch, P, steps):
     """The scaled configuration (16 heads, N = 16384, 6+2 primes): first of its 64 decode steps, where
     the appended ciphertext is among those the products read."""
@@ -235,6 +257,7 @@ def main():
         secondary = {"metric": "ct-ct mult+relin/sec at N=8192", "value": round(H * C / (mr_ms * 1e-3), 1),
                      "unit": "1/s", "batch": H * C,
                      "value_at_batch_%d" % big: round(big / (mrb_ms * 1e-3), 1),
+                     "transform": transform_rate(torch, ws),
                      "scaled_config": c5_step_ms(torch, ws.P, 10)}
 
     result = {

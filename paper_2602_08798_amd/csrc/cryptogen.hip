@@ -621,13 +621,22 @@ static int public_transform(cg_ctx *c, void *stream, const uint64_t *in, uint64_
     CG_REQUIRE(c && idx && ptrs_ok({in, out}) && n_limbs >= 1 && n_limbs <= c->tab_cap);
     for (uint32_t i = 0; i < n_limbs; i++) CG_REQUIRE(idx[i] < (uint32_t)c->L);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // the index table is staged through a context-owned device buffer; the copy is
-    // ordered on the caller's stream before the kernel
-    CG_HIP(hipMemcpyAsync(c->tab, idx, n_limbs * sizeof(uint32_t), hipMemcpyHostToDevice, s));
+    // The usual pattern -- row i modulo prime i % period, as in stacked ring elements -- needs no
+    // table.  Any other assignment is staged through a context-owned device buffer; that copy
+    // is ordered on the caller's stream before the kernel.
+    uint32_t period = 0;
+    for (uint32_t i = 0; i < n_limbs; i++) if (idx[i] >= period) period = idx[i] + 1;
+    bool periodic = true;
+    for (uint32_t i = 0; i < n_limbs && periodic; i++) periodic = idx[i] == i % period;
+    const uint32_t *tab = nullptr;
+    if (!periodic) {
+        CG_HIP(hipMemcpyAsync(c->tab, idx, n_limbs * sizeof(uint32_t), hipMemcpyHostToDevice, s));
+        tab = c->tab;
+    }
     if (!inverse)
-        return launch_fwd(c, s, n_limbs, LdRowsU64{in, c->tab, 1, c->logn}, StU64{out, c->logn}, KID_FWD_ROWS,
+        return launch_fwd(c, s, n_limbs, LdRowsU64{in, tab, (int)period, c->logn}, StU64{out, c->logn}, KID_FWD_ROWS,
                           2.0 * limb_bytes(c) * n_limbs);
-    return launch_inv(c, s, n_limbs, LdInvU64{in, c->tab, 1, c->logn}, StInvU64{out, c->logn}, KID_INV_U64,
+    return launch_inv(c, s, n_limbs, LdInvU64{in, tab, (int)period, c->logn}, StInvU64{out, c->logn}, KID_INV_U64,
                       2.0 * limb_bytes(c) * n_limbs);
 }
 extern "C" int cg_ntt_forward(cg_ctx *c, void *stream, const uint64_t *in, uint64_t *out, const uint32_t *idx,

@@ -77,6 +77,13 @@ def test_transform_matches_definition(env):
         assert np.array_equal(got[r], bfv.ntt_forward(rows[r], env.qp[i])), (env.name, r)
     back = env.host(env.ctx.ntt_inverse(env.dev(got), idx))
     assert np.array_equal(back, rows)
+    # an arbitrary assignment of primes to rows (goes through the staged index table)
+    idx2 = [(L - 1 - i) % L for i in range(L)] + [0, 0, L - 1]
+    rows2 = np.stack([rng.integers(0, env.qp[i], env.n, dtype=np.uint64) for i in idx2])
+    got2 = env.host(env.ctx.ntt_forward(env.dev(rows2), idx2))
+    for r, i in enumerate(idx2):
+        assert np.array_equal(got2[r], bfv.ntt_forward(rows2[r], env.qp[i])), (env.name, r)
+    assert np.array_equal(env.host(env.ctx.ntt_inverse(env.dev(got2), idx2)), rows2)
 
 
 def test_mul_matches_oracle(env):
