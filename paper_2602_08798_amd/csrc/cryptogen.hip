@@ -107,12 +107,12 @@ struct cg_ctx {
 // kernel classes for the timing facility
 enum KernelId {
     KID_FWD_MULQ = 0, KID_FWD_MULB, KID_FWD_MODUP, KID_FWD_ROWS, KID_FWD_PLAIN,
-    KID_TENSOR, KID_INV_F64, KID_INV_U64, KID_INV_MULPLAIN, KID_SCALE, KID_INV_KSINNER, KID_MODDOWN,
+    KID_INV_TENSOR, KID_INV_U64, KID_INV_MULPLAIN, KID_SCALE, KID_INV_KSINNER, KID_MODDOWN,
     KID_ADD, KID_SUM_GROUPS, KID_COUNT
 };
 static const char *const kKernelNames[KID_COUNT] = {
     "ntt_fwd<mul,q-rows>", "ntt_fwd<mul,aux-rows>", "ntt_fwd<modup>", "ntt_fwd<rows>",
-    "ntt_fwd<plain>", "tensor", "ntt_inv<f64>", "ntt_inv<u64>", "ntt_inv<mul_plain>", "scale",
+    "ntt_fwd<plain>", "ntt_inv<tensor>", "ntt_inv<u64>", "ntt_inv<mul_plain>", "scale",
     "ntt_inv<ks_inner>", "moddown", "add", "sum_groups"};
 
 // Brackets one launch with two events when profiling is on.
@@ -497,12 +497,12 @@ static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *
     const double LB = (double)limb_bytes(c), B = batch;
     const MulSrc src{a2, b2, (int)n_a, (int)b_group, (int)b_stride, c->logn, 0};
     CG_TRY(transform_ext(c, s, src, polys, ntt));
-    CG_LAUNCH_PW(KID_TENSOR, LB * c->KL * (2.0 * ((double)n_a + B) + 3.0 * B), tensor_kernel,
-                 pw_blocks(c, (size_t)batch * c->KL), ntt, tens, (int)batch, (int)a_group, (int)n_a, b_ext,
-                 (int)b_group, (int)b_stride, c->dc);
+    // tensor product fused into the inverse transform's load
     const size_t rows = (size_t)batch * 3 * c->KL;
-    CG_TRY(launch_inv(c, s, rows, LdInvF64{tens, nullptr, c->KL, c->logn}, StInvF64{tens, c->logn}, KID_INV_F64,
-                      LB * 2.0 * rows));
+    CG_TRY(launch_inv(c, s, rows,
+                      LdInvTensor{ntt, b_ext, (int)a_group, (int)n_a, (int)b_group, (int)b_stride, c->logn},
+                      StInvF64{tens, c->logn}, KID_INV_TENSOR,
+                      LB * c->KL * (2.0 * ((double)n_a + B) + 3.0 * B)));
     const double sbytes = LB * (3.0 * c->KL + 3.0 * c->k * (accumulate ? 2 : 1)) * B;
     const unsigned sblocks = pw_blocks(c, (size_t)batch * 3);
 #define CG_SCALE(K) CG_LAUNCH_PW(KID_SCALE, sbytes, scale_kernel<K>, sblocks, tens, out3, (int)batch * 3, accumulate, c->dc)

@@ -748,24 +748,6 @@ struct LdPlain {
 };
 
 // inverse-transform loaders (finish may return any lazy value below 8p)
-struct LdInvF64 {
-    static constexpr int kRaw = 1;
-    static constexpr bool kPrefetch = true;
-    const double *src;
-    const uint32_t *tab;
-    int pmod, logn;
-    __device__ __forceinline__ int prime(int wg, const DevConst *) const { return tab ? (int)tab[wg] : wg % pmod; }
-    __device__ __forceinline__ int share(const DevConst *) const { return 1; }
-    __device__ __forceinline__ int out_row(int wg, const DevConst *) const { return wg; }
-    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *, uint64_t *raw) const
-    {
-        raw[0] = f64_bits(src[((size_t)wg << logn) + idx]);
-    }
-    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD, const DevConst *) const
-    {
-        return bits_f64(raw[0]);
-    }
-};
 struct LdInvU64 {
     static constexpr int kRaw = 1;
     static constexpr bool kPrefetch = true;
@@ -820,6 +802,47 @@ struct LdInvKsInner {
             const double d = bits_f64(raw[2 * j]);
             s += mulmod(DNUM <= 4 ? d : red(d, m), bits_f64(raw[2 * j + 1]), m);
         }
+        return s;
+    }
+};
+
+// tensor product fused into the load: workgroup -> (unit u, prime r of the k+l, component c in 0..2),
+// the component running fastest so that the three rows reading the same four operand rows are
+// neighbours; element = a0 b0 (c = 0), a0 b1 + a1 b0 (c = 1), a1 b1 (c = 2); result row [u][c][r].
+// a polys of unit u: ntt[2 * (u / a_group) + {0,1}]; b polys: ntt[2 * (n_a + u) + {0,1}], or, with
+// bext given, the transformed ciphertext bext[(u / b_group) * b_stride + u % b_group].
+struct LdInvTensor {
+    static constexpr int kRaw = 4;
+    static constexpr bool kPrefetch = false;
+    const double *ntt, *bext;
+    int a_group, n_a, b_group, b_stride, logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return (wg / 3) % C->KL; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 3; }
+    __device__ __forceinline__ int out_row(int wg, const DevConst *C) const
+    {
+        const int KL = C->KL, r = (wg / 3) % KL, u = wg / (3 * KL);
+        return (u * 3 + wg % 3) * KL + r;
+    }
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
+    {
+        const int KL = C->KL, c = wg % 3, r = (wg / 3) % KL, u = wg / (3 * KL);
+        const size_t ps = (size_t)KL << logn, off = ((size_t)r << logn) + idx;
+        const double *sa = ntt + (size_t)(2 * (u / a_group)) * ps + off;
+        const double *sb = (bext ? bext + (size_t)(2 * ((u / b_group) * b_stride + u % b_group)) * ps
+                                 : ntt + (size_t)(2 * (n_a + u)) * ps) + off;
+        // c = 0: a0 b0; c = 2: a1 b1; c = 1: all four
+        raw[0] = f64_bits(sa[c == 2 ? ps : 0]);
+        raw[1] = f64_bits(sb[c == 2 ? ps : (c == 1 ? ps : 0)]);
+        if (c == 1) {
+            raw[2] = f64_bits(sa[ps]);
+            raw[3] = f64_bits(sb[0]);
+        }
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int wg, int, const ModD m, const DevConst *) const
+    {
+        // forward outputs are lazy: bring them to p/2 so that the two-term sum stays far below 2^53
+        double s = mulmod(red(bits_f64(raw[0]), m), red(bits_f64(raw[1]), m), m);
+        if (wg % 3 == 1) s += mulmod(red(bits_f64(raw[2]), m), red(bits_f64(raw[3]), m), m);
         return s;
     }
 };
@@ -884,34 +907,6 @@ struct StInvAppend {
 // pointwise kernels
 // ---------------------------------------------------------------------------
 constexpr int PW_THREADS = 256;
-
-// tensor product in the transform domain over all k+l primes:
-// ntt[pp][r][n] (lazy) -> tens[u*3+c][r][n] (lazy); a polys of unit u: pp = 2*(u / a_group) + {0,1},
-// b polys: pp = 2*(n_a + u) + {0,1}, or, with bext given, the transformed ciphertext
-// bext[(u / b_group) * b_stride + u % b_group] ([2][k+l][N] each)
-__global__ void __launch_bounds__(PW_THREADS)
-tensor_kernel(const double *__restrict__ ntt, double *__restrict__ tens, int batch, int a_group, int n_a,
-              const double *__restrict__ bext, int b_group, int b_stride, const DevConst *__restrict__ C)
-{
-    const int logn = C->logn, N = 1 << logn, KL = C->KL;
-    const size_t gid = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
-    const int n = (int)(gid & (N - 1));
-    const int br = (int)(gid >> logn);
-    if (br >= batch * KL) return;
-    const int r = br % KL, u = br / KL;
-    const ModD m = C->mod[r];
-    const size_t pstride = (size_t)KL << logn;
-    const double *sa = ntt + (size_t)(2 * (u / a_group)) * pstride + ((size_t)r << logn) + n;
-    const double *sb = (bext ? bext + (size_t)(2 * ((u / b_group) * b_stride + u % b_group)) * pstride
-                             : ntt + (size_t)(2 * (n_a + u)) * pstride) + ((size_t)r << logn) + n;
-    // forward outputs are lazy (< 4p); bring them to p/2 so the two-term sum stays far below 2^53
-    const double a0 = red(sa[0], m), a1 = red(sa[pstride], m);
-    const double b0 = red(sb[0], m), b1 = red(sb[pstride], m);
-    double *dst = tens + (size_t)u * 3 * pstride + ((size_t)r << logn) + n;
-    dst[0] = mulmod(a0, b0, m);
-    dst[pstride] = mulmod(a0, b1, m) + mulmod(a1, b0, m);
-    dst[2 * pstride] = mulmod(a1, b1, m);
-}
 
 // exact round(t e / Q) mod Q from e known modulo Q and the auxiliary basis:
 //   r = centred (t e mod Q);  y = (t e - r) / Q computed modulo each b_j;
