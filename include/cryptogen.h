@@ -17,7 +17,8 @@
  *   ring element  uint64[k][N]: row i holds the canonical residues in [0,q_i)
  *               of the N coefficients (coefficient order, degree ascending).
  *   ciphertext  uint64[ncomp][k][N], ncomp = 2 (c0,c1) or 3 (d0,d1,d2).
- *   batch       `batch` ciphertexts are stored back to back.
+ *   batch       `batch` ciphertexts are stored back to back; 1 <= batch <= 65536 units per
+ *               call (an empty batch is CG_EINVAL, like any other invalid size).
  *   switch key  as generated: uint64[dnum][2][k+nsp][N], coefficient order,
  *               ciphertext primes first, then special primes (hybrid key
  *               switching, digit j = alpha consecutive ciphertext primes,

@@ -360,6 +360,10 @@ def test_invalid_arguments_are_rejected_without_launching():
     with pytest.raises(CgError):
         env.ctx.add(x, x, 4, 1)                         # ncomp must be 2 or 3
     with pytest.raises(CgError):
+        env.ctx.add(x, x, 2, 0)                         # an empty batch is an error, not a silent no-op
+    with pytest.raises(CgError):
+        env.ctx.rotate(x, 3, gk, (1 << 16) + 1, out=env.ctx.empty_ct(1))   # above the largest batch
+    with pytest.raises(CgError):
         env.ctx.kv_append(x, 1, 1, env.n, x, gk, env.n // 4)   # token beyond the cache
     # unsupported parameter sets never reach the device
     import dataclasses
