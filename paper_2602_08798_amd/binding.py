@@ -129,6 +129,16 @@ class CgError(RuntimeError):
     pass
 
 
+class CgSizeError(CgError, ValueError):
+    """A tensor handed to the binding is smaller than the call's arguments imply."""
+
+
+def _need(t, numel: int, what: str):
+    """Buffers cross the C ABI as bare pointers: catch undersized tensors here, on the host."""
+    if t.numel() < numel:
+        raise CgSizeError(f"{what}: {t.numel()} elements, at least {numel} needed")
+
+
 def _ptr(t) -> int:
     if t is None:
         return 0
@@ -261,7 +271,15 @@ class Context:
                                               _ptr(out), batch, _ptr(ws)))
         return out
 
+    def _check_append(self, cache, cache_stride_cts, n_caches, tau, rows, masks, d2):
+        ct = 2 * self.k * self.n
+        blocks = max(1, self.n // max(1, d2))
+        _need(cache, n_caches * cache_stride_cts * ct, "cache")
+        _need(rows, n_caches * ct, "rows")
+        _need(masks, (tau % blocks + 1) * self.k * self.n, "masks (prepared, indexed by block)")
+
     def kv_append(self, cache, cache_stride_cts, n_caches, tau, rows, masks, d2):
+        self._check_append(cache, cache_stride_cts, n_caches, tau, rows, masks, d2)
         ws = self.workspace(n_caches)
         self._check(self.lib.dll.cg_kv_append(self.h, self.stream, _ptr(cache), cache_stride_cts, n_caches,
                                               tau, _ptr(rows), _ptr(masks), d2, _ptr(ws)))
@@ -315,6 +333,14 @@ class Context:
                     gk_block, scores=None, context=None, cache_ext=None):
         scores = self.empty_ct(heads, n_cts) if scores is None else scores
         context = self.empty_ct(heads) if context is None else context
+        ct = 2 * self.k * self.n
+        self._check_append(cache, cache_stride_cts, 2 * heads, tau, rows, masks, d2)
+        _need(q, heads * ct, "q")
+        _need(a, heads * n_cts * ct, "a")
+        _need(scores, heads * n_cts * ct, "scores")
+        _need(context, heads * ct, "context")
+        if cache_ext is not None:
+            _need(cache_ext, 2 * heads * cache_stride_cts * (int(self.sizes.ct_ext_bytes) // 8), "cache_ext")
         need = int(self.lib.dll.cg_decode_step_workspace_bytes(self.h, heads, n_cts))
         if need == 0:
             raise CgError("cryptogen: invalid decode-step shape")

@@ -486,8 +486,9 @@ def test_invalid_arguments_of_the_step_and_prompt_entry_points():
     fold = [key] * 6
     block = [key] * (len(_block_keys(env, d2)))
     masks = env.ctx.plain_prepare(env.dev(np.zeros((B, n), dtype=np.uint64)))
-    step = lambda **kw: env.ctx.decode_step(q, q, x, heads, kw.get("n_cts", n_cts), kw.get("stride", stride),
-                                            kw.get("d2", d2), kw.get("tau", 0), rows, masks, key, fold, block)
+    a3 = env.dev(env.cts(4, 3))                          # large enough for every n_cts tried below
+    step = lambda **kw: env.ctx.decode_step(q, a3, x, heads, kw.get("n_cts", n_cts), kw.get("stride", stride),
+                                            kw.get("d2", d2), kw.get("tau", 0), rows, kw.get("masks", masks), key, fold, block)
     before = env.host(x).copy()
     with pytest.raises(CgError):
         step(tau=stride * B)                             # token beyond the last cache ciphertext
@@ -497,6 +498,8 @@ def test_invalid_arguments_of_the_step_and_prompt_entry_points():
         step(d2=48)                                      # block size must be a power of two
     with pytest.raises(CgError):
         env.ctx.decode_step(q, q, x, 1 << 15, 4, 4, d2, 0, rows, masks, key, fold, block)   # batch too large
+    with pytest.raises(CgError, match="masks"):
+        step(tau=1, masks=masks[:masks.numel() // B])    # prepared masks end before the block in use
     with pytest.raises(CgError):
         env.ctx.cache_extend(x, 2, 3, 2, env.ctx.empty_ext(4))      # group longer than its stride
     with pytest.raises(CgError):
@@ -571,3 +574,56 @@ def test_rotate_and_mul_relin_at_ragged_batches(batch):
     got = env.host(env.ctx.mul_relin(env.dev(x), env.dev(y), key, batch))
     for u in range(batch):
         assert np.array_equal(got[u], env.orc.relin(env.orc.mul(x[u], y[u]), raw)), (batch, u)
+
+
+def test_decode_step_random_shapes_match_oracle():
+    """Seeded sweep over heads, ciphertexts read, cache stride, head dimension and token position (also
+    with the transformed copy of the cache), each compared in full with the oracle's step."""
+    from oracle import run_configs
+    import torch
+    env = _envs.get("C1") or Env("C1")
+    _envs["C1"] = env
+    n = env.n
+    rng = np.random.default_rng(2026)
+    raw_rlk, rlk = env.key(70)
+    for case in range(6):
+        d2 = int(rng.choice([16, 64, 256, 1024]))
+        B = n // d2
+        heads = int(rng.integers(1, 4))
+        n_cts = int(rng.integers(1, 4))
+        stride = n_cts + int(rng.integers(0, 3))
+        tau = int(rng.integers(0, stride * B))
+        use_ext = bool(case % 2)
+        say(f"decode_step sweep {case}: heads {heads}, n_cts {n_cts}, stride {stride}, d2 {d2}, tau {tau}, ext {use_ext}")
+        gs_f, gs_b = _fold_keys(env, d2), _block_keys(env, d2)
+        kf = {g: env.key(900 + i) for i, g in enumerate(gs_f)}
+        kb = {g: env.key(930 + i) for i, g in enumerate(gs_b)}
+        blk = tau % B
+        mask_pt = rng.integers(0, env.prm.t, n, dtype=np.uint64)
+        # prepared masks are indexed by block: only the one in use is filled in, at its index
+        one = env.ctx.plain_prepare(env.dev(mask_pt[None, :]))          # flat: k * n doubles
+        per = one.numel()
+        masks_dev = torch.zeros((blk + 1) * per, dtype=one.dtype, device=one.device)
+        masks_dev[blk * per:(blk + 1) * per] = one
+        q, a = env.cts(1000 + case, heads), env.cts(1100 + case, heads * n_cts)
+        rows, cache = env.cts(1200 + case, 2 * heads), env.cts(1300 + case, 2 * heads * stride)
+        dcache = env.dev(cache)
+        ext = None
+        if use_ext:
+            ext = env.ctx.empty_ext(2 * heads * stride)
+            env.ctx.cache_extend(dcache, 2 * heads, n_cts, stride, ext)
+        scores, context = env.ctx.decode_step(env.dev(q), env.dev(a), dcache, heads, n_cts, stride, d2, tau,
+                                              env.dev(rows), masks_dev, rlk, [kf[g][1] for g in gs_f],
+                                              [kb[g][1] for g in gs_b], cache_ext=ext)
+        st = {"heads": heads, "stride": stride, "B": B, "d2": d2, "fold": gs_f, "block": gs_b,
+              "masks": {blk: mask_pt}, "rlk": raw_rlk,
+              "gk": {**{g: kf[g][0] for g in gs_f}, **{g: kb[g][0] for g in gs_b}}}
+        # (when the appended ciphertext lies beyond those read, append and products commute)
+        want, wcache = {}, cache.copy()
+        run_configs._decode_step(env.orc, st, q, a, wcache, rows, tau, n_cts, want)
+        scores, context, got_cache = env.host(scores), env.host(context), env.host(dcache)
+        assert np.array_equal(got_cache, wcache), case
+        for h in range(heads):
+            for c in range(n_cts):
+                assert np.array_equal(scores[h, c], want[f"score{h}_{c}"]), (case, h, c)
+            assert np.array_equal(context[h], want[f"context{h}"]), (case, h)
