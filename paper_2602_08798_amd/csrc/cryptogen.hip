@@ -428,7 +428,7 @@ static int launch_inv(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int ki
 {
     if (nwg == 0) return CG_OK;
     ProfScope ps(c, s, kid, bytes);
-    const int e = ntt_elems(c);
+    const int e = (c->logn == 13 && inv_wide<LD>::value) ? 16 : ntt_elems(c);
     const int threads = c->N / e;
 #define CG_INV(LG, EL)                                                                                      \
     hipLaunchKernelGGL((ntt_inv_kernel<LG, EL, LD, ST>),                                                    \

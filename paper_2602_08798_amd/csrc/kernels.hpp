@@ -189,7 +189,7 @@ template <int LOGN, int E, bool CHUNKED, class LD, class F>
 __device__ __forceinline__ void load_row_now(const LD &ld, int wg, int tid, const ModD m, const DevConst *C, F &&sink)
 {
     constexpr int T = (1 << LOGN) / E;
-    constexpr int CH0 = LD::kRaw <= 2 ? 16 : (LD::kRaw <= 4 ? 8 : 4);
+    constexpr int CH0 = LD::kRaw <= 2 ? 16 : (LD::kRaw <= 4 ? (E >= 16 && CHUNKED ? 4 : 8) : (E >= 16 && CHUNKED ? 2 : 4));
     constexpr int CH = CH0 < E ? CH0 : E;
     const int first = CHUNKED ? ((tid >> 6) << chunk_log<E>()) + (tid & 63) : tid;
     constexpr int step = CHUNKED ? 64 : T;
@@ -200,6 +200,9 @@ __device__ __forceinline__ void load_row_now(const LD &ld, int wg, int tid, cons
         for (int i = 0; i < CH; i++) ld.fetch(wg, first + (c0 + i) * step, C, rw[i]);
 #pragma unroll
         for (int i = 0; i < CH; i++) sink(c0 + i, ld.finish(rw[i], wg, first + (c0 + i) * step, m, C));
+        // keep the slices apart: hoisting the next slice's loads above this one's arithmetic
+        // would bring back the register pressure the slicing is there to avoid
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -465,6 +468,12 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
         lds_barrier();   // pass 0's LDS reads precede the next row's LDS writes
     }
 }
+
+// Inverse loaders marked here run with 16 elements per thread at N = 8192, like the forward
+// transforms (two co-resident 512-thread workgroups per compute unit).  It pays for the tensor
+// product, whose launches are large; the key-switch inner product is launched over a few hundred
+// rows at a time and finishes a row sooner on 1024 threads.
+template <class LD> struct inv_wide { static constexpr bool value = false; };
 
 // ---------------------------------------------------------------------------
 // exact base conversion helpers (per coefficient, registers only)
@@ -768,6 +777,9 @@ struct LdInvU64 {
 };
 // key-switch inner product fused into the load: workgroup -> (unit b, prime r, component c), the
 // component running fastest so that the two rows reading the same digits are neighbours;
+struct LdInvTensor;
+template <> struct inv_wide<LdInvTensor> { static constexpr bool value = true; };
+
 // element = sum_j digit_j[b][r] * key[j][c][r] (both in transform order); result row [b][c][r]
 template <int DNUM>
 struct LdInvKsInner {

@@ -5,6 +5,7 @@
     python -m paper_2602_08798_amd.microbench copy     plain device copy of known size (counter calibration)
     python -m paper_2602_08798_amd.microbench c5curve  the scaled configuration: per-step time over its 64 decode steps
     python -m paper_2602_08798_amd.microbench prefill  the prompt configuration: appends, Q K^T, score compaction, A V
+    python -m paper_2602_08798_amd.microbench mulrelin mult+relin rate against batch size, whole and in chunks
 
 Kernel durations printed by `ntt` include the host-side staging of the prime-index table that the
 public transform entry point performs; use `rocprofv3 --kernel-trace` around it for kernel-only times.
@@ -153,6 +154,46 @@ def prefill():
     print(f"{'prompt attention of one layer':58s} {total:8.2f} ms")
 
 
+def mulrelin(preset="C2", batches=(12, 24, 48, 96, 192, 384, 768), chunks=(24, 48, 96, 192)):
+    """Products per second against batch size: one call over the whole batch, and the same batch as
+    back-to-back calls over chunks (whose intermediates stay in the 256 MiB last-level cache)."""
+    prm = PRESETS[preset]
+    ctx = Context(prm)
+    top = max(batches)
+    lim = min(prm.q + prm.p)                     # below every prime: valid residues in every row
+    a = torch.randint(0, lim, (top, 2, prm.k, prm.n), dtype=torch.int64, device="cuda")
+    b = torch.randint(0, lim, (top, 2, prm.k, prm.n), dtype=torch.int64, device="cuda")
+    rlk = ctx.ksk_prepare(torch.randint(0, lim, (ctx.dnum, 2, ctx.L, prm.n), dtype=torch.int64, device="cuda"))
+    out = ctx.empty_ct(top)
+    for batch in batches:
+        whole = _time(lambda: ctx.mul_relin(a, b, rlk, batch, out=out), 5)
+        line = f"{preset} batch {batch:4d}: whole {batch / whole * 1e6:9.0f}/s ({whole:8.1f} us)"
+        for c in chunks:
+            if c >= batch:
+                continue
+
+            def chunked():
+                for o in range(0, batch, c):
+                    m = min(c, batch - o)
+                    ctx.mul_relin(a[o:o + m], b[o:o + m], rlk, m, out=out[o:o + m])
+            us = _time(chunked, 5)
+            line += f"  | by {c}: {batch / us * 1e6:9.0f}/s"
+        print(line, flush=True)
+    # where the time of a saturating batch goes (every launch bracketed by events: sequential, kernel time)
+    ctx.profile_begin()
+    for _ in range(3):
+        ctx.mul_relin(a, b, rlk, top, out=out)
+    torch.cuda.synchronize()
+    stats = ctx.profile_end()
+    total = sum(s["total_ms"] for s in stats)
+    for s in sorted(stats, key=lambda s: -s["total_ms"]):
+        if s["launches"]:
+            us = s["total_ms"] * 1e3 / s["launches"]
+            print(f"  {s['name']:24s} {us:8.1f} us/launch  {s['algo_bytes'] / s['launches'] / us / 1e3:7.0f} GB/s"
+                  f"  {100 * s['total_ms'] / total:5.1f} % of the batch of {top}", flush=True)
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "modmul"
-    {"modmul": modmul, "ntt": ntt, "copy": copy, "c5curve": c5curve, "prefill": prefill}[what]()
+    {"modmul": modmul, "ntt": ntt, "copy": copy, "c5curve": c5curve, "prefill": prefill,
+     "mulrelin": mulrelin}[what]()
