@@ -195,5 +195,8 @@ def mulrelin(preset="C2", batches=(12, 24, 48, 96, 192, 384, 768), chunks=(24, 4
 
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "modmul"
-    {"modmul": modmul, "ntt": ntt, "copy": copy, "c5curve": c5curve, "prefill": prefill,
-     "mulrelin": mulrelin}[what]()
+    if what == "mulrelin" and len(sys.argv) > 2:      # e.g. `mulrelin 768`: that batch only
+        mulrelin(batches=tuple(int(a) for a in sys.argv[2:]))
+    else:
+        {"modmul": modmul, "ntt": ntt, "copy": copy, "c5curve": c5curve, "prefill": prefill,
+         "mulrelin": mulrelin}[what]()
