@@ -201,9 +201,18 @@ class Context:
     def empty_ct(self, *lead, ncomp=2) -> torch.Tensor:
         return torch.empty(*lead, ncomp, self.k, self.n, dtype=torch.int64, device=self.device)
 
+    # element counts implied by the arguments, checked before a pointer crosses the C ABI
+    def _cts(self, count, ncomp=2) -> int:
+        return max(0, int(count)) * ncomp * self.k * self.n
+
+    def _need_key(self, key, what="key"):
+        _need(key, int(self.sizes.ksk_bytes) // 8, what + " (prepared)")
+
     # ---- entry points (same names as the C ABI, without the cg_ prefix) ----
     def ntt_forward(self, x, prime_idx, out=None, inverse=False):
         out = torch.empty_like(x) if out is None else out
+        _need(x, len(prime_idx) * self.n, "x")
+        _need(out, len(prime_idx) * self.n, "out")
         idx = (C.c_uint32 * len(prime_idx))(*prime_idx)
         f = self.lib.dll.cg_ntt_inverse if inverse else self.lib.dll.cg_ntt_forward
         self._check(f(self.h, self.stream, _ptr(x), _ptr(out), idx, len(prime_idx)))
@@ -226,13 +235,22 @@ class Context:
 
     def mul(self, a2, b2, batch, a_group=1, out=None):
         out = self.empty_ct(batch, ncomp=3) if out is None else out
+        self._need_mul(a2, b2, batch, a_group)
+        _need(out, self._cts(batch, 3), "out")
         ws = self.workspace(batch)
         self._check(self.lib.dll.cg_mul(self.h, self.stream, _ptr(a2), _ptr(b2), _ptr(out), batch,
                                         a_group, _ptr(ws)))
         return out
 
+    def _need_mul(self, a2, b2, batch, a_group):
+        _need(a2, self._cts(-(-int(batch) // max(1, int(a_group)))), "a")
+        _need(b2, self._cts(batch), "b")
+
     def relin(self, in3, rlk, batch, out=None):
         out = self.empty_ct(batch) if out is None else out
+        _need(in3, self._cts(batch, 3), "in")
+        _need(out, self._cts(batch), "out")
+        self._need_key(rlk, "rlk")
         ws = self.workspace(batch)
         self._check(self.lib.dll.cg_relin(self.h, self.stream, _ptr(in3), _ptr(rlk), _ptr(out), batch,
                                           _ptr(ws)))
@@ -240,6 +258,9 @@ class Context:
 
     def mul_relin(self, a2, b2, rlk, batch, a_group=1, out=None):
         out = self.empty_ct(batch) if out is None else out
+        self._need_mul(a2, b2, batch, a_group)
+        _need(out, self._cts(batch), "out")
+        self._need_key(rlk, "rlk")
         ws = self.workspace(batch)
         self._check(self.lib.dll.cg_mul_relin(self.h, self.stream, _ptr(a2), _ptr(b2), _ptr(rlk),
                                               _ptr(out), batch, a_group, _ptr(ws)))
@@ -247,6 +268,9 @@ class Context:
 
     def rotate(self, in2, galois_elt, gk, batch, accumulate=False, out=None):
         out = self.empty_ct(batch) if out is None else out
+        _need(in2, self._cts(batch), "in")
+        _need(out, self._cts(batch), "out")
+        self._need_key(gk, "gk")
         ws = self.workspace(batch)
         self._check(self.lib.dll.cg_rotate(self.h, self.stream, _ptr(in2), galois_elt, _ptr(gk),
                                            _ptr(out), batch, int(accumulate), _ptr(ws)))
@@ -254,18 +278,26 @@ class Context:
 
     def add(self, a, b, ncomp, batch, out=None):
         out = torch.empty_like(a) if out is None else out
+        for t, what in ((a, "a"), (b, "b"), (out, "out")):
+            _need(t, self._cts(batch, max(0, int(ncomp))), what)
         self._check(self.lib.dll.cg_add(self.h, self.stream, _ptr(a), _ptr(b), _ptr(out), ncomp, batch))
         return out
 
     def add_plain(self, in2, pt, batch, negative=False, out=None):
         """pt: uint64 tensor [n_plain][N] of plaintext polynomials (coefficients in [0, t))."""
         out = torch.empty_like(in2) if out is None else out
+        _need(in2, self._cts(batch), "in")
+        _need(out, self._cts(batch), "out")
+        _need(pt, pt.shape[0] * self.n, "pt")
         self._check(self.lib.dll.cg_add_plain(self.h, self.stream, _ptr(in2), _ptr(pt), pt.shape[0],
                                               1 if negative else 0, _ptr(out), batch))
         return out
 
     def mul_plain(self, in2, plain, batch, plain_stride=0, out=None):
         out = self.empty_ct(batch) if out is None else out
+        _need(in2, self._cts(batch), "in")
+        _need(out, self._cts(batch), "out")
+        _need(plain, ((int(batch) - 1) * int(plain_stride) + 1) * self.k * self.n if batch > 0 else 0, "plain (prepared)")
         ws = self.workspace(batch)
         self._check(self.lib.dll.cg_mul_plain(self.h, self.stream, _ptr(in2), _ptr(plain), plain_stride,
                                               _ptr(out), batch, _ptr(ws)))
@@ -288,10 +320,22 @@ class Context:
     def _keys(self, keys):
         return (C.c_void_p * len(keys))(*[_ptr(k) for k in keys])
 
+    def _need_products(self, left, n_left, cache, per_ct, heads, n_cts, stride, out, n_out, rlk, keys):
+        """Operands of the decode products: `left` ciphertexts against `heads` cache groups of n_cts
+        ciphertexts (per_ct elements each) spaced `stride` apart."""
+        heads, n_cts, stride = max(0, int(heads)), max(0, int(n_cts)), max(0, int(stride))
+        _need(left, self._cts(n_left), "left operand")
+        _need(cache, ((heads - 1) * stride + n_cts) * per_ct if heads and n_cts else 0, "cache")
+        _need(out, self._cts(n_out), "out")
+        self._need_key(rlk, "rlk")
+        for i, key in enumerate(keys):
+            self._need_key(key, f"Galois key {i}")
+
     def decode_scores(self, q, kcache, heads, n_cts, d2, rlk, gk_fold, out=None, cache_stride_cts=None):
         out = self.empty_ct(heads, n_cts) if out is None else out
         ws = self.workspace(heads * n_cts)
         stride = n_cts if cache_stride_cts is None else cache_stride_cts
+        self._need_products(q, heads, kcache, self._cts(1), heads, n_cts, stride, out, heads * n_cts, rlk, gk_fold)
         self._check(self.lib.dll.cg_decode_scores(self.h, self.stream, _ptr(q), _ptr(kcache), heads, n_cts,
                                                   stride, d2, _ptr(rlk), self._keys(gk_fold), _ptr(out), _ptr(ws)))
         return out
@@ -300,6 +344,7 @@ class Context:
         out = self.empty_ct(heads) if out is None else out
         ws = self.workspace(heads * n_cts)
         stride = n_cts if cache_stride_cts is None else cache_stride_cts
+        self._need_products(a, heads * n_cts, vcache, self._cts(1), heads, n_cts, stride, out, heads, rlk, gk_block)
         self._check(self.lib.dll.cg_decode_context(self.h, self.stream, _ptr(a), _ptr(vcache), heads, n_cts,
                                                    stride, d2, _ptr(rlk), self._keys(gk_block), _ptr(out), _ptr(ws)))
         return out
@@ -309,6 +354,9 @@ class Context:
         return torch.empty(n_cts, int(self.sizes.ct_ext_bytes) // 8, dtype=torch.float64, device=self.device)
 
     def cache_extend(self, cts, n_groups, group_len, group_stride_cts, ext):
+        span = (max(0, int(n_groups)) - 1) * int(group_stride_cts) + int(group_len) if n_groups > 0 else 0
+        _need(cts, self._cts(span), "cts")
+        _need(ext, span * (int(self.sizes.ct_ext_bytes) // 8), "ext")
         self._check(self.lib.dll.cg_cache_extend(self.h, self.stream, _ptr(cts), n_groups, group_len,
                                                  group_stride_cts, _ptr(ext)))
         return ext
@@ -317,6 +365,8 @@ class Context:
         out = self.empty_ct(heads, n_cts) if out is None else out
         ws = self.workspace(heads * n_cts)
         stride = n_cts if cache_stride_cts is None else cache_stride_cts
+        self._need_products(q, heads, kext, int(self.sizes.ct_ext_bytes) // 8, heads, n_cts, stride, out,
+                            heads * n_cts, rlk, gk_fold)
         self._check(self.lib.dll.cg_decode_scores_ext(self.h, self.stream, _ptr(q), _ptr(kext), heads, n_cts, stride,
                                                       d2, _ptr(rlk), self._keys(gk_fold), _ptr(out), _ptr(ws)))
         return out
@@ -325,6 +375,8 @@ class Context:
         out = self.empty_ct(heads) if out is None else out
         ws = self.workspace(heads * n_cts)
         stride = n_cts if cache_stride_cts is None else cache_stride_cts
+        self._need_products(a, heads * n_cts, vext, int(self.sizes.ct_ext_bytes) // 8, heads, n_cts, stride, out,
+                            heads, rlk, gk_block)
         self._check(self.lib.dll.cg_decode_context_ext(self.h, self.stream, _ptr(a), _ptr(vext), heads, n_cts, stride,
                                                        d2, _ptr(rlk), self._keys(gk_block), _ptr(out), _ptr(ws)))
         return out

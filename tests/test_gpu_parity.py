@@ -627,3 +627,31 @@ def test_decode_step_random_shapes_match_oracle():
             for c in range(n_cts):
                 assert np.array_equal(scores[h, c], want[f"score{h}_{c}"]), (case, h, c)
             assert np.array_equal(context[h], want[f"context{h}"]), (case, h)
+
+
+def test_binding_rejects_undersized_tensors_before_any_launch():
+    """Pointers cross the C ABI without sizes: the binding compares every tensor with what the
+    call's arguments imply and raises instead of letting a kernel run off the end of a buffer."""
+    from paper_2602_08798_amd.binding import CgSizeError
+    env = _envs.get("C1") or Env("C1")
+    _envs["C1"] = env
+    say("undersized tensors")
+    x2 = env.dev(env.cts(5, 2))
+    raw, key = env.key(31)
+    with pytest.raises(CgSizeError, match="b"):
+        env.ctx.mul(x2, x2[:1], 2)
+    with pytest.raises(CgSizeError, match="a"):
+        env.ctx.mul_relin(x2[:1], x2, key, 2)            # a_group 1: one a operand per product
+    env.ctx.mul_relin(x2[:1], x2, key, 2, a_group=2)     # shared a operand: fits
+    with pytest.raises(CgSizeError, match="in"):
+        env.ctx.rotate(x2, 3, key, 3)
+    with pytest.raises(CgSizeError, match="gk"):
+        env.ctx.rotate(x2, 3, key[:key.numel() // 2], 2)
+    with pytest.raises(CgSizeError, match="out"):
+        env.ctx.add(x2, x2, 2, 2, out=env.ctx.empty_ct(1))
+    with pytest.raises(CgSizeError, match="cache"):
+        env.ctx.decode_scores(x2, x2, 2, 1, 64, key, [key] * 6, cache_stride_cts=2)   # 2 heads, stride 2: 3 cts
+    with pytest.raises(CgSizeError, match="ext"):
+        env.ctx.cache_extend(x2, 1, 2, 2, env.ctx.empty_ext(1))
+    import torch
+    torch.cuda.synchronize()
