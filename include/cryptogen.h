@@ -324,6 +324,28 @@ int cg_prefill_repack(cg_ctx *ctx, void *stream, const uint64_t *x_dev, uint32_t
                       const void *mask0_dev, const void *const *gk_right_dev_host, uint64_t *out_dev,
                       void *ws_dev);
 
+/* Ciphertext x plaintext vector-matrix product of the decode step (section 4.2, "inner-diagonal
+ * CPVM": one token in one ciphertext, about d1 d2 / N plaintext products and O(log) rotations per
+ * matrix, cost independent of the prompt length; the paper states the operation and these counts,
+ * the procedure is this library's):
+ *   y[u] = x W_u  for u < units, every W_u a d1 x d2 plaintext matrix given as n_diag diagonals.
+ * Layout (D1 = tile length: the power of two >= max(d1, d2, N/d2), at most N/2; T = N/D1 tiles;
+ * n_diag = d2 / T): x_dev is one ciphertext whose flat slot r D1 + i holds feature
+ * (i + n_diag r) mod D1 of the token (zero beyond d1); diagonal c of a matrix holds at flat slot
+ * s the entry W[f][s mod d2], f being the feature that slot s of x shows after a left rotation by c
+ * (zero for f >= d1).  diags_dev: prepared plaintexts (cg_plain_prepare) [units][n_diag].
+ * Procedure: copies x_c = rotate(x, 3^c), c < n_diag, by a doubling tree (copy 2^l + i = copy i
+ * rotated by 3^(2^l)); y[u] = sum_c x_c * diag[u][c]; then y += rotate(y, g) for g = 3^d2, 3^(2 d2),
+ * ..., 3^(N/4), 2N-1.  Every slot s of out_dev[u] then decrypts to (x W_u)[s mod d2] mod t: the
+ * layout cg_decode_scores takes its query in and cg_kv_append its new row.
+ * gk_shift_dev_host: host array of log2(n_diag) device pointers, prepared keys for 3^1, 3^2,
+ * 3^4, ... (may be NULL when n_diag is 1); gk_block_dev_host: as for cg_decode_context.
+ * n_diag: a power of two, at most min(d2, 64).  out_dev: [units] ciphertexts, must not overlap
+ * x_dev.  ws_dev: cg_workspace_bytes(ctx, units + n_diag) bytes. */
+int cg_cpvm(cg_ctx *ctx, void *stream, const uint64_t *x_dev, const void *diags_dev, uint32_t units,
+            uint32_t n_diag, uint32_t d2, const void *const *gk_shift_dev_host,
+            const void *const *gk_block_dev_host, uint64_t *out_dev, void *ws_dev);
+
 /* Benchmark support: between cg_profile_begin and cg_profile_end every kernel
  * launch of this context is bracketed by a pair of HIP events on the stream it is
  * launched on.  cg_profile_end waits for the recorded events and returns, per

@@ -27,6 +27,14 @@ slots [b d, (b+1) d)) of a cache ciphertext holds one token's d-vector.
                   one ciphertext per diagonal, broadcast over each token's block.
   prefill_repack  compaction of the score ciphertexts (useful values in slot 0 of
                   each block) into ciphertexts with d useful values per block.
+  cpvm            section 4.2, the decode step's ciphertext-plaintext vector-matrix
+                  product ("inner-diagonal"): one token of d1 features in one
+                  ciphertext times a plaintext d1 x d2 matrix, the result tiled with
+                  period d2 over all slots, which is the layout decode_scores takes
+                  its query in and append takes its new row in.  The paper gives the
+                  operation, its operand counts (one ciphertext per token, about
+                  d1 d2 / N plaintext products, O(log) rotations) and no procedure;
+                  the procedure here is the reading documented in the design notes.
 """
 import numpy as np
 
@@ -229,4 +237,87 @@ def required_galois(n: int, d: int):
     gs = [galois_rot(n, sh) for sh in fold_shifts(d)]
     gs += [galois_rot(n, sh) for sh in block_shifts(n, d)]
     gs.append(galois_swap(n))
+    return sorted(set(gs))
+
+
+# ---------------------------------------------------------------------------
+# ciphertext-plaintext vector-matrix product of the decode step (section 4.2)
+#
+# Layout.  D1 = the tile length: a power of two, at least d1, d2 and N/d2 and at most N/2; the N
+# slots are T = N/D1 tiles (T/2 per slot row).  C = d2 / T "diagonals".  The token x (zero-padded
+# to D1) sits in tile r shifted by C r features: flat slot r D1 + i holds x[(i + C r) mod D1].
+# Diagonal c of the weights holds, at flat slot s, W[f][s mod d2] with f the feature that the
+# token's ciphertext shows at s once it has been rotated left by c (zero for f >= d1).
+# Then y = sum_c rotate(x, c) * P_c has, at slot s, C terms of output s mod d2, every pair
+# (feature, output) exactly once over the slots of one residue class modulo d2; the sum over those
+# classes (rotate by d2, 2 d2, ... N/4 and add, then the row swap) leaves output j in every slot
+# congruent to j.
+# ---------------------------------------------------------------------------
+def cpvm_shape(n: int, d1: int, d2: int):
+    """-> (D1, T, C)."""
+    D1 = 1
+    while D1 < max(d1, d2, n // d2):
+        D1 *= 2
+    assert D1 <= n // 2 and d2 >= 2 and d2 & (d2 - 1) == 0, "token longer than a slot row, or d2 not a power of two"
+    T = n // D1
+    return D1, T, d2 // T
+
+
+def cpvm_feature_of_slot(n: int, d1: int, d2: int) -> np.ndarray:
+    """Feature index shown by every flat slot of the token's ciphertext (>= d1: padding)."""
+    D1, T, C = cpvm_shape(n, d1, d2)
+    s = np.arange(n)
+    return (s % D1 + C * (s // D1)) % D1
+
+
+def cpvm_token_values(n: int, d1: int, d2: int, x) -> np.ndarray:
+    f = cpvm_feature_of_slot(n, d1, d2)
+    xp = np.zeros(cpvm_shape(n, d1, d2)[0], dtype=np.int64)
+    xp[:d1] = x
+    return xp[f]
+
+
+def cpvm_weight_values(n: int, d1: int, d2: int, W, c: int) -> np.ndarray:
+    """Slot values of diagonal c of the d1 x d2 matrix W."""
+    f = cpvm_feature_of_slot(n, d1, d2)
+    half = n // 2
+    s = np.arange(n)
+    shown = f[(s // half) * half + (s % half + c) % half]     # feature at s after a left rotation by c
+    Wp = np.zeros((cpvm_shape(n, d1, d2)[0], d2), dtype=np.int64)
+    Wp[:d1] = W
+    return Wp[shown, s % d2]
+
+
+def cpvm_shifts(c_count: int):
+    sh = 1
+    while sh < c_count:
+        yield sh
+        sh *= 2
+
+
+def cpvm(orc, x_ct, diag_polys, gks, d2: int, counts=None):
+    """y = x W for one token and one weight matrix given as its C diagonal plaintexts.
+
+    The C rotated copies of the token come from a doubling tree (copy 2^l + i = copy i rotated by
+    2^l: log2 C levels, C - 1 rotations, shared by every matrix applied to this token), then C
+    plaintext products are summed and the residue classes modulo d2 folded together."""
+    n = orc.n
+    copies = [x_ct]
+    for sh in cpvm_shifts(len(diag_polys)):
+        g = galois_rot(n, sh)
+        copies += [orc.rotate(copies[i], g, gks[g]) for i in range(sh)]
+    y = orc.mul_plain(copies[0], diag_polys[0])
+    for c in range(1, len(diag_polys)):
+        y = orc.add(y, orc.mul_plain(copies[c], diag_polys[c]))
+    gs = [galois_rot(n, sh) for sh in block_shifts(n, d2)] + [galois_swap(n)]
+    for g in gs:
+        y = orc.add(y, orc.rotate(y, g, gks[g]))
+    if counts is not None:
+        counts.update(mul_plain=len(diag_polys), rotate_shared=len(diag_polys) - 1, rotate=len(gs))
+    return y
+
+
+def cpvm_galois(n: int, c_count: int, d2: int):
+    gs = [galois_rot(n, sh) for sh in cpvm_shifts(c_count)]
+    gs += [galois_rot(n, sh) for sh in block_shifts(n, d2)] + [galois_swap(n)]
     return sorted(set(gs))

@@ -19,7 +19,7 @@ _SYMBOLS = [
     "cg_mul", "cg_relin", "cg_mul_relin", "cg_rotate", "cg_add", "cg_mul_plain", "cg_add_plain",
     "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_decode_scores_outer", "cg_decode_context_outer", "cg_prefill_qk",
     "cg_decode_step", "cg_decode_step_workspace_bytes", "cg_prefill_av", "cg_prefill_repack",
-    "cg_cache_extend", "cg_decode_scores_ext", "cg_decode_context_ext", "cg_decode_step_ext",
+    "cg_cpvm", "cg_cache_extend", "cg_decode_scores_ext", "cg_decode_context_ext", "cg_decode_step_ext",
     "cg_bench_modmul", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
 ]
 
@@ -84,6 +84,7 @@ class Library:
                                          C.POINTER(vp), vp, vp, vp]
         d.cg_prefill_av.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp, vp, vp]
         d.cg_prefill_repack.argtypes = [vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
+        d.cg_cpvm.argtypes = [vp, vp, vp, vp, u32, u32, u32, C.POINTER(vp), C.POINTER(vp), vp, vp]
         d.cg_decode_step.argtypes = [vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp, vp, C.POINTER(vp),
                                      C.POINTER(vp), vp, vp, vp]
         d.cg_decode_step_workspace_bytes.argtypes = [vp, u32, u32]
@@ -449,6 +450,20 @@ class Context:
         ws = self.workspace(heads * m)
         self._check(self.lib.dll.cg_prefill_repack(self.h, self.stream, _ptr(x), heads, d2, _ptr(mask0),
                                                    self._keys(gk_right), _ptr(out), _ptr(ws)))
+        return out
+
+    def cpvm(self, x, diags, units, n_diag, d2, gk_shift, gk_block, out=None):
+        """x: one ciphertext (the token); diags: prepared plaintexts [units][n_diag] (flat)."""
+        out = self.empty_ct(units) if out is None else out
+        _need(x, self._cts(1), "x")
+        _need(diags, max(0, int(units)) * max(0, int(n_diag)) * self.k * self.n, "diags (prepared)")
+        _need(out, self._cts(units), "out")
+        for i, key in enumerate(list(gk_shift) + list(gk_block)):
+            self._need_key(key, f"Galois key {i}")
+        ws = self.workspace(units + n_diag)
+        shift = self._keys(gk_shift) if len(gk_shift) else None
+        self._check(self.lib.dll.cg_cpvm(self.h, self.stream, _ptr(x), _ptr(diags), units, n_diag, d2, shift,
+                                         self._keys(gk_block), _ptr(out), _ptr(ws)))
         return out
 
     def profile_begin(self, max_launches=65536):

@@ -1105,6 +1105,43 @@ extern "C" int cg_prefill_repack(cg_ctx *c, void *stream, const uint64_t *x, uin
     return CG_OK;
 }
 
+// One token times `units` plaintext matrices (the decode step's ciphertext-plaintext vector-matrix
+// product): rotated copies of the token by a doubling tree, the products with the diagonals summed
+// on the way into one inverse transform per unit, then the sum over residue classes modulo d2.
+extern "C" int cg_cpvm(cg_ctx *c, void *stream, const uint64_t *x, const void *diags, uint32_t units,
+                       uint32_t n_diag, uint32_t d2, const void *const *gk_shift, const void *const *gk_block,
+                       uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({x, diags, out, ws}) && gk_block && batch_ok(units) && pow2_d(c, d2));
+    CG_REQUIRE(n_diag >= 1 && n_diag <= 64 && (n_diag & (n_diag - 1)) == 0 && n_diag <= d2);
+    CG_REQUIRE(n_diag == 1 || gk_shift);
+    int levels = 0;
+    for (uint32_t sh = 1; sh < n_diag; sh <<= 1, levels++) CG_REQUIRE(gk_shift[levels] && aligned16(gk_shift[levels]));
+    int nrot = 0;
+    uint32_t gs[20];
+    for (uint32_t sh = d2; sh <= (uint32_t)c->N / 4; sh <<= 1) gs[nrot++] = pow3_mod(sh, 2u * c->N);
+    gs[nrot++] = 2u * c->N - 1;
+    for (int i = 0; i < nrot; i++) CG_REQUIRE(gk_block[i] && aligned16(gk_block[i]));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    const double LB = (double)limb_bytes(c);
+    Bump w = bump(c, ws);
+    uint64_t *copies = w.take<uint64_t>((size_t)2 * c->k * n_diag);
+    double *f = w.take<double>((size_t)2 * c->k * n_diag);
+    uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * units), *xb = w.take<uint64_t>((size_t)2 * c->k * units);
+    // copy 2^l + i = copy i rotated left by 2^l
+    CG_HIP(hipMemcpyAsync(copies, x, ct2 * 8, hipMemcpyDeviceToDevice, s));
+    for (uint32_t sh = 1, l = 0; sh < n_diag; sh <<= 1, l++)
+        CG_TRY(do_rotate(c, s, copies, pow3_mod(sh, 2u * c->N), gk_shift[l], copies + (size_t)sh * ct2, sh, 0, w.p));
+    const size_t crows = (size_t)n_diag * 2 * c->k, rows = (size_t)units * 2 * c->k;
+    CG_TRY(launch_fwd(c, s, crows, LdRowsU64{copies, nullptr, c->k, c->logn}, StF64Red{f, c->logn}, KID_FWD_ROWS,
+                      LB * 2.0 * crows));
+    CG_TRY(launch_inv(c, s, rows, LdInvPlainSum{f, static_cast<const double *>(diags), (int)n_diag, c->logn},
+                      StInvU64{xa, c->logn}, KID_INV_MULPLAIN,
+                      LB * (crows + (double)units * n_diag * c->k + rows)));
+    return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, units, w.p);
+}
+
 extern "C" int cg_profile_begin(cg_ctx *c, uint32_t max_launches)
 {
     CG_REQUIRE(c && max_launches >= 1 && max_launches <= (1u << 20) && !c->prof_on);

@@ -883,6 +883,36 @@ struct LdInvMulPlain {
     }
 };
 
+// sum of ciphertext-plaintext products fused into the load (the decode step's vector-matrix
+// product): workgroup -> (unit u, comp c2, prime i); element = sum over the cn rotated copies of
+// the token of copy_c[c2][i] * diagonal_(u, c)[i].  The 2 cn operands of an element are read
+// where they are used (they would not fit the register slices of the other loaders); the copies
+// are stored reduced, so every product is below 0.6 p and eight of them sum to less than 5 p.
+struct LdInvPlainSum {
+    static constexpr int kRaw = 1;
+    static constexpr bool kPrefetch = false;
+    const double *ctf;     // transformed copies [cn][2][k][N], |x| <= p/2
+    const double *plain;   // prepared plaintexts [units][cn][k][N]
+    int cn, logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return wg % C->k; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 1; }
+    __device__ __forceinline__ int out_row(int wg, const DevConst *) const { return wg; }
+    __device__ __forceinline__ void fetch(int, int, const DevConst *, uint64_t *raw) const { raw[0] = 0; }
+    __device__ __forceinline__ double finish(const uint64_t *, int wg, int idx, const ModD m, const DevConst *C) const
+    {
+        const int k = C->k, i = wg % k, c2 = (wg / k) & 1, u = wg / (2 * k);
+        const double *a = ctf + ((size_t)(c2 * k + i) << logn) + idx;
+        const double *b = plain + ((((size_t)u * cn) * k + i) << logn) + idx;
+        const size_t sa = (size_t)(2 * k) << logn, sb = (size_t)k << logn;
+        double s = 0.0;
+        for (int c = 0; c < cn; c++) {
+            s += mulmod(a[c * sa], b[c * sb], m);
+            if ((c & 7) == 7) s = red(s, m);
+        }
+        return s;
+    }
+};
+
 struct StInvF64 {
     double *dst;
     int logn;

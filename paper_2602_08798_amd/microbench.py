@@ -6,6 +6,7 @@
     python -m paper_2602_08798_amd.microbench c5curve  the scaled configuration: per-step time over its 64 decode steps
     python -m paper_2602_08798_amd.microbench prefill  the prompt configuration: appends, Q K^T, score compaction, A V
     python -m paper_2602_08798_amd.microbench mulrelin mult+relin rate against batch size, whole and in chunks
+    python -m paper_2602_08798_amd.microbench cpvm     one token times the 36 plaintext 768 x 64 matrices of a layer's Q, K, V
 
 Kernel durations printed by `ntt` include the host-side staging of the prime-index table that the
 public transform entry point performs; use `rocprofv3 --kernel-trace` around it for kernel-only times.
@@ -193,10 +194,38 @@ def mulrelin(preset="C2", batches=(12, 24, 48, 96, 192, 384, 768), chunks=(24, 4
                   f"  {100 * s['total_ms'] / total:5.1f} % of the batch of {top}", flush=True)
 
 
+def cpvm(preset="C2", d2=64, n_diag=8, heads=12):
+    """Ciphertext-plaintext vector-matrix product of the decode step at the sizes of the paper's
+    CT x PT table (d1 = 768, d2 = 64, N = 8192: tiles of 1024 slots, 8 diagonals per matrix), for the
+    3 * heads matrices of one layer's Q, K and V projections (random residues: timing only)."""
+    prm = PRESETS[preset]
+    ctx = Context(prm)
+    units = 3 * heads
+    lim = min(prm.q + prm.p)
+    x = torch.randint(0, lim, (1, 2, prm.k, prm.n), dtype=torch.int64, device="cuda")
+    diags = ctx.plain_prepare(torch.randint(0, prm.t, (units * n_diag, prm.n), dtype=torch.int64, device="cuda"))
+    key = lambda: ctx.ksk_prepare(torch.randint(0, lim, (ctx.dnum, 2, ctx.L, prm.n), dtype=torch.int64,
+                                                device="cuda"))
+    shift = [key() for _ in range(n_diag.bit_length() - 1)]
+    block = [key() for _ in range((prm.n // d2).bit_length() - 1)]
+    out = ctx.empty_ct(units)
+    fn = lambda: ctx.cpvm(x, diags, units, n_diag, d2, shift, block, out=out)
+    us = _time(fn, 20)
+    print(f"{preset}: one token x {units} matrices (768 x {d2}, {n_diag} diagonals each): {us:8.1f} us "
+          f"= {us / units:6.2f} us per matrix", flush=True)
+    ctx.profile_begin()
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    for s in sorted(ctx.profile_end(), key=lambda s: -s["total_ms"]):
+        if s["launches"]:
+            print(f"  {s['name']:24s} {s['launches'] // 3:3d} launches  {s['total_ms'] * 1e3 / 3:8.1f} us per call", flush=True)
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "modmul"
     if what == "mulrelin" and len(sys.argv) > 2:      # e.g. `mulrelin 768`: that batch only
         mulrelin(batches=tuple(int(a) for a in sys.argv[2:]))
     else:
         {"modmul": modmul, "ntt": ntt, "copy": copy, "c5curve": c5curve, "prefill": prefill,
-         "mulrelin": mulrelin}[what]()
+         "mulrelin": mulrelin, "cpvm": cpvm}[what]()

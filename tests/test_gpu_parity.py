@@ -655,3 +655,53 @@ def test_binding_rejects_undersized_tensors_before_any_launch():
         env.ctx.cache_extend(x2, 1, 2, 2, env.ctx.empty_ext(1))
     import torch
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name,d1,d2,units", [("C1", 200, 64, 3), ("C1", 1000, 64, 2), ("C1", 100, 16, 5),
+                                             ("C1", 37, 256, 1), ("C2", 768, 64, 6), ("C5", 1024, 64, 2)])
+def test_cpvm_matches_oracle(name, d1, d2, units):
+    """The decode step's ciphertext-plaintext vector-matrix product (section 4.2) against the oracle's
+    procedure, on pseudo-ciphertexts and pseudo-keys (bit-exactness needs no valid encryption);
+    the paper's sizes (768 x 64 at N = 8192) are the C2 case."""
+    from oracle import attention
+    from oracle.client import SlotCodec
+    env = _envs.get(name) or Env(name)
+    _envs[name] = env
+    n = env.n
+    D1, T, C = attention.cpvm_shape(n, d1, d2)
+    say(f"cpvm {name}: d1 {d1}, d2 {d2}, tile {D1}, {C} diagonals, {units} matrices")
+    codec = SlotCodec(env.prm)
+    g = Stream(1500 + d1, units)
+    polys = np.stack([codec.encode(attention.cpvm_weight_values(n, d1, d2, g.integers(-128, 128, (d1, d2)), c))
+                      for u in range(units) for c in range(C)])
+    x = env.cts(1501 + d1, 1)[0]
+    g_shift = [pow(3, sh, 2 * n) for sh in attention.cpvm_shifts(C)]
+    g_block = _block_keys(env, d2)
+    keys = {gal: env.key(1600 + i) for i, gal in enumerate(sorted(set(g_shift + g_block)))}
+    got = env.host(env.ctx.cpvm(env.dev(x[None]), env.ctx.plain_prepare(env.dev(polys)), units, C, d2,
+                                [keys[gal][1] for gal in g_shift], [keys[gal][1] for gal in g_block]))
+    raw = {gal: keys[gal][0] for gal in keys}
+    for u in range(units):
+        want = attention.cpvm(env.orc, x, list(polys[u * C:(u + 1) * C]), raw, d2)
+        assert np.array_equal(got[u], want), (name, d1, d2, u)
+
+
+def test_cpvm_rejects_invalid_arguments():
+    from paper_2602_08798_amd.binding import CgError
+    env = _envs.get("C1") or Env("C1")
+    _envs["C1"] = env
+    say("cpvm negative tests")
+    raw, key = env.key(30)
+    x = env.dev(env.cts(1, 1))
+    plain = env.ctx.plain_prepare(env.dev(np.zeros((4, env.n), dtype=np.uint64)))
+    block = [key] * len(_block_keys(env, 64))
+    with pytest.raises(CgError):
+        env.ctx.cpvm(x, plain, 1, 3, 64, [key, key], block)          # diagonals: a power of two
+    with pytest.raises(CgError):
+        env.ctx.cpvm(x, plain, 1, 4, 48, [key, key], block)          # d2: a power of two
+    with pytest.raises(CgError):
+        env.ctx.cpvm(x, plain, 1, 4, 2, [key, key], block)           # more diagonals than outputs
+    with pytest.raises(CgError, match="diags"):
+        env.ctx.cpvm(x, plain, 2, 4, 64, [key, key], block)          # two matrices need eight diagonals
+    import torch
+    torch.cuda.synchronize()

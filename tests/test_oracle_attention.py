@@ -348,3 +348,91 @@ def test_a_full_cache_ciphertext_stays_far_from_the_refresh_threshold():
     out = attention.decode_scores(orc, cl.encrypt_slots(np.tile(q, B)), cache[0], rlk, gks, d)
     assert np.array_equal(cl.decrypt_slots(out)[::d], (K @ q) % t)
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
+
+
+def _cpvm_case(prm, d1, d2, seed, want_shape):
+    """Decrypts to x W mod t, tiled with period d2 (the layout the decode scores take a query in)."""
+    orc = Oracle(prm)
+    cl = Client(prm, seed, orc)
+    n, t = prm.n, prm.t
+    D1, T, C = attention.cpvm_shape(n, d1, d2)
+    assert (D1, T, C) == want_shape
+    g = Stream(seed, 1)
+    x = attention_activations(g, 1, 1, d1)[0, 0]
+    W = attention_activations(g, 1, d1, d2)[0]
+    gks = {gal: cl.galois_key(gal) for gal in attention.cpvm_galois(n, C, d2)}
+    diags = [cl.codec.encode(attention.cpvm_weight_values(n, d1, d2, W, c)) for c in range(C)]
+    x_ct = cl.encrypt_slots(attention.cpvm_token_values(n, d1, d2, x))
+    counts = {}
+    y = attention.cpvm(orc, x_ct, diags, gks, d2, counts)
+    levels = (n // d2).bit_length() - 1
+    assert counts == {"mul_plain": C, "rotate_shared": C - 1, "rotate": levels}
+    want = (x.astype(object) @ W.astype(object)) % t
+    assert np.array_equal(cl.decrypt_slots(y), np.tile(np.array(want, dtype=np.int64), n // d2))
+    assert cl.noise_budget_bits(y, cl.decrypt_poly(y)) > 20
+    return counts
+
+
+def test_cpvm_layout_shows_every_feature_output_pair_once_per_residue_class():
+    """The counting argument behind the procedure, checked on the slot values alone: summing
+    token * diagonal_c over the diagonals and over the slots of one residue class modulo d2
+    gives x W exactly (integers, no encryption)."""
+    for n, d1, d2 in ((128, 20, 8), (256, 100, 16), (4096, 200, 64), (8192, 768, 64), (4096, 1000, 64), (256, 5, 64)):
+        D1, T, C = attention.cpvm_shape(n, d1, d2)
+        assert T * C == d2 and D1 * T == n
+        g = Stream(70, n, d1)
+        x = g.integers(-128, 128, d1)
+        W = g.integers(-128, 128, (d1, d2))
+        tok = attention.cpvm_token_values(n, d1, d2, x)
+        half = n // 2
+        acc = np.zeros(n, dtype=np.int64)
+        for c in range(C):
+            rot = np.concatenate([np.roll(tok[:half], -c), np.roll(tok[half:], -c)])   # rows rotate left by c
+            acc += rot * attention.cpvm_weight_values(n, d1, d2, W, c)
+        assert np.array_equal(acc.reshape(-1, d2).sum(axis=0), x @ W), (n, d1, d2)
+
+
+def test_cpvm_on_small_rings():
+    _cpvm_case(toy_params(7, 3, 1, 1), 20, 8, 71, (32, 4, 2))
+    _cpvm_case(toy_params(8, 3, 1, 1), 100, 16, 72, (128, 2, 8))
+    _cpvm_case(toy_params(8, 2, 1, 1), 5, 64, 73, (64, 4, 16))     # a token much shorter than a tile
+
+
+def test_cpvm_at_the_paper_sizes_takes_eight_products_and_seven_rotations_per_matrix():
+    """d1 = 768, d2 = 64, N = 8192 (the sizes of the paper's CT x PT complexity table): one
+    ciphertext per token, 8 plaintext products (768 padded to 1024: 1024 * 64 / 8192) and
+    log2(N / d2) = 7 rotations per matrix, plus 7 rotations of the token shared by all matrices."""
+    counts = _cpvm_case(PRESETS["C2"], 768, 64, 74, (1024, 8, 8))
+    assert counts == {"mul_plain": 8, "rotate_shared": 7, "rotate": 7}
+
+
+def test_cpvm_output_is_the_layout_the_attention_products_and_the_append_take():
+    """Section 4.2's claim that the projection's result feeds the CT x CT kernels without
+    re-encoding, on a small ring: q = x Wq goes straight into decode_scores as the tiled query,
+    k = x Wk straight into append as the tiled new row."""
+    prm = toy_params(8, 3, 1, 1)
+    orc = Oracle(prm)
+    cl = Client(prm, 75, orc)
+    n, t, d1, d2 = prm.n, prm.t, 40, 8
+    B = n // d2
+    D1, T, C = attention.cpvm_shape(n, d1, d2)
+    g = Stream(75, 1)
+    x = g.integers(-8, 8, d1)
+    Wq, Wk = g.integers(-8, 8, (d1, d2)), g.integers(-8, 8, (d1, d2))
+    K = g.integers(-8, 8, (B, d2))
+    gals = set(attention.cpvm_galois(n, C, d2)) | set(attention.required_galois(n, d2))
+    gks = {gal: cl.galois_key(gal) for gal in gals}
+    rlk = cl.relin_key()
+    x_ct = cl.encrypt_slots(attention.cpvm_token_values(n, d1, d2, x))
+    enc = lambda W: [cl.codec.encode(attention.cpvm_weight_values(n, d1, d2, W, c)) for c in range(C)]
+    q_ct = attention.cpvm(orc, x_ct, enc(Wq), gks, d2)
+    k_ct = attention.cpvm(orc, x_ct, enc(Wk), gks, d2)
+    # scores of the projected query against a cache of B tokens
+    scores = attention.decode_scores(orc, q_ct, cl.encrypt_slots(K.reshape(-1)), rlk, gks, d2)
+    assert np.array_equal(cl.decrypt_slots(scores)[::d2], (K @ (x @ Wq)) % t)
+    # the projected key appended as token 3 of an empty cache
+    masks = {3: cl.codec.encode(attention.block_mask_values(n, d2, 3))}
+    cache = attention.append(orc, [], 3, k_ct, masks, d2)
+    want = np.zeros(n, dtype=np.int64)
+    want[3 * d2:4 * d2] = (x @ Wk) % t
+    assert np.array_equal(cl.decrypt_slots(cache[0]), want)
