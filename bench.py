@@ -154,6 +154,25 @@ def c5_step_ms(torch, P, steps):
             "value": round(ms, 4), "unit": "ms"}
 
 
+def cpvm_layer_us(torch, ws, reps=20):
+    """The decode step's CT x PT side at the sizes of the paper's CT x PT table: one token times the
+    36 plaintext 768 x 64 matrices of a layer's Q, K and V projections (8 diagonals each at N = 8192)."""
+    ctx, prm = ws.ctx, ws.prm
+    units, n_diag, d2 = 3 * ws.heads, 8, ws.d2
+    lim = min(prm.q + prm.p)
+    rnd = lambda hi, *shape: torch.randint(0, hi, shape, dtype=torch.int64, device="cuda")
+    x = rnd(lim, 1, 2, prm.k, prm.n)
+    diags = ctx.plain_prepare(rnd(prm.t, units * n_diag, prm.n))
+    shift = [ws.gk[g] for g in ws.g_fold[:3]]                  # keys for 3^1, 3^2, 3^4
+    block = [ws.gk[g] for g in ws.g_block]
+    out = ctx.empty_ct(units)
+    fn = lambda: ctx.cpvm(x, diags, units, n_diag, d2, shift, block, out=out)
+    fn()
+    ms = timed(torch, fn, reps)
+    return {"metric": "decode-step CT x PT projections of one layer (one token x 36 matrices of 768 x 64)",
+            "value": round(ms * 1e3, 1), "unit": "us"}
+
+
 def cpu_baseline(ws: DecodeStep):
     """Time the oracle on the whole step (same seeded inputs) and compare every output ciphertext
     of the GPU step with it."""
@@ -259,6 +278,7 @@ def main():
                      "unit": "1/s", "batch": H * C,
                      "value_at_batch_%d" % big: round(big / (mrb_ms * 1e-3), 1),
                      "transform": transform_rate(torch, ws),
+                     "ct_pt_projections": cpvm_layer_us(torch, ws),
                      "scaled_config": c5_step_ms(torch, ws.P, 10)}
 
     result = {
