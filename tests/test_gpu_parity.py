@@ -705,3 +705,59 @@ def test_cpvm_rejects_invalid_arguments():
         env.ctx.cpvm(x, plain, 2, 4, 64, [key, key], block)          # two matrices need eight diagonals
     import torch
     torch.cuda.synchronize()
+
+
+def test_one_head_of_a_decode_layer_on_real_encryptions():
+    """The pieces in the order a decode layer uses them (section 3.2's workflow), on real encryptions
+    at the N = 8192 set: CT x PT projections of the token, append of the new key and value, scores
+    against the cache, (client: decrypt, pick integer weights, re-encrypt them broadcast per block),
+    context.  What the client decrypts must be the plaintext attention arithmetic modulo t."""
+    from oracle import Client, attention
+    env = _envs.get("C2") or Env("C2")
+    _envs["C2"] = env
+    say("semantic decode layer C2 (one head)")
+    prm, n, t, d1, d2 = env.prm, env.n, env.prm.t, 768, 64
+    B = n // d2
+    tau = 5                                             # the cache holds tokens 0..4; the new token is 5
+    cl = Client(prm, 777, env.orc)
+    g = Stream(777, 1)
+    x = g.integers(-8, 8, d1)
+    W = [g.integers(-8, 8, (d1, d2)) for _ in range(3)]            # Wq, Wk, Wv
+    Kc, Vc = g.integers(-8, 8, (tau, d2)), g.integers(-8, 8, (tau, d2))
+    D1, T, C = attention.cpvm_shape(n, d1, d2)
+    gals = sorted(set(attention.cpvm_galois(n, C, d2)) | set(attention.required_galois(n, d2)))
+    say(f"  {len(gals)} Galois keys")
+    raw_g = {gal: cl.galois_key(gal) for gal in gals}
+    key = {gal: env.ctx.ksk_prepare(env.dev(raw_g[gal])) for gal in gals}
+    rlk = env.ctx.ksk_prepare(env.dev(cl.relin_key()))
+    fold = [key[gal] for gal in _fold_keys(env, d2)]
+    block = [key[gal] for gal in _block_keys(env, d2)]
+    shift = [key[pow(3, sh, 2 * n)] for sh in attention.cpvm_shifts(C)]
+    # projections: q, k, v tiled with period d2
+    diags = np.stack([cl.codec.encode(attention.cpvm_weight_values(n, d1, d2, Wm, c)) for Wm in W for c in range(C)])
+    x_ct = cl.encrypt_slots(attention.cpvm_token_values(n, d1, d2, x))
+    qkv = env.ctx.cpvm(env.dev(x_ct[None]), env.ctx.plain_prepare(env.dev(diags)), 3, C, d2, shift, block)
+    q_want, k_want, v_want = [(x @ Wm) % t for Wm in W]
+    assert np.array_equal(cl.decrypt_slots(env.host(qkv)[0]), np.tile(q_want, B))
+    # caches of the head (K then V), tokens 0..tau-1 in blocks 0..tau-1; append the new rows
+    pad = lambda M: np.concatenate([M.reshape(-1), np.zeros(n - M.size, dtype=np.int64)])
+    cache = env.dev(np.stack([cl.encrypt_slots(pad(Kc)), cl.encrypt_slots(pad(Vc))]))
+    per = env.k * n
+    import torch
+    one = env.ctx.plain_prepare(env.dev(cl.codec.encode(attention.block_mask_values(n, d2, tau))[None, :]))
+    masks = torch.zeros((tau + 1) * per, dtype=one.dtype, device=one.device)
+    masks[tau * per:] = one
+    env.ctx.kv_append(cache, 1, 2, tau, qkv[1:], masks, d2)
+    Kn, Vn = np.vstack([Kc, k_want]), np.vstack([Vc, v_want])
+    assert np.array_equal(cl.decrypt_slots(env.host(cache)[0]), pad(Kn) % t)
+    # scores of the projected query against the cache that now includes the new token
+    scores = env.ctx.decode_scores(qkv[:1], cache[:1], 1, 1, d2, rlk, fold)
+    s = cl.decrypt_slots(env.host(scores)[0, 0])[::d2]
+    assert np.array_equal(s[:tau + 1], (Kn @ q_want) % t)
+    # the client's turn: integer weights from the scores (any function will do), broadcast per block
+    a = (s[:tau + 1] % 7).astype(np.int64)
+    a_ct = cl.encrypt_slots(np.concatenate([np.repeat(a, d2), np.zeros(n - (tau + 1) * d2, dtype=np.int64)]))
+    ctxt = env.ctx.decode_context(env.dev(a_ct[None]), cache[1:], 1, 1, d2, rlk, block)
+    got = cl.decrypt_slots(env.host(ctxt)[0])
+    assert np.array_equal(got, np.tile((a @ Vn) % t, B))
+    assert cl.noise_budget_bits(env.host(ctxt)[0], cl.decrypt_poly(env.host(ctxt)[0])) > 10
