@@ -21,8 +21,9 @@ slots [b d, (b+1) d)) of a cache ciphertext holds one token's d-vector.
                   (column-per-ciphertext) cache segment; each query feature is masked,
                   broadcast by rotations and multiplied with its column ciphertext.
   prefill_qk      the prompt's Q K^T as m "generalised diagonals" (the paper
-                  names an outer-outer product and gives no procedure; this is
-                  the reading documented in the design notes).
+                  names an outer-outer product and gives no procedure; the one
+                  used is stated at the function: K rotated by whole blocks and
+                  optionally row-swapped, slot-wise product, folding sum).
   prefill_av      the prompt's A V over the same diagonals: the weights arrive
                   one ciphertext per diagonal, broadcast over each token's block.
   prefill_repack  compaction of the score ciphertexts (useful values in slot 0 of
@@ -34,7 +35,7 @@ slots [b d, (b+1) d)) of a cache ciphertext holds one token's d-vector.
                   its query in and append takes its new row in.  The paper gives the
                   operation, its operand counts (one ciphertext per token, about
                   d1 d2 / N plaintext products, O(log) rotations) and no procedure;
-                  the procedure here is the reading documented in the design notes.
+                  the one used is laid out in the comment above cpvm_shape.
 """
 import numpy as np
 
