@@ -191,15 +191,16 @@ __device__ __forceinline__ void load_row_now(const LD &ld, int wg, int tid, cons
     constexpr int T = (1 << LOGN) / E;
     constexpr int CH0 = LD::kRaw <= 2 ? 16 : (LD::kRaw <= 4 ? (E >= 16 && CHUNKED ? 4 : 8) : (E >= 16 && CHUNKED ? 2 : 4));
     constexpr int CH = CH0 < E ? CH0 : E;
-    const int first = CHUNKED ? ((tid >> 6) << chunk_log<E>()) + (tid & 63) : tid;
-    constexpr int step = CHUNKED ? 64 : T;
+    // CHUNKED: a lane takes pairs of neighbouring elements (16 bytes per operand and lane)
+    const int first = CHUNKED ? ((tid >> 6) << chunk_log<E>()) + 2 * (tid & 63) : tid;
+    auto at = [&](int it) { return CHUNKED ? first + (it & 1) + 128 * (it >> 1) : first + it * T; };
 #pragma unroll
     for (int c0 = 0; c0 < E; c0 += CH) {
         uint64_t rw[CH][LD::kRaw];
 #pragma unroll
-        for (int i = 0; i < CH; i++) ld.fetch(wg, first + (c0 + i) * step, C, rw[i]);
+        for (int i = 0; i < CH; i++) ld.fetch(wg, at(c0 + i), C, rw[i]);
 #pragma unroll
-        for (int i = 0; i < CH; i++) sink(c0 + i, ld.finish(rw[i], wg, first + (c0 + i) * step, m, C));
+        for (int i = 0; i < CH; i++) sink(c0 + i, at(c0 + i), ld.finish(rw[i], wg, at(c0 + i), m, C));
         // keep the slices apart: hoisting the next slice's loads above this one's arithmetic
         // would bring back the register pressure the slicing is there to avoid
         __builtin_amdgcn_sched_barrier(0);
@@ -309,7 +310,7 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
             for (int it = 0; it < E; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
             if (more) fetch_row<LOGN, E, false>(ld, wg_next, tid, C, raw);
         } else {
-            load_row_now<LOGN, E, false>(ld, wg, tid, m, C, [&](int it, double v) { in[it] = v; });
+            load_row_now<LOGN, E, false>(ld, wg, tid, m, C, [&](int it, int, double v) { in[it] = v; });
         }
         if constexpr (LD::kScatter) {
 #pragma unroll
@@ -435,7 +436,7 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
                 for (int it = 0; it < E; it++)
                     lds[pc + pad(it * 64)] = ld.finish(raw[it], wg, cb + it * 64, m, C);
             } else {
-                load_row_now<LOGN, E, true>(ld, wg, tid, m, C, [&](int it, double v) { lds[pc + pad(it * 64)] = v; });
+                load_row_now<LOGN, E, true>(ld, wg, tid, m, C, [&](int, int idx, double v) { lds[pad(idx)] = v; });
             }
         }
         p += (int)gridDim.x;
