@@ -1012,58 +1012,81 @@ struct ModdownArgs {
 __global__ void __launch_bounds__(PW_THREADS)
 moddown_kernel(ModdownArgs A, const DevConst *__restrict__ C)
 {
+    // a thread takes two neighbouring coefficients: 16 bytes per row and lane on every read and
+    // write that is not a permuted one
     const int logn = C->logn, N = 1 << logn, k = C->k, nsp = C->nsp, L = C->L;
-    // the N / PW_THREADS blocks of one (unit, component) run on one XCD: the permuted reads of a
+    // the N / (2 PW_THREADS) blocks of one (unit, component) run on one XCD: the permuted reads of a
     // c0 row touch all of its cache lines, which that XCD's L2 then fetches once instead of once
     // per XCD
-    const size_t gid = (size_t)xcd_row((int)blockIdx.x, (int)gridDim.x, N / PW_THREADS) * PW_THREADS + threadIdx.x;
+    const size_t gid =
+        ((size_t)xcd_row((int)blockIdx.x, (int)gridDim.x, N / (2 * PW_THREADS)) * PW_THREADS + threadIdx.x) * 2;
     const int n = (int)(gid & (N - 1));
     const int bc = (int)(gid >> logn);
     if (bc >= A.batch * 2) return;
     const int c = bc & 1, b = bc >> 1;
     const double *src = A.acc + (((size_t)bc * L) << logn) + n;
-    double xp[MAXS], dg[MAXS];
+    double xp[2][MAXS], dg[2][MAXS];
 #pragma unroll
     for (int s = 0; s < 2; s++)
         if (s < nsp) {
             const ModD mp = C->mod[k + s];
-            xp[s] = addmod_canon(canon(src[(size_t)(k + s) << logn], mp), C->halfP[k + s], mp);
+            const double2 x2 = *reinterpret_cast<const double2 *>(src + ((size_t)(k + s) << logn));
+            xp[0][s] = addmod_canon(canon(x2.x, mp), C->halfP[k + s], mp);
+            xp[1][s] = addmod_canon(canon(x2.y, mp), C->halfP[k + s], mp);
         }
-    garner<false>(C->p2q, C, xp, dg);
-    int src_idx = 0;
-    bool negate = false;
+    garner<false>(C->p2q, C, xp[0], dg[0]);
+    garner<false>(C->p2q, C, xp[1], dg[1]);
+    int src_idx[2] = {0, 0};
+    bool negate[2] = {false, false};
     if (A.galois) {
         // inverse map: output index n takes the coefficient from index n * g^-1 mod 2N
         // (A.galois already holds g^-1 mod 2N)
-        const uint32_t e = ((uint32_t)n * A.galois) & (2 * N - 1);
-        negate = e >= (uint32_t)N;
-        src_idx = (int)(negate ? e - N : e);
+#pragma unroll
+        for (int e2 = 0; e2 < 2; e2++) {
+            const uint32_t e = ((uint32_t)(n + e2) * A.galois) & (2 * N - 1);
+            negate[e2] = e >= (uint32_t)N;
+            src_idx[e2] = (int)(negate[e2] ? e - N : e);
+        }
     }
     uint64_t *o = A.out + (size_t)b * A.out_stride + (((size_t)c * k) << logn) + n;
 #pragma unroll
     for (int i = 0; i < MAXS; i++)
         if (i < k) {
             const ModD mq = C->mod[i];
-            const double ai = addmod_canon(canon(src[(size_t)i << logn], mq), C->halfP[i], mq);
-            const double ri = horner(C->p2q, C, dg, i, false);
-            double v = canon(mulmod(red(ai - ri, mq), C->Pinv_q[i], mq), mq);
+            const double2 a2 = *reinterpret_cast<const double2 *>(src + ((size_t)i << logn));
+            const double ain[2] = {a2.x, a2.y};
+            double v[2];
+#pragma unroll
+            for (int e2 = 0; e2 < 2; e2++) {
+                const double ai = addmod_canon(canon(ain[e2], mq), C->halfP[i], mq);
+                const double ri = horner(C->p2q, C, dg[e2], i, false);
+                v[e2] = canon(mulmod(red(ai - ri, mq), C->Pinv_q[i], mq), mq);
+            }
             if (A.add) {
                 const uint64_t *ad = A.add + (size_t)b * A.add_stride;
                 if (A.galois) {
                     if (c == 0) {
-                        double w = u64_to_f64(ad[((size_t)i << logn) + src_idx]);
-                        if (negate) w = (w == 0.0) ? 0.0 : mq.p - w;
-                        v = addmod_canon(v, w, mq);
+#pragma unroll
+                        for (int e2 = 0; e2 < 2; e2++) {
+                            double w = u64_to_f64(ad[((size_t)i << logn) + src_idx[e2]]);
+                            if (negate[e2]) w = (w == 0.0) ? 0.0 : mq.p - w;
+                            v[e2] = addmod_canon(v[e2], w, mq);
+                        }
                     }
                     if (A.accumulate) {
                         const uint64_t *aa = A.acc_add + (size_t)b * A.acc_stride;
-                        v = addmod_canon(v, u64_to_f64(aa[((size_t)(c * k + i) << logn) + n]), mq);
+                        const ulonglong2 w2 =
+                            *reinterpret_cast<const ulonglong2 *>(aa + ((size_t)(c * k + i) << logn) + n);
+                        v[0] = addmod_canon(v[0], u64_to_f64(w2.x), mq);
+                        v[1] = addmod_canon(v[1], u64_to_f64(w2.y), mq);
                     }
                 } else {
-                    v = addmod_canon(v, u64_to_f64(ad[((size_t)(c * k + i) << logn) + n]), mq);
+                    const ulonglong2 w2 = *reinterpret_cast<const ulonglong2 *>(ad + ((size_t)(c * k + i) << logn) + n);
+                    v[0] = addmod_canon(v[0], u64_to_f64(w2.x), mq);
+                    v[1] = addmod_canon(v[1], u64_to_f64(w2.y), mq);
                 }
             }
-            o[(size_t)i << logn] = f64_to_u64(v);
+            *reinterpret_cast<ulonglong2 *>(o + ((size_t)i << logn)) = make_ulonglong2(f64_to_u64(v[0]), f64_to_u64(v[1]));
         }
 }
 
