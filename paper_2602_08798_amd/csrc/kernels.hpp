@@ -273,10 +273,13 @@ __device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST
     if constexpr (last) {
         // results leave through LDS so that consecutive lanes write consecutive addresses; each
         // wave copies out its own chunk
-        const int cb = ((tid >> 6) << chunk_log<E>()) + (tid & 63);
-        const int pc = pad(cb);
+        // (a lane takes pairs of neighbouring elements: 16 bytes per lane and store)
+        const int cb = ((tid >> 6) << chunk_log<E>()) + 2 * (tid & 63);
 #pragma unroll
-        for (int it = 0; it < E; it++) st.store(dst_limb, cb + it * 64, lds[pc + pad(it * 64)], m);
+        for (int it = 0; it < E; it++) {
+            const int idx = cb + (it & 1) + 128 * (it >> 1);
+            st.store(dst_limb, idx, lds[pad(idx)], m);
+        }
     }
 }
 
@@ -351,7 +354,10 @@ __device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int 
     int base[G];
 #pragma unroll
     for (int g = 0; g < G; g++) {
-        const int gidx = group_index<LOGN, E, PASS>(tid, g);
+        // the last pass stores straight to global memory and all its groups share their twiddles:
+        // with an even number of groups a thread takes neighbouring ones (16 bytes per lane and store)
+        const int gidx = (last && G % 2 == 0) ? 2 * tid + (g & 1) + 2 * ((1 << LOGN) / E) * (g >> 1)
+                                              : group_index<LOGN, E, PASS>(tid, g);
         const int lo = gidx & ((1 << L) - 1);
         const int hi = last ? 0 : (gidx >> L);
         base[g] = (hi << (L + R)) | lo;
