@@ -173,14 +173,20 @@ __device__ __forceinline__ int xcd_row(int p, int nwg, int S)
 // (pass 0); CHUNKED = true: (wave << chunk_log) + lane + 64 * it (the wave's chunk).
 // Both put consecutive lanes on consecutive addresses.
 // ---------------------------------------------------------------------------
+// element `it` of a thread in the chunked ownership: a lane takes pairs of neighbouring elements of
+// its wave's chunk, so that every operand comes in (and every result goes out) 16 bytes per lane
+template <int E> __device__ __forceinline__ int chunk_elem(int tid, int it)
+{
+    return ((tid >> 6) << chunk_log<E>()) + 2 * (tid & 63) + (it & 1) + 128 * (it >> 1);
+}
+
 template <int LOGN, int E, bool CHUNKED, class LD>
 __device__ __forceinline__ void fetch_row(const LD &ld, int wg, int tid, const DevConst *C,
                                           uint64_t (&raw)[E][LD::kRaw])
 {
     constexpr int T = (1 << LOGN) / E;
-    const int first = CHUNKED ? ((tid >> 6) << chunk_log<E>()) + (tid & 63) : tid;
 #pragma unroll
-    for (int it = 0; it < E; it++) ld.fetch(wg, first + it * (CHUNKED ? 64 : T), C, raw[it]);
+    for (int it = 0; it < E; it++) ld.fetch(wg, CHUNKED ? chunk_elem<E>(tid, it) : tid + it * T, C, raw[it]);
 }
 
 // Loaders that do not prefetch fetch and finish a row in slices, so that at most about 32 raw
@@ -191,9 +197,7 @@ __device__ __forceinline__ void load_row_now(const LD &ld, int wg, int tid, cons
     constexpr int T = (1 << LOGN) / E;
     constexpr int CH0 = LD::kRaw <= 2 ? 16 : (LD::kRaw <= 4 ? (E >= 16 && CHUNKED ? 4 : 8) : (E >= 16 && CHUNKED ? 2 : 4));
     constexpr int CH = CH0 < E ? CH0 : E;
-    // CHUNKED: a lane takes pairs of neighbouring elements (16 bytes per operand and lane)
-    const int first = CHUNKED ? ((tid >> 6) << chunk_log<E>()) + 2 * (tid & 63) : tid;
-    auto at = [&](int it) { return CHUNKED ? first + (it & 1) + 128 * (it >> 1) : first + it * T; };
+    auto at = [&](int it) { return CHUNKED ? chunk_elem<E>(tid, it) : tid + it * T; };
 #pragma unroll
     for (int c0 = 0; c0 < E; c0 += CH) {
         uint64_t rw[CH][LD::kRaw];
@@ -274,10 +278,9 @@ __device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST
         // results leave through LDS so that consecutive lanes write consecutive addresses; each
         // wave copies out its own chunk
         // (a lane takes pairs of neighbouring elements: 16 bytes per lane and store)
-        const int cb = ((tid >> 6) << chunk_log<E>()) + 2 * (tid & 63);
 #pragma unroll
         for (int it = 0; it < E; it++) {
-            const int idx = cb + (it & 1) + 128 * (it >> 1);
+            const int idx = chunk_elem<E>(tid, it);
             st.store(dst_limb, idx, lds[pad(idx)], m);
         }
     }
@@ -295,8 +298,11 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
     const int S = ld.share(C);
     int p = blockIdx.x;
     int wg = xcd_row(p, nwg, S);
+    // loaders that scatter into LDS before pass 0 are free in which elements a thread brings in:
+    // they use the chunked ownership; the others bring in what pass 0 works on in registers
+    constexpr bool CH = LD::kScatter;
     uint64_t raw[PF ? E : 1][LD::kRaw];
-    if constexpr (PF) fetch_row<LOGN, E, false>(ld, wg, tid, C, raw);
+    if constexpr (PF) fetch_row<LOGN, E, CH>(ld, wg, tid, C, raw);
     for (;;) {
         const int pr = ld.prime(wg, C);
         const ModD m = C->mod[pr];
@@ -310,14 +316,15 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
         const int wg_next = more ? xcd_row(p, nwg, S) : 0;
         if constexpr (PF) {
 #pragma unroll
-            for (int it = 0; it < E; it++) in[it] = ld.finish(raw[it], wg, tid + it * T, m, C);
-            if (more) fetch_row<LOGN, E, false>(ld, wg_next, tid, C, raw);
+            for (int it = 0; it < E; it++)
+                in[it] = ld.finish(raw[it], wg, CH ? chunk_elem<E>(tid, it) : tid + it * T, m, C);
+            if (more) fetch_row<LOGN, E, CH>(ld, wg_next, tid, C, raw);
         } else {
-            load_row_now<LOGN, E, false>(ld, wg, tid, m, C, [&](int it, int, double v) { in[it] = v; });
+            load_row_now<LOGN, E, CH>(ld, wg, tid, m, C, [&](int it, int, double v) { in[it] = v; });
         }
         if constexpr (LD::kScatter) {
 #pragma unroll
-            for (int it = 0; it < E; it++) lds[pad(ld.place(tid + it * T, 1 << LOGN))] = in[it];
+            for (int it = 0; it < E; it++) lds[pad(ld.place(chunk_elem<E>(tid, it), 1 << LOGN))] = in[it];
             lds_barrier();
             fwd_pass<LOGN, E, 0, false>(lds, in, st, tid, tw, twa, twb, m, dl);
         } else {
@@ -435,12 +442,12 @@ ntt_inv_kernel(LD ld, ST st, const double *__restrict__ itw_all, const DevConst 
         {
             // each wave brings in its own chunk (consecutive lanes on consecutive addresses) and
             // re-reads it from LDS in the stride-1 pattern of the first pass
-            const int cb = ((tid >> 6) << chunk_log<E>()) + (tid & 63);
-            const int pc = pad(cb);
             if constexpr (PF) {
 #pragma unroll
-                for (int it = 0; it < E; it++)
-                    lds[pc + pad(it * 64)] = ld.finish(raw[it], wg, cb + it * 64, m, C);
+                for (int it = 0; it < E; it++) {
+                    const int idx = chunk_elem<E>(tid, it);
+                    lds[pad(idx)] = ld.finish(raw[it], wg, idx, m, C);
+                }
             } else {
                 load_row_now<LOGN, E, true>(ld, wg, tid, m, C, [&](int, int idx, double v) { lds[pad(idx)] = v; });
             }
