@@ -67,7 +67,9 @@ typedef struct {
     uint32_t log2n;       /* ring degree N = 2^log2n, 12 <= log2n <= 14 */
     uint32_t k;           /* number of ciphertext primes, 1..6 */
     uint32_t nsp;         /* number of special (key-switching) primes, 1..2 */
-    uint32_t alpha;       /* ciphertext primes per key-switch digit; divides k; <= 3 */
+    uint32_t alpha;       /* ciphertext primes per key-switch digit; divides k; <= min(3, nsp): with
+                             fewer special primes than digit primes P < Q_j and every key switch
+                             would add noise of the size of a whole prime */
     uint64_t t;           /* plaintext modulus, odd, < 2^20 */
     const uint64_t *q;    /* host: k distinct primes, q_i = 1 mod 2N, 2^40 < q_i < 2^50 */
     const uint64_t *p;    /* host: nsp primes, same conditions, distinct from q */
@@ -98,7 +100,10 @@ const char *cg_strerror(int status);
  * prime selected by prime_idx[i] (host array; 0..k-1 ciphertext primes,
  * k..k+nsp-1 special primes).  out[i][j] = in_i(psi^(2*bitrev(j)+1)) mod that
  * prime, psi its smallest primitive 2N-th root of unity; the inverse call
- * undoes it.  Canonical in, canonical out; in == out allowed.  This is the
+ * undoes it.  Canonical in, canonical out; in == out allowed.  Rows that follow the pattern
+ * prime_idx[i] = i mod period need no table on the device; any other assignment is copied
+ * from the host array when the call is made, which a graph replay would not repeat: on a
+ * capturing stream that form returns CG_EINVAL.  This is the
  * transform every product below is built on (the paper's CT x CT cost is
  * dominated by it; it is not described there). */
 int cg_ntt_forward(cg_ctx *ctx, void *stream, const uint64_t *in_dev, uint64_t *out_dev,
@@ -144,7 +149,7 @@ int cg_mul_relin(cg_ctx *ctx, void *stream, const uint64_t *a2_dev, const uint64
  * galois_elt g must be odd, 0 < g < 2N, and gk the prepared key for s(X^g) -> s.
  * accumulate = 0: out2 = rot;  accumulate = 1: out2 = in2 + rot (one step of a
  * rotate-and-add reduction).  out2 must not overlap in2 (the permuted read of c0
- * happens while other outputs are written); in2 == out2 is rejected. */
+ * happens while other outputs are written): any overlap of the two batch ranges is rejected. */
 int cg_rotate(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, uint32_t galois_elt,
               const void *gk_dev, uint64_t *out2_dev, uint32_t batch, int accumulate,
               void *ws_dev);
@@ -345,31 +350,6 @@ int cg_prefill_repack(cg_ctx *ctx, void *stream, const uint64_t *x_dev, uint32_t
 int cg_cpvm(cg_ctx *ctx, void *stream, const uint64_t *x_dev, const void *diags_dev, uint32_t units,
             uint32_t n_diag, uint32_t d2, const void *const *gk_shift_dev_host,
             const void *const *gk_block_dev_host, uint64_t *out_dev, void *ws_dev);
-
-/* Benchmark support: between cg_profile_begin and cg_profile_end every kernel
- * launch of this context is bracketed by a pair of HIP events on the stream it is
- * launched on.  cg_profile_end waits for the recorded events and returns, per
- * kernel class, the number of launches, their summed duration and their summed
- * algorithmic bytes (distinct inputs read once plus outputs written once).
- * At most max_launches launches are recorded (later ones run untimed).  Not
- * thread-safe; do not use around graph capture. */
-typedef struct {
-    uint32_t kernel_id;   /* see cg_kernel_name */
-    uint32_t launches;
-    double total_ms;
-    double algo_bytes;
-} cg_kernel_stat;
-int cg_profile_begin(cg_ctx *ctx, uint32_t max_launches);
-int cg_profile_end(cg_ctx *ctx, cg_kernel_stat *stats_host, uint32_t cap, uint32_t *n_out_host);
-const char *cg_kernel_name(uint32_t kernel_id);
-
-/* Micro-benchmark of the modular multiply used by every kernel (evidence for
- * the arithmetic choice): runs `iters` dependent modular multiplications per
- * lane on n_lanes lanes with kind 0 = FP64 FMA quotient estimate,
- * 1 = 64-bit Barrett on 32-bit integer multiplies; results go to out_dev
- * (uint64[n_lanes]) and are identical for both kinds. */
-int cg_bench_modmul(cg_ctx *ctx, void *stream, int kind, uint32_t n_lanes, uint32_t iters,
-                    uint64_t *out_dev);
 
 #ifdef __cplusplus
 }

@@ -7,6 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "cryptogen.hip")
 LIB = os.path.join(HERE, "libcryptogen_hip.so")
 DEPS = [SRC] + [os.path.join(HERE, "csrc", f) for f in ("kernels.hpp", "tables.hpp", "modarith.hpp")] + [
+    os.path.join(os.path.dirname(HERE), "include", "cryptogen_bench.h"),
     os.path.join(os.path.dirname(HERE), "include", "cryptogen.h")]
 
 FLAGS = [

@@ -1,13 +1,17 @@
 // C ABI of the library (see include/cryptogen.h): context set-up on the host,
 // argument checks, and the launch sequences of the evaluator operations.
 #include "../../include/cryptogen.h"
+#include "../../include/cryptogen_bench.h"
 
 #include <hip/hip_runtime.h>
 
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <tuple>
+#include <unordered_map>
 #include <vector>
 
 #include "kernels.hpp"
@@ -15,6 +19,7 @@
 using namespace cg;
 
 typedef unsigned __int128 u128;
+
 
 // ---------------------------------------------------------------------------
 // host integer helpers (set-up only)
@@ -89,6 +94,12 @@ struct cg_ctx {
     uint32_t *tab;        // scratch prime-index table for the public transform entry points
     uint32_t tab_cap;
     int device, n_cu;
+    // resident workgroups per compute unit of every transform-kernel instantiation this context
+    // launches, keyed by the kernel's address: filled by cg_create (a dry pass over all launch
+    // sequences), so that no launch has to ask the runtime; the lock covers a late first use
+    std::mutex *occ_mu;
+    std::unordered_map<const void *, int> *occ;
+    bool dry;             // set-up pass: launches compute their grid and return without launching
     int elems, elems_fwd; // elements per thread in the inverse / forward transform kernels (8 or 16)
     // workspace limbs (N * 8 bytes) per unit
     int ws_total;
@@ -173,7 +184,18 @@ static void fill_conv(ConvTab &T, const uint64_t *pr, const int *sidx, int ns, c
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 #define CG_REQUIRE(cond) do { if (!(cond)) return CG_EINVAL; } while (0)
 #define CG_HIP(call) do { if ((call) != hipSuccess) return CG_EHIP; } while (0)
-static int check_launch() { return hipGetLastError() == hipSuccess ? CG_OK : CG_EHIP; }
+// Launch through the runtime's C entry point: its return value is this launch's own status, so an
+// error that other code left pending in the thread is neither reported as ours nor cleared.
+template <class... P, class... A>
+static int launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t s, A... args)
+{
+    std::tuple<P...> pack{static_cast<P>(args)...};
+    void *ptrs[sizeof...(P)];
+    int i = 0;
+    std::apply([&](auto &...e) { ((ptrs[i++] = static_cast<void *>(&e)), ...); }, pack);
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, 0, s) == hipSuccess ? CG_OK
+                                                                                                         : CG_EHIP;
+}
 
 extern "C" const char *cg_strerror(int status)
 {
@@ -186,6 +208,8 @@ extern "C" const char *cg_strerror(int status)
     }
 }
 
+static int warm_launch_table(cg_ctx *c);
+
 extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
 {
     CG_REQUIRE(out && prm && prm->q && prm->p);
@@ -193,11 +217,18 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
     CG_REQUIRE(prm->log2n >= 12 && prm->log2n <= 14);
     CG_REQUIRE(prm->k >= 1 && prm->k <= 6 && prm->nsp >= 1 && prm->nsp <= 2);
     CG_REQUIRE(prm->alpha >= 1 && prm->alpha <= 3 && prm->k % prm->alpha == 0);
+    // a digit of alpha primes against fewer special primes makes P smaller than Q_j by a whole prime:
+    // every result would still match its definition, but a key switch would add noise of the size of
+    // a prime and silently use up the decryption budget
+    CG_REQUIRE(prm->alpha <= prm->nsp);
     CG_REQUIRE((prm->t & 1) && prm->t > 2 && prm->t < (1u << 20));
     const uint64_t N = 1ull << prm->log2n;
     cg_ctx *c = new (std::nothrow) cg_ctx();
     if (!c) return CG_ENOMEM;
     memset(c, 0, sizeof(*c));
+    c->occ_mu = new (std::nothrow) std::mutex();
+    c->occ = new (std::nothrow) std::unordered_map<const void *, int>();
+    if (!c->occ_mu || !c->occ) { cg_destroy(c); return CG_ENOMEM; }
     c->logn = (int)prm->log2n; c->N = (int)N; c->k = (int)prm->k; c->nsp = (int)prm->nsp;
     c->alpha = (int)prm->alpha; c->dnum = c->k / c->alpha; c->t = prm->t;
     c->l = c->k + 1;
@@ -214,7 +245,7 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
     };
     for (uint32_t i = 0; i < prm->k + prm->nsp; i++) {
         const uint64_t p = i < prm->k ? prm->q[i] : prm->p[i - prm->k];
-        if (!ok_prime(p) || p == prm->t) { delete c; return CG_EINVAL; }
+        if (!ok_prime(p) || p == prm->t) { cg_destroy(c); return CG_EINVAL; }
         c->pr[np++] = p;
         if (p < lowest) lowest = p;
     }
@@ -223,7 +254,7 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
     uint64_t cand = lowest;
     while (np < c->k + c->l) {
         cand -= 2 * N;
-        if (cand <= (1ull << 40)) { delete c; return CG_EINVAL; }
+        if (cand <= (1ull << 40)) { cg_destroy(c); return CG_EINVAL; }
         if (ok_prime(cand) && cand != prm->t) c->pr[np++] = cand;
     }
     c->np = np;
@@ -232,7 +263,7 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
     double lgQ = 0, lgB = 0;
     for (int i = 0; i < c->k; i++) lgQ += std::log2((double)c->pr[i]);
     for (int j = 0; j < c->l; j++) lgB += std::log2((double)c->pr[c->k + j]);
-    if (!(lgB > lgQ + std::log2((double)c->t) + c->logn + 3)) { delete c; return CG_EINVAL; }
+    if (!(lgB > lgQ + std::log2((double)c->t) + c->logn + 3)) { cg_destroy(c); return CG_EINVAL; }
 
     DevConst &H = c->hc;
     memset(&H, 0, sizeof(H));
@@ -295,7 +326,7 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
     if (hipGetDevice(&c->device) != hipSuccess ||
         hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess ||
         c->n_cu < 1) {
-        delete c;
+        cg_destroy(c);
         return CG_EHIP;
     }
     const size_t tbytes = (size_t)np * N * sizeof(double);
@@ -321,6 +352,14 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
         cg_destroy(c);
         return CG_EHIP;
     }
+    // one dry pass over every launch sequence fills the occupancy table
+    c->dry = true;
+    const int wrc = warm_launch_table(c);
+    c->dry = false;
+    if (wrc != CG_OK) {
+        cg_destroy(c);
+        return wrc;
+    }
     *out = c;
     return CG_OK;
 }
@@ -342,6 +381,8 @@ extern "C" int cg_destroy(cg_ctx *c)
     delete[] c->prof_ev;
     delete[] c->prof_id;
     delete[] c->prof_bytes;
+    delete c->occ;
+    delete c->occ_mu;
     delete c;
     return CG_OK;
 }
@@ -388,13 +429,21 @@ static Bump bump(const cg_ctx *c, void *ws) { return Bump{static_cast<char *>(ws
 // resident at once (what the runtime reports for this instantiation's registers and LDS), so
 // that every workgroup starts immediately and walks over its rows with the next row prefetched.
 template <auto KERNEL>
-static unsigned ntt_grid(const cg_ctx *c, size_t nwg, int threads)
+static unsigned ntt_grid(cg_ctx *c, size_t nwg, int threads)
 {
-    static int per_cu = 0;   // one value per kernel instantiation (the kernel is a template argument)
+    const void *key = reinterpret_cast<const void *>(KERNEL);
+    int per_cu = 0;
+    {
+        std::lock_guard<std::mutex> g(*c->occ_mu);
+        auto it = c->occ->find(key);
+        if (it != c->occ->end()) per_cu = it->second;
+    }
     if (per_cu == 0) {
         int n = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, KERNEL, threads, 0) != hipSuccess || n < 1) n = 1;
         per_cu = n;
+        std::lock_guard<std::mutex> g(*c->occ_mu);
+        (*c->occ)[key] = per_cu;
     }
     const size_t resident = (size_t)per_cu * (size_t)c->n_cu;
     return (unsigned)(nwg < resident ? nwg : resident);
@@ -410,19 +459,21 @@ static int launch_fwd(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int ki
     // N = 8192: a launch with no more rows than compute units finishes a row sooner on 1024 threads
     const int e = (c->logn == 13 && nwg <= (size_t)c->n_cu) ? c->elems : c->elems_fwd;
     const int threads = c->N / e;
-#define CG_FWD(LG, EL)                                                                                      \
-    hipLaunchKernelGGL((ntt_fwd_kernel<LG, EL, LD, ST>),                                                    \
-                       dim3(ntt_grid<ntt_fwd_kernel<LG, EL, LD, ST>>(c, nwg, threads)), dim3(threads), 0, s, \
-                       ld, st, c->tw, c->dc, (int)nwg)
+#define CG_FWD(LG, EL)                                                                          \
+    do {                                                                                        \
+        const unsigned grid = ntt_grid<ntt_fwd_kernel<LG, EL, LD, ST>>(c, nwg, threads);        \
+        if (c->dry) return CG_OK;                                                               \
+        return launch_kernel(ntt_fwd_kernel<LG, EL, LD, ST>, dim3(grid), dim3(threads), s, ld, st, \
+                             (const double *)c->tw, (const DevConst *)c->dc, (int)nwg);         \
+    } while (0)
     switch (c->logn * 100 + e) {
-    case 1416: CG_FWD(14, 16); break;
-    case 1208: CG_FWD(12, 8); break;
-    case 1308: CG_FWD(13, 8); break;
-    case 1316: CG_FWD(13, 16); break;
+    case 1416: CG_FWD(14, 16);
+    case 1208: CG_FWD(12, 8);
+    case 1308: CG_FWD(13, 8);
+    case 1316: CG_FWD(13, 16);
     default: return CG_EINVAL;
     }
 #undef CG_FWD
-    return check_launch();
 }
 template <class LD, class ST>
 static int launch_inv(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int kid, double bytes)
@@ -431,19 +482,21 @@ static int launch_inv(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int ki
     ProfScope ps(c, s, kid, bytes);
     const int e = (c->logn == 13 && inv_wide<LD>::value) ? 16 : ntt_elems(c);
     const int threads = c->N / e;
-#define CG_INV(LG, EL)                                                                                      \
-    hipLaunchKernelGGL((ntt_inv_kernel<LG, EL, LD, ST>),                                                    \
-                       dim3(ntt_grid<ntt_inv_kernel<LG, EL, LD, ST>>(c, nwg, threads)), dim3(threads), 0, s, \
-                       ld, st, c->itw, c->dc, (int)nwg)
+#define CG_INV(LG, EL)                                                                          \
+    do {                                                                                        \
+        const unsigned grid = ntt_grid<ntt_inv_kernel<LG, EL, LD, ST>>(c, nwg, threads);        \
+        if (c->dry) return CG_OK;                                                               \
+        return launch_kernel(ntt_inv_kernel<LG, EL, LD, ST>, dim3(grid), dim3(threads), s, ld, st, \
+                             (const double *)c->itw, (const DevConst *)c->dc, (int)nwg);        \
+    } while (0)
     switch (c->logn * 100 + e) {
-    case 1416: CG_INV(14, 16); break;
-    case 1208: CG_INV(12, 8); break;
-    case 1308: CG_INV(13, 8); break;
-    case 1316: CG_INV(13, 16); break;
+    case 1416: CG_INV(14, 16);
+    case 1208: CG_INV(12, 8);
+    case 1308: CG_INV(13, 8);
+    case 1316: CG_INV(13, 16);
     default: return CG_EINVAL;
     }
 #undef CG_INV
-    return check_launch();
 }
 static unsigned pw_blocks(const cg_ctx *c, size_t rows) { return (unsigned)((rows * c->N + PW_THREADS - 1) / PW_THREADS); }
 #define CG_TRY(expr) do { int rc_ = (expr); if (rc_ != CG_OK) return rc_; } while (0)
@@ -454,11 +507,13 @@ static unsigned pw_blocks(const cg_ctx *c, size_t rows) { return (unsigned)((row
 // one pointwise launch, bracketed by the timing scope
 #define CG_LAUNCH_PW(kid, bytes, kernel, blocks, ...)                                                  \
     do {                                                                                               \
+        if (c->dry) break;                                                                             \
+        int rc_pw_;                                                                                    \
         {                                                                                              \
             ProfScope ps_(c, s, kid, bytes);                                                           \
-            hipLaunchKernelGGL(kernel, dim3(blocks), dim3(PW_THREADS), 0, s, __VA_ARGS__);             \
+            rc_pw_ = launch_kernel(kernel, dim3(blocks), dim3(PW_THREADS), s, __VA_ARGS__);            \
         }                                                                                              \
-        CG_TRY(check_launch());                                                                        \
+        CG_TRY(rc_pw_);                                                                                \
     } while (0)
 
 // Every polynomial named by src -> its transform over the k ciphertext primes and the l auxiliary
@@ -610,6 +665,12 @@ static bool ptrs_ok(std::initializer_list<const void *> ps)
     for (const void *p : ps) if (!p || !aligned16(p)) return false;
     return true;
 }
+// two device ranges of `bytes` bytes each share at least one byte
+static bool overlap(const void *a, const void *b, size_t bytes)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + bytes && y < x + bytes;
+}
 static bool batch_ok(uint32_t batch) { return batch >= 1 && batch <= (1u << 16); }
 static bool galois_ok(const cg_ctx *c, uint32_t g) { return (g & 1) && g > 0 && g < 2u * c->N; }
 
@@ -631,6 +692,11 @@ static int public_transform(cg_ctx *c, void *stream, const uint64_t *in, uint64_
     for (uint32_t i = 0; i < n_limbs && periodic; i++) periodic = idx[i] == i % period;
     const uint32_t *tab = nullptr;
     if (!periodic) {
+        // the table is copied from the caller's (pageable) host array when the call is made, not when
+        // a captured graph replays: refuse that form on a capturing stream
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        CG_HIP(hipStreamIsCapturing(s, &cap));
+        CG_REQUIRE(cap == hipStreamCaptureStatusNone);
         CG_HIP(hipMemcpyAsync(c->tab, idx, n_limbs * sizeof(uint32_t), hipMemcpyHostToDevice, s));
         tab = c->tab;
     }
@@ -695,7 +761,8 @@ extern "C" int cg_mul_relin(cg_ctx *c, void *stream, const uint64_t *a2, const u
 extern "C" int cg_rotate(cg_ctx *c, void *stream, const uint64_t *in2, uint32_t g, const void *gk, uint64_t *out2,
                          uint32_t batch, int accumulate, void *ws)
 {
-    CG_REQUIRE(c && ptrs_ok({in2, gk, out2, ws}) && batch_ok(batch) && galois_ok(c, g) && in2 != out2);
+    CG_REQUIRE(c && ptrs_ok({in2, gk, out2, ws}) && batch_ok(batch) && galois_ok(c, g));
+    CG_REQUIRE(!overlap(in2, out2, (size_t)batch * 2 * c->k * limb_bytes(c)));
     return do_rotate(c, static_cast<hipStream_t>(stream), in2, g, gk, out2, batch, accumulate, ws);
 }
 
@@ -1142,6 +1209,35 @@ extern "C" int cg_cpvm(cg_ctx *c, void *stream, const uint64_t *x, const void *d
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, units, w.p);
 }
 
+// Every transform-kernel instantiation this context can launch, at a batch below and one above the
+// number of compute units (the forward plan depends on it).  Runs with c->dry set: the launch
+// helpers look the kernel's occupancy up, record it and return before launching, so the dummy
+// addresses are never dereferenced.
+static int warm_launch_table(cg_ctx *c)
+{
+    hipStream_t s = nullptr;
+    uint64_t *u = reinterpret_cast<uint64_t *>(uintptr_t(1) << 20);
+    double *f = reinterpret_cast<double *>(uintptr_t(1) << 20);
+    const double LB = 0.0;
+    for (uint32_t batch : {1u, 4096u}) {
+        CG_TRY(do_mul(c, s, u, u, u, batch, 1, f, 0));
+        CG_TRY(do_keyswitch(c, s, u, 0, 0, f, u, 0, u, 0, 0, 0, batch, f));
+        CG_TRY(do_keyswitch(c, s, u, 0, 3, f, u, 0, u, 0, 3, 1, batch, f));
+        const size_t rows = (size_t)batch * 2 * c->k;
+        const LdRowsU64 ld{u, nullptr, c->k, c->logn};
+        CG_TRY(launch_fwd(c, s, rows, ld, StU64{u, c->logn}, KID_FWD_ROWS, LB));
+        CG_TRY(launch_fwd(c, s, rows, ld, StF64{f, c->logn}, KID_FWD_ROWS, LB));
+        CG_TRY(launch_fwd(c, s, rows, ld, StF64Red{f, c->logn}, KID_FWD_ROWS, LB));
+        CG_TRY(launch_fwd(c, s, rows, LdPlain{u, c->logn}, StF64Red{f, c->logn}, KID_FWD_PLAIN, LB));
+        CG_TRY(launch_inv(c, s, rows, LdInvU64{u, nullptr, c->k, c->logn}, StInvU64{u, c->logn}, KID_INV_U64, LB));
+        const LdInvMulPlain mp{f, f, 1, 1, 0, 0, c->logn};
+        CG_TRY(launch_inv(c, s, rows, mp, StInvU64{u, c->logn}, KID_INV_MULPLAIN, LB));
+        CG_TRY(launch_inv(c, s, rows, mp, StInvAppend{u, 0, 1, c->logn}, KID_INV_MULPLAIN, LB));
+        CG_TRY(launch_inv(c, s, rows, LdInvPlainSum{f, f, 1, c->logn}, StInvU64{u, c->logn}, KID_INV_MULPLAIN, LB));
+    }
+    return CG_OK;
+}
+
 extern "C" int cg_profile_begin(cg_ctx *c, uint32_t max_launches)
 {
     CG_REQUIRE(c && max_launches >= 1 && max_launches <= (1u << 20) && !c->prof_on);
@@ -1192,7 +1288,6 @@ extern "C" int cg_bench_modmul(cg_ctx *c, void *stream, int kind, uint32_t n_lan
 {
     CG_REQUIRE(c && ptrs_ok({out}) && (kind == 0 || kind == 1) && n_lanes >= 1 && c->pr[0] > (1ull << 49));
     ModI mi{c->pr[0], (uint64_t)((((u128)1) << 100) / c->pr[0])};
-    hipLaunchKernelGGL(bench_modmul_kernel, dim3((n_lanes + PW_THREADS - 1) / PW_THREADS), dim3(PW_THREADS), 0,
-                       static_cast<hipStream_t>(stream), kind, n_lanes, iters, out, c->hc.mod[0], mi);
-    return check_launch();
+    return launch_kernel(bench_modmul_kernel, dim3((n_lanes + PW_THREADS - 1) / PW_THREADS), dim3(PW_THREADS),
+                         static_cast<hipStream_t>(stream), kind, n_lanes, iters, out, c->hc.mod[0], mi);
 }

@@ -357,6 +357,9 @@ def test_invalid_arguments_are_rejected_without_launching():
         env.ctx.rotate(x, 2 * env.n + 1, gk, 1)         # out of range
     with pytest.raises(CgError):
         env.ctx.rotate(x, 3, gk, 1, out=x)              # in-place is not supported
+    x3 = env.dev(env.cts(1, 3))
+    with pytest.raises(CgError):
+        env.ctx.rotate(x3[:2], 3, gk, 2, out=x3[1:])    # nor is a partial overlap of the two batches
     with pytest.raises(CgError):
         env.ctx.add(x, x, 4, 1)                         # ncomp must be 2 or 3
     with pytest.raises(CgError):
@@ -372,6 +375,9 @@ def test_invalid_arguments_are_rejected_without_launching():
     with pytest.raises(CgError):
         P.Context(bad)
     bad = dataclasses.replace(env.prm, q=(env.prm.q[0], (1 << 50) - 27))   # not 1 mod 2N
+    with pytest.raises(CgError):
+        P.Context(bad)
+    bad = dataclasses.replace(env.prm, alpha=2)          # a two-prime digit against one special prime
     with pytest.raises(CgError):
         P.Context(bad)
     torch.cuda.synchronize()
@@ -708,7 +714,7 @@ def test_cpvm_rejects_invalid_arguments():
 
 
 def test_one_head_of_a_decode_layer_on_real_encryptions():
-    """The pieces in the order a decode layer uses them (section 3.2's workflow), on real encryptions
+    """The pieces in the order a decode layer uses them (section 4.1's workflow), on real encryptions
     at the N = 8192 set: CT x PT projections of the token, append of the new key and value, scores
     against the cache, (client: decrypt, pick integer weights, re-encrypt them broadcast per block),
     context.  What the client decrypts must be the plaintext attention arithmetic modulo t."""
