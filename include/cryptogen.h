@@ -60,7 +60,8 @@ typedef enum {
     CG_OK = 0,
     CG_EINVAL = -1,   /* null / misaligned pointer, bad size, unsupported parameter */
     CG_ENOMEM = -2,   /* table allocation failed in cg_create */
-    CG_EHIP = -3      /* a HIP runtime call or kernel launch reported an error */
+    CG_EHIP = -3,     /* a HIP runtime call or kernel launch reported an error */
+    CG_ESCRATCH = -4  /* cg_mul_relin_static: the batch needs more scratch than the static array holds */
 } cg_status;
 
 typedef struct {
@@ -142,6 +143,23 @@ int cg_relin(cg_ctx *ctx, void *stream, const uint64_t *in3_dev, const void *rlk
 int cg_mul_relin(cg_ctx *ctx, void *stream, const uint64_t *a2_dev, const uint64_t *b2_dev,
                  const void *rlk_dev, uint64_t *out2_dev, uint32_t batch, uint32_t a_group,
                  void *ws_dev);
+
+/* cg_mul_relin for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and bit-identical results, but the scratch is an array of CG_STATIC_SCRATCH_BYTES
+ * bytes that is part of the loaded library (every GPU the library is used on holds its own copy
+ * until the process ends).  Neither this call nor anything below it allocates or frees memory.
+ * A batch with cg_workspace_bytes(ctx, batch) > CG_STATIC_SCRATCH_BYTES is rejected with
+ * CG_ESCRATCH before anything is launched (the limit is 9 products at N = 8192 with three
+ * ciphertext primes, 28 at N = 4096 with two); the context's device must be the current one
+ * (CG_EINVAL otherwise).  Every call on a GPU uses that GPU's one array: calls that overlap
+ * in time on the same GPU -- from any context, stream or thread -- race on it and must be
+ * ordered by the caller.  The array's previous contents never matter (every row is written
+ * before it is read), so nothing is cleared. */
+#define CG_STATIC_SCRATCH_BYTES (64u << 20)
+size_t cg_static_scratch_bytes(void);
+int cg_mul_relin_static(cg_ctx *ctx, void *stream, const uint64_t *a2_dev, const uint64_t *b2_dev,
+                        const void *rlk_dev, uint64_t *out2_dev, uint32_t batch, uint32_t a_group);
 
 /* Galois rotation (the "rotations" of the folding sum, section 4.3):
  * sigma_g moves the coefficient at index i to index i*g mod N, negated when

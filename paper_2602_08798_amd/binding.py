@@ -21,6 +21,7 @@ _SYMBOLS = [
     "cg_decode_step", "cg_decode_step_workspace_bytes", "cg_prefill_av", "cg_prefill_repack",
     "cg_cpvm", "cg_cache_extend", "cg_decode_scores_ext", "cg_decode_context_ext", "cg_decode_step_ext",
     "cg_bench_modmul", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
+    "cg_mul_relin_static", "cg_static_scratch_bytes",
 ]
 
 
@@ -67,6 +68,9 @@ class Library:
         d.cg_mul.argtypes = [vp, vp, vp, vp, vp, u32, u32, vp]
         d.cg_relin.argtypes = [vp, vp, vp, vp, vp, u32, vp]
         d.cg_mul_relin.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, vp]
+        d.cg_mul_relin_static.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32]
+        d.cg_static_scratch_bytes.argtypes = []
+        d.cg_static_scratch_bytes.restype = C.c_size_t
         d.cg_rotate.argtypes = [vp, vp, vp, u32, vp, vp, u32, i32, vp]
         d.cg_add.argtypes = [vp, vp, vp, vp, vp, u32, u32]
         d.cg_add_plain.argtypes = [vp, vp, vp, vp, u32, i32, vp, u32]
@@ -95,7 +99,8 @@ class Library:
         d.cg_kernel_name.argtypes = [u32]
         d.cg_kernel_name.restype = C.c_char_p
         for name in _SYMBOLS:
-            if name not in ("cg_workspace_bytes", "cg_decode_step_workspace_bytes", "cg_strerror", "cg_kernel_name"):
+            if name not in ("cg_workspace_bytes", "cg_decode_step_workspace_bytes", "cg_strerror", "cg_kernel_name",
+                            "cg_static_scratch_bytes"):
                 getattr(d, name).restype = i32
 
     def strerror(self, status: int) -> str:
@@ -265,6 +270,17 @@ class Context:
         ws = self.workspace(batch)
         self._check(self.lib.dll.cg_mul_relin(self.h, self.stream, _ptr(a2), _ptr(b2), _ptr(rlk),
                                               _ptr(out), batch, a_group, _ptr(ws)))
+        return out
+
+    def mul_relin_static(self, a2, b2, rlk, batch, a_group=1, out=None):
+        """cg_mul_relin_static: the scratch is the library's own static array; `out` should be given
+        by callers that must not allocate."""
+        out = self.empty_ct(batch) if out is None else out
+        self._need_mul(a2, b2, batch, a_group)
+        _need(out, self._cts(batch), "out")
+        self._need_key(rlk, "rlk")
+        self._check(self.lib.dll.cg_mul_relin_static(self.h, self.stream, _ptr(a2), _ptr(b2), _ptr(rlk),
+                                                     _ptr(out), batch, a_group))
         return out
 
     def rotate(self, in2, galois_elt, gk, batch, accumulate=False, out=None):

@@ -20,6 +20,27 @@ using namespace cg;
 
 typedef unsigned __int128 u128;
 
+// Workspace of cg_mul_relin_static, the entry point for callers that cannot allocate: device
+// memory that belongs to the loaded library itself (one copy per GPU, held until the process
+// ends).  In host code this name is only a handle for the runtime's symbol look-up; the address the
+// kernels get is the one hipGetSymbolAddress returns on the device in question, kept below.
+__device__ __align__(256) unsigned char scratch[CG_STATIC_SCRATCH_BYTES];
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices];   // per device; null until a context was created there
+// the array's address on `device`, which must be the current device
+static int static_scratch_address(int device, void **out)
+{
+    if (device < 0 || device >= kMaxDevices) return CG_EINVAL;
+    std::lock_guard<std::mutex> g(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CG_EHIP;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return CG_OK;
+}
 
 // ---------------------------------------------------------------------------
 // host integer helpers (set-up only)
@@ -94,6 +115,7 @@ struct cg_ctx {
     uint32_t *tab;        // scratch prime-index table for the public transform entry points
     uint32_t tab_cap;
     int device, n_cu;
+    void *static_ws;      // this device's copy of the library-owned scratch array
     // resident workgroups per compute unit of every transform-kernel instantiation this context
     // launches, keyed by the kernel's address: filled by cg_create (a dry pass over all launch
     // sequences), so that no launch has to ask the runtime; the lock covers a late first use
@@ -204,6 +226,7 @@ extern "C" const char *cg_strerror(int status)
     case CG_EINVAL: return "invalid argument";
     case CG_ENOMEM: return "out of device memory";
     case CG_EHIP: return "HIP runtime error";
+    case CG_ESCRATCH: return "batch needs more scratch than the library's static array holds";
     default: return "unknown status";
     }
 }
@@ -328,6 +351,10 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
         c->n_cu < 1) {
         cg_destroy(c);
         return CG_EHIP;
+    }
+    {
+        const int src = static_scratch_address(c->device, &c->static_ws);
+        if (src != CG_OK) { cg_destroy(c); return src; }
     }
     const size_t tbytes = (size_t)np * N * sizeof(double);
     c->tab_cap = 1u << 16;
@@ -756,6 +783,21 @@ extern "C" int cg_mul_relin(cg_ctx *c, void *stream, const uint64_t *a2, const u
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
     CG_TRY(do_mul(c, s, a2, b2, d3, batch, a_group, w.p, 0));
     return do_relin(c, s, d3, rlk, out2, batch, w.p);
+}
+
+extern "C" size_t cg_static_scratch_bytes(void) { return CG_STATIC_SCRATCH_BYTES; }
+
+// cg_mul_relin on the library's own scratch array: no allocation, by this call or by anything it
+// calls (launches and, with profiling on, event records only)
+extern "C" int cg_mul_relin_static(cg_ctx *c, void *stream, const uint64_t *a2, const uint64_t *b2, const void *rlk,
+                                   uint64_t *out2, uint32_t batch, uint32_t a_group)
+{
+    CG_REQUIRE(c && ptrs_ok({a2, b2, rlk, out2}) && batch_ok(batch) && a_group >= 1);
+    if (cg_workspace_bytes(c, batch) > (size_t)CG_STATIC_SCRATCH_BYTES) return CG_ESCRATCH;
+    int dev = -1;
+    CG_HIP(hipGetDevice(&dev));
+    CG_REQUIRE(dev == c->device && c->static_ws);   // the array's address differs from GPU to GPU
+    return cg_mul_relin(c, stream, a2, b2, rlk, out2, batch, a_group, c->static_ws);
 }
 
 extern "C" int cg_rotate(cg_ctx *c, void *stream, const uint64_t *in2, uint32_t g, const void *gk, uint64_t *out2,
