@@ -121,7 +121,6 @@ struct cg_ctx {
     // sequences), so that no launch has to ask the runtime; the lock covers a late first use
     std::mutex *occ_mu;
     std::unordered_map<const void *, int> *occ;
-    bool fused;           // key switches run as ks_fused_kernel + mod-down (N <= 8192); keys in register order
     bool dry;             // set-up pass: launches compute their grid and return without launching
     int elems, elems_fwd; // elements per thread in the inverse / forward transform kernels (8 or 16)
     // workspace limbs (N * 8 bytes) per unit
@@ -142,12 +141,12 @@ struct cg_ctx {
 enum KernelId {
     KID_FWD_MULQ = 0, KID_FWD_MULB, KID_FWD_MODUP, KID_FWD_ROWS, KID_FWD_PLAIN,
     KID_INV_TENSOR, KID_INV_U64, KID_INV_MULPLAIN, KID_SCALE, KID_INV_KSINNER, KID_MODDOWN,
-    KID_ADD, KID_SUM_GROUPS, KID_KS_FUSED, KID_COUNT
+    KID_ADD, KID_SUM_GROUPS, KID_COUNT
 };
 static const char *const kKernelNames[KID_COUNT] = {
     "ntt_fwd<mul,q-rows>", "ntt_fwd<mul,aux-rows>", "ntt_fwd<modup>", "ntt_fwd<rows>",
     "ntt_fwd<plain>", "ntt_inv<tensor>", "ntt_inv<u64>", "ntt_inv<mul_plain>", "scale",
-    "ntt_inv<ks_inner>", "moddown", "add", "sum_groups", "ks_fused<modup,ntt,inner,intt>"};
+    "ntt_inv<ks_inner>", "moddown", "add", "sum_groups"};
 
 // Brackets one launch with two events when profiling is on.
 struct ProfScope {
@@ -260,7 +259,6 @@ extern "C" int cg_create(cg_ctx **out, const cg_params *prm)
     c->elems_fwd = c->logn == 13 ? 16 : c->elems;   // two 512-thread workgroups per compute unit at N = 8192
     c->L = c->k + c->nsp;
     c->KL = c->k + c->l;
-    c->fused = c->logn <= 13;
     int np = 0;
     uint64_t lowest = ~0ull;
     auto ok_prime = [&](uint64_t p) {
@@ -603,33 +601,6 @@ static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *
     return CG_OK;
 }
 
-// mod-up, forward transforms, inner product with the key and inverse transforms of a batch of ring
-// elements in one launch (rings up to N = 8192)
-static int launch_ks_fused(cg_ctx *c, hipStream_t s, const KsFusedArgs &F, bool galois, double bytes)
-{
-    if (F.n_items == 0) return CG_OK;
-    ProfScope ps(c, s, KID_KS_FUSED, bytes);
-#define CG_KSF(LG, EL, AL, GA)                                                                      \
-    do {                                                                                            \
-        const unsigned grid = ntt_grid<ks_fused_kernel<LG, EL, AL, GA>>(c, (size_t)F.n_items, (1 << LG) / EL); \
-        if (c->dry) return CG_OK;                                                                   \
-        return launch_kernel(ks_fused_kernel<LG, EL, AL, GA>, dim3(grid), dim3((1 << LG) / EL), s, F, \
-                             (const double *)c->tw, (const double *)c->itw, (const DevConst *)c->dc); \
-    } while (0)
-    switch (c->logn * 100 + c->alpha * 10 + (galois ? 1 : 0)) {
-    case 1210: CG_KSF(12, 8, 1, false);
-    case 1211: CG_KSF(12, 8, 1, true);
-    case 1220: CG_KSF(12, 8, 2, false);
-    case 1221: CG_KSF(12, 8, 2, true);
-    case 1310: CG_KSF(13, 16, 1, false);
-    case 1311: CG_KSF(13, 16, 1, true);
-    case 1320: CG_KSF(13, 16, 2, false);
-    case 1321: CG_KSF(13, 16, 2, true);
-    default: return CG_EINVAL;
-    }
-#undef CG_KSF
-}
-
 // key switch of one ring element per unit (src + b*src_stride), then the final additions
 static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t src_stride, uint32_t galois,
                         const double *key, uint64_t *out2, size_t out_stride, const uint64_t *add, size_t add_stride,
@@ -642,18 +613,6 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     double *acc = w.take<double>((size_t)2 * c->L * batch);
     const double LB = (double)limb_bytes(c), B = batch;
     const double dig_rows = (double)c->dnum * c->L;
-    if (c->fused) {
-        KsFusedArgs F{};
-        F.seg[0] = KsSeg{src, src_stride, key, galois, (int)batch};
-        F.acc = acc;
-        F.n_items = (int)batch * c->L;
-        CG_TRY(launch_ks_fused(c, s, F, galois != 0, LB * ((c->k + 2.0 * c->L) * B + 2.0 * dig_rows)));
-        ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch, acc_add, acc_stride};
-        const double add_rows = !add ? 0.0 : (galois_inv ? c->k + (accumulate ? 2.0 * c->k : 0.0) : 2.0 * c->k);
-        CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, moddown_kernel,
-                     pw_blocks(c, (size_t)batch * 2) / 2, A, c->dc);
-        return CG_OK;
-    }
     const size_t nrows = (size_t)batch * c->dnum * c->L;
     const double mbytes = LB * (c->k + dig_rows) * B;
     const StF64 st{dig, c->logn};
@@ -788,15 +747,9 @@ extern "C" int cg_ntt_inverse(cg_ctx *c, void *stream, const uint64_t *in, uint6
 extern "C" int cg_ksk_prepare(cg_ctx *c, void *stream, const uint64_t *raw, void *ksk)
 {
     CG_REQUIRE(c && ptrs_ok({raw, ksk}));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const size_t rows = (size_t)c->dnum * 2 * c->L;
-    const LdRowsU64 ld{raw, nullptr, c->L, c->logn};
-    const double bytes = 4.0 * limb_bytes(c) * c->dnum * c->L;
-    double *dst = static_cast<double *>(ksk);
-    // the fused key switch reads its keys in the order its threads hold the transformed digits
-    if (c->fused && c->logn == 12) return launch_fwd(c, s, rows, ld, StF64RedReg<12, 8>{dst}, KID_FWD_ROWS, bytes);
-    if (c->fused && c->logn == 13) return launch_fwd(c, s, rows, ld, StF64RedReg<13, 16>{dst}, KID_FWD_ROWS, bytes);
-    return launch_fwd(c, s, rows, ld, StF64Red{dst, c->logn}, KID_FWD_ROWS, bytes);
+    return launch_fwd(c, static_cast<hipStream_t>(stream), (size_t)c->dnum * 2 * c->L,
+                      LdRowsU64{raw, nullptr, c->L, c->logn}, StF64Red{static_cast<double *>(ksk), c->logn},
+                      KID_FWD_ROWS, 4.0 * limb_bytes(c) * c->dnum * c->L);
 }
 
 extern "C" int cg_plain_prepare(cg_ctx *c, void *stream, const uint64_t *pt, void *plain, uint32_t batch)
@@ -1317,7 +1270,6 @@ static int warm_launch_table(cg_ctx *c)
         CG_TRY(launch_fwd(c, s, rows, ld, StU64{u, c->logn}, KID_FWD_ROWS, LB));
         CG_TRY(launch_fwd(c, s, rows, ld, StF64{f, c->logn}, KID_FWD_ROWS, LB));
         CG_TRY(launch_fwd(c, s, rows, ld, StF64Red{f, c->logn}, KID_FWD_ROWS, LB));
-        CG_TRY(cg_ksk_prepare(c, s, u, f));
         CG_TRY(launch_fwd(c, s, rows, LdPlain{u, c->logn}, StF64Red{f, c->logn}, KID_FWD_PLAIN, LB));
         CG_TRY(launch_inv(c, s, rows, LdInvU64{u, nullptr, c->k, c->logn}, StInvU64{u, c->logn}, KID_INV_U64, LB));
         const LdInvMulPlain mp{f, f, 1, 1, 0, 0, c->logn};

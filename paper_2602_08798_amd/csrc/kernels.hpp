@@ -214,12 +214,10 @@ __device__ __forceinline__ void load_row_now(const LD &ld, int wg, int tid, cons
 // ---------------------------------------------------------------------------
 // forward transform
 // ---------------------------------------------------------------------------
-// KEEP (last pass only): the results stay in registers -- keep[g * 2^R + c] = element
-// base(g) + c -- instead of leaving through LDS; nothing is written anywhere.
-template <int LOGN, int E, int PASS, bool FROM_REGS, class ST, bool KEEP = false>
+template <int LOGN, int E, int PASS, bool FROM_REGS, class ST>
 __device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST &st, int tid,
                                          const double *__restrict__ tw, const double *twr, double *twr_next,
-                                         const ModD m, int dst_limb, double *keep = nullptr)
+                                         const ModD m, int dst_limb)
 {
     using P = Plan<LOGN, E>;
     constexpr int R = P::R[PASS];
@@ -234,7 +232,6 @@ __device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST
     static_assert(!FROM_REGS || (first && L + R == LOGN), "register input only for the first pass");
     static_assert(cross || L + R <= chunk_log<E>(), "wave-local passes must stay inside one chunk");
     static_assert(!last || !cross, "the last pass must be wave-local (chunk-wise copy-out)");
-    static_assert(!KEEP || last, "only the last pass can hand its results over in registers");
     double v[G][1 << R];
     int base[G];
 #pragma unroll
@@ -266,13 +263,6 @@ __device__ __forceinline__ void fwd_pass(double *lds, const double *in, const ST
                 bfly_fwd(v[g][c], v[g][c + half], twr[g * PER + (1 << u) - 1 + (c >> (R - u))], m);
             }
         }
-    }
-    if constexpr (KEEP) {
-#pragma unroll
-        for (int g = 0; g < G; g++)
-#pragma unroll
-            for (int c = 0; c < (1 << R); c++) keep[(g << R) + c] = v[g][c];
-        return;
     }
     // fetch the next pass's factors while this pass's results drain to LDS
     if constexpr (!last) load_tw<LOGN, E, PASS + 1, false>(tw, tid, twr_next);
@@ -353,12 +343,10 @@ ntt_fwd_kernel(LD ld, ST st, const double *__restrict__ tw_all, const DevConst *
 // ---------------------------------------------------------------------------
 // inverse transform (passes in reverse order; N^-1 folded into the last stage)
 // ---------------------------------------------------------------------------
-// FROM_REGS (first inverse pass only): the inputs come from registers in the layout the forward
-// transform's last pass keeps them in (in[g * 2^R + c] = element base(g) + c).
-template <int LOGN, int E, int PASS, class ST, bool FROM_REGS = false>
+template <int LOGN, int E, int PASS, class ST>
 __device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int tid,
                                          const double *__restrict__ itw, const double *twr, double *twr_next,
-                                         const ModD m, int pr, const DevConst *C, const double *in = nullptr)
+                                         const ModD m, int pr, const DevConst *C)
 {
     using P = Plan<LOGN, E>;
     constexpr int R = P::R[PASS];
@@ -369,7 +357,6 @@ __device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int 
     constexpr bool last = PASS == 0;
     constexpr bool cross = PASS < P::NC;
     static_assert(cross || L + R <= chunk_log<E>(), "wave-local passes must stay inside one chunk");
-    static_assert(!FROM_REGS || (PASS == P::NP - 1 && !last), "register input only for the first inverse pass");
     double v[G][1 << R];
     int base[G];
 #pragma unroll
@@ -383,7 +370,7 @@ __device__ __forceinline__ void inv_pass(double *lds, const ST &st, int wg, int 
         base[g] = (hi << (L + R)) | lo;
         const int pb = pad(base[g]);
 #pragma unroll
-        for (int c = 0; c < (1 << R); c++) v[g][c] = FROM_REGS ? in[(g << R) + c] : lds[pb + pad(c << L)];
+        for (int c = 0; c < (1 << R); c++) v[g][c] = lds[pb + pad(c << L)];
     }
 #pragma unroll
     for (int g = 0; g < G; g++) {
@@ -971,158 +958,6 @@ struct StInvAppend {
         *p = f64_to_u64(r);
     }
 };
-
-// ---------------------------------------------------------------------------
-// Key switch up to (not including) the mod-down, in one kernel: a workgroup takes one
-// (ring element b, target prime r) and runs
-//     for every digit j:  lift digit j modulo q_r (the mod-up; with the Galois permutation for a
-//                         rotation), forward transform, multiply with key[j][0][r] and
-//                         key[j][1][r] and add into two accumulators held in registers;
-//     inverse transform of each accumulator  ->  acc[b][0][r], acc[b][1][r].
-// The transformed digits never leave the compute unit, and the forward transform's last pass
-// hands its results to the products -- and the accumulators theirs to the inverse transform's
-// first pass -- in registers: both passes own the same elements.  The keys are stored in that
-// "register order" (reg_order_pos), so a lane reads its 2 x E key words as 16-byte loads with
-// consecutive lanes on consecutive addresses.
-// Two segments of ring elements, each with its own source, Galois element and key, can share
-// one launch (two independent rotate-and-add chains advancing in step).
-// ---------------------------------------------------------------------------
-// position of transform-order element e of a row in register order: the thread that owns e in the
-// last forward pass (radix 8) holds it as word `half` of its i-th 16-byte pair
-template <int LOGN, int E> __host__ __device__ constexpr int reg_order_pos(int e)
-{
-    constexpr int GL = ilog2c(E / 8);                 // log2 of the groups per thread in the last pass
-    const int c = e & 7, gidx = e >> 3;
-    const int lane = gidx & 63, g = (gidx >> 6) & ((1 << GL) - 1), wave = gidx >> (6 + GL);
-    const int i = g * 4 + (c >> 1), half = c & 1;
-    return ((wave * (E / 2) + i) * 64 + lane) * 2 + half;
-}
-// forward output reduced to |x| <= p/2 and stored in register order (prepared switching keys)
-template <int LOGN, int E>
-struct StF64RedReg {
-    double *base;
-    __device__ __forceinline__ void store(int limb, int idx, double v, const ModD m) const
-    {
-        base[((size_t)limb << LOGN) + reg_order_pos<LOGN, E>(idx)] = red(v, m);
-    }
-};
-
-struct KsSeg {
-    const uint64_t *src;   // ring element of the segment's unit 0 (k rows; c1 of a ciphertext, d2 of a product)
-    size_t unit_stride;    // uint64 between consecutive units
-    const double *key;     // prepared key [dnum][2][L][N], register order
-    uint32_t galois;       // Galois element of the segment (ignored without GALOIS)
-    int units;
-};
-struct KsFusedArgs {
-    KsSeg seg[2];
-    double *acc;           // [b][2][L][N] lazy, coefficient order; b runs over segment 0, then segment 1
-    int n_items;           // (units of both segments) * L
-};
-
-template <int LOGN, int E, int ALPHA, bool GALOIS>
-__global__ void __launch_bounds__((1 << LOGN) / E, ((1 << LOGN) / E) / 256)
-ks_fused_kernel(KsFusedArgs A, const double *__restrict__ tw_all, const double *__restrict__ itw_all,
-                const DevConst *__restrict__ C)
-{
-    using P = Plan<LOGN, E>;
-    constexpr int NP = P::NP, T = (1 << LOGN) / E;
-    static_assert(P::R[NP - 1] == 3 && NP == 4, "register order assumes four passes ending in a radix-8 pass");
-    __shared__ double lds[lds_doubles<LOGN>()];
-    const int tid = threadIdx.x, Lp = C->L, dnum = C->dnum;
-    const StF64 no_store{nullptr, LOGN};
-    const StInvF64 ist{A.acc, LOGN};
-    bool first_item = true;
-    for (int pi = blockIdx.x; pi < A.n_items; pi += (int)gridDim.x) {
-        // the L items of one ring element read the same source rows: keep them on one XCD
-        const int item = xcd_row(pi, A.n_items, Lp);
-        const int b = item / Lp, r = item - b * Lp;
-        const int sg = b >= A.seg[0].units ? 1 : 0;
-        const KsSeg &S = A.seg[sg];
-        const int bb = b - (sg ? A.seg[0].units : 0);
-        const ModD m = C->mod[r];
-        const double *tw = tw_all + ((size_t)r << LOGN);
-        const double *itw = itw_all + ((size_t)r << LOGN);
-        const LdModup<GALOIS, ALPHA> ld{S.src, S.unit_stride, S.galois, LOGN};
-        double acc0[E], acc1[E];
-#pragma unroll
-        for (int i = 0; i < E; i++) acc0[i] = acc1[i] = 0.0;
-        // raw words of digit 0; the words of digit j + 1 are fetched while digit j is transformed
-        uint64_t raw[E][ALPHA];
-        fetch_row<LOGN, E, GALOIS>(ld, bb * dnum * Lp + r, tid, C, raw);
-#pragma unroll 1
-        for (int j = 0; j < dnum; j++) {
-            const int wg = (bb * dnum + j) * Lp + r;
-            double twa[TWREGS], twb[TWREGS];
-            load_tw<LOGN, E, 0, true>(tw, tid, twa);
-            double in[E];
-#pragma unroll
-            for (int it = 0; it < E; it++)
-                in[it] = ld.finish(raw[it], wg, GALOIS ? chunk_elem<E>(tid, it) : tid + it * T, m, C);
-            if (j + 1 < dnum) fetch_row<LOGN, E, GALOIS>(ld, wg + Lp, tid, C, raw);
-            // the previous transform's last reads of LDS (other waves') precede this one's first writes
-            if (!first_item || j > 0) lds_barrier();
-            first_item = false;
-            if constexpr (GALOIS) {
-#pragma unroll
-                for (int it = 0; it < E; it++) lds[pad(ld.place(chunk_elem<E>(tid, it), 1 << LOGN))] = in[it];
-                lds_barrier();
-                fwd_pass<LOGN, E, 0, false>(lds, in, no_store, tid, tw, twa, twb, m, 0);
-            } else {
-                fwd_pass<LOGN, E, 0, true>(lds, in, no_store, tid, tw, twa, twb, m, 0);
-            }
-            fwd_pass<LOGN, E, 1, false>(lds, in, no_store, tid, tw, twb, twa, m, 0);
-            fwd_pass<LOGN, E, 2, false>(lds, in, no_store, tid, tw, twa, twb, m, 0);
-            // the two key rows of (j, r), in the order this thread holds the transformed digit
-            const double2 *k0 = reinterpret_cast<const double2 *>(S.key + ((size_t)((j * 2 + 0) * Lp + r) << LOGN)) +
-                                ((tid >> 6) * (E / 2)) * 64 + (tid & 63);
-            const double2 *k1 = k0 + ((size_t)Lp << (LOGN - 1));
-            double2 kv0[E / 2], kv1[E / 2];
-#pragma unroll
-            for (int i = 0; i < E / 2; i++) {
-                kv0[i] = k0[i * 64];
-                kv1[i] = k1[i * 64];
-            }
-            double v[E];
-            fwd_pass<LOGN, E, 3, false, StF64, true>(lds, in, no_store, tid, tw, twb, twa, m, 0, v);
-            // digits are lazy (|x| < 8 p), keys reduced: each product is below 1.91 p, so up to four of
-            // them sum to less than 8 p without reducing the digit first
-            const bool rd = dnum > 4;
-#pragma unroll
-            for (int i = 0; i < E / 2; i++) {
-                const double d0 = rd ? red(v[2 * i], m) : v[2 * i], d1 = rd ? red(v[2 * i + 1], m) : v[2 * i + 1];
-                acc0[2 * i] += mulmod(d0, kv0[i].x, m);
-                acc0[2 * i + 1] += mulmod(d1, kv0[i].y, m);
-                acc1[2 * i] += mulmod(d0, kv1[i].x, m);
-                acc1[2 * i + 1] += mulmod(d1, kv1[i].y, m);
-            }
-            if (rd && (j & 3) == 3) {
-#pragma unroll
-                for (int i = 0; i < E; i++) {
-                    acc0[i] = red(acc0[i], m);
-                    acc1[i] = red(acc1[i], m);
-                }
-            }
-        }
-        // both accumulators back to coefficient order; the first pass takes them from registers and
-        // writes only this wave's chunk of LDS, which nobody else reads before the next barrier
-#pragma unroll 1
-        for (int c = 0; c < 2; c++) {
-            double x[E];
-#pragma unroll
-            for (int i = 0; i < E; i++) x[i] = c ? acc1[i] : acc0[i];
-            const int orow = (b * 2 + c) * Lp + r;
-            double twa[TWREGS], twb[TWREGS];
-            load_tw<LOGN, E, NP - 1, false>(itw, tid, twa);
-            // pass 0 of the previous inverse transform read other waves' elements
-            if (c) lds_barrier();
-            inv_pass<LOGN, E, 3, StInvF64, true>(lds, ist, orow, tid, itw, twa, twb, m, r, C, x);
-            inv_pass<LOGN, E, 2>(lds, ist, orow, tid, itw, twb, twa, m, r, C);
-            inv_pass<LOGN, E, 1>(lds, ist, orow, tid, itw, twa, twb, m, r, C);
-            inv_pass<LOGN, E, 0>(lds, ist, orow, tid, itw, twb, twa, m, r, C);
-        }
-    }
-}
 
 // ---------------------------------------------------------------------------
 // pointwise kernels

@@ -3,7 +3,7 @@ benchmark configurations as computed by the CPU oracle (and by nothing else).
 
     python -m tests.golden.make_digests C1 C2 C4        (about a minute)
     python -m tests.golden.make_digests C3              (all 12 heads: tens of minutes)
-    python -m tests.golden.make_digests C5              (first 4 of the 64 steps: several minutes)
+    python -m tests.golden.make_digests C5              (all 64 steps: about 40 minutes on 8 cores)
 
 The GPU tests recompute the same units with the HIP library from the same seeded inputs
 (workloads.configs) and compare digests, i.e. every residue of every output, bit for bit.
@@ -20,7 +20,7 @@ from oracle import Oracle, run_configs
 from workloads import configs
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-C5_STEPS = 4
+C5_STEPS = 64
 
 
 def digest(arr) -> str:
@@ -42,7 +42,7 @@ def main(names):
             note = "prefill: 3072 appends, 12 x 128 generalised diagonals of Q K^T, their compaction (12 x 2), A V (12)"
         elif name == "C5":
             inp = configs.c5_inputs(); out = run_configs.run_c5(Oracle(inp["prm"]), inp, C5_STEPS)
-            note = f"first {C5_STEPS} of 64 decode steps with cache growth, 16 heads, N = 16384"
+            note = f"{C5_STEPS} successive decode steps with cache growth, 16 heads, N = 16384"
         else:
             raise SystemExit(f"unknown configuration {name}")
         doc = {"config": name, "what": note, "source": "oracle/ only (tests/golden/make_digests.py)",
