@@ -9,19 +9,25 @@ for one generated token (GPT-2-small shape: 12 heads x d = 64, N = 8192, three
     append   the new K and V rows into 24 caches at token 512 (opens ciphertext 5)
 Inputs are seeded uniform residues (stand-ins for ciphertexts and keys; see
 workloads.synth) already resident in HBM when the timed region starts.  The
-timed step is one cg_decode_step_ext call (the three parts side by side on three
-streams, the products reading the transformed copy of the cache that earlier
-steps maintain, this step refreshing the copy of the ciphertexts it appends to);
---serial times three plain calls in sequence instead.
+step is timed as one call in two forms, K steps each: cg_decode_step (plain
+cache) and cg_decode_step_ext (the products read a transformed copy of the
+cache, which the step keeps up to date); the faster of the two is the
+headline `value`, the other is listed beside it.  --serial times three plain
+calls in sequence instead and nothing else (profiling runs).
 
-Prints ONE JSON line.  `roofline` is for the kernel class with the largest
+Prints ONE JSON line.  `roofline` describes the kernel class with the largest
 share of the step, timed with HIP events by the library itself in a further
 pass over the same work issued as three calls in sequence (so that each
-kernel has the device to itself while it is timed); `cpu_baseline` times the
-CPU oracle on the whole step of the same workload (a few seconds on the host's
-cores) and checks every output ciphertext of the GPU step against it.
+kernel has the device to itself while it is timed): its algorithmic bytes per
+second against the HBM peak and its FP64 vector instructions per second
+against the FP64 vector peak, `bound` naming the larger fraction; `roofline.step`
+gives the same two fractions for the whole step (compulsory bytes: the step's
+input and output ciphertexts and its keys, once each).  `cpu_baseline` times
+the CPU oracle on the whole step of the same workload (a few seconds on the
+host's cores) and checks every output ciphertext of the GPU step against it.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -29,8 +35,41 @@ import time
 
 import numpy as np
 
-HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-FP64_VALU_PEAK_TFLOPS = 78.6   # MI355X published vector FP64
+HBM_PEAK_GBS = 8000.0               # MI355X published HBM3E bandwidth
+FP64_VALU_PEAK_TFLOPS = 78.6        # MI355X published vector FP64 (an FMA counts as two operations)
+FP64_PEAK_LANE_INSTR = FP64_VALU_PEAK_TFLOPS * 1e12 / 2.0   # lane-instructions per second
+
+# FP64 vector instructions (per lane) that one work item of each kernel class executes at N = 8192
+# with three ciphertext primes: instructions per thread counted in the generated code of each
+# instantiation, times the threads of a workgroup (transform kernels: one item = one residue row);
+# for the pointwise kernels instructions per thread on the path taken, times the threads per batch
+# unit.  The table and its derivation are in profiles/fp64_instruction_counts.txt.
+FP64_LANE_INSTR_PER_ITEM = {
+    "ntt_fwd<mul,q-rows>": 472 * 1024,
+    "ntt_fwd<mul,aux-rows>": 936 * 1024,
+    "ntt_fwd<modup>": 528 * 1024,
+    "ntt_fwd<rows>": 472 * 1024,
+    "ntt_fwd<plain>": 514 * 1024,
+    "ntt_inv<tensor>": 760 * 1024,
+    "ntt_inv<u64>": 616 * 1024,
+    "ntt_inv<mul_plain>": 688 * 1024,
+    "ntt_inv<ks_inner>": 728 * 1024,
+    "scale": 373 * 3 * 8192,
+    "moddown": 230 * 8192,
+    "sum_groups": 16 * 9 * 8192,
+    "add": 6 * 8192,
+}
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+
+
+def kernel_sources_digest():
+    """SHA-256 over the kernel sources: stored counter readings are only quoted for the code they were taken on."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2602_08798_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()
 
 
 class DecodeStep:
@@ -95,6 +134,18 @@ class DecodeStep:
         return {"mul": 2 * H * C, "relin": H * C + H,
                 "rotate": H * C * len(self.g_fold) + H * len(self.g_block), "append": 2 * H}
 
+    def compulsory_bytes(self):
+        """What one step has to move whatever the implementation: every input ciphertext (K and V
+        caches, queries, weights, new rows), every key and block mask it uses, once each, and every
+        output ciphertext (scores, contexts, the ciphertext each cache was appended to)."""
+        H, C = self.heads, self.n_cts
+        ct = 2 * self.prm.k * self.n * 8
+        key = self.prm.dnum * 2 * (self.prm.k + self.prm.nsp) * self.n * 8
+        cts_in = 2 * H * C + H + H * C + 2 * H
+        cts_out = H * C + H + 2 * H
+        n_keys = 1 + len(self.g_fold) + len(self.g_block)
+        return (cts_in + cts_out) * ct + n_keys * key + self.n * 8
+
 
 def timed(torch, fn, steps):
     torch.cuda.synchronize()
@@ -122,14 +173,51 @@ def transform_rate(torch, ws, rows=16384, reps=5):
     st = [s for s in ws.ctx.profile_end() if s["name"] == "ntt_fwd<rows>"][0]
     ms = st["total_ms"] / st["launches"]
     gbs = rows * prm.n * 16 / (ms * 1e-3) / 1e9
+    fp64 = rows * 520 * 1024 / (ms * 1e-3)          # the uint64-out storer: 520 instructions per thread
     return {"metric": "negacyclic NTT rows/s at N=8192 (%d rows per launch, kernel time)" % rows,
             "value": round(rows / (ms * 1e-3), 1), "unit": "1/s", "avg_launch_us": round(ms * 1e3, 1),
-            "algo_GBps": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4)}
+            "algo_GBps": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
+            "fp64_valu_frac": round(fp64 / FP64_PEAK_LANE_INSTR, 4)}
 
 
-def c5_step_ms(torch, P, steps):
-    """The scaled configuration (16 heads, N = 16384, 6+2 primes): first of its 64 decode steps, where
-    the appended ciphertext is among those the products read."""
+def mult_relin_rates(torch, P, ws, steps):
+    """ct-ct mult+relin per second: N = 8192 (three primes) at batch 16, 48 and 768, and the small
+    configuration (C1: N = 4096, two primes, its 16 seeded pairs)."""
+    from workloads import configs
+    out = {}
+    H, C = ws.heads, ws.n_cts
+    b_dense = ws.cache[:H * C]
+    for batch in (16, H * C, 16 * H * C):
+        reps = -(-batch // (H * C))
+        a = ws.a.repeat(reps, 1, 1, 1)[:batch].contiguous()
+        b = b_dense.repeat(reps, 1, 1, 1)[:batch].contiguous()
+        o = ws.ctx.empty_ct(batch)
+        fn = lambda: ws.ctx.mul_relin(a, b, ws.rlk, batch, out=o)
+        for _ in range(3):
+            fn()
+        ms = timed(torch, fn, max(5, steps) if batch <= H * C else 5)
+        out["n8192_batch_%d" % batch] = round(batch / (ms * 1e-3), 1)
+        del a, b, o
+    st = configs.c1_inputs()
+    ctx = P.Context(st["prm"])
+    a, b = P.to_device(st["a"]), P.to_device(st["b"])
+    rlk = ctx.ksk_prepare(P.to_device(st["rlk"]))
+    batch = a.shape[0]
+    o = ctx.empty_ct(batch)
+    fn = lambda: ctx.mul_relin(a, b, rlk, batch, out=o)
+    for _ in range(3):
+        fn()
+    ms = timed(torch, fn, max(5, steps))
+    out["n4096_k2_batch_%d" % batch] = round(batch / (ms * 1e-3), 1)
+    ctx.close()
+    return out
+
+
+def c5_curve(torch, P):
+    """The scaled configuration (16 heads, N = 16384, 6+2 primes): all 64 successive decode steps
+    with cache growth (token 512 + i goes into the third ciphertext of every cache, which the
+    products read), each step timed on its own.  Step 0's seeded inputs are reused for the later
+    steps (kernel time does not depend on the residues); the append position is the real one."""
     from workloads import configs
     st = configs.c5_inputs()
     ctx = P.Context(st["prm"])
@@ -144,14 +232,18 @@ def c5_step_ms(torch, P, steps):
     C = si["n_cts"]
     q, a, rows = dev(si["q"]), dev(si["a"]), dev(si["rows"])
     scores, context = ctx.empty_ct(H, C), ctx.empty_ct(H)
-    step = lambda: ctx.decode_step(q, a, cache, H, C, S, d2, 512, rows, masks, rlk, fold, block,
-                                   scores=scores, context=context)
+    step = lambda tau: ctx.decode_step(q, a, cache, H, C, S, d2, tau, rows, masks, rlk, fold, block,
+                                       scores=scores, context=context)
     for _ in range(3):
-        step()
-    ms = timed(torch, step, steps)
+        step(512)
+    per = []
+    for i in range(st["steps"]):
+        per.append(timed(torch, lambda: step(512 + i), 1))
     ctx.close()
-    return {"metric": "C5 scaled decode step ms/token (one layer: 16 heads, N=16384, 6+2 primes, step 0 of 64)",
-            "value": round(ms, 4), "unit": "ms"}
+    return {"metric": "C5 scaled decode step ms/token (one layer: 16 heads, N=16384, 6+2 primes), "
+                      "64 successive steps with cache growth",
+            "value": round(float(np.mean(per)), 4), "unit": "ms", "min": round(min(per), 4),
+            "max": round(max(per), 4), "first": round(per[0], 4), "last": round(per[-1], 4)}
 
 
 def cpvm_layer_us(torch, ws, reps=20):
@@ -200,6 +292,18 @@ def cpu_baseline(ws: DecodeStep):
     }
 
 
+def stored_traffic(kernel_name):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
+    (profiles/hbm_traffic.json), or None when they were taken on other kernel sources."""
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(tpath):
+        return None, "no counter file"
+    doc = json.load(open(tpath))
+    if doc.get("kernel_sources_sha256") != kernel_sources_digest():
+        return None, "the committed counter readings were taken on other kernel sources"
+    return doc.get("bytes_per_launch", {}).get(kernel_name), None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -207,7 +311,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true",
-                    help="time the three calls in sequence instead of the one-call step (profiling runs)")
+                    help="issue the step as three calls in sequence and nothing else: every kernel has the "
+                         "device to itself (profiling runs)")
+    ap.add_argument("--one-call", choices=["plain", "ext"], default=None,
+                    help="time only this form of the one-call step and nothing else (profiling runs)")
     ap.add_argument("--no-secondary", action="store_true",
                     help="skip the mult+relin/sec loops (used when profiling the step alone)")
     args = ap.parse_args()
@@ -221,66 +328,96 @@ def main():
         sys.exit(1)
 
     ws = DecodeStep()
-    step = ws.step_serial if args.serial else ws.step
-    for _ in range(args.warmup):
-        step()
-    ms = timed(torch, step, args.steps)
-    ms_serial = ms if args.serial else timed(torch, ws.step_serial, args.steps)
-    ms_plain = timed(torch, ws.step_plain_cache, args.steps)
+    profiling_run = args.serial or args.one_call is not None
+    ms_ext = ms_plain = ms_serial = None
+    if args.serial:
+        for _ in range(args.warmup):
+            ws.step_serial()
+        ms = ms_serial = timed(torch, ws.step_serial, args.steps)
+        form = "serial"
+    elif args.one_call:
+        fn = ws.step if args.one_call == "ext" else ws.step_plain_cache
+        for _ in range(args.warmup):
+            fn()
+        ms = timed(torch, fn, args.steps)
+        form = args.one_call
+    else:
+        for _ in range(args.warmup):
+            ws.step()
+            ws.step_plain_cache()
+        ms_ext = timed(torch, ws.step, args.steps)
+        ms_plain = timed(torch, ws.step_plain_cache, args.steps)
+        ms_serial = timed(torch, ws.step_serial, args.steps)
+        ms, form = (ms_ext, "ext") if ms_ext <= ms_plain else (ms_plain, "plain")
 
-    # second pass over the same work, one call after the other, with the library's event
-    # bracketing for per-kernel figures
-    ws.ctx.profile_begin(200 * args.steps)
-    for _ in range(args.steps):
-        ws.step_serial()
-    stats = ws.ctx.profile_end()
-    kernels = []
-    for s in stats:
-        avg_us = s["total_ms"] * 1e3 / s["launches"]
-        gbs = s["algo_bytes"] / (s["total_ms"] * 1e-3) / 1e9
-        kernels.append({"name": s["name"], "launches_per_step": s["launches"] / args.steps,
-                        "avg_us": round(avg_us, 2), "ms_per_step": round(s["total_ms"] / args.steps, 4),
-                        "algo_GBps": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4)})
-    kernels.sort(key=lambda k: -k["ms_per_step"])
-    dom = kernels[0]
-    dom_stat = next(s for s in stats if s["name"] == dom["name"])
-    traffic = None
-    tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(dom["name"])
-    roofline = {"bound": "hbm", "kernel": dom["name"], "achieved": dom["algo_GBps"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(dom["algo_GBps"] / HBM_PEAK_GBS, 4),
-                "traffic": traffic,
-                "algo_bytes_per_launch": dom_stat["algo_bytes"] / dom_stat["launches"],
-                "avg_launch_us": dom["avg_us"]}
+    kernels, roofline = [], None
+    if args.one_call is None:
+        # a pass over the same work, one call after the other, with the library's event
+        # bracketing for per-kernel figures
+        ws.ctx.profile_begin(200 * args.steps)
+        for _ in range(args.steps):
+            ws.step_serial()
+        stats = ws.ctx.profile_end()
+        fp64_step = 0.0
+        for s in stats:
+            sec = s["total_ms"] * 1e-3
+            gbs = s["algo_bytes"] / sec / 1e9
+            fp64 = s["work_items"] * FP64_LANE_INSTR_PER_ITEM.get(s["name"], 0)
+            fp64_step += fp64 / args.steps
+            kernels.append({"name": s["name"], "launches_per_step": s["launches"] / args.steps,
+                            "avg_us": round(s["total_ms"] * 1e3 / s["launches"], 2),
+                            "ms_per_step": round(s["total_ms"] / args.steps, 4),
+                            "algo_GBps": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
+                            "fp64_valu_frac": round(fp64 / sec / FP64_PEAK_LANE_INSTR, 4)})
+        kernels.sort(key=lambda k: -k["ms_per_step"])
+        dom = kernels[0]
+        dom_stat = next(s for s in stats if s["name"] == dom["name"])
+        traffic, traffic_note = stored_traffic(dom["name"])
+        bound = "hbm" if dom["hbm_frac"] >= dom["fp64_valu_frac"] else "alu"
+        step_bytes = ws.compulsory_bytes()
+        roofline = {
+            "bound": bound, "kernel": dom["name"],
+            "achieved": dom["algo_GBps"] if bound == "hbm" else round(dom["fp64_valu_frac"] * FP64_VALU_PEAK_TFLOPS, 2),
+            "peak": HBM_PEAK_GBS if bound == "hbm" else FP64_VALU_PEAK_TFLOPS,
+            "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+            "frac": dom["hbm_frac"] if bound == "hbm" else dom["fp64_valu_frac"],
+            "traffic": traffic,
+            "hbm_frac": dom["hbm_frac"], "fp64_valu_frac": dom["fp64_valu_frac"],
+            "algo_bytes_per_launch": dom_stat["algo_bytes"] / dom_stat["launches"],
+            "avg_launch_us": dom["avg_us"],
+            "note": "neither unit is near its peak: at the step's launch sizes (96 to 1008 rows on 256 compute "
+                    "units) a kernel's time is the latency of one or two rows per unit, not a rate",
+            "step": {"ms": round(ms, 4), "compulsory_bytes": step_bytes,
+                     "hbm_frac": round(step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "fp64_lane_instr": round(fp64_step),
+                     "fp64_valu_frac": round(fp64_step / (ms * 1e-3) / FP64_PEAK_LANE_INSTR, 4)},
+        }
+        if traffic_note:
+            roofline["traffic_note"] = traffic_note
 
     secondary = None
-    if not args.no_secondary:
-        # secondary metric: ct-ct mult+relin per second at N = 8192, batch 48
-        H, C = ws.heads, ws.n_cts
-        out2 = ws.ctx.empty_ct(H * C)
-        b_dense = ws.cache[:H * C]
-        mr = lambda: ws.ctx.mul_relin(ws.a, b_dense, ws.rlk, H * C, out=out2)
-        mr()
-        mr_ms = timed(torch, mr, max(5, args.steps))
-
-        # same metric at a batch large enough to keep every compute unit busy for several rows
-        big = 16 * H * C
-        a_big = ws.a.repeat(16, 1, 1, 1)
-        b_big = b_dense.repeat(16, 1, 1, 1)
-        out_big = ws.ctx.empty_ct(big)
-        mrb = lambda: ws.ctx.mul_relin(a_big, b_big, ws.rlk, big, out=out_big)
-        for _ in range(3):
-            mrb()
-        mrb_ms = timed(torch, mrb, 5)
-        del a_big, b_big, out_big
-        secondary = {"metric": "ct-ct mult+relin/sec at N=8192", "value": round(H * C / (mr_ms * 1e-3), 1),
-                     "unit": "1/s", "batch": H * C,
-                     "value_at_batch_%d" % big: round(big / (mrb_ms * 1e-3), 1),
+    if not args.no_secondary and not profiling_run:
+        rates = mult_relin_rates(torch, ws.P, ws, args.steps)
+        secondary = {"metric": "ct-ct mult+relin/sec at N=8192", "value": rates["n8192_batch_48"],
+                     "unit": "1/s", "batch": 48, "all": rates,
                      "transform": transform_rate(torch, ws),
                      "ct_pt_projections": cpvm_layer_us(torch, ws),
-                     "scaled_config": c5_step_ms(torch, ws.P, 10)}
+                     "scaled_config": c5_curve(torch, ws.P)}
 
+    launch = {"serial": "three calls in sequence",
+              "ext": "cg_decode_step_ext: scores, context and append side by side on three streams; the products "
+                     "read the cache's transformed copy and the step refreshes the copy of the 24 ciphertexts it "
+                     "appends to",
+              "plain": "cg_decode_step: scores, context and append side by side on three streams"}[form]
+    config = {"workload": "C4: decode step, 12 heads x d=64, 512-token encrypted KV cache, N=8192, "
+                          "3+1 primes < 2^50, t=65537", "ops_per_step": ws.op_counts(),
+              "arithmetic": "exact integer residues < 2^50 carried in FP64 registers; uint64 at the ABI",
+              "derived_12_layers_ms_per_token": round(12 * ms, 3), "launch": launch}
+    if ms_ext is not None:
+        config["ms_per_step_cg_decode_step_ext"] = round(ms_ext, 4)
+        config["ms_per_step_cg_decode_step"] = round(ms_plain, 4)
+    if ms_serial is not None:
+        config["ms_per_step_three_calls_in_sequence"] = round(ms_serial, 4)
     result = {
         "metric": "encrypted decode-step ms/token at 512 ctx",
         "value": round(ms, 4), "unit": "ms/token (one layer: 12 heads, CT x CT path)",
@@ -288,21 +425,12 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64",
         "data": "synthetic",
-        "config": {"workload": "C4: decode step, 12 heads x d=64, 512-token encrypted KV cache, N=8192, "
-                               "3+1 primes < 2^50, t=65537", "ops_per_step": ws.op_counts(),
-                   "arithmetic": "exact integer residues < 2^50 carried in FP64 registers; uint64 at the ABI",
-                   "derived_12_layers_ms_per_token": round(12 * ms, 3),
-                   "launch": "three calls in sequence" if args.serial else
-                             "cg_decode_step_ext: scores, context and append side by side on three streams; the "
-                             "products read the cache's transformed copy and the step refreshes the copy of the "
-                             "24 ciphertexts it appends to",
-                   "ms_per_step_without_transformed_cache_copy": round(ms_plain, 4),
-                   "ms_per_step_three_calls_in_sequence": round(ms_serial, 4)},
+        "config": config,
         "secondary": secondary,
         "roofline": roofline,
         "kernels": kernels,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not profiling_run:
         result["cpu_baseline"] = cpu_baseline(ws)
     print(json.dumps(result))
 

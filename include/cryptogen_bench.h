@@ -16,8 +16,9 @@ extern "C" {
 /* Benchmark support: between cg_profile_begin and cg_profile_end every kernel
  * launch of this context is bracketed by a pair of HIP events on the stream it is
  * launched on.  cg_profile_end waits for the recorded events and returns, per
- * kernel class, the number of launches, their summed duration and their summed
- * algorithmic bytes (distinct inputs read once plus outputs written once).
+ * kernel class, the number of launches, their summed duration, their summed
+ * algorithmic bytes (distinct inputs read once plus outputs written once) and the
+ * rows (transforms) or batch units (pointwise kernels) they processed.
  * At most max_launches launches are recorded (later ones run untimed).  Not
  * thread-safe; do not use around graph capture. */
 typedef struct {
@@ -25,6 +26,7 @@ typedef struct {
     uint32_t launches;
     double total_ms;
     double algo_bytes;
+    double work_items;    /* residue rows worked through by transform launches; batch units for pointwise ones */
 } cg_kernel_stat;
 int cg_profile_begin(cg_ctx *ctx, uint32_t max_launches);
 int cg_profile_end(cg_ctx *ctx, cg_kernel_stat *stats_host, uint32_t cap, uint32_t *n_out_host);

@@ -39,7 +39,7 @@ class _Sizes(C.Structure):
 
 class _KernelStat(C.Structure):
     _fields_ = [("kernel_id", C.c_uint32), ("launches", C.c_uint32),
-                ("total_ms", C.c_double), ("algo_bytes", C.c_double)]
+                ("total_ms", C.c_double), ("algo_bytes", C.c_double), ("work_items", C.c_double)]
 
 
 class Library:
@@ -486,13 +486,14 @@ class Context:
         self._check(self.lib.dll.cg_profile_begin(self.h, max_launches))
 
     def profile_end(self):
-        """-> list of dicts {name, launches, total_ms, algo_bytes} per kernel class."""
+        """-> list of dicts {name, launches, total_ms, algo_bytes, work_items} per kernel class."""
         stats = (_KernelStat * 32)()
         n = C.c_uint32(0)
         self._check(self.lib.dll.cg_profile_end(self.h, stats, 32, C.byref(n)))
         return [dict(name=self.lib.dll.cg_kernel_name(stats[i].kernel_id).decode(),
                      launches=int(stats[i].launches), total_ms=float(stats[i].total_ms),
-                     algo_bytes=float(stats[i].algo_bytes)) for i in range(n.value)]
+                     algo_bytes=float(stats[i].algo_bytes), work_items=float(stats[i].work_items))
+                for i in range(n.value)]
 
     def bench_modmul(self, kind, n_lanes, iters, out=None):
         out = torch.empty(n_lanes, dtype=torch.int64, device=self.device) if out is None else out

@@ -135,6 +135,7 @@ struct cg_ctx {
     hipEvent_t *prof_ev;      // 2 * prof_cap events
     uint8_t *prof_id;
     double *prof_bytes;
+    double *prof_items;
 };
 
 // kernel classes for the timing facility
@@ -153,12 +154,14 @@ struct ProfScope {
     cg_ctx *c;
     hipStream_t s;
     int slot;
-    ProfScope(cg_ctx *c_, hipStream_t s_, int id, double bytes) : c(c_), s(s_), slot(-1)
+    // items: residue rows a transform launch works through, batch units for a pointwise launch
+    ProfScope(cg_ctx *c_, hipStream_t s_, int id, double bytes, double items) : c(c_), s(s_), slot(-1)
     {
         if (c->prof_on && c->prof_n < c->prof_cap) {
             slot = (int)c->prof_n++;
             c->prof_id[slot] = (uint8_t)id;
             c->prof_bytes[slot] = bytes;
+            c->prof_items[slot] = items;
             (void)hipEventRecord(c->prof_ev[2 * slot], s);
         }
     }
@@ -408,6 +411,7 @@ extern "C" int cg_destroy(cg_ctx *c)
     delete[] c->prof_ev;
     delete[] c->prof_id;
     delete[] c->prof_bytes;
+    delete[] c->prof_items;
     delete c->occ;
     delete c->occ_mu;
     delete c;
@@ -482,7 +486,7 @@ template <class LD, class ST>
 static int launch_fwd(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int kid, double bytes)
 {
     if (nwg == 0) return CG_OK;
-    ProfScope ps(c, s, kid, bytes);
+    ProfScope ps(c, s, kid, bytes, (double)nwg);
     // N = 8192: a launch with no more rows than compute units finishes a row sooner on 1024 threads
     const int e = (c->logn == 13 && nwg <= (size_t)c->n_cu) ? c->elems : c->elems_fwd;
     const int threads = c->N / e;
@@ -506,7 +510,7 @@ template <class LD, class ST>
 static int launch_inv(cg_ctx *c, hipStream_t s, size_t nwg, LD ld, ST st, int kid, double bytes)
 {
     if (nwg == 0) return CG_OK;
-    ProfScope ps(c, s, kid, bytes);
+    ProfScope ps(c, s, kid, bytes, (double)nwg);
     const int e = (c->logn == 13 && inv_wide<LD>::value) ? 16 : ntt_elems(c);
     const int threads = c->N / e;
 #define CG_INV(LG, EL)                                                                          \
@@ -532,12 +536,12 @@ static unsigned pw_blocks(const cg_ctx *c, size_t rows) { return (unsigned)((row
 // internal operations (arguments already validated)
 // ---------------------------------------------------------------------------
 // one pointwise launch, bracketed by the timing scope
-#define CG_LAUNCH_PW(kid, bytes, kernel, blocks, ...)                                                  \
+#define CG_LAUNCH_PW(kid, bytes, items, kernel, blocks, ...)                                                \
     do {                                                                                               \
         if (c->dry) break;                                                                             \
         int rc_pw_;                                                                                    \
         {                                                                                              \
-            ProfScope ps_(c, s, kid, bytes);                                                           \
+            ProfScope ps_(c, s, kid, bytes, items);                                                    \
             rc_pw_ = launch_kernel(kernel, dim3(blocks), dim3(PW_THREADS), s, __VA_ARGS__);            \
         }                                                                                              \
         CG_TRY(rc_pw_);                                                                                \
@@ -588,7 +592,7 @@ static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *
                       LB * c->KL * (2.0 * ((double)n_a + B) + 3.0 * B)));
     const double sbytes = LB * (3.0 * c->KL + 3.0 * c->k * (accumulate ? 2 : 1)) * B;
     const unsigned sblocks = pw_blocks(c, (size_t)batch * 3);
-#define CG_SCALE(K) CG_LAUNCH_PW(KID_SCALE, sbytes, scale_kernel<K>, sblocks, tens, out3, (int)batch * 3, accumulate, c->dc)
+#define CG_SCALE(K) CG_LAUNCH_PW(KID_SCALE, sbytes, (double)batch, scale_kernel<K>, sblocks, tens, out3, (int)batch * 3, accumulate, c->dc)
     switch (c->k) {
     case 1: CG_SCALE(1); break;
     case 2: CG_SCALE(2); break;
@@ -645,7 +649,7 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     CG_TRY(rc);
     ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch, acc_add, acc_stride};
     const double add_rows = !add ? 0.0 : (galois_inv ? c->k + (accumulate ? 2.0 * c->k : 0.0) : 2.0 * c->k);
-    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, moddown_kernel,
+    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, B, moddown_kernel,
                  pw_blocks(c, (size_t)batch * 2) / 2, A, c->dc);
     return CG_OK;
 }
@@ -682,7 +686,7 @@ static int do_rotate(cg_ctx *c, hipStream_t s, const uint64_t *in2, uint32_t g, 
 
 static int do_add(cg_ctx *c, hipStream_t s, const uint64_t *a, const uint64_t *b, uint64_t *out, size_t rows)
 {
-    CG_LAUNCH_PW(KID_ADD, (double)limb_bytes(c) * 3.0 * rows, add_kernel, pw_blocks(c, rows), a, b, out, (int)rows,
+    CG_LAUNCH_PW(KID_ADD, (double)limb_bytes(c) * 3.0 * rows, (double)rows, add_kernel, pw_blocks(c, rows), a, b, out, (int)rows,
                  c->dc);
     return CG_OK;
 }
@@ -821,7 +825,7 @@ extern "C" int cg_add_plain(cg_ctx *c, void *stream, const uint64_t *in2, const 
     CG_REQUIRE(c && ptrs_ok({in2, pt, out2}) && batch_ok(batch) && n_plain >= 1 && n_plain <= batch);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t rows = (size_t)batch * 2 * c->k;
-    CG_LAUNCH_PW(KID_ADD, (double)limb_bytes(c) * (2.0 * rows + n_plain), add_plain_kernel, pw_blocks(c, rows), in2, pt,
+    CG_LAUNCH_PW(KID_ADD, (double)limb_bytes(c) * (2.0 * rows + n_plain), (double)rows, add_plain_kernel, pw_blocks(c, rows), in2, pt,
                  out2, (int)batch, (int)n_plain, negative ? 1 : 0, c->dc);
     return CG_OK;
 }
@@ -947,7 +951,7 @@ static int context_impl(cg_ctx *c, void *stream, const uint64_t *a, const uint64
     CG_TRY(do_mul(c, s, a, vc, d3, batch, 1, w.p, 0, n_cts, cache_stride_cts, vext));
     // y[h] = sum_c d3[h][c]  (three components)
     const int rows = 3 * c->k;
-    CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), sum_groups_kernel,
+    CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), (double)batch, sum_groups_kernel,
                  pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)n_cts, rows, c->dc);
     CG_TRY(do_relin(c, s, y, rlk, xa, heads, w.p));
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, heads, w.p);
@@ -1085,7 +1089,7 @@ extern "C" int cg_decode_scores_outer(cg_ctx *c, void *stream, const uint64_t *q
     if (nrot) CG_TRY(rotate_add_chain(c, s, xa, xb, bc, gs, gk_fold, nrot, batch, w.p));
     CG_TRY(do_mul(c, s, bc, kcols, d3, batch, 1, w.p, 0));
     const int rows = 3 * c->k;
-    CG_LAUNCH_PW(KID_SUM_GROUPS, LB * rows * (batch + heads), sum_groups_kernel, pw_blocks(c, (size_t)heads * rows),
+    CG_LAUNCH_PW(KID_SUM_GROUPS, LB * rows * (batch + heads), (double)batch, sum_groups_kernel, pw_blocks(c, (size_t)heads * rows),
                  d3, y, (int)heads, (int)d2, rows, c->dc);
     return do_relin(c, s, y, rlk, out, heads, w.p);
 }
@@ -1170,7 +1174,7 @@ extern "C" int cg_prefill_av(cg_ctx *c, void *stream, const uint64_t *a, const u
     CG_TRY(rotated_copies(c, s, v, heads, d2, gk_blk, gk_swap, vp, w.p));
     CG_TRY(do_mul(c, s, a, vp, d3, batch, 1, w.p, 0));
     const int rows = 3 * c->k;
-    CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), sum_groups_kernel,
+    CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), (double)batch, sum_groups_kernel,
                  pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)m, rows, c->dc);
     return do_relin(c, s, y, rlk, out, heads, w.p);
 }
@@ -1285,12 +1289,13 @@ extern "C" int cg_profile_begin(cg_ctx *c, uint32_t max_launches)
     CG_REQUIRE(c && max_launches >= 1 && max_launches <= (1u << 20) && !c->prof_on);
     if (c->prof_cap < max_launches) {
         for (uint32_t i = 0; i < 2 * c->prof_cap; i++) (void)hipEventDestroy(c->prof_ev[i]);
-        delete[] c->prof_ev; delete[] c->prof_id; delete[] c->prof_bytes;
+        delete[] c->prof_ev; delete[] c->prof_id; delete[] c->prof_bytes; delete[] c->prof_items;
         c->prof_cap = 0;
         c->prof_ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_launches];
         c->prof_id = new (std::nothrow) uint8_t[max_launches];
         c->prof_bytes = new (std::nothrow) double[max_launches];
-        if (!c->prof_ev || !c->prof_id || !c->prof_bytes) return CG_ENOMEM;
+        c->prof_items = new (std::nothrow) double[max_launches];
+        if (!c->prof_ev || !c->prof_id || !c->prof_bytes || !c->prof_items) return CG_ENOMEM;
         for (uint32_t i = 0; i < 2 * max_launches; i++) CG_HIP(hipEventCreate(&c->prof_ev[i]));
         c->prof_cap = max_launches;
     }
@@ -1313,6 +1318,7 @@ extern "C" int cg_profile_end(cg_ctx *c, cg_kernel_stat *stats, uint32_t cap, ui
         k.launches++;
         k.total_ms += ms;
         k.algo_bytes += c->prof_bytes[i];
+        k.work_items += c->prof_items[i];
     }
     uint32_t n = 0;
     for (int id = 0; id < KID_COUNT; id++)

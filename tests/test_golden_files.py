@@ -20,7 +20,7 @@ def test_digest_files_cover_every_output_unit():
     assert len(_load("C2")["digests"]) == 1
     assert len(_load("C4")["digests"]) == 48 + 12 + 24
     assert len(_load("C3")["digests"]) == 24 + 12 * (128 + 2 + 1)
-    assert len(_load("C5")["digests"]) == 4 * (32 + 16 * 3 + 16)
+    assert len(_load("C5")["digests"]) == 64 * (32 + 16 * 3 + 16)     # all 64 steps
     for name in ("C1", "C2", "C3", "C4", "C5"):
         assert _load(name)["source"].startswith("oracle/ only")
 
