@@ -375,6 +375,13 @@ def main():
         traffic, traffic_note = stored_traffic(dom["name"])
         bound = "hbm" if dom["hbm_frac"] >= dom["fp64_valu_frac"] else "alu"
         step_bytes = ws.compulsory_bytes()
+        if form == "ext":
+            # the timed step read the cache's transformed copy: no lift and forward transform of the 2 H C
+            # cache operands (2 polynomials each: k ciphertext-prime rows, k + 1 auxiliary rows), but
+            # the same for the 2 H ciphertexts the step appended to
+            saved = 2 * (2 * ws.heads * ws.n_cts - 2 * ws.heads)
+            fp64_step -= saved * (ws.prm.k * FP64_LANE_INSTR_PER_ITEM["ntt_fwd<mul,q-rows>"]
+                                  + (ws.prm.k + 1) * FP64_LANE_INSTR_PER_ITEM["ntt_fwd<mul,aux-rows>"])
         roofline = {
             "bound": bound, "kernel": dom["name"],
             "achieved": dom["algo_GBps"] if bound == "hbm" else round(dom["fp64_valu_frac"] * FP64_VALU_PEAK_TFLOPS, 2),

@@ -42,6 +42,7 @@ def load_library():
     lib.orc_relin.argtypes = [C.c_void_p, _U64P, _U64P, _U64P]
     lib.orc_galois_poly.argtypes = [C.c_void_p, _U64P, C.c_uint64, _U64P]
     lib.orc_rotate.argtypes = [C.c_void_p, _U64P, C.c_uint64, _U64P, _U64P]
+    lib.orc_rotate_hoisted.argtypes = [C.c_void_p, _U64P, C.c_uint64, _U64P, _U64P]
     lib.orc_mul_plain.argtypes = [C.c_void_p, _U64P, _U64P, _U64P]
     lib.orc_add_plain.argtypes = [C.c_void_p, _U64P, _U64P, C.c_int, _U64P]
     lib.orc_test_crt.restype = C.c_int
@@ -231,6 +232,19 @@ class Oracle:
         out = np.empty_like(in2)
         self.lib.orc_rotate(self.ctx, _p(in2), g, _p(gk), _p(out))
         return out
+
+    def rotate_hoisted(self, in2, g: int, gk):
+        """Rotation with the digits taken from c1 before the Galois map (the form in which one
+        decomposition serves a whole series of rotations of the same ciphertext)."""
+        assert g % 2 == 1 and 0 < g < 2 * self.n
+        in2, gk = self._ct(in2, 2), self._key(gk)
+        out = np.empty_like(in2)
+        self.lib.orc_rotate_hoisted(self.ctx, _p(in2), g, _p(gk), _p(out))
+        return out
+
+    def rotate_many(self, in2, gs, gks):
+        """[rotate_hoisted(in2, g, gks[g]) for g in gs]: a series of rotations of one ciphertext."""
+        return [self.rotate_hoisted(in2, g, gks[g]) for g in gs]
 
     def add_plain(self, in2, pt, negative=False):
         """(c0 +- floor(Q/t) pt, c1): Algorithm 1 step 1, the server's masking and unmasking."""

@@ -600,23 +600,13 @@ void orc_mul(const orc_ctx *c, const u64 *a2, const u64 *b2, u64 *out3)
     free(prod);
 }
 
-/* hybrid key switch of one ring element d (uint64[k][N]) with key ksk; u2 = uint64[2][k][N] */
-void orc_keyswitch(const orc_ctx *c, const u64 *d, const u64 *ksk, u64 *u2)
+/* Second half of a key switch, from the digits already reduced modulo every prime of P*Q
+ * (dig = uint64[dnum][k+nsp][N]): A_c = sum_j digit_j * ksk_{j,c} in Z_{PQ}[X]/(X^N+1),
+ * u_c = floor((A_c + floor(P/2)) / P) mod Q with A_c taken in [0, PQ); u2 = uint64[2][k][N] */
+static void switch_digits(const orc_ctx *c, const u64 *dig, const u64 *ksk, u64 *u2)
 {
-    const int N = c->N, k = c->k, nsp = c->nsp, L = k + nsp, dnum = c->dnum, alpha = c->alpha;
-    u64 *dig = (u64 *)malloc(sizeof(u64) * (size_t)dnum * L * N);
+    const int N = c->N, k = c->k, nsp = c->nsp, L = k + nsp, dnum = c->dnum;
     u64 *acc = (u64 *)calloc((size_t)2 * L * N, sizeof(u64));
-    /* digit j = d mod Q_j as the integer in [0, Q_j), reduced modulo every prime of P*Q */
-#pragma omp parallel for collapse(2) schedule(static)
-    for (int j = 0; j < dnum; j++)
-        for (int n = 0; n < N; n++) {
-            u64 res[MAXP];
-            for (int a = 0; a < alpha; a++) res[a] = d[(size_t)(j * alpha + a) * N + n];
-            bn x;
-            crt_lift(&c->cDig[j], res, &x);
-            for (int r = 0; r < L; r++) dig[((size_t)j * L + r) * N + n] = bn_mod_u64(&x, c->qp[r]);
-        }
-    /* A_c = sum_j digit_j * ksk_{j,c}  in Z_{PQ}[X]/(X^N+1), one prime at a time */
 #pragma omp parallel for collapse(2) schedule(static)
     for (int cc = 0; cc < 2; cc++)
         for (int r = 0; r < L; r++) {
@@ -630,7 +620,6 @@ void orc_keyswitch(const orc_ctx *c, const u64 *d, const u64 *ksk, u64 *u2)
             }
             free(tmp);
         }
-    /* u_c = floor((A_c + floor(P/2)) / P) mod Q with A_c taken in [0, PQ) */
 #pragma omp parallel for collapse(2) schedule(static)
     for (int cc = 0; cc < 2; cc++)
         for (int n = 0; n < N; n++) {
@@ -643,8 +632,26 @@ void orc_keyswitch(const orc_ctx *c, const u64 *d, const u64 *ksk, u64 *u2)
             for (int i = 0; i < k; i++)
                 u2[((size_t)cc * k + i) * N + n] = bn_mod_u64(&quo, c->q[i]);
         }
-    free(dig);
     free(acc);
+}
+
+/* hybrid key switch of one ring element d (uint64[k][N]) with key ksk; u2 = uint64[2][k][N] */
+void orc_keyswitch(const orc_ctx *c, const u64 *d, const u64 *ksk, u64 *u2)
+{
+    const int N = c->N, k = c->k, nsp = c->nsp, L = k + nsp, dnum = c->dnum, alpha = c->alpha;
+    u64 *dig = (u64 *)malloc(sizeof(u64) * (size_t)dnum * L * N);
+    /* digit j = d mod Q_j as the integer in [0, Q_j), reduced modulo every prime of P*Q */
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int j = 0; j < dnum; j++)
+        for (int n = 0; n < N; n++) {
+            u64 res[MAXP];
+            for (int a = 0; a < alpha; a++) res[a] = d[(size_t)(j * alpha + a) * N + n];
+            bn x;
+            crt_lift(&c->cDig[j], res, &x);
+            for (int r = 0; r < L; r++) dig[((size_t)j * L + r) * N + n] = bn_mod_u64(&x, c->qp[r]);
+        }
+    switch_digits(c, dig, ksk, u2);
+    free(dig);
 }
 
 /* (d0, d1, d2) -> (d0 + u0, d1 + u1), u = keyswitch(d2, rlk) */
@@ -687,6 +694,50 @@ void orc_rotate(const orc_ctx *c, const u64 *in2, u64 g, const u64 *gk, u64 *out
             out2[comp + o] = u[comp + o];
         }
     free(s);
+    free(u);
+}
+
+/* Hoisted rotation: the digits are taken from c1 as it stands -- digit_j = c1 mod Q_j as the
+ * integer polynomial with coefficients in [0, Q_j), the same for every Galois element applied to
+ * this ciphertext -- and the Galois map acts on those integer polynomials: the coefficient x at
+ * index i goes to index i*g mod N as +x or, when i*g mod 2N >= N, as the negative integer -x.
+ *   u = second half of the key switch on (sigma_g(digit_j))_j with gk;  out = (sigma_g(c0) + u0, u1).
+ * Differs from orc_rotate in where the lift happens (there sigma_g(c1) mod Q_j is lifted to
+ * [0, Q_j), i.e. a negated coefficient becomes Q_j - x): the results decrypt to the same slots but
+ * are different ciphertexts. */
+void orc_rotate_hoisted(const orc_ctx *c, const u64 *in2, u64 g, const u64 *gk, u64 *out2)
+{
+    const int N = c->N, k = c->k, nsp = c->nsp, L = k + nsp, dnum = c->dnum, alpha = c->alpha;
+    const size_t comp = (size_t)k * N;
+    u64 *dig = (u64 *)malloc(sizeof(u64) * (size_t)dnum * L * N);
+    u64 *s0 = (u64 *)malloc(sizeof(u64) * comp);
+    u64 *u = (u64 *)malloc(sizeof(u64) * 2 * comp);
+    const u64 *c1 = in2 + comp;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int j = 0; j < dnum; j++)
+        for (int n = 0; n < N; n++) {   /* sigma_g is a bijection on the indices: every (j, n) writes its own place */
+            u64 res[MAXP];
+            for (int a = 0; a < alpha; a++) res[a] = c1[(size_t)(j * alpha + a) * N + n];
+            bn x;
+            crt_lift(&c->cDig[j], res, &x);
+            const u64 e = ((u64)n * g) % (2 * (u64)N);
+            const int neg = e >= (u64)N;
+            const size_t dst = (size_t)(neg ? e - N : e);
+            for (int r = 0; r < L; r++) {
+                const u64 v = bn_mod_u64(&x, c->qp[r]);
+                dig[((size_t)j * L + r) * N + dst] = (neg && v) ? c->qp[r] - v : v;
+            }
+        }
+    switch_digits(c, dig, gk, u);
+    orc_galois_poly(c, in2, g, s0);
+    for (int i = 0; i < k; i++)
+        for (int n = 0; n < N; n++) {
+            size_t o = (size_t)i * N + n;
+            out2[o] = addmod(s0[o], u[o], c->q[i]);
+            out2[comp + o] = u[comp + o];
+        }
+    free(dig);
+    free(s0);
     free(u);
 }
 

@@ -100,6 +100,32 @@ def bf_keyswitch(d, ksk, q, p, alpha):
     return out
 
 
+def bf_rotate_hoisted(c2, g, ksk, q, p, alpha):
+    """Rotation with the digits lifted before the Galois map, all over the integers: digit_j = c1 mod Q_j
+    in [0, Q_j); sigma_g moves coefficient x at index i to index i g mod n as x, or as -x when
+    i g mod 2n >= n; A_c = sum_j sigma_g(digit_j) key_{j,c} mod PQ; u_c = floor((A_c + floor(P/2)) / P)
+    mod Q; result (sigma_g(c0) + u0, u1) as [2][k][n] residues."""
+    k, n = len(q), len(c2[0][0])
+    P, Q = prod(p), prod(q)
+    PQ = P * Q
+    qp = list(q) + list(p)
+    acc = [[0] * n, [0] * n]
+    for j in range(k // alpha):
+        mods = q[j * alpha:(j + 1) * alpha]
+        digit = ring_from_rns(c2[1][j * alpha:(j + 1) * alpha], mods)
+        moved = [0] * n
+        for i, x in enumerate(digit):
+            e = i * g % (2 * n)
+            moved[e - n if e >= n else e] = -x if e >= n else x
+        for c in range(2):
+            pr = negacyclic(moved, ring_from_rns(ksk[j][c], qp))
+            acc[c] = [(x + y) % PQ for x, y in zip(acc[c], pr)]
+    u = [[((x + P // 2) // P) % Q for x in acc[c]] for c in range(2)]
+    s0 = [bf_galois(c2[0][i], g, m) for i, m in enumerate(q)]
+    return [[[(a + x) % m for a, x in zip(s0[i], u[0])] for i, m in enumerate(q)],
+            [[x % m for x in u[1]] for m in q]]
+
+
 def bf_galois(poly, g, m):
     n = len(poly)
     out = [0] * n

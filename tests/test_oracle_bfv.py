@@ -96,6 +96,48 @@ def test_relin_and_rotate_compose_as_defined(prm):
         assert orc.rotate(np.array(c2, dtype=np.uint64), g, key).tolist() == want
 
 
+@pytest.mark.parametrize("prm", TOYS, ids=lambda p: f"{p.name}_a{p.alpha}")
+def test_hoisted_rotation_against_the_definition_over_the_integers(prm):
+    """Digits lifted from c1 before the Galois map (one decomposition for a series of rotations):
+    brute force with Python integers, for block rotations and the row swap; with g = 1 nothing is
+    negated and the hoisted form coincides with the ordinary rotation, otherwise it does not."""
+    rnd = random.Random(15)
+    orc = Oracle(prm)
+    q, p, n = list(prm.q), list(prm.p), prm.n
+    key = np.array([[_rand_ring(rnd, q + p, n) for _ in range(2)] for _ in range(prm.dnum)], dtype=np.uint64)
+    c2 = [_rand_ring(rnd, q, n) for _ in range(2)]
+    c2[1][0][1] = 0                      # a zero coefficient: -0 is 0, not q
+    ct = np.array(c2, dtype=np.uint64)
+    for g in (3, 9, 2 * n - 1, 2 * n - 3):
+        got = orc.rotate_hoisted(ct, g, key)
+        assert got.tolist() == bf.bf_rotate_hoisted(c2, g, key.tolist(), q, p, prm.alpha)
+        assert not np.array_equal(got, orc.rotate(ct, g, key))
+    assert np.array_equal(orc.rotate_hoisted(ct, 1, key), orc.rotate(ct, 1, key))
+    many = orc.rotate_many(ct, [3, 9], {3: key, 9: key})
+    assert np.array_equal(many[0], orc.rotate_hoisted(ct, 3, key)) and np.array_equal(many[1], orc.rotate_hoisted(ct, 9, key))
+
+
+def test_hoisted_rotations_move_slots_like_ordinary_ones_within_the_noise_bound():
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 32, orc)
+    n, h = prm.n, prm.n // 2
+    v = slot_values(Stream(32, 1), n, -128, 128)
+    ct = cl.encrypt_slots(v)
+    vm = v % prm.t
+    fresh = cl.noise_budget_bits(ct, cl.codec.encode(v))
+    gs = [galois_rot(n, r) for r in (1, 64, 640)] + [galois_swap(n)]
+    outs = orc.rotate_many(ct, gs, {g: cl.galois_key(g) for g in gs})
+    for r, out in zip((1, 64, 640), outs):
+        dec = cl.decrypt_slots(out)
+        assert np.array_equal(dec[:h], np.roll(vm[:h], -r)) and np.array_equal(dec[h:], np.roll(vm[h:], -r))
+        want = np.concatenate([np.roll(v[:h], -r), np.roll(v[h:], -r)])
+        # a key switch adds about dnum N 19 max(Q_j)/P + N/2 to the noise: a few bits off a fresh budget
+        assert fresh - cl.noise_budget_bits(out, cl.codec.encode(want)) < 12
+    dec = cl.decrypt_slots(outs[3])
+    assert np.array_equal(dec[:h], vm[h:]) and np.array_equal(dec[h:], vm[:h])
+
+
 def test_keyswitch_of_zero_is_zero_and_relin_keeps_two_component_input():
     prm = PRESETS["C2"]
     orc = Oracle(prm)
