@@ -204,6 +204,43 @@ def prefill_av(orc, a_cts, v_ct, rlk, gks, d: int):
     return orc.relin(y, rlk)
 
 
+def copy_galois(n: int, d: int):
+    """Galois elements that take a token-major ciphertext straight to its m = N/d rotated copies:
+    unit sigma*H + r -> 3^(d r), times 2N - 1 for the row-swapped half (unit 0: the identity)."""
+    H = n // d // 2
+    g_swap = galois_swap(n)
+    return [galois_rot(n, d * r) * (g_swap if sigma else 1) % (2 * n) for sigma in (0, 1) for r in range(H)]
+
+
+def rotated_copies_hoisted(orc, ct, gks, d: int):
+    """The same m copies as rotated_copies, every one of them rotated out of the source ciphertext
+    itself as a series of hoisted rotations (one decomposition of its c1, one key per copy)."""
+    gs = copy_galois(orc.n, d)
+    return [ct] + orc.rotate_many(ct, gs[1:], gks)
+
+
+def prefill_qk_hoisted(orc, q_ct, k_ct, rlk, gks, d: int):
+    """prefill_qk with the rotated copies of K made by hoisted rotations (same slots, other bits)."""
+    n = orc.n
+    out = []
+    for kk in rotated_copies_hoisted(orc, k_ct, gks, d):
+        x = orc.relin(orc.mul(q_ct, kk), rlk)
+        for sh in fold_shifts(d):
+            g = galois_rot(n, sh)
+            x = orc.add(x, orc.rotate(x, g, gks[g]))
+        out.append(x)
+    return out
+
+
+def prefill_av_hoisted(orc, a_cts, v_ct, rlk, gks, d: int):
+    """prefill_av with the rotated copies of V made by hoisted rotations."""
+    vs = rotated_copies_hoisted(orc, v_ct, gks, d)
+    y = orc.mul(a_cts[0], vs[0])
+    for u in range(1, len(vs)):
+        y = orc.add(y, orc.mul(a_cts[u], vs[u]))
+    return orc.relin(y, rlk)
+
+
 def slot0_mask_values(n: int, d: int) -> np.ndarray:
     v = np.zeros(n, dtype=np.int64)
     v[::d] = 1
@@ -316,6 +353,29 @@ def cpvm(orc, x_ct, diag_polys, gks, d2: int, counts=None):
     if counts is not None:
         counts.update(mul_plain=len(diag_polys), rotate_shared=len(diag_polys) - 1, rotate=len(gs))
     return y
+
+
+def cpvm_hoisted(orc, x_ct, diag_polys, gks, d2: int, counts=None):
+    """cpvm with the C - 1 rotated copies of the token made as one series of hoisted rotations of the
+    token itself (copy c = token rotated by c, key for 3^c) instead of a doubling tree."""
+    n = orc.n
+    C = len(diag_polys)
+    copies = [x_ct] + orc.rotate_many(x_ct, [galois_rot(n, c) for c in range(1, C)], gks)
+    y = orc.mul_plain(copies[0], diag_polys[0])
+    for c in range(1, C):
+        y = orc.add(y, orc.mul_plain(copies[c], diag_polys[c]))
+    gs = [galois_rot(n, sh) for sh in block_shifts(n, d2)] + [galois_swap(n)]
+    for g in gs:
+        y = orc.add(y, orc.rotate(y, g, gks[g]))
+    if counts is not None:
+        counts.update(mul_plain=C, rotate_shared=C - 1, rotate=len(gs))
+    return y
+
+
+def cpvm_hoisted_galois(n: int, c_count: int, d2: int):
+    """Galois elements cpvm_hoisted needs keys for."""
+    return sorted(set([galois_rot(n, c) for c in range(1, c_count)] +
+                      [galois_rot(n, sh) for sh in block_shifts(n, d2)] + [galois_swap(n)]))
 
 
 def cpvm_galois(n: int, c_count: int, d2: int):

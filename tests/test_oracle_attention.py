@@ -4,6 +4,7 @@ arithmetic mod t, and the operation counts are the ones the paper states
 decode scores, section 4.3 and its complexity table; B = N/d tokens per cache
 ciphertext, Algorithm 1)."""
 import numpy as np
+import pytest
 
 from oracle import Client, Oracle, attention
 from oracle.client import galois_rot
@@ -80,7 +81,9 @@ def test_decode_context_is_the_weighted_sum_of_value_rows():
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
 
 
-def test_prefill_generalised_diagonals_on_a_small_ring():
+@pytest.mark.parametrize("hoisted", [False, True])
+def test_prefill_generalised_diagonals_on_a_small_ring(hoisted):
+    """Also with the copies of K made by hoisted rotations of K itself: other ciphertexts, same slots."""
     prm = toy_params(8, 3, 1, 1)
     orc = Oracle(prm)
     cl = Client(prm, 64, orc)
@@ -91,8 +94,11 @@ def test_prefill_generalised_diagonals_on_a_small_ring():
     Qm = attention_activations(g, 1, m, d)[0]
     Km = attention_activations(g, 1, m, d)[0]
     rlk, gks = cl.relin_key(), _keys(cl, n, d)
-    outs = attention.prefill_qk(orc, cl.encrypt_slots(Qm.reshape(-1)),
-                                cl.encrypt_slots(Km.reshape(-1)), rlk, gks, d)
+    if hoisted:
+        assert len(set(attention.copy_galois(n, d))) == m and attention.copy_galois(n, d)[0] == 1
+        gks.update({g: cl.galois_key(g) for g in attention.copy_galois(n, d)[1:]})
+    fn = attention.prefill_qk_hoisted if hoisted else attention.prefill_qk
+    outs = fn(orc, cl.encrypt_slots(Qm.reshape(-1)), cl.encrypt_slots(Km.reshape(-1)), rlk, gks, d)
     assert len(outs) == m
     S = (Qm @ Km.T) % t
     seen = np.zeros((m, m), dtype=bool)
@@ -170,7 +176,8 @@ def _diag_col(i, sigma, r, H):
     return (row ^ sigma) * H + (pos + r) % H
 
 
-def test_prefill_context_is_the_matrix_product_on_a_small_ring():
+@pytest.mark.parametrize("hoisted", [False, True])
+def test_prefill_context_is_the_matrix_product_on_a_small_ring(hoisted):
     """O = A V over the generalised diagonals: block i of the result is row i of A V mod t."""
     prm = toy_params(8, 3, 1, 1)
     orc = Oracle(prm)
@@ -189,7 +196,10 @@ def test_prefill_context_is_the_matrix_product_on_a_small_ring():
         for i in range(m):
             slots[i * d:(i + 1) * d] = Am[i, _diag_col(i, sigma, r, H)]
         a_cts.append(cl.encrypt_slots(slots))
-    out = attention.prefill_av(orc, a_cts, cl.encrypt_slots(Vm.reshape(-1)), rlk, gks, d)
+    if hoisted:
+        gks.update({g: cl.galois_key(g) for g in attention.copy_galois(n, d)[1:]})
+    fn = attention.prefill_av_hoisted if hoisted else attention.prefill_av
+    out = fn(orc, a_cts, cl.encrypt_slots(Vm.reshape(-1)), rlk, gks, d)
     dec = cl.decrypt_slots(out).reshape(m, d)
     assert np.array_equal(dec, (Am @ Vm) % t)
 
@@ -350,7 +360,7 @@ def test_a_full_cache_ciphertext_stays_far_from_the_refresh_threshold():
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
 
 
-def _cpvm_case(prm, d1, d2, seed, want_shape):
+def _cpvm_case(prm, d1, d2, seed, want_shape, hoisted=False):
     """Decrypts to x W mod t, tiled with period d2 (the layout the decode scores take a query in)."""
     orc = Oracle(prm)
     cl = Client(prm, seed, orc)
@@ -360,11 +370,12 @@ def _cpvm_case(prm, d1, d2, seed, want_shape):
     g = Stream(seed, 1)
     x = attention_activations(g, 1, 1, d1)[0, 0]
     W = attention_activations(g, 1, d1, d2)[0]
-    gks = {gal: cl.galois_key(gal) for gal in attention.cpvm_galois(n, C, d2)}
+    need = attention.cpvm_hoisted_galois(n, C, d2) if hoisted else attention.cpvm_galois(n, C, d2)
+    gks = {gal: cl.galois_key(gal) for gal in need}
     diags = [cl.codec.encode(attention.cpvm_weight_values(n, d1, d2, W, c)) for c in range(C)]
     x_ct = cl.encrypt_slots(attention.cpvm_token_values(n, d1, d2, x))
     counts = {}
-    y = attention.cpvm(orc, x_ct, diags, gks, d2, counts)
+    y = (attention.cpvm_hoisted if hoisted else attention.cpvm)(orc, x_ct, diags, gks, d2, counts)
     levels = (n // d2).bit_length() - 1
     assert counts == {"mul_plain": C, "rotate_shared": C - 1, "rotate": levels}
     want = (x.astype(object) @ W.astype(object)) % t
@@ -396,6 +407,12 @@ def test_cpvm_on_small_rings():
     _cpvm_case(toy_params(7, 3, 1, 1), 20, 8, 71, (32, 4, 2))
     _cpvm_case(toy_params(8, 3, 1, 1), 100, 16, 72, (128, 2, 8))
     _cpvm_case(toy_params(8, 2, 1, 1), 5, 64, 73, (64, 4, 16))     # a token much shorter than a tile
+
+
+def test_cpvm_with_hoisted_token_copies_on_small_rings():
+    """The token's copies as one series of hoisted rotations of the token: same plaintext result."""
+    _cpvm_case(toy_params(7, 3, 1, 1), 20, 8, 76, (32, 4, 2), hoisted=True)
+    _cpvm_case(toy_params(8, 3, 1, 1), 100, 16, 77, (128, 2, 8), hoisted=True)
 
 
 def test_cpvm_at_the_paper_sizes_takes_eight_products_and_seven_rotations_per_matrix():
