@@ -172,6 +172,22 @@ int cg_rotate(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, uint32_t galoi
               const void *gk_dev, uint64_t *out2_dev, uint32_t batch, int accumulate,
               void *ws_dev);
 
+/* A series of rotations of the same ciphertexts (section 4.3 speaks of "a series of rotations";
+ * this is the hoisted form, in which one decomposition of c1 serves the whole series):
+ *   digit_j = c1 mod Q_j as the integer polynomial with coefficients in [0,Q_j), for every g the same;
+ *   sigma_g acts on these integer polynomials (coefficient x at index i goes to index i*g mod N,
+ *   as the negative integer -x when i*g mod 2N >= N);
+ *   A_c = sum_j sigma_g(digit_j) * key^(g)_{j,c} mod P Q;  u_c = floor((A_c + floor(P/2)) / P) mod Q;
+ *   out2[b][i] = (sigma_g(c0) + u0, u1) for g = galois_elts[i], key^(g) = gk[i].
+ * The result decrypts to the same slots as cg_rotate's but is a different ciphertext (cg_rotate
+ * lifts the digits of sigma_g(c1), where a negated coefficient is Q_j - x).  galois_elts_host /
+ * gk_dev_host: host arrays of n_rot Galois elements (odd, < 2N) and device pointers to their
+ * prepared keys; n_rot <= 4096 and batch * n_rot <= 65536.  out2: [batch][n_rot] ciphertexts, must
+ * not overlap in2.  ws_dev: cg_workspace_bytes(ctx, batch * min(n_rot, 128) + batch) bytes. */
+int cg_rotate_hoisted(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, uint32_t n_rot,
+                      const uint32_t *galois_elts_host, const void *const *gk_dev_host, uint64_t *out2_dev,
+                      uint32_t batch, void *ws_dev);
+
 /* out = a + b component-wise mod q_i ("accumulated", section 4.3); ncomp = 2 or 3;
  * out may alias a or b. */
 int cg_add(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *b_dev,
@@ -333,6 +349,21 @@ int cg_prefill_av(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64
                   uint32_t heads, uint32_t d2, const void *rlk_dev, const void *gk_blk_dev,
                   const void *gk_swap_dev, uint64_t *out_dev, void *ws_dev);
 
+/* cg_prefill_qk / cg_prefill_av with the m - 1 rotated copies of K (of V) made as one series of
+ * hoisted rotations of K (V) itself (cg_rotate_hoisted) instead of m/2 - 1 successive block
+ * rotations and m/2 row swaps: copy sigma*H + r is rotate_hoisted(K, g), g = 3^(d2 r) mod 2N for
+ * sigma = 0 and (2N-1) 3^(d2 r) mod 2N for sigma = 1; everything after the copies is unchanged.
+ * The outputs decrypt to the same values as the unhoisted calls' but are other ciphertexts (each
+ * copy has seen one key switch instead of up to m/2).  gk_copies_dev_host: host array of m - 1
+ * device pointers, prepared keys of copies 1 .. m-1 in that order. */
+int cg_prefill_qk_hoisted(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *k_dev,
+                          uint32_t heads, uint32_t d2, const void *rlk_dev,
+                          const void *const *gk_fold_dev_host, const void *const *gk_copies_dev_host,
+                          uint64_t *out_dev, void *ws_dev);
+int cg_prefill_av_hoisted(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *v_dev,
+                          uint32_t heads, uint32_t d2, const void *rlk_dev,
+                          const void *const *gk_copies_dev_host, uint64_t *out_dev, void *ws_dev);
+
 /* Compaction of the m score ciphertexts of cg_prefill_qk, whose useful values sit in slot 0 of
  * every block (a step the score hand-over to the non-linear protocol needs; not described in
  * the paper).  Units come in groups of w = min(d2, H) consecutive diagonals; every unit is
@@ -368,6 +399,14 @@ int cg_prefill_repack(cg_ctx *ctx, void *stream, const uint64_t *x_dev, uint32_t
 int cg_cpvm(cg_ctx *ctx, void *stream, const uint64_t *x_dev, const void *diags_dev, uint32_t units,
             uint32_t n_diag, uint32_t d2, const void *const *gk_shift_dev_host,
             const void *const *gk_block_dev_host, uint64_t *out_dev, void *ws_dev);
+
+/* cg_cpvm with the n_diag - 1 rotated copies of the token made as one series of hoisted rotations
+ * of the token (copy c = rotate_hoisted(x, 3^c)) instead of the doubling tree: n_diag - 1 keys
+ * instead of log2(n_diag), one decomposition instead of n_diag - 1.  gk_copies_dev_host: prepared
+ * keys for 3^1, 3^2, ..., 3^(n_diag - 1) (may be NULL when n_diag is 1). */
+int cg_cpvm_hoisted(cg_ctx *ctx, void *stream, const uint64_t *x_dev, const void *diags_dev, uint32_t units,
+                    uint32_t n_diag, uint32_t d2, const void *const *gk_copies_dev_host,
+                    const void *const *gk_block_dev_host, uint64_t *out_dev, void *ws_dev);
 
 #ifdef __cplusplus
 }

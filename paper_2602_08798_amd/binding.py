@@ -22,6 +22,7 @@ _SYMBOLS = [
     "cg_cpvm", "cg_cache_extend", "cg_decode_scores_ext", "cg_decode_context_ext", "cg_decode_step_ext",
     "cg_bench_modmul", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
     "cg_mul_relin_static", "cg_static_scratch_bytes",
+    "cg_rotate_hoisted", "cg_prefill_qk_hoisted", "cg_prefill_av_hoisted", "cg_cpvm_hoisted",
 ]
 
 
@@ -68,6 +69,10 @@ class Library:
         d.cg_mul.argtypes = [vp, vp, vp, vp, vp, u32, u32, vp]
         d.cg_relin.argtypes = [vp, vp, vp, vp, vp, u32, vp]
         d.cg_mul_relin.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, vp]
+        d.cg_rotate_hoisted.argtypes = [vp, vp, vp, u32, C.POINTER(u32), C.POINTER(vp), vp, u32, vp]
+        d.cg_prefill_qk_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
+        d.cg_prefill_av_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
+        d.cg_cpvm_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, u32, C.POINTER(vp), C.POINTER(vp), vp, vp]
         d.cg_mul_relin_static.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32]
         d.cg_static_scratch_bytes.argtypes = []
         d.cg_static_scratch_bytes.restype = C.c_size_t
@@ -293,6 +298,22 @@ class Context:
                                            _ptr(out), batch, int(accumulate), _ptr(ws)))
         return out
 
+    def rotate_hoisted(self, in2, galois_elts, gks, batch, out=None):
+        """A series of rotations of each of `batch` ciphertexts: out[b][i] = rotation i of in2[b]."""
+        n_rot = len(galois_elts)
+        out = self.empty_ct(batch, n_rot) if out is None else out
+        _need(in2, self._cts(batch), "in")
+        _need(out, self._cts(batch * n_rot), "out")
+        for i, key in enumerate(gks):
+            self._need_key(key, f"Galois key {i}")
+        if len(gks) != n_rot:
+            raise CgSizeError(f"{n_rot} Galois elements but {len(gks)} keys")
+        ws = self.workspace(batch * min(n_rot, 128) + batch)
+        gs = (C.c_uint32 * max(1, n_rot))(*[int(g) for g in galois_elts])
+        self._check(self.lib.dll.cg_rotate_hoisted(self.h, self.stream, _ptr(in2), n_rot, gs, self._keys(gks),
+                                                   _ptr(out), batch, _ptr(ws)))
+        return out
+
     def add(self, a, b, ncomp, batch, out=None):
         out = torch.empty_like(a) if out is None else out
         for t, what in ((a, "a"), (b, "b"), (out, "out")):
@@ -459,6 +480,27 @@ class Context:
                                                _ptr(gk_blk), _ptr(gk_swap), _ptr(out), _ptr(ws)))
         return out
 
+    def prefill_qk_hoisted(self, q, k, heads, d2, rlk, gk_fold, gk_copies, out=None):
+        m = self.n // d2
+        out = self.empty_ct(heads, m) if out is None else out
+        if len(gk_copies) != m - 1:
+            raise CgSizeError(f"{m - 1} copy keys needed, {len(gk_copies)} given")
+        ws = self.workspace(heads * m)
+        self._check(self.lib.dll.cg_prefill_qk_hoisted(self.h, self.stream, _ptr(q), _ptr(k), heads, d2, _ptr(rlk),
+                                                       self._keys(gk_fold), self._keys(gk_copies), _ptr(out),
+                                                       _ptr(ws)))
+        return out
+
+    def prefill_av_hoisted(self, a, v, heads, d2, rlk, gk_copies, out=None):
+        m = self.n // d2
+        out = self.empty_ct(heads) if out is None else out
+        if len(gk_copies) != m - 1:
+            raise CgSizeError(f"{m - 1} copy keys needed, {len(gk_copies)} given")
+        ws = self.workspace(heads * m)
+        self._check(self.lib.dll.cg_prefill_av_hoisted(self.h, self.stream, _ptr(a), _ptr(v), heads, d2, _ptr(rlk),
+                                                       self._keys(gk_copies), _ptr(out), _ptr(ws)))
+        return out
+
     def prefill_repack(self, x, heads, d2, mask0, gk_right, out=None):
         m = self.n // d2
         w = min(d2, m // 2)
@@ -480,6 +522,20 @@ class Context:
         shift = self._keys(gk_shift) if len(gk_shift) else None
         self._check(self.lib.dll.cg_cpvm(self.h, self.stream, _ptr(x), _ptr(diags), units, n_diag, d2, shift,
                                          self._keys(gk_block), _ptr(out), _ptr(ws)))
+        return out
+
+    def cpvm_hoisted(self, x, diags, units, n_diag, d2, gk_copies, gk_block, out=None):
+        """cpvm with the token's copies made by one series of hoisted rotations (keys for 3^1 .. 3^(n_diag-1))."""
+        out = self.empty_ct(units) if out is None else out
+        _need(x, self._cts(1), "x")
+        _need(diags, max(0, int(units)) * max(0, int(n_diag)) * self.k * self.n, "diags (prepared)")
+        _need(out, self._cts(units), "out")
+        for i, key in enumerate(list(gk_copies) + list(gk_block)):
+            self._need_key(key, f"Galois key {i}")
+        ws = self.workspace(units + n_diag)
+        copies = self._keys(gk_copies) if len(gk_copies) else None
+        self._check(self.lib.dll.cg_cpvm_hoisted(self.h, self.stream, _ptr(x), _ptr(diags), units, n_diag, d2, copies,
+                                                 self._keys(gk_block), _ptr(out), _ptr(ws)))
         return out
 
     def profile_begin(self, max_launches=65536):

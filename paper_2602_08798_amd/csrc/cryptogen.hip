@@ -649,8 +649,8 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     CG_TRY(rc);
     ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch, acc_add, acc_stride};
     const double add_rows = !add ? 0.0 : (galois_inv ? c->k + (accumulate ? 2.0 * c->k : 0.0) : 2.0 * c->k);
-    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, B, moddown_kernel,
-                 pw_blocks(c, (size_t)batch * 2) / 2, A, c->dc);
+    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, B, moddown_kernel<false>,
+                 pw_blocks(c, (size_t)batch * 2) / 2, A, ModdownHoist{}, c->dc);
     return CG_OK;
 }
 
@@ -684,6 +684,66 @@ static int do_rotate(cg_ctx *c, hipStream_t s, const uint64_t *in2, uint32_t g, 
                         acc_stride);
 }
 
+// A series of rotations of each of `batch` ciphertexts (in2 + b*in_stride): out2 + (b*out_per_b + i)
+// ciphertexts receives rotation i (Galois element gs[i], prepared key keys[i]) in the hoisted form:
+// one lift, extension and transform of the digits of c1, then per rotation a permuted inner
+// product, inverse transforms and the mod-down with sigma_g(c0).  More than MAXROT rotations go in
+// several rounds over the same digits.  ws: dnum (k+nsp) rows per ciphertext + 2 (k+nsp) rows per
+// rotation of a round.
+static int do_rotate_hoisted(cg_ctx *c, hipStream_t s, const uint64_t *in2, size_t in_stride, uint32_t n_rot,
+                             const uint32_t *gs, const void *const *keys, uint64_t *out2, uint32_t out_per_b,
+                             uint32_t batch, void *ws)
+{
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    const double LB = (double)limb_bytes(c), B = batch;
+    const double dig_rows = (double)c->dnum * c->L;
+    const uint32_t round_max = n_rot < (uint32_t)MAXROT ? n_rot : (uint32_t)MAXROT;
+    Bump w = bump(c, ws);
+    double *dig = w.take<double>((size_t)c->dnum * c->L * batch);
+    double *acc = w.take<double>((size_t)2 * c->L * batch * round_max);
+    const size_t nrows = (size_t)batch * c->dnum * c->L;
+    const StF64 st{dig, c->logn};
+    const uint64_t *src = in2 + (size_t)c->k * c->N;
+    int rc;
+    switch (c->alpha) {
+    case 1: rc = launch_fwd(c, s, nrows, LdModup<false, 1>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
+    case 2: rc = launch_fwd(c, s, nrows, LdModup<false, 2>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
+    default: rc = launch_fwd(c, s, nrows, LdModup<false, 3>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
+    }
+    CG_TRY(rc);
+    for (uint32_t i0 = 0; i0 < n_rot; i0 += MAXROT) {
+        const uint32_t nr = n_rot - i0 < (uint32_t)MAXROT ? n_rot - i0 : (uint32_t)MAXROT;
+        HoistTab T{};
+        ModdownHoist H{};
+        for (uint32_t i = 0; i < nr; i++) {
+            T.g[i] = gs[i0 + i];
+            T.key[i] = static_cast<const double *>(keys[i0 + i]);
+            H.ginv[i] = inv_mod_pow2(gs[i0 + i], 2u * c->N);
+        }
+        H.rot_batch = (int)batch;
+        H.out_per_b = (int)out_per_b;
+        const size_t units = (size_t)batch * nr, irows = units * 2 * c->L;
+        const double ibytes = LB * (dig_rows * B + 2.0 * c->L * units + 2.0 * dig_rows * nr);
+        const StInvF64 ist{acc, c->logn};
+#define CG_KSH(D) rc = launch_inv(c, s, irows, LdInvKsInnerHoisted<D>{dig, T, (int)batch, c->logn}, ist, KID_INV_KSINNER, ibytes)
+        switch (c->dnum) {
+        case 1: CG_KSH(1); break;
+        case 2: CG_KSH(2); break;
+        case 3: CG_KSH(3); break;
+        case 4: CG_KSH(4); break;
+        case 5: CG_KSH(5); break;
+        default: CG_KSH(6); break;
+        }
+#undef CG_KSH
+        CG_TRY(rc);
+        // galois != 0 marks the rotation form; the element itself comes from the table
+        ModdownArgs A{acc, out2 + (size_t)i0 * ct2, ct2, in2, in_stride, 1u, 0, (int)units, in2, in_stride};
+        CG_LAUNCH_PW(KID_MODDOWN, LB * ((2.0 * c->L + 2.0 * c->k) * units + c->k * B), (double)units,
+                     moddown_kernel<true>, pw_blocks(c, units * 2) / 2, A, H, c->dc);
+    }
+    return CG_OK;
+}
+
 static int do_add(cg_ctx *c, hipStream_t s, const uint64_t *a, const uint64_t *b, uint64_t *out, size_t rows)
 {
     CG_LAUNCH_PW(KID_ADD, (double)limb_bytes(c) * 3.0 * rows, (double)rows, add_kernel, pw_blocks(c, rows), a, b, out, (int)rows,
@@ -696,12 +756,13 @@ static bool ptrs_ok(std::initializer_list<const void *> ps)
     for (const void *p : ps) if (!p || !aligned16(p)) return false;
     return true;
 }
-// two device ranges of `bytes` bytes each share at least one byte
-static bool overlap(const void *a, const void *b, size_t bytes)
+// two device ranges share at least one byte
+static bool overlap(const void *a, size_t a_bytes, const void *b, size_t b_bytes)
 {
     const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
-    return x < y + bytes && y < x + bytes;
+    return x < y + b_bytes && y < x + a_bytes;
 }
+static bool overlap(const void *a, const void *b, size_t bytes) { return overlap(a, bytes, b, bytes); }
 static bool batch_ok(uint32_t batch) { return batch >= 1 && batch <= (1u << 16); }
 static bool galois_ok(const cg_ctx *c, uint32_t g) { return (g & 1) && g > 0 && g < 2u * c->N; }
 
@@ -810,6 +871,25 @@ extern "C" int cg_rotate(cg_ctx *c, void *stream, const uint64_t *in2, uint32_t 
     CG_REQUIRE(c && ptrs_ok({in2, gk, out2, ws}) && batch_ok(batch) && galois_ok(c, g));
     CG_REQUIRE(!overlap(in2, out2, (size_t)batch * 2 * c->k * limb_bytes(c)));
     return do_rotate(c, static_cast<hipStream_t>(stream), in2, g, gk, out2, batch, accumulate, ws);
+}
+
+static bool rot_series_ok(const cg_ctx *c, uint32_t n_rot, const uint32_t *gs, const void *const *keys)
+{
+    if (!gs || !keys || n_rot < 1 || n_rot > 4096) return false;
+    for (uint32_t i = 0; i < n_rot; i++)
+        if (!galois_ok(c, gs[i]) || !keys[i] || !aligned16(keys[i])) return false;
+    return true;
+}
+
+extern "C" int cg_rotate_hoisted(cg_ctx *c, void *stream, const uint64_t *in2, uint32_t n_rot, const uint32_t *gs,
+                                 const void *const *gks, uint64_t *out2, uint32_t batch, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({in2, out2, ws}) && batch_ok(batch) && rot_series_ok(c, n_rot, gs, gks));
+    CG_REQUIRE((uint64_t)batch * n_rot <= (1u << 16));
+    const size_t ct2b = (size_t)2 * c->k * limb_bytes(c);
+    CG_REQUIRE(!overlap(in2, ct2b * batch, out2, ct2b * batch * n_rot));
+    return do_rotate_hoisted(c, static_cast<hipStream_t>(stream), in2, (size_t)2 * c->k * c->N, n_rot, gs, gks, out2,
+                             n_rot, batch, ws);
 }
 
 extern "C" int cg_add(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *b, uint64_t *out, uint32_t ncomp,
@@ -1133,13 +1213,36 @@ static int rotated_copies(cg_ctx *c, hipStream_t s, const uint64_t *src, uint32_
     return CG_OK;
 }
 
-extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads,
-                             uint32_t d2, const void *rlk, const void *const *gk_fold, const void *gk_blk,
-                             const void *gk_swap, uint64_t *out, void *ws)
+// The same m copies per head, every one rotated out of the source itself as one series of hoisted
+// rotations: unit sigma*H + r by 3^(d2 r), times 2N-1 for sigma = 1 (keys gk_copies[unit - 1])
+static int rotated_copies_hoisted(cg_ctx *c, hipStream_t s, const uint64_t *src, uint32_t heads, uint32_t d2,
+                                  const void *const *gk_copies, uint64_t *kp, void *ws)
 {
-    CG_REQUIRE(c && ptrs_ok({q, kk, rlk, gk_blk, gk_swap, out, ws}) && gk_fold && heads >= 1 && pow2_d(c, d2));
+    const uint32_t m = (uint32_t)c->N / d2, H = m / 2, two_n = 2u * c->N;
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    for (uint32_t h = 0; h < heads; h++)
+        CG_HIP(hipMemcpyAsync(kp + (size_t)h * m * ct2, src + (size_t)h * ct2, ct2 * 8, hipMemcpyDeviceToDevice, s));
+    std::vector<uint32_t> gs(m - 1);
+    for (uint32_t u = 1; u < m; u++) {
+        const uint64_t g = pow3_mod(d2 * (u % H), two_n);
+        gs[u - 1] = (uint32_t)(u >= H ? g * (two_n - 1) % two_n : g);
+    }
+    return do_rotate_hoisted(c, s, src, ct2, m - 1, gs.data(), gk_copies, kp + ct2, m, heads, ws);
+}
+
+// gk_copies != null: the copies of K come from hoisted rotations (gk_blk / gk_swap are then not used)
+static int prefill_qk_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads, uint32_t d2,
+                           const void *rlk, const void *const *gk_fold, const void *gk_blk, const void *gk_swap,
+                           const void *const *gk_copies, uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({q, kk, rlk, out, ws}) && gk_fold && heads >= 1 && pow2_d(c, d2));
     const uint32_t m = (uint32_t)c->N / d2, batch = heads * m;
     CG_REQUIRE(batch_ok(batch));
+    if (gk_copies) {
+        for (uint32_t u = 1; u < m; u++) CG_REQUIRE(gk_copies[u - 1] && aligned16(gk_copies[u - 1]));
+    } else {
+        CG_REQUIRE(ptrs_ok({gk_blk, gk_swap}));
+    }
     int nrot = 0;
     uint32_t gs[16];
     for (uint32_t sh = 1; sh < d2; sh <<= 1) {
@@ -1152,31 +1255,64 @@ extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const u
     uint64_t *kp = w.take<uint64_t>((size_t)2 * c->k * batch);
     uint64_t *xb = w.take<uint64_t>((size_t)2 * c->k * batch);
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
-    CG_TRY(rotated_copies(c, s, kk, heads, d2, gk_blk, gk_swap, kp, w.p));
+    if (gk_copies) CG_TRY(rotated_copies_hoisted(c, s, kk, heads, d2, gk_copies, kp, w.p));
+    else CG_TRY(rotated_copies(c, s, kk, heads, d2, gk_blk, gk_swap, kp, w.p));
     // all heads x m products at once
     CG_TRY(do_mul(c, s, q, kp, d3, batch, m, w.p, 0));
     CG_TRY(do_relin(c, s, d3, rlk, kp, batch, w.p));   // the rotated keys are consumed: reuse as x0
     return rotate_add_chain(c, s, kp, xb, out, gs, gk_fold, nrot, batch, w.p);
 }
-
-extern "C" int cg_prefill_av(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *v, uint32_t heads,
-                             uint32_t d2, const void *rlk, const void *gk_blk, const void *gk_swap, uint64_t *out,
-                             void *ws)
+extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads,
+                             uint32_t d2, const void *rlk, const void *const *gk_fold, const void *gk_blk,
+                             const void *gk_swap, uint64_t *out, void *ws)
 {
-    CG_REQUIRE(c && ptrs_ok({a, v, rlk, gk_blk, gk_swap, out, ws}) && heads >= 1 && pow2_d(c, d2));
+    return prefill_qk_impl(c, stream, q, kk, heads, d2, rlk, gk_fold, gk_blk, gk_swap, nullptr, out, ws);
+}
+extern "C" int cg_prefill_qk_hoisted(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads,
+                                     uint32_t d2, const void *rlk, const void *const *gk_fold,
+                                     const void *const *gk_copies, uint64_t *out, void *ws)
+{
+    CG_REQUIRE(gk_copies);
+    return prefill_qk_impl(c, stream, q, kk, heads, d2, rlk, gk_fold, nullptr, nullptr, gk_copies, out, ws);
+}
+
+static int prefill_av_impl(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *v, uint32_t heads, uint32_t d2,
+                           const void *rlk, const void *gk_blk, const void *gk_swap, const void *const *gk_copies,
+                           uint64_t *out, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({a, v, rlk, out, ws}) && heads >= 1 && pow2_d(c, d2));
     const uint32_t m = (uint32_t)c->N / d2, batch = heads * m;
     CG_REQUIRE(batch_ok(batch));
+    if (gk_copies) {
+        for (uint32_t u = 1; u < m; u++) CG_REQUIRE(gk_copies[u - 1] && aligned16(gk_copies[u - 1]));
+    } else {
+        CG_REQUIRE(ptrs_ok({gk_blk, gk_swap}));
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     Bump w = bump(c, ws);
     uint64_t *vp = w.take<uint64_t>((size_t)2 * c->k * batch);
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
     uint64_t *y = w.take<uint64_t>((size_t)3 * c->k * heads);
-    CG_TRY(rotated_copies(c, s, v, heads, d2, gk_blk, gk_swap, vp, w.p));
+    if (gk_copies) CG_TRY(rotated_copies_hoisted(c, s, v, heads, d2, gk_copies, vp, w.p));
+    else CG_TRY(rotated_copies(c, s, v, heads, d2, gk_blk, gk_swap, vp, w.p));
     CG_TRY(do_mul(c, s, a, vp, d3, batch, 1, w.p, 0));
     const int rows = 3 * c->k;
     CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), (double)batch, sum_groups_kernel,
                  pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)m, rows, c->dc);
     return do_relin(c, s, y, rlk, out, heads, w.p);
+}
+extern "C" int cg_prefill_av(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *v, uint32_t heads,
+                             uint32_t d2, const void *rlk, const void *gk_blk, const void *gk_swap, uint64_t *out,
+                             void *ws)
+{
+    return prefill_av_impl(c, stream, a, v, heads, d2, rlk, gk_blk, gk_swap, nullptr, out, ws);
+}
+extern "C" int cg_prefill_av_hoisted(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *v, uint32_t heads,
+                                     uint32_t d2, const void *rlk, const void *const *gk_copies, uint64_t *out,
+                                     void *ws)
+{
+    CG_REQUIRE(gk_copies);
+    return prefill_av_impl(c, stream, a, v, heads, d2, rlk, nullptr, nullptr, gk_copies, out, ws);
 }
 
 extern "C" int cg_prefill_repack(cg_ctx *c, void *stream, const uint64_t *x, uint32_t heads, uint32_t d2,
@@ -1221,15 +1357,21 @@ extern "C" int cg_prefill_repack(cg_ctx *c, void *stream, const uint64_t *x, uin
 // One token times `units` plaintext matrices (the decode step's ciphertext-plaintext vector-matrix
 // product): rotated copies of the token by a doubling tree, the products with the diagonals summed
 // on the way into one inverse transform per unit, then the sum over residue classes modulo d2.
-extern "C" int cg_cpvm(cg_ctx *c, void *stream, const uint64_t *x, const void *diags, uint32_t units,
-                       uint32_t n_diag, uint32_t d2, const void *const *gk_shift, const void *const *gk_block,
-                       uint64_t *out, void *ws)
+// gk_copies != null: the rotated copies of the token are a series of hoisted rotations of the token
+// itself (copy c by 3^c, key gk_copies[c - 1]) instead of the doubling tree over gk_shift
+static int cpvm_impl(cg_ctx *c, void *stream, const uint64_t *x, const void *diags, uint32_t units, uint32_t n_diag,
+                     uint32_t d2, const void *const *gk_shift, const void *const *gk_copies,
+                     const void *const *gk_block, uint64_t *out, void *ws)
 {
     CG_REQUIRE(c && ptrs_ok({x, diags, out, ws}) && gk_block && batch_ok(units) && pow2_d(c, d2));
     CG_REQUIRE(n_diag >= 1 && n_diag <= 64 && (n_diag & (n_diag - 1)) == 0 && n_diag <= d2);
-    CG_REQUIRE(n_diag == 1 || gk_shift);
-    int levels = 0;
-    for (uint32_t sh = 1; sh < n_diag; sh <<= 1, levels++) CG_REQUIRE(gk_shift[levels] && aligned16(gk_shift[levels]));
+    CG_REQUIRE(n_diag == 1 || gk_shift || gk_copies);
+    if (gk_copies) {
+        for (uint32_t cc = 1; cc < n_diag; cc++) CG_REQUIRE(gk_copies[cc - 1] && aligned16(gk_copies[cc - 1]));
+    } else {
+        int levels = 0;
+        for (uint32_t sh = 1; sh < n_diag; sh <<= 1, levels++) CG_REQUIRE(gk_shift[levels] && aligned16(gk_shift[levels]));
+    }
     int nrot = 0;
     uint32_t gs[20];
     for (uint32_t sh = d2; sh <= (uint32_t)c->N / 4; sh <<= 1) gs[nrot++] = pow3_mod(sh, 2u * c->N);
@@ -1242,10 +1384,16 @@ extern "C" int cg_cpvm(cg_ctx *c, void *stream, const uint64_t *x, const void *d
     uint64_t *copies = w.take<uint64_t>((size_t)2 * c->k * n_diag);
     double *f = w.take<double>((size_t)2 * c->k * n_diag);
     uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * units), *xb = w.take<uint64_t>((size_t)2 * c->k * units);
-    // copy 2^l + i = copy i rotated left by 2^l
     CG_HIP(hipMemcpyAsync(copies, x, ct2 * 8, hipMemcpyDeviceToDevice, s));
-    for (uint32_t sh = 1, l = 0; sh < n_diag; sh <<= 1, l++)
-        CG_TRY(do_rotate(c, s, copies, pow3_mod(sh, 2u * c->N), gk_shift[l], copies + (size_t)sh * ct2, sh, 0, w.p));
+    if (gk_copies && n_diag > 1) {
+        uint32_t cg[64];
+        for (uint32_t cc = 1; cc < n_diag; cc++) cg[cc - 1] = pow3_mod(cc, 2u * c->N);
+        CG_TRY(do_rotate_hoisted(c, s, x, ct2, n_diag - 1, cg, gk_copies, copies + ct2, n_diag, 1, w.p));
+    } else {
+        // copy 2^l + i = copy i rotated left by 2^l
+        for (uint32_t sh = 1, l = 0; sh < n_diag; sh <<= 1, l++)
+            CG_TRY(do_rotate(c, s, copies, pow3_mod(sh, 2u * c->N), gk_shift[l], copies + (size_t)sh * ct2, sh, 0, w.p));
+    }
     const size_t crows = (size_t)n_diag * 2 * c->k, rows = (size_t)units * 2 * c->k;
     CG_TRY(launch_fwd(c, s, crows, LdRowsU64{copies, nullptr, c->k, c->logn}, StF64Red{f, c->logn}, KID_FWD_ROWS,
                       LB * 2.0 * crows));
@@ -1253,6 +1401,19 @@ extern "C" int cg_cpvm(cg_ctx *c, void *stream, const uint64_t *x, const void *d
                       StInvU64{xa, c->logn}, KID_INV_MULPLAIN,
                       LB * (crows + (double)units * n_diag * c->k + rows)));
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, units, w.p);
+}
+extern "C" int cg_cpvm(cg_ctx *c, void *stream, const uint64_t *x, const void *diags, uint32_t units,
+                       uint32_t n_diag, uint32_t d2, const void *const *gk_shift, const void *const *gk_block,
+                       uint64_t *out, void *ws)
+{
+    return cpvm_impl(c, stream, x, diags, units, n_diag, d2, gk_shift, nullptr, gk_block, out, ws);
+}
+extern "C" int cg_cpvm_hoisted(cg_ctx *c, void *stream, const uint64_t *x, const void *diags, uint32_t units,
+                               uint32_t n_diag, uint32_t d2, const void *const *gk_copies,
+                               const void *const *gk_block, uint64_t *out, void *ws)
+{
+    CG_REQUIRE(n_diag == 1 || gk_copies);
+    return cpvm_impl(c, stream, x, diags, units, n_diag, d2, nullptr, gk_copies, gk_block, out, ws);
 }
 
 // Every transform-kernel instantiation this context can launch, at a batch below and one above the
@@ -1269,6 +1430,11 @@ static int warm_launch_table(cg_ctx *c)
         CG_TRY(do_mul(c, s, u, u, u, batch, 1, f, 0));
         CG_TRY(do_keyswitch(c, s, u, 0, 0, f, u, 0, u, 0, 0, 0, batch, f));
         CG_TRY(do_keyswitch(c, s, u, 0, 3, f, u, 0, u, 0, 3, 1, batch, f));
+        {
+            const uint32_t gs1[1] = {3};
+            const void *const keys1[1] = {f};
+            CG_TRY(do_rotate_hoisted(c, s, u, 0, 1, gs1, keys1, u, 1, batch, f));
+        }
         const size_t rows = (size_t)batch * 2 * c->k;
         const LdRowsU64 ld{u, nullptr, c->k, c->logn};
         CG_TRY(launch_fwd(c, s, rows, ld, StU64{u, c->logn}, KID_FWD_ROWS, LB));

@@ -832,6 +832,56 @@ struct LdInvKsInner {
     }
 };
 
+// A series of rotations of the same ciphertexts ("hoisted" rotations): the digits of c1 are lifted,
+// extended and transformed once, and every Galois element is applied to the transformed digits,
+// where it is a permutation of the evaluation points: row element i is the value at
+// psi^(2 bitrev(i) + 1), and sigma_g(a) takes there the value of a at psi^((2 bitrev(i) + 1) g).
+constexpr int MAXROT = 128;   // rotations per launch
+struct HoistTab {
+    uint32_t g[MAXROT];            // Galois element of rotation i (inner product), its inverse mod 2N (mod-down)
+    const double *key[MAXROT];     // prepared key of rotation i
+};
+// inner product of rotation i of unit b: workgroup -> (unit u = i * batch + b, prime r, component c);
+// element = sum_j digit_j[b][r][pi_g(idx)] * key_i[j][c][r][idx]; result row [u][c][r]
+template <int DNUM>
+struct LdInvKsInnerHoisted {
+    static constexpr int kRaw = 2 * DNUM;
+    static constexpr bool kPrefetch = false;
+    const double *dig;   // [b][DNUM][L][N] lazy, transform order
+    HoistTab T;
+    int batch, logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return (wg >> 1) % C->L; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 2; }
+    __device__ __forceinline__ int out_row(int wg, const DevConst *C) const
+    {
+        const int L = C->L, r = (wg >> 1) % L, u = wg / (2 * L);
+        return (u * 2 + (wg & 1)) * L + r;
+    }
+    __device__ __forceinline__ void fetch(int wg, int idx, const DevConst *C, uint64_t *raw) const
+    {
+        const int L = C->L, r = (wg >> 1) % L, c = wg & 1, u = wg / (2 * L);
+        const int i = u / batch, b = u - i * batch;
+        const uint32_t e = ((2u * (__brev((uint32_t)idx) >> (32 - logn)) + 1u) * T.g[i]) & ((2u << logn) - 1u);
+        const int sidx = (int)(__brev(e >> 1) >> (32 - logn));
+        const double *kb = T.key[i];
+#pragma unroll
+        for (int j = 0; j < DNUM; j++) {
+            raw[2 * j] = f64_bits(dig[(((size_t)(b * DNUM + j) * L + r) << logn) + sidx]);
+            raw[2 * j + 1] = f64_bits(kb[(((size_t)(j * 2 + c) * L + r) << logn) + idx]);
+        }
+    }
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD m, const DevConst *) const
+    {
+        double s = 0.0;
+#pragma unroll
+        for (int j = 0; j < DNUM; j++) {
+            const double d = bits_f64(raw[2 * j]);
+            s += mulmod(DNUM <= 4 ? d : red(d, m), bits_f64(raw[2 * j + 1]), m);
+        }
+        return s;
+    }
+};
+
 // tensor product fused into the load: workgroup -> (unit u, prime r of the k+l, component c in 0..2),
 // the component running fastest so that the three rows reading the same four operand rows are
 // neighbours; element = a0 b0 (c = 0), a0 b1 + a1 b0 (c = 1), a1 b1 (c = 2); result row [u][c][r].
@@ -1022,8 +1072,16 @@ struct ModdownArgs {
     const uint64_t *acc_add;  // base of the ciphertexts added un-permuted (accumulate)
     size_t acc_stride;
 };
+// HOIST: the units are the rotations of a series, unit u = i * rot_batch + b being rotation i of
+// ciphertext b: its Galois element comes from the table, its addend is ciphertext b and its output
+// ciphertext b * out_per_b + i.
+struct ModdownHoist {
+    uint32_t ginv[MAXROT];
+    int rot_batch, out_per_b;
+};
+template <bool HOIST>
 __global__ void __launch_bounds__(PW_THREADS)
-moddown_kernel(ModdownArgs A, const DevConst *__restrict__ C)
+moddown_kernel(ModdownArgs A, ModdownHoist H, const DevConst *__restrict__ C)
 {
     // a thread takes two neighbouring coefficients: 16 bytes per row and lane on every read and
     // write that is not a permuted one
@@ -1036,7 +1094,14 @@ moddown_kernel(ModdownArgs A, const DevConst *__restrict__ C)
     const int n = (int)(gid & (N - 1));
     const int bc = (int)(gid >> logn);
     if (bc >= A.batch * 2) return;
-    const int c = bc & 1, b = bc >> 1;
+    const int c = bc & 1;
+    int b = bc >> 1, bo = b;       // addend index, output index
+    if (HOIST) {
+        const int i = b / H.rot_batch;
+        b -= i * H.rot_batch;
+        bo = b * H.out_per_b + i;
+        A.galois = H.ginv[i];
+    }
     const double *src = A.acc + (((size_t)bc * L) << logn) + n;
     double xp[2][MAXS], dg[2][MAXS];
 #pragma unroll
@@ -1061,7 +1126,7 @@ moddown_kernel(ModdownArgs A, const DevConst *__restrict__ C)
             src_idx[e2] = (int)(negate[e2] ? e - N : e);
         }
     }
-    uint64_t *o = A.out + (size_t)b * A.out_stride + (((size_t)c * k) << logn) + n;
+    uint64_t *o = A.out + (size_t)bo * A.out_stride + (((size_t)c * k) << logn) + n;
 #pragma unroll
     for (int i = 0; i < MAXS; i++)
         if (i < k) {
