@@ -148,11 +148,24 @@ def prefill():
                                                                   gk[st["g_swap"]])),
     ]
     total = 0.0
+    part_ms = []
     for name, fn in parts:
         ms = timed(fn)
         total += ms
+        part_ms.append(ms)
         print(f"{name:58s} {ms:8.2f} ms", flush=True)
     print(f"{'prompt attention of one layer':58s} {total:8.2f} ms")
+    # the same with the rotated copies of K and V made by hoisted rotation series (one decomposition
+    # per cache ciphertext, m - 1 = 127 keys of uniform residues: timing does not depend on them)
+    n = st["prm"].n
+    L = st["prm"].k + st["prm"].nsp
+    copies = [ctx.ksk_prepare(torch.randint(0, 1 << 49, (st["prm"].dnum, 2, L, n), dtype=torch.int64, device="cuda"))
+              for _ in range(m - 1)]
+    qk_h = timed(lambda: ctx.prefill_qk_hoisted(q, cache[:H], H, d2, rlk, fold, copies, out=out))
+    av_h = timed(lambda: ctx.prefill_av_hoisted(a, cache[H:], H, d2, rlk, copies))
+    print(f"{'Q K^T with hoisted copies of K':58s} {qk_h:8.2f} ms", flush=True)
+    print(f"{'A V with hoisted copies of V':58s} {av_h:8.2f} ms", flush=True)
+    print(f"{'prompt attention of one layer, hoisted copies':58s} {part_ms[0] + qk_h + part_ms[2] + av_h:8.2f} ms")
 
 
 def mulrelin(preset="C2", batches=(12, 24, 48, 96, 192, 384, 768), chunks=(24, 48, 96, 192)):
@@ -220,6 +233,9 @@ def cpvm(preset="C2", d2=64, n_diag=8, heads=12):
     for s in sorted(ctx.profile_end(), key=lambda s: -s["total_ms"]):
         if s["launches"]:
             print(f"  {s['name']:24s} {s['launches'] // 3:3d} launches  {s['total_ms'] * 1e3 / 3:8.1f} us per call", flush=True)
+    copies = [key() for _ in range(n_diag - 1)]
+    us_h = _time(lambda: ctx.cpvm_hoisted(x, diags, units, n_diag, d2, copies, block, out=out), 20)
+    print(f"{preset}: the same with the token's {n_diag - 1} copies as one hoisted rotation series: {us_h:8.1f} us", flush=True)
 
 
 if __name__ == "__main__":
