@@ -40,6 +40,14 @@ const char *cg_kernel_name(uint32_t kernel_id);
 int cg_bench_modmul(cg_ctx *ctx, void *stream, int kind, uint32_t n_lanes, uint32_t iters,
                     uint64_t *out_dev);
 
+/* Micro-benchmark of the wave-local exchange between two transform stages that pair elements 32
+ * lanes apart (evidence for keeping that exchange in LDS): n_blocks workgroups of 1024 threads,
+ * every lane holding 16 doubles, run `iters` exchanges of 8 doubles per lane with kind 0 = through
+ * the wave's region of LDS, 1 = v_permlane32_swap on the 32-bit halves.  out_dev: double[n_blocks *
+ * 1024], one checksum per lane, identical for both kinds. */
+int cg_bench_exchange(cg_ctx *ctx, void *stream, int kind, uint32_t n_blocks, uint32_t iters,
+                      double *out_dev);
+
 #ifdef __cplusplus
 }
 #endif

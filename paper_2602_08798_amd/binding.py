@@ -20,7 +20,7 @@ _SYMBOLS = [
     "cg_kv_append", "cg_decode_scores", "cg_decode_context", "cg_decode_scores_outer", "cg_decode_context_outer", "cg_prefill_qk",
     "cg_decode_step", "cg_decode_step_workspace_bytes", "cg_prefill_av", "cg_prefill_repack",
     "cg_cpvm", "cg_cache_extend", "cg_decode_scores_ext", "cg_decode_context_ext", "cg_decode_step_ext",
-    "cg_bench_modmul", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
+    "cg_bench_modmul", "cg_bench_exchange", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
     "cg_mul_relin_static", "cg_static_scratch_bytes",
     "cg_rotate_hoisted", "cg_prefill_qk_hoisted", "cg_prefill_av_hoisted", "cg_cpvm_hoisted",
 ]
@@ -99,6 +99,7 @@ class Library:
         d.cg_decode_step_workspace_bytes.argtypes = [vp, u32, u32]
         d.cg_decode_step_workspace_bytes.restype = C.c_size_t
         d.cg_bench_modmul.argtypes = [vp, vp, i32, u32, u32, vp]
+        d.cg_bench_exchange.argtypes = [vp, vp, i32, u32, u32, vp]
         d.cg_profile_begin.argtypes = [vp, u32]
         d.cg_profile_end.argtypes = [vp, C.POINTER(_KernelStat), u32, C.POINTER(u32)]
         d.cg_kernel_name.argtypes = [u32]
@@ -550,6 +551,11 @@ class Context:
                      launches=int(stats[i].launches), total_ms=float(stats[i].total_ms),
                      algo_bytes=float(stats[i].algo_bytes), work_items=float(stats[i].work_items))
                 for i in range(n.value)]
+
+    def bench_exchange(self, kind, n_blocks, iters, out=None):
+        out = torch.empty(n_blocks * 1024, dtype=torch.float64, device=self.device) if out is None else out
+        self._check(self.lib.dll.cg_bench_exchange(self.h, self.stream, kind, n_blocks, iters, _ptr(out)))
+        return out
 
     def bench_modmul(self, kind, n_lanes, iters, out=None):
         out = torch.empty(n_lanes, dtype=torch.int64, device=self.device) if out is None else out

@@ -1498,6 +1498,13 @@ extern "C" int cg_profile_end(cg_ctx *c, cg_kernel_stat *stats, uint32_t cap, ui
 
 extern "C" const char *cg_kernel_name(uint32_t id) { return id < KID_COUNT ? kKernelNames[id] : "?"; }
 
+extern "C" int cg_bench_exchange(cg_ctx *c, void *stream, int kind, uint32_t n_blocks, uint32_t iters, double *out)
+{
+    CG_REQUIRE(c && ptrs_ok({out}) && (kind == 0 || kind == 1) && n_blocks >= 1 && n_blocks <= (1u << 16));
+    return launch_kernel(bench_exchange_kernel, dim3(n_blocks), dim3(1024), static_cast<hipStream_t>(stream), kind,
+                         iters, out);
+}
+
 extern "C" int cg_bench_modmul(cg_ctx *c, void *stream, int kind, uint32_t n_lanes, uint32_t iters, uint64_t *out)
 {
     CG_REQUIRE(c && ptrs_ok({out}) && (kind == 0 || kind == 1) && n_lanes >= 1 && c->pr[0] > (1ull << 49));

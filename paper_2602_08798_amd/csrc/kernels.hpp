@@ -47,7 +47,11 @@ template <int LOGN, int E, int PASS> __device__ __forceinline__ int group_index(
 {
     constexpr int R = Plan<LOGN, E>::R[PASS];
     if (PASS < Plan<LOGN, E>::NC) return tid + g * ((1 << LOGN) / E);
-    return ((tid >> 6) << (chunk_log<E>() - R)) + (tid & 63) + 64 * g;
+    int lane = tid & 63;
+    // a radix-2 pass works on pairs of neighbours, 16 bytes per lane: which pair a lane takes is
+    // permuted as in chunk_elem, for the same reason (LDS banks)
+    if (R == 1) lane = (lane & 7) | (((lane >> 4) & 3) << 3) | (((lane >> 3) & 1) << 5);
+    return ((tid >> 6) << (chunk_log<E>() - R)) + lane + 64 * g;
 }
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
 // outstanding global load (vmcnt(0)), which would drain the next row's prefetch at each
@@ -174,10 +178,21 @@ __device__ __forceinline__ int xcd_row(int p, int nwg, int S)
 // Both put consecutive lanes on consecutive addresses.
 // ---------------------------------------------------------------------------
 // element `it` of a thread in the chunked ownership: a lane takes pairs of neighbouring elements of
-// its wave's chunk, so that every operand comes in (and every result goes out) 16 bytes per lane
+// its wave's chunk, so that every operand comes in (and every result goes out) 16 bytes per lane.
+// Which pair: lane bits 0-2 give pair bits 0-2, lane bit 3 pair bit 5, lane bits 4-5 pair bits 3-4,
+// the iteration the bits above.  Eight consecutive lanes then cover one 128-byte line in memory,
+// and in the padded LDS row (position = index + index / 8) any sixteen consecutive lanes land on
+// sixteen different 8-byte banks: pair u = a + 4 b sits at 2 a + 9 b, and b in {0, 1, 8, 9} gives
+// offsets 0, 9, 8, 1 modulo 16.  With lane l simply taking pair l, lanes l and l + 8 collide.
 template <int E> __device__ __forceinline__ int chunk_elem(int tid, int it)
 {
-    return ((tid >> 6) << chunk_log<E>()) + 2 * (tid & 63) + (it & 1) + 128 * (it >> 1);
+    const int lane = tid & 63;
+#ifdef CG_CHUNK_LINEAR
+    const int u = lane;
+#else
+    const int u = (lane & 7) | (((lane >> 4) & 3) << 3) | (((lane >> 3) & 1) << 5);
+#endif
+    return ((tid >> 6) << chunk_log<E>()) + 2 * u + (it & 1) + 128 * (it >> 1);
 }
 
 template <int LOGN, int E, bool CHUNKED, class LD>
@@ -1217,6 +1232,55 @@ sum_groups_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out, i
     double s = u64_to_f64(in[(g * group) * per + e]);
     for (int c = 1; c < group; c++) s = addmod_canon(s, u64_to_f64(in[(g * group + c) * per + e]), m);
     out[gid] = f64_to_u64(s);
+}
+
+// Exchange micro-benchmark: the wave-local regrouping a transform pass boundary needs when the
+// next stage pairs elements 32 lanes apart.  Every lane holds 16 doubles; one exchange hands the
+// upper 8 of lanes 0-31 to lanes 32-63 in return for their lower 8 (afterwards a lane holds both
+// halves of 8 butterflies).  kind 0: through the wave's own region of LDS (8 stores, wave-level
+// ordering, 8 loads per lane); kind 1: v_permlane32_swap on the 32-bit halves (16 instructions per
+// lane, no memory).  One add per held double between exchanges keeps the values moving.
+typedef unsigned cg_uint2v __attribute__((ext_vector_type(2)));
+__global__ void __launch_bounds__(1024)
+bench_exchange_kernel(int kind, uint32_t iters, double *__restrict__ out)
+{
+    __shared__ double lds[16 * 64 * 8];
+    const int tid = threadIdx.x, lane = tid & 63;
+    double *mine = lds + (tid >> 6) * (64 * 8);
+    double v[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) v[k] = (double)(tid * 16 + k);
+    for (uint32_t i = 0; i < iters; i++) {
+        if (kind == 0) {
+            // a lane gives away its upper half (lanes 0-31) or its lower half (lanes 32-63)
+#pragma unroll
+            for (int k = 0; k < 8; k++) mine[k * 64 + lane] = lane < 32 ? v[8 + k] : v[k];
+            wave_sync();
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const double got = mine[k * 64 + (lane ^ 32)];
+                if (lane < 32) v[8 + k] = got;
+                else v[k] = got;
+            }
+            wave_sync();
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                uint64_t a = f64_bits(v[k]), b = f64_bits(v[8 + k]);
+                // upper 32 lanes of the first operand <-> lower 32 lanes of the second
+                const cg_uint2v lo = __builtin_amdgcn_permlane32_swap((unsigned)a, (unsigned)b, false, false);
+                const cg_uint2v hi = __builtin_amdgcn_permlane32_swap((unsigned)(a >> 32), (unsigned)(b >> 32), false, false);
+                v[k] = bits_f64(((uint64_t)hi.x << 32) | lo.x);
+                v[8 + k] = bits_f64(((uint64_t)hi.y << 32) | lo.y);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 16; k++) v[k] += 1.0;
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int k = 0; k < 16; k++) s += v[k] * (double)(k + 1);
+    out[(size_t)blockIdx.x * blockDim.x + tid] = s;
 }
 
 // arithmetic micro-benchmark: `iters` dependent products per lane

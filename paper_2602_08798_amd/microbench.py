@@ -1,6 +1,7 @@
 """Micro-benchmarks of the library's building blocks (run on a GPU machine).
 
     python -m paper_2602_08798_amd.microbench modmul   FP64-FMA vs 32-bit-integer Barrett modular multiply
+    python -m paper_2602_08798_amd.microbench exchange wave-local regrouping through LDS vs v_permlane32_swap
     python -m paper_2602_08798_amd.microbench ntt      forward/inverse transform throughput vs number of rows
     python -m paper_2602_08798_amd.microbench copy     plain device copy of known size (counter calibration)
     python -m paper_2602_08798_amd.microbench c5curve  the scaled configuration: per-step time over its 64 decode steps
@@ -49,6 +50,24 @@ def modmul(preset="C2"):
     torch.cuda.synchronize()
     assert torch.equal(a, b), "the two arithmetic kinds disagree"
     print("both kinds produce identical residues")
+
+
+def exchange(preset="C2"):
+    """The regrouping of 8 doubles per lane between lanes 32 apart: LDS round trip against
+    v_permlane32_swap, in clocks per exchange and compute unit (16 waves per unit, 2.4 GHz)."""
+    ctx = Context(PRESETS[preset])
+    blocks, iters = 256 * 4, 4096
+    res = []
+    for kind, name in ((0, "LDS (8 ds_write_b64 + 8 ds_read_b64 per lane)"), (1, "v_permlane32_swap (16 per lane)")):
+        out = torch.empty(blocks * 1024, dtype=torch.float64, device="cuda")
+        us = _time(lambda: ctx.bench_exchange(kind, blocks, iters, out), 3)
+        clk = us * 1e-6 * 2.4e9 / (iters * (blocks / 256))       # per exchange of one workgroup's 16 waves
+        print(f"{name:48s} {us:9.1f} us  {clk:7.1f} clk per exchange of a 1024-thread workgroup "
+              f"({clk / 16:5.1f} per wave)", flush=True)
+        res.append(out.clone())
+    torch.cuda.synchronize()
+    assert torch.equal(res[0], res[1]), "the two exchanges disagree"
+    print("both kinds leave identical values")
 
 
 def ntt(preset="C2", sizes=(512, 4096), reps=5):
@@ -243,5 +262,5 @@ if __name__ == "__main__":
     if what == "mulrelin" and len(sys.argv) > 2:      # e.g. `mulrelin 768`: that batch only
         mulrelin(batches=tuple(int(a) for a in sys.argv[2:]))
     else:
-        {"modmul": modmul, "ntt": ntt, "copy": copy, "c5curve": c5curve, "prefill": prefill,
+        {"modmul": modmul, "exchange": exchange, "ntt": ntt, "copy": copy, "c5curve": c5curve, "prefill": prefill,
          "mulrelin": mulrelin, "cpvm": cpvm}[what]()
