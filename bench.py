@@ -55,7 +55,7 @@ FP64_LANE_INSTR_PER_ITEM = {
     "ntt_inv<mul_plain>": 688 * 1024,
     "ntt_inv<ks_inner>": 728 * 1024,
     "scale": 373 * 3 * 8192,
-    "moddown": 230 * 8192,
+    "moddown": 320 * 8192,
     "sum_groups": 16 * 9 * 8192,
     "add": 6 * 8192,
 }
