@@ -55,44 +55,45 @@ static uint64_t h_pow(uint64_t a, uint64_t e, uint64_t m)
     return r;
 }
 static uint64_t h_inv(uint64_t a, uint64_t m) { return h_pow(a % m, m - 2, m); }
+// Primality below 2^64 by strong-probable-prime tests to the seven bases of Sinclair's set, which
+// has no composite below 2^64 passing all of them; trial division first, to leave early.
 static bool h_is_prime(uint64_t n)
 {
-    if (n < 2) return false;
-    static const uint64_t small[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
-    for (uint64_t s : small) {
-        if (n == s) return true;
-        if (n % s == 0) return false;
+    if (n < 4) return n == 2 || n == 3;
+    if (!(n & 1)) return false;
+    for (uint64_t f = 3; f < 64; f += 2) {
+        if (n == f) return true;
+        if (n % f == 0) return false;
     }
-    uint64_t d = n - 1;
-    int r = 0;
-    while (!(d & 1)) { d >>= 1; r++; }
-    for (uint64_t a : small) {   // these 12 bases are a deterministic witness set below 2^64
-        uint64_t x = h_pow(a, d, n);
-        if (x == 1 || x == n - 1) continue;
-        bool composite = true;
-        for (int i = 1; i < r && composite; i++) {
-            x = h_mul(x, x, n);
-            if (x == n - 1) composite = false;
-        }
-        if (composite) return false;
+    const int two = __builtin_ctzll(n - 1);
+    const uint64_t odd = (n - 1) >> two;
+    static const uint64_t bases[7] = {2, 325, 9375, 28178, 450775, 9780504, 1795265022};
+    for (uint64_t b : bases) {
+        uint64_t y = h_pow(b % n, odd, n);
+        if (y <= 1 || y == n - 1) continue;            // b = 0 mod n gives y = 0: no witness
+        int sq = 1;
+        while (sq < two && y != n - 1) { y = h_mul(y, y, n); sq++; }
+        if (y != n - 1) return false;
     }
     return true;
 }
-// smallest primitive 2N-th root of unity mod p
+// smallest primitive 2N-th root of unity mod p (the convention of cg_ntt_forward): any primitive
+// root, then the minimum over its N odd powers, which are all the primitive 2N-th roots
 static uint64_t h_min_root(uint64_t p, uint64_t n)
 {
-    uint64_t root = 0;
-    for (uint64_t x = 2; x < p; x++) {
-        const uint64_t r = h_pow(x, (p - 1) / (2 * n), p);
-        if (h_pow(r, n, p) == p - 1) { root = r; break; }
+    const uint64_t cof = (p - 1) / (2 * n);
+    uint64_t any = 0;
+    for (uint64_t cand = 2; !any; cand++) {
+        const uint64_t r = h_pow(cand, cof, p);      // order divides 2N; it is 2N iff r^N = -1
+        if (h_pow(r, n, p) == p - 1) any = r;
     }
-    uint64_t best = root, cur = root;
-    const uint64_t sq = h_mul(root, root, p);
+    const uint64_t step = h_mul(any, any, p);
+    uint64_t lo = any, w = any;
     for (uint64_t i = 1; i < n; i++) {
-        cur = h_mul(cur, sq, p);
-        if (cur < best) best = cur;
+        w = h_mul(w, step, p);
+        lo = w < lo ? w : lo;
     }
-    return best;
+    return lo;
 }
 static uint32_t h_bitrev(uint32_t x, int bits)
 {
@@ -1366,6 +1367,7 @@ static int cpvm_impl(cg_ctx *c, void *stream, const uint64_t *x, const void *dia
     CG_REQUIRE(c && ptrs_ok({x, diags, out, ws}) && gk_block && batch_ok(units) && pow2_d(c, d2));
     CG_REQUIRE(n_diag >= 1 && n_diag <= 64 && (n_diag & (n_diag - 1)) == 0 && n_diag <= d2);
     CG_REQUIRE(n_diag == 1 || gk_shift || gk_copies);
+    CG_REQUIRE(!overlap(x, 2 * (size_t)c->k * limb_bytes(c), out, 2 * (size_t)c->k * limb_bytes(c) * units));
     if (gk_copies) {
         for (uint32_t cc = 1; cc < n_diag; cc++) CG_REQUIRE(gk_copies[cc - 1] && aligned16(gk_copies[cc - 1]));
     } else {

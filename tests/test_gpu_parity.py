@@ -377,6 +377,10 @@ def test_invalid_arguments_are_rejected_without_launching():
     bad = dataclasses.replace(env.prm, q=(env.prm.q[0], (1 << 50) - 27))   # not 1 mod 2N
     with pytest.raises(CgError):
         P.Context(bad)
+    for composite in (1125899906818049, 1125899906670593):   # 1 mod 2N, 11 * ... and 1733 * 20129 * 32275949
+        bad = dataclasses.replace(env.prm, q=(env.prm.q[0], composite))
+        with pytest.raises(CgError):
+            P.Context(bad)
     bad = dataclasses.replace(env.prm, alpha=2)          # a two-prime digit against one special prime
     with pytest.raises(CgError):
         P.Context(bad)
