@@ -187,11 +187,7 @@ __device__ __forceinline__ int xcd_row(int p, int nwg, int S)
 template <int E> __device__ __forceinline__ int chunk_elem(int tid, int it)
 {
     const int lane = tid & 63;
-#ifdef CG_CHUNK_LINEAR
-    const int u = lane;
-#else
     const int u = (lane & 7) | (((lane >> 4) & 3) << 3) | (((lane >> 3) & 1) << 5);
-#endif
     return ((tid >> 6) << chunk_log<E>()) + 2 * u + (it & 1) + 128 * (it >> 1);
 }
 
