@@ -17,6 +17,9 @@ slots [b d, (b+1) d)) of a cache ciphertext holds one token's d-vector.
                   sum of slot-wise products over the cache ciphertexts (three
                   components), one relinearisation, then a sum over blocks
                   (rotate by d, 2d, ... N/4, then swap the two slot rows).
+  decode_scores_hoisted, decode_context_hoisted  the same two products with their folding
+                  sums regrouped into rounds of several rotations of one ciphertext each
+                  (hoisted, one division by P per round); defined above round_chunks.
   decode_scores_outer  section 4.3, inner-inner mode: scores against an outer-packed
                   (column-per-ciphertext) cache segment; each query feature is masked,
                   broadcast by rotations and multiplied with its column ciphertext.
@@ -102,6 +105,85 @@ def decode_context(orc, a_cts, v_cts, rlk, gks, d: int, counts=None):
         if counts is not None:
             counts["rotate"] = counts.get("rotate", 0) + 1
     return x
+
+
+# ---------------------------------------------------------------------------
+# folding sums by rounds of hoisted rotations
+#
+# A folding sum x -> sum over all products of a subset of the generators g_0 .. g_{B-1}
+# (sigma applied to x) is what "rotate by g_b and add" for b = 0 .. B-1 computes in B dependent
+# steps.  The Galois maps commute, so the bits can be taken in chunks instead: a round over bits
+# [b0, b0 + c) maps x to the sum of sigma_e(x) over the 2^c products e of subsets of g_b0 ..
+# g_{b0+c-1}, and the rounds over consecutive chunks compose to the same sum.  Within a round all
+# 2^c - 1 rotations act on the same ciphertext, so they are hoisted and their key-switch
+# accumulators summed before one division by P (rotate_sum_hoisted): ceil(B / w) dependent steps
+# instead of B, for 2^c - 1 keys per round instead of c.  Same slots, other ciphertext bits.
+# ---------------------------------------------------------------------------
+def round_chunks(n_bits: int, w: int):
+    """Chunk lengths: ceil(n_bits / w) rounds, as even as possible, the longer ones first."""
+    assert n_bits >= 0 and w >= 1
+    if n_bits == 0:
+        return []
+    rounds = -(-n_bits // w)
+    lo, extra = divmod(n_bits, rounds)
+    return [lo + 1] * extra + [lo] * (rounds - extra)
+
+
+def round_galois(n: int, gens, w: int):
+    """[[Galois elements of round 0], [of round 1], ...] for the generators gens (bit b -> gens[b]);
+    within a round, entry m - 1 is the product of the generators whose bit is set in m = 1 .. 2^c - 1."""
+    out, b0 = [], 0
+    for c in round_chunks(len(gens), w):
+        elts = []
+        for m in range(1, 1 << c):
+            e = 1
+            for i in range(c):
+                if (m >> i) & 1:
+                    e = e * gens[b0 + i] % (2 * n)
+            elts.append(e)
+        out.append(elts)
+        b0 += c
+    return out
+
+
+def fold_generators(n: int, d: int):
+    return [galois_rot(n, sh) for sh in fold_shifts(d)]
+
+
+def block_generators(n: int, d: int):
+    return [galois_rot(n, sh) for sh in block_shifts(n, d)] + [galois_swap(n)]
+
+
+def fold_by_rounds(orc, x, gens, gks, w: int, counts=None):
+    for elts in round_galois(orc.n, gens, w):
+        x = orc.rotate_sum_hoisted(x, elts, gks)
+        if counts is not None:
+            counts["rounds"] = counts.get("rounds", 0) + 1
+            counts["rotate"] = counts.get("rotate", 0) + len(elts)
+    return x
+
+
+def decode_scores_hoisted(orc, q_ct, k_ct, rlk, gks, d: int, w: int, counts=None):
+    """decode_scores with the folding sum taken in rounds of w bits (hoisted rotation sums)."""
+    x = orc.relin(orc.mul(q_ct, k_ct), rlk)
+    return fold_by_rounds(orc, x, fold_generators(orc.n, d), gks, w, counts)
+
+
+def decode_context_hoisted(orc, a_cts, v_cts, rlk, gks, d: int, w: int, counts=None):
+    """decode_context with the sum over blocks (and the two slot rows) taken in rounds of w bits."""
+    y = None
+    for a_ct, v_ct in zip(a_cts, v_cts):
+        prod3 = orc.mul(a_ct, v_ct)
+        y = prod3 if y is None else orc.add(y, prod3)
+    x = orc.relin(y, rlk)
+    return fold_by_rounds(orc, x, block_generators(orc.n, d), gks, w, counts)
+
+
+def hoisted_fold_galois(n: int, d: int, w_fold: int, w_block: int):
+    """Galois elements the two hoisted decode products need keys for."""
+    gs = [e for r in round_galois(n, fold_generators(n, d), w_fold) for e in r]
+    gs += [e for r in round_galois(n, block_generators(n, d), w_block) for e in r]
+    return sorted(set(gs))
 
 
 def residue_mask_values(n: int, d: int, j: int) -> np.ndarray:

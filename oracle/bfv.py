@@ -43,6 +43,7 @@ def load_library():
     lib.orc_galois_poly.argtypes = [C.c_void_p, _U64P, C.c_uint64, _U64P]
     lib.orc_rotate.argtypes = [C.c_void_p, _U64P, C.c_uint64, _U64P, _U64P]
     lib.orc_rotate_hoisted.argtypes = [C.c_void_p, _U64P, C.c_uint64, _U64P, _U64P]
+    lib.orc_rotate_sum_hoisted.argtypes = [C.c_void_p, _U64P, C.c_int, _U64P, C.POINTER(_U64P), _U64P]
     lib.orc_mul_plain.argtypes = [C.c_void_p, _U64P, _U64P, _U64P]
     lib.orc_add_plain.argtypes = [C.c_void_p, _U64P, _U64P, C.c_int, _U64P]
     lib.orc_test_crt.restype = C.c_int
@@ -245,6 +246,18 @@ class Oracle:
     def rotate_many(self, in2, gs, gks):
         """[rotate_hoisted(in2, g, gks[g]) for g in gs]: a series of rotations of one ciphertext."""
         return [self.rotate_hoisted(in2, g, gks[g]) for g in gs]
+
+    def rotate_sum_hoisted(self, in2, gs, gks):
+        """in2 + the sum of its hoisted rotations by every g of gs (keys gks[g]), the key-switch
+        accumulators of the series summed before the one division by P."""
+        in2 = self._ct(in2, 2)
+        keys = [self._key(gks[g]) for g in gs]
+        assert all(g % 2 == 1 and 0 < g < 2 * self.n for g in gs)
+        garr = np.asarray(list(gs), dtype=np.uint64)
+        kptr = (_U64P * max(1, len(keys)))(*[_p(k) for k in keys])
+        out = np.empty_like(in2)
+        self.lib.orc_rotate_sum_hoisted(self.ctx, _p(in2), len(keys), _p(garr), kptr, _p(out))
+        return out
 
     def add_plain(self, in2, pt, negative=False):
         """(c0 +- floor(Q/t) pt, c1): Algorithm 1 step 1, the server's masking and unmasking."""

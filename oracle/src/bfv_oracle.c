@@ -600,13 +600,11 @@ void orc_mul(const orc_ctx *c, const u64 *a2, const u64 *b2, u64 *out3)
     free(prod);
 }
 
-/* Second half of a key switch, from the digits already reduced modulo every prime of P*Q
- * (dig = uint64[dnum][k+nsp][N]): A_c = sum_j digit_j * ksk_{j,c} in Z_{PQ}[X]/(X^N+1),
- * u_c = floor((A_c + floor(P/2)) / P) mod Q with A_c taken in [0, PQ); u2 = uint64[2][k][N] */
-static void switch_digits(const orc_ctx *c, const u64 *dig, const u64 *ksk, u64 *u2)
+/* acc_c += sum_j digit_j * ksk_{j,c} in Z_{PQ}[X]/(X^N+1), residue by residue
+ * (dig = uint64[dnum][k+nsp][N], acc = uint64[2][k+nsp][N]) */
+static void add_digit_products(const orc_ctx *c, const u64 *dig, const u64 *ksk, u64 *acc)
 {
     const int N = c->N, k = c->k, nsp = c->nsp, L = k + nsp, dnum = c->dnum;
-    u64 *acc = (u64 *)calloc((size_t)2 * L * N, sizeof(u64));
 #pragma omp parallel for collapse(2) schedule(static)
     for (int cc = 0; cc < 2; cc++)
         for (int r = 0; r < L; r++) {
@@ -620,6 +618,13 @@ static void switch_digits(const orc_ctx *c, const u64 *dig, const u64 *ksk, u64 
             }
             free(tmp);
         }
+}
+
+/* u_c = floor((A_c + floor(P/2)) / P) mod Q with A_c, given by its residues, taken in [0, PQ);
+ * acc = uint64[2][k+nsp][N], u2 = uint64[2][k][N] */
+static void divide_by_special(const orc_ctx *c, const u64 *acc, u64 *u2)
+{
+    const int N = c->N, k = c->k, L = k + c->nsp;
 #pragma omp parallel for collapse(2) schedule(static)
     for (int cc = 0; cc < 2; cc++)
         for (int n = 0; n < N; n++) {
@@ -632,6 +637,15 @@ static void switch_digits(const orc_ctx *c, const u64 *dig, const u64 *ksk, u64 
             for (int i = 0; i < k; i++)
                 u2[((size_t)cc * k + i) * N + n] = bn_mod_u64(&quo, c->q[i]);
         }
+}
+
+/* Second half of a key switch, from the digits already reduced modulo every prime of P*Q:
+ * A_c = sum_j digit_j * ksk_{j,c}, u_c = round(A_c / P) mod Q as above */
+static void switch_digits(const orc_ctx *c, const u64 *dig, const u64 *ksk, u64 *u2)
+{
+    u64 *acc = (u64 *)calloc((size_t)2 * (c->k + c->nsp) * c->N, sizeof(u64));
+    add_digit_products(c, dig, ksk, acc);
+    divide_by_special(c, acc, u2);
     free(acc);
 }
 
@@ -697,27 +711,17 @@ void orc_rotate(const orc_ctx *c, const u64 *in2, u64 g, const u64 *gk, u64 *out
     free(u);
 }
 
-/* Hoisted rotation: the digits are taken from c1 as it stands -- digit_j = c1 mod Q_j as the
- * integer polynomial with coefficients in [0, Q_j), the same for every Galois element applied to
- * this ciphertext -- and the Galois map acts on those integer polynomials: the coefficient x at
- * index i goes to index i*g mod N as +x or, when i*g mod 2N >= N, as the negative integer -x.
- *   u = second half of the key switch on (sigma_g(digit_j))_j with gk;  out = (sigma_g(c0) + u0, u1).
- * Differs from orc_rotate in where the lift happens (there sigma_g(c1) mod Q_j is lifted to
- * [0, Q_j), i.e. a negated coefficient becomes Q_j - x): the results decrypt to the same slots but
- * are different ciphertexts. */
-void orc_rotate_hoisted(const orc_ctx *c, const u64 *in2, u64 g, const u64 *gk, u64 *out2)
+/* digit_j of the ring element d (uint64[k][N]) as integer polynomials, mapped by sigma_g over the
+ * integers (index i -> i*g mod N, negated when i*g mod 2N >= N) and then reduced modulo every
+ * prime of P*Q: dig = uint64[dnum][k+nsp][N] */
+static void galois_of_digits(const orc_ctx *c, const u64 *d, u64 g, u64 *dig)
 {
-    const int N = c->N, k = c->k, nsp = c->nsp, L = k + nsp, dnum = c->dnum, alpha = c->alpha;
-    const size_t comp = (size_t)k * N;
-    u64 *dig = (u64 *)malloc(sizeof(u64) * (size_t)dnum * L * N);
-    u64 *s0 = (u64 *)malloc(sizeof(u64) * comp);
-    u64 *u = (u64 *)malloc(sizeof(u64) * 2 * comp);
-    const u64 *c1 = in2 + comp;
+    const int N = c->N, L = c->k + c->nsp, dnum = c->dnum, alpha = c->alpha;
 #pragma omp parallel for collapse(2) schedule(static)
     for (int j = 0; j < dnum; j++)
-        for (int n = 0; n < N; n++) {   /* sigma_g is a bijection on the indices: every (j, n) writes its own place */
+        for (int n = 0; n < N; n++) {
             u64 res[MAXP];
-            for (int a = 0; a < alpha; a++) res[a] = c1[(size_t)(j * alpha + a) * N + n];
+            for (int a = 0; a < alpha; a++) res[a] = d[(size_t)(j * alpha + a) * N + n];
             bn x;
             crt_lift(&c->cDig[j], res, &x);
             const u64 e = ((u64)n * g) % (2 * (u64)N);
@@ -728,6 +732,24 @@ void orc_rotate_hoisted(const orc_ctx *c, const u64 *in2, u64 g, const u64 *gk, 
                 dig[((size_t)j * L + r) * N + dst] = (neg && v) ? c->qp[r] - v : v;
             }
         }
+}
+
+/* Hoisted rotation: the digits are taken from c1 as it stands -- digit_j = c1 mod Q_j as the
+ * integer polynomial with coefficients in [0, Q_j), the same for every Galois element applied to
+ * this ciphertext -- and the Galois map acts on those integer polynomials: the coefficient x at
+ * index i goes to index i*g mod N as +x or, when i*g mod 2N >= N, as the negative integer -x.
+ *   u = second half of the key switch on (sigma_g(digit_j))_j with gk;  out = (sigma_g(c0) + u0, u1).
+ * Differs from orc_rotate in where the lift happens (there sigma_g(c1) mod Q_j is lifted to
+ * [0, Q_j), i.e. a negated coefficient becomes Q_j - x): the results decrypt to the same slots but
+ * are different ciphertexts. */
+void orc_rotate_hoisted(const orc_ctx *c, const u64 *in2, u64 g, const u64 *gk, u64 *out2)
+{
+    const int N = c->N, k = c->k, L = k + c->nsp, dnum = c->dnum;
+    const size_t comp = (size_t)k * N;
+    u64 *dig = (u64 *)malloc(sizeof(u64) * (size_t)dnum * L * N);
+    u64 *s0 = (u64 *)malloc(sizeof(u64) * comp);
+    u64 *u = (u64 *)malloc(sizeof(u64) * 2 * comp);
+    galois_of_digits(c, in2 + comp, g, dig);
     switch_digits(c, dig, gk, u);
     orc_galois_poly(c, in2, g, s0);
     for (int i = 0; i < k; i++)
@@ -737,6 +759,47 @@ void orc_rotate_hoisted(const orc_ctx *c, const u64 *in2, u64 g, const u64 *gk, 
             out2[comp + o] = u[comp + o];
         }
     free(dig);
+    free(s0);
+    free(u);
+}
+
+/* Sum of a ciphertext and a series of its hoisted rotations with ONE division by P:
+ *   A_c = sum_i sum_j sigma_{g_i}(digit_j) * gk_i[j][c]  in Z_{PQ}[X]/(X^N+1),  digits of c1 as in
+ *   orc_rotate_hoisted;  u_c = floor((A_c + floor(P/2)) / P) mod Q;
+ *   out = (c0 + sum_i sigma_{g_i}(c0) + u0,  c1 + u1).
+ * Rounding A_c / P is additive up to the rounding itself, so u differs from the sum of the n_rot
+ * separately rounded key-switch outputs by less than n_rot per coefficient: the result decrypts to
+ * the slot-wise sum x + sum_i rotate(x, g_i) with one rounding error instead of n_rot, and is a
+ * different ciphertext from the sum of n_rot separately rotated ones.  gks = n_rot key pointers. */
+void orc_rotate_sum_hoisted(const orc_ctx *c, const u64 *in2, int n_rot, const u64 *gs, const u64 *const *gks,
+                            u64 *out2)
+{
+    const int N = c->N, k = c->k, L = k + c->nsp, dnum = c->dnum;
+    const size_t comp = (size_t)k * N;
+    u64 *dig = (u64 *)malloc(sizeof(u64) * (size_t)dnum * L * N);
+    u64 *acc = (u64 *)calloc((size_t)2 * L * N, sizeof(u64));
+    u64 *s0 = (u64 *)malloc(sizeof(u64) * comp);
+    u64 *u = (u64 *)malloc(sizeof(u64) * 2 * comp);
+    memcpy(out2, in2, sizeof(u64) * 2 * comp);
+    for (int i = 0; i < n_rot; i++) {
+        galois_of_digits(c, in2 + comp, gs[i], dig);
+        add_digit_products(c, dig, gks[i], acc);
+        orc_galois_poly(c, in2, gs[i], s0);
+        for (int r = 0; r < k; r++)
+            for (int n = 0; n < N; n++) {
+                size_t o = (size_t)r * N + n;
+                out2[o] = addmod(out2[o], s0[o], c->q[r]);
+            }
+    }
+    divide_by_special(c, acc, u);
+    for (int r = 0; r < k; r++)
+        for (int n = 0; n < N; n++) {
+            size_t o = (size_t)r * N + n;
+            out2[o] = addmod(out2[o], u[o], c->q[r]);
+            out2[comp + o] = addmod(out2[comp + o], u[comp + o], c->q[r]);
+        }
+    free(dig);
+    free(acc);
     free(s0);
     free(u);
 }

@@ -23,6 +23,7 @@ _SYMBOLS = [
     "cg_bench_modmul", "cg_bench_exchange", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
     "cg_mul_relin_static", "cg_static_scratch_bytes",
     "cg_rotate_hoisted", "cg_prefill_qk_hoisted", "cg_prefill_av_hoisted", "cg_cpvm_hoisted",
+    "cg_rotate_sum_hoisted",
 ]
 
 
@@ -70,6 +71,7 @@ class Library:
         d.cg_relin.argtypes = [vp, vp, vp, vp, vp, u32, vp]
         d.cg_mul_relin.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, vp]
         d.cg_rotate_hoisted.argtypes = [vp, vp, vp, u32, C.POINTER(u32), C.POINTER(vp), vp, u32, vp]
+        d.cg_rotate_sum_hoisted.argtypes = d.cg_rotate_hoisted.argtypes
         d.cg_prefill_qk_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
         d.cg_prefill_av_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_cpvm_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, u32, C.POINTER(vp), C.POINTER(vp), vp, vp]
@@ -313,6 +315,22 @@ class Context:
         gs = (C.c_uint32 * max(1, n_rot))(*[int(g) for g in galois_elts])
         self._check(self.lib.dll.cg_rotate_hoisted(self.h, self.stream, _ptr(in2), n_rot, gs, self._keys(gks),
                                                    _ptr(out), batch, _ptr(ws)))
+        return out
+
+    def rotate_sum_hoisted(self, in2, galois_elts, gks, batch, out=None):
+        """out[b] = in2[b] + the sum of its rotations by the given Galois elements (hoisted, one mod-down)."""
+        n_rot = len(galois_elts)
+        out = self.empty_ct(batch) if out is None else out
+        _need(in2, self._cts(batch), "in")
+        _need(out, self._cts(batch), "out")
+        for i, key in enumerate(gks):
+            self._need_key(key, f"Galois key {i}")
+        if len(gks) != n_rot:
+            raise CgSizeError(f"{n_rot} Galois elements but {len(gks)} keys")
+        ws = self.workspace(batch)
+        gs = (C.c_uint32 * max(1, n_rot))(*[int(g) for g in galois_elts])
+        self._check(self.lib.dll.cg_rotate_sum_hoisted(self.h, self.stream, _ptr(in2), n_rot, gs, self._keys(gks),
+                                                       _ptr(out), batch, _ptr(ws)))
         return out
 
     def add(self, a, b, ncomp, batch, out=None):

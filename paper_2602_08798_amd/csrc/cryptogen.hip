@@ -650,7 +650,7 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     CG_TRY(rc);
     ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch, acc_add, acc_stride};
     const double add_rows = !add ? 0.0 : (galois_inv ? c->k + (accumulate ? 2.0 * c->k : 0.0) : 2.0 * c->k);
-    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, B, moddown_kernel<false>,
+    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, B, moddown_kernel<0>,
                  pw_blocks(c, (size_t)batch * 2) / 2, A, ModdownHoist{}, c->dc);
     return CG_OK;
 }
@@ -740,8 +740,61 @@ static int do_rotate_hoisted(cg_ctx *c, hipStream_t s, const uint64_t *in2, size
         // galois != 0 marks the rotation form; the element itself comes from the table
         ModdownArgs A{acc, out2 + (size_t)i0 * ct2, ct2, in2, in_stride, 1u, 0, (int)units, in2, in_stride};
         CG_LAUNCH_PW(KID_MODDOWN, LB * ((2.0 * c->L + 2.0 * c->k) * units + c->k * B), (double)units,
-                     moddown_kernel<true>, pw_blocks(c, units * 2) / 2, A, H, c->dc);
+                     moddown_kernel<1>, pw_blocks(c, units * 2) / 2, A, H, c->dc);
     }
+    return CG_OK;
+}
+
+// out2[b] = in2[b] + sum_i rotation i of in2[b] (Galois elements gs, prepared keys), the rotations
+// hoisted and their key-switch accumulators summed before the one division by P.  in_stride /
+// out_stride as in do_rotate.  ws: (dnum + 2)(k+nsp) rows per ciphertext.
+static int do_rotate_sum(cg_ctx *c, hipStream_t s, const uint64_t *in2, size_t in_stride, uint32_t n_rot,
+                         const uint32_t *gs, const void *const *keys, uint64_t *out2, size_t out_stride,
+                         uint32_t batch, void *ws)
+{
+    const size_t ct2 = (size_t)2 * c->k * c->N;
+    if (!in_stride) in_stride = ct2;
+    if (!out_stride) out_stride = ct2;
+    const double LB = (double)limb_bytes(c), B = batch;
+    const double dig_rows = (double)c->dnum * c->L;
+    Bump w = bump(c, ws);
+    double *dig = w.take<double>((size_t)c->dnum * c->L * batch);
+    double *acc = w.take<double>((size_t)2 * c->L * batch);
+    const size_t nrows = (size_t)batch * c->dnum * c->L;
+    const StF64 st{dig, c->logn};
+    const uint64_t *src = in2 + (size_t)c->k * c->N;
+    int rc;
+    switch (c->alpha) {
+    case 1: rc = launch_fwd(c, s, nrows, LdModup<false, 1>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
+    case 2: rc = launch_fwd(c, s, nrows, LdModup<false, 2>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
+    default: rc = launch_fwd(c, s, nrows, LdModup<false, 3>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
+    }
+    CG_TRY(rc);
+    HoistTab T{};
+    ModdownHoist H{};
+    for (uint32_t i = 0; i < n_rot; i++) {
+        T.g[i] = gs[i];
+        T.key[i] = static_cast<const double *>(keys[i]);
+        H.ginv[i] = inv_mod_pow2(gs[i], 2u * c->N);
+    }
+    H.n_sum = (int)n_rot;
+    const size_t irows = (size_t)batch * 2 * c->L;
+    const double ibytes = LB * ((dig_rows + 2.0 * c->L) * B + 2.0 * dig_rows * n_rot);
+    const StInvF64 ist{acc, c->logn};
+#define CG_KSS(D) rc = launch_inv(c, s, irows, LdInvKsInnerSum<D>{dig, T, (int)n_rot, c->logn}, ist, KID_INV_KSINNER, ibytes)
+    switch (c->dnum) {
+    case 1: CG_KSS(1); break;
+    case 2: CG_KSS(2); break;
+    case 3: CG_KSS(3); break;
+    case 4: CG_KSS(4); break;
+    case 5: CG_KSS(5); break;
+    default: CG_KSS(6); break;
+    }
+#undef CG_KSS
+    CG_TRY(rc);
+    ModdownArgs A{acc, out2, out_stride, in2, in_stride, 1u, 1, (int)batch, in2, in_stride};
+    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + 4.0 * c->k) * B, B, moddown_kernel<2>, pw_blocks(c, (size_t)batch * 2) / 2,
+                 A, H, c->dc);
     return CG_OK;
 }
 
@@ -891,6 +944,16 @@ extern "C" int cg_rotate_hoisted(cg_ctx *c, void *stream, const uint64_t *in2, u
     CG_REQUIRE(!overlap(in2, ct2b * batch, out2, ct2b * batch * n_rot));
     return do_rotate_hoisted(c, static_cast<hipStream_t>(stream), in2, (size_t)2 * c->k * c->N, n_rot, gs, gks, out2,
                              n_rot, batch, ws);
+}
+
+extern "C" int cg_rotate_sum_hoisted(cg_ctx *c, void *stream, const uint64_t *in2, uint32_t n_rot, const uint32_t *gs,
+                                     const void *const *gks, uint64_t *out2, uint32_t batch, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({in2, out2, ws}) && batch_ok(batch) && rot_series_ok(c, n_rot, gs, gks));
+    CG_REQUIRE(n_rot <= (uint32_t)MAXROT);
+    const size_t ct2b = (size_t)2 * c->k * limb_bytes(c);
+    CG_REQUIRE(!overlap(in2, ct2b * batch, out2, ct2b * batch));
+    return do_rotate_sum(c, static_cast<hipStream_t>(stream), in2, 0, n_rot, gs, gks, out2, 0, batch, ws);
 }
 
 extern "C" int cg_add(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *b, uint64_t *out, uint32_t ncomp,

@@ -200,6 +200,10 @@ __device__ __forceinline__ void fetch_row(const LD &ld, int wg, int tid, const D
     for (int it = 0; it < E; it++) ld.fetch(wg, CHUNKED ? chunk_elem<E>(tid, it) : tid + it * T, C, raw[it]);
 }
 
+// Loaders whose element is a sum over several rounds of fetches (ld.rounds() of them, each with
+// ld.fetch_round / ld.finish, the partial sums joined by ld.join) are marked here.
+template <class LD> struct ld_rounds { static constexpr bool value = false; };
+
 // Loaders that do not prefetch fetch and finish a row in slices, so that at most about 32 raw
 // words are live per thread however many words an element needs.
 template <int LOGN, int E, bool CHUNKED, class LD, class F>
@@ -209,6 +213,26 @@ __device__ __forceinline__ void load_row_now(const LD &ld, int wg, int tid, cons
     constexpr int CH0 = LD::kRaw <= 2 ? 16 : (LD::kRaw <= 4 ? (E >= 16 && CHUNKED ? 4 : 8) : (E >= 16 && CHUNKED ? 2 : 4));
     constexpr int CH = CH0 < E ? CH0 : E;
     auto at = [&](int it) { return CHUNKED ? chunk_elem<E>(tid, it) : tid + it * T; };
+    if constexpr (ld_rounds<LD>::value) {
+        const int nr = ld.rounds();
+#pragma unroll
+        for (int c0 = 0; c0 < E; c0 += CH) {
+            double sum[CH];
+#pragma unroll
+            for (int i = 0; i < CH; i++) sum[i] = 0.0;
+            for (int r = 0; r < nr; r++) {
+                uint64_t rw[CH][LD::kRaw];
+#pragma unroll
+                for (int i = 0; i < CH; i++) ld.fetch_round(wg, at(c0 + i), r, C, rw[i]);
+#pragma unroll
+                for (int i = 0; i < CH; i++) sum[i] = ld.join(sum[i], ld.finish(rw[i], wg, at(c0 + i), m, C), m);
+            }
+#pragma unroll
+            for (int i = 0; i < CH; i++) sink(c0 + i, at(c0 + i), sum[i]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        return;
+    }
 #pragma unroll
     for (int c0 = 0; c0 < E; c0 += CH) {
         uint64_t rw[CH][LD::kRaw];
@@ -893,6 +917,57 @@ struct LdInvKsInnerHoisted {
     }
 };
 
+// The sum of a series of rotations of one ciphertext, as one key-switch accumulator: workgroup ->
+// (unit b, prime r, component c); element = sum_i sum_j digit_j[b][r][pi_{g_i}(idx)] * key_i[j][c][r][idx];
+// result row [b][c][r].  Summing before the inverse transform and the division by P costs one
+// inverse transform and one mod-down per ciphertext instead of one per rotation.
+template <int DNUM>
+struct LdInvKsInnerSum {
+    static constexpr int kRaw = 2 * DNUM;
+    static constexpr bool kPrefetch = false;
+    const double *dig;   // [b][DNUM][L][N] lazy, transform order
+    HoistTab T;
+    int n_rot, logn;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return (wg >> 1) % C->L; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 2; }
+    __device__ __forceinline__ int out_row(int wg, const DevConst *C) const
+    {
+        const int L = C->L, r = (wg >> 1) % L, b = wg / (2 * L);
+        return (b * 2 + (wg & 1)) * L + r;
+    }
+    __device__ __forceinline__ int rounds() const { return n_rot; }
+    __device__ __forceinline__ void fetch_round(int wg, int idx, int i, const DevConst *C, uint64_t *raw) const
+    {
+        const int L = C->L, r = (wg >> 1) % L, c = wg & 1, b = wg / (2 * L);
+        const uint32_t e = ((2u * (__brev((uint32_t)idx) >> (32 - logn)) + 1u) * T.g[i]) & ((2u << logn) - 1u);
+        const int sidx = (int)(__brev(e >> 1) >> (32 - logn));
+        const double *kb = T.key[i];
+#pragma unroll
+        for (int j = 0; j < DNUM; j++) {
+            raw[2 * j] = f64_bits(dig[(((size_t)(b * DNUM + j) * L + r) << logn) + sidx]);
+            raw[2 * j + 1] = f64_bits(kb[(((size_t)(j * 2 + c) * L + r) << logn) + idx]);
+        }
+    }
+    __device__ __forceinline__ void fetch(int, int, const DevConst *, uint64_t *) const {}
+    __device__ __forceinline__ double finish(const uint64_t *raw, int, int, const ModD m, const DevConst *) const
+    {
+        double s = 0.0;
+#pragma unroll
+        for (int j = 0; j < DNUM; j++) {
+            const double d = bits_f64(raw[2 * j]);
+            s += mulmod(DNUM <= 4 ? d : red(d, m), bits_f64(raw[2 * j + 1]), m);
+        }
+        return s;
+    }
+    // one rotation's products are below 1.91 DNUM p; with the running sum reduced to p/2 first the
+    // total stays below 8 p for DNUM <= 3, and for more digits the new term is reduced as well
+    __device__ __forceinline__ double join(double sum, double term, const ModD m) const
+    {
+        return red(sum, m) + (DNUM <= 3 ? term : red(term, m));
+    }
+};
+template <int DNUM> struct ld_rounds<LdInvKsInnerSum<DNUM>> { static constexpr bool value = true; };
+
 // tensor product fused into the load: workgroup -> (unit u, prime r of the k+l, component c in 0..2),
 // the component running fastest so that the three rows reading the same four operand rows are
 // neighbours; element = a0 b0 (c = 0), a0 b1 + a1 b0 (c = 1), a1 b1 (c = 2); result row [u][c][r].
@@ -1086,11 +1161,13 @@ struct ModdownArgs {
 // HOIST: the units are the rotations of a series, unit u = i * rot_batch + b being rotation i of
 // ciphertext b: its Galois element comes from the table, its addend is ciphertext b and its output
 // ciphertext b * out_per_b + i.
+// HOIST == 2: the units are ciphertexts, acc holds the summed accumulators of n_sum rotations of
+// each, and the output is ciphertext b + sum_i (sigma_{g_i}(c0 of b), 0) + u.
 struct ModdownHoist {
     uint32_t ginv[MAXROT];
-    int rot_batch, out_per_b;
+    int rot_batch, out_per_b, n_sum;
 };
-template <bool HOIST>
+template <int HOIST>
 __global__ void __launch_bounds__(PW_THREADS)
 moddown_kernel(ModdownArgs A, ModdownHoist H, const DevConst *__restrict__ C)
 {
@@ -1107,7 +1184,7 @@ moddown_kernel(ModdownArgs A, ModdownHoist H, const DevConst *__restrict__ C)
     if (bc >= A.batch * 2) return;
     const int c = bc & 1;
     int b = bc >> 1, bo = b;       // addend index, output index
-    if (HOIST) {
+    if (HOIST == 1) {
         const int i = b / H.rot_batch;
         b -= i * H.rot_batch;
         bo = b * H.out_per_b + i;
@@ -1151,7 +1228,24 @@ moddown_kernel(ModdownArgs A, ModdownHoist H, const DevConst *__restrict__ C)
                 const double ri = horner(C->p2q, C, dg[e2], i, false);
                 v[e2] = canon(mulmod(red(ai - ri, mq), C->Pinv_q[i], mq), mq);
             }
-            if (A.add) {
+            if constexpr (HOIST == 2) {
+                const uint64_t *ad = A.add + (size_t)b * A.add_stride;
+                if (c == 0)
+                    for (int r = 0; r < H.n_sum; r++) {
+                        const uint32_t gi = H.ginv[r];
+#pragma unroll
+                        for (int e2 = 0; e2 < 2; e2++) {
+                            const uint32_t e = ((uint32_t)(n + e2) * gi) & (2 * N - 1);
+                            const bool ng = e >= (uint32_t)N;
+                            double w = u64_to_f64(ad[((size_t)i << logn) + (ng ? e - N : e)]);
+                            if (ng) w = (w == 0.0) ? 0.0 : mq.p - w;
+                            v[e2] = addmod_canon(v[e2], w, mq);
+                        }
+                    }
+                const ulonglong2 w2 = *reinterpret_cast<const ulonglong2 *>(ad + ((size_t)(c * k + i) << logn) + n);
+                v[0] = addmod_canon(v[0], u64_to_f64(w2.x), mq);
+                v[1] = addmod_canon(v[1], u64_to_f64(w2.y), mq);
+            } else if (A.add) {
                 const uint64_t *ad = A.add + (size_t)b * A.add_stride;
                 if (A.galois) {
                     if (c == 0) {

@@ -126,6 +126,34 @@ def bf_rotate_hoisted(c2, g, ksk, q, p, alpha):
             [[x % m for x in u[1]] for m in q]]
 
 
+def bf_rotate_sum_hoisted(c2, gs, ksks, q, p, alpha):
+    """c2 + the sum of its hoisted rotations with one division by P, all over the integers:
+    A_c = sum_i sum_j sigma_{g_i}(digit_j) key_{i,j,c} mod PQ with the digits and sigma as in
+    bf_rotate_hoisted; u_c = floor((A_c + floor(P/2)) / P) mod Q; result
+    (c0 + sum_i sigma_{g_i}(c0) + u0, c1 + u1) as [2][k][n] residues."""
+    k, n = len(q), len(c2[0][0])
+    P, Q = prod(p), prod(q)
+    PQ = P * Q
+    qp = list(q) + list(p)
+    digits = [ring_from_rns(c2[1][j * alpha:(j + 1) * alpha], q[j * alpha:(j + 1) * alpha]) for j in range(k // alpha)]
+    acc = [[0] * n, [0] * n]
+    out0 = [[int(x) for x in row] for row in c2[0]]
+    for g, ksk in zip(gs, ksks):
+        for j, digit in enumerate(digits):
+            moved = [0] * n
+            for i, x in enumerate(digit):
+                e = i * g % (2 * n)
+                moved[e - n if e >= n else e] = -x if e >= n else x
+            for c in range(2):
+                pr = negacyclic(moved, ring_from_rns(ksk[j][c], qp))
+                acc[c] = [(x + y) % PQ for x, y in zip(acc[c], pr)]
+        for i, m in enumerate(q):
+            out0[i] = [(a + b) % m for a, b in zip(out0[i], bf_galois(c2[0][i], g, m))]
+    u = [[((x + P // 2) // P) % Q for x in acc[c]] for c in range(2)]
+    return [[[(a + x) % m for a, x in zip(out0[i], u[0])] for i, m in enumerate(q)],
+            [[(int(a) + x) % m for a, x in zip(c2[1][i], u[1])] for i, m in enumerate(q)]]
+
+
 def bf_galois(poly, g, m):
     n = len(poly)
     out = [0] * n

@@ -81,6 +81,74 @@ def test_decode_context_is_the_weighted_sum_of_value_rows():
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
 
 
+def test_round_chunks_and_round_elements_cover_every_subset_of_generators_once():
+    assert attention.round_chunks(6, 2) == [2, 2, 2] and attention.round_chunks(7, 3) == [3, 2, 2]
+    assert attention.round_chunks(7, 4) == [4, 3] and attention.round_chunks(6, 1) == [1] * 6
+    assert attention.round_chunks(3, 8) == [3] and attention.round_chunks(0, 2) == []
+    n, d = 1 << 12, 32
+    for gens, w in ((attention.fold_generators(n, d), 2), (attention.block_generators(n, d), 3),
+                    (attention.block_generators(n, d), 1)):
+        rounds = attention.round_galois(n, gens, w)
+        assert [len(r) for r in rounds] == [(1 << c) - 1 for c in attention.round_chunks(len(gens), w)]
+        # composing the rounds reaches each of the 2^B subset products exactly once
+        reached = [1]
+        for elts in rounds:
+            reached = [a * b % (2 * n) for a in reached for b in [1] + elts]
+        want = [1]
+        for g in gens:
+            want = want + [a * g % (2 * n) for a in want]
+        assert sorted(reached) == sorted(want) and len(set(reached)) == 1 << len(gens)
+    # one bit per round: the rotate-and-add chain's own elements, in its order
+    assert attention.round_galois(n, attention.fold_generators(n, d), 1) == [[g] for g in attention.fold_generators(n, d)]
+
+
+@pytest.mark.parametrize("w", [1, 2, 3, 6])
+def test_decode_scores_by_rounds_of_hoisted_rotations_are_the_same_dot_products(w):
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 62, orc)
+    n, d, t = prm.n, 64, prm.t
+    B = n // d
+    act = attention_activations(Stream(62, 1), 1, B + 1, d)[0]
+    q, K = act[0], act[1:]
+    rlk = cl.relin_key()
+    gks = {g: cl.galois_key(g) for g in attention.hoisted_fold_galois(n, d, w, 1)}
+    counts = {}
+    out = attention.decode_scores_hoisted(orc, cl.encrypt_slots(np.tile(q, B)), cl.encrypt_slots(K.reshape(-1)),
+                                          rlk, gks, d, w, counts)
+    assert counts == {1: {"rounds": 6, "rotate": 6}, 2: {"rounds": 3, "rotate": 9}, 3: {"rounds": 2, "rotate": 14},
+                      6: {"rounds": 1, "rotate": 63}}[w]
+    dec = cl.decrypt_slots(out)
+    assert np.array_equal(dec[::d], (K @ q) % t)
+    # every slot of a block holds the sum over the block's d slots rotated to it: the full fold
+    prod = (np.tile(q, B) * K.reshape(-1)).reshape(2, n // 2)
+    want = sum(np.roll(prod, -s, axis=1) for s in range(d)).reshape(-1)
+    assert np.array_equal(dec, want % t)
+    assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
+
+
+@pytest.mark.parametrize("w", [2, 3, 4])
+def test_decode_context_by_rounds_of_hoisted_rotations_is_the_same_weighted_sum(w):
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 63, orc)
+    n, d, t = prm.n, 64, prm.t
+    B = n // d
+    g = Stream(63, 1)
+    V = attention_activations(g, 1, 2 * B, d)[0]
+    a = attention_activations(g, 1, 2 * B, 1)[0, :, 0]
+    rlk = cl.relin_key()
+    gks = {e: cl.galois_key(e) for e in attention.hoisted_fold_galois(n, d, 1, w)}
+    a_cts = [cl.encrypt_slots(np.repeat(a[c * B:(c + 1) * B], d)) for c in range(2)]
+    v_cts = [cl.encrypt_slots(V[c * B:(c + 1) * B].reshape(-1)) for c in range(2)]
+    counts = {}
+    out = attention.decode_context_hoisted(orc, a_cts, v_cts, rlk, gks, d, w, counts)
+    assert counts == {2: {"rounds": 4, "rotate": 3 + 3 + 3 + 1}, 3: {"rounds": 3, "rotate": 7 + 3 + 3},
+                      4: {"rounds": 2, "rotate": 15 + 7}}[w]
+    assert np.array_equal(cl.decrypt_slots(out), np.tile((a @ V) % t, B))
+    assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
+
+
 @pytest.mark.parametrize("hoisted", [False, True])
 def test_prefill_generalised_diagonals_on_a_small_ring(hoisted):
     """Also with the copies of K made by hoisted rotations of K itself: other ciphertexts, same slots."""

@@ -138,6 +138,60 @@ def test_hoisted_rotations_move_slots_like_ordinary_ones_within_the_noise_bound(
     assert np.array_equal(dec[:h], vm[h:]) and np.array_equal(dec[h:], vm[:h])
 
 
+@pytest.mark.parametrize("prm", TOYS, ids=lambda p: f"{p.name}_a{p.alpha}")
+def test_hoisted_rotation_sum_against_the_definition_over_the_integers(prm):
+    """One division by P for a whole series: brute force with Python integers for one, two and three
+    rotations with different keys; a series of one is the ciphertext plus its hoisted rotation; a
+    longer series is NOT the sum of separately rounded rotations (else the single division would
+    be untested) but differs from it by less than the number of rotations per coefficient."""
+    rnd = random.Random(16)
+    orc = Oracle(prm)
+    q, p, n = list(prm.q), list(prm.p), prm.n
+    keys = {g: np.array([[_rand_ring(rnd, q + p, n) for _ in range(2)] for _ in range(prm.dnum)], dtype=np.uint64)
+            for g in (3, 9, 2 * n - 1)}
+    c2 = [_rand_ring(rnd, q, n) for _ in range(2)]
+    c2[1][0][1] = 0
+    ct = np.array(c2, dtype=np.uint64)
+    for gs in ([3], [9, 2 * n - 1], [3, 9, 2 * n - 1]):
+        got = orc.rotate_sum_hoisted(ct, gs, keys)
+        assert got.tolist() == bf.bf_rotate_sum_hoisted(c2, gs, [keys[g].tolist() for g in gs], q, p, prm.alpha)
+        apart = ct
+        for g in gs:
+            apart = orc.add(apart, orc.rotate_hoisted(ct, g, keys[g]))
+        if len(gs) == 1:
+            assert np.array_equal(got, apart)
+        else:
+            assert not np.array_equal(got, apart)
+            Q = 1
+            for m in q:
+                Q *= m
+            for c in range(2):
+                a = bf.ring_from_rns(got[c].tolist(), q)
+                b = bf.ring_from_rns(apart[c].tolist(), q)
+                assert max(min((x - y) % Q, (y - x) % Q) for x, y in zip(a, b)) < len(gs)
+    assert np.array_equal(orc.rotate_sum_hoisted(ct, [], keys), ct)
+
+
+def test_hoisted_rotation_sum_adds_the_rotated_slots_within_the_noise_bound():
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 33, orc)
+    n, h = prm.n, prm.n // 2
+    v = slot_values(Stream(33, 1), n, -128, 128)
+    ct = cl.encrypt_slots(v)
+    fresh = cl.noise_budget_bits(ct, cl.codec.encode(v))
+    shifts = (1, 2, 3, 64)
+    gs = [galois_rot(n, r) for r in shifts] + [galois_swap(n)]
+    out = orc.rotate_sum_hoisted(ct, gs, {g: cl.galois_key(g) for g in gs})
+    want = v.copy()
+    for r in shifts:
+        want = want + np.concatenate([np.roll(v[:h], -r), np.roll(v[h:], -r)])
+    want = want + np.concatenate([v[h:], v[:h]])
+    assert np.array_equal(cl.decrypt_slots(out), want % prm.t)
+    # six ciphertexts' noise and five key switches' noise add up: log2(6) + a few bits
+    assert fresh - cl.noise_budget_bits(out, cl.codec.encode(want)) < 15
+
+
 def test_keyswitch_of_zero_is_zero_and_relin_keeps_two_component_input():
     prm = PRESETS["C2"]
     orc = Oracle(prm)
