@@ -9,11 +9,16 @@ for one generated token (GPT-2-small shape: 12 heads x d = 64, N = 8192, three
     append   the new K and V rows into 24 caches at token 512 (opens ciphertext 5)
 Inputs are seeded uniform residues (stand-ins for ciphertexts and keys; see
 workloads.synth) already resident in HBM when the timed region starts.  The
-step is timed as one call in two forms, K steps each: cg_decode_step (plain
-cache) and cg_decode_step_ext (the products read a transformed copy of the
-cache, which the step keeps up to date); the faster of the two is the
-headline `value`, the other is listed beside it.  --serial times three plain
-calls in sequence instead and nothing else (profiling runs).
+step is timed as one call in four forms, K steps each: cg_decode_step (plain
+cache), cg_decode_step_ext (the products read a transformed copy of the cache,
+which the step keeps up to date), and cg_decode_step_hoisted without and with
+that copy (the same products with both folding sums regrouped into rounds of
+hoisted rotation sums: 3 + 3 dependent key switches after the
+relinearisations instead of 6 + 7, for 9 + 13 rotation keys instead of 6 + 7;
+the results decrypt to the same slots and each form is checked against the
+oracle's definition of that form).  The fastest is the headline `value`, the
+others are listed beside it.  --serial times three calls in sequence instead
+and nothing else (profiling runs; with --hoisted the hoisted calls).
 
 Prints ONE JSON line.  `roofline` describes the kernel class with the largest
 share of the step, timed with HIP events by the library itself in a further
@@ -54,13 +59,20 @@ FP64_LANE_INSTR_PER_ITEM = {
     "ntt_inv<u64>": 616 * 1024,
     "ntt_inv<mul_plain>": 688 * 1024,
     "ntt_inv<ks_inner>": 728 * 1024,
+    # summed inner product of n_rot rotations: 560 per thread outside the rotation loop, 200 per rotation
+    "ntt_inv<ks_sum>": 560 * 1024,
+    "ntt_inv<ks_sum> per rotation": 200 * 1024,
     "scale": 373 * 3 * 8192,
     "moddown": 320 * 8192,
+    "moddown<sum>": 320 * 8192,
+    "moddown<sum> per rotation": 18 * 8192,
     "sum_groups": 16 * 9 * 8192,
     "add": 6 * 8192,
 }
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
+
+FORMS = ("plain", "ext", "hoisted", "hoisted_ext")
 
 
 def kernel_sources_digest():
@@ -99,6 +111,13 @@ class DecodeStep:
         self.masks = ctx.plain_prepare(dev(self.h_masks))
         self.rlk = ctx.ksk_prepare(dev(self.h_rlk))
         self.gk = {gal: ctx.ksk_prepare(dev(k)) for gal, k in self.h_gk.items()}
+        # the folding sums in rounds: elements in the library's key order, stand-in keys drawn per element
+        # bits per round (scores: 6 bits, context: 7): the measured optimum on MI355X
+        self.w_fold, self.w_block = configs.C4_ROUND_BITS
+        self.g_fold_rounds = ctx.round_galois(0, self.d2, self.w_fold)
+        self.g_block_rounds = ctx.round_galois(1, self.d2, self.w_block)
+        self.h_gk_rounds = configs.galois_keys("C4", sorted(set(self.g_fold_rounds + self.g_block_rounds)))
+        self.gk_rounds = {gal: ctx.ksk_prepare(dev(k)) for gal, k in self.h_gk_rounds.items()}
         self.scores = ctx.empty_ct(H, C)
         self.context = ctx.empty_ct(H)
         ctx.workspace(H * C)
@@ -119,6 +138,38 @@ class DecodeStep:
     def step_plain_cache(self):
         self.step(transformed_cache=False)
 
+    def step_hoisted(self, transformed_cache=True):
+        """The step with both folding sums in rounds of hoisted rotation sums."""
+        self.ctx.decode_step_hoisted(self.q, self.a, self.cache, self.heads, self.n_cts, self.stride, self.d2,
+                                     self.tau, self.rows, self.masks, self.rlk, self.w_fold,
+                                     [self.gk_rounds[g] for g in self.g_fold_rounds], self.w_block,
+                                     [self.gk_rounds[g] for g in self.g_block_rounds], scores=self.scores,
+                                     context=self.context, cache_ext=self.ext if transformed_cache else None)
+
+    def step_hoisted_plain_cache(self):
+        self.step_hoisted(transformed_cache=False)
+
+    def step_serial_hoisted(self):
+        c, H, C = self.ctx, self.heads, self.n_cts
+        c.decode_scores_hoisted(self.q, self.kcache, H, C, self.d2, self.w_fold, self.rlk,
+                                [self.gk_rounds[g] for g in self.g_fold_rounds], out=self.scores,
+                                cache_stride_cts=self.stride)
+        c.decode_context_hoisted(self.a, self.vcache, H, C, self.d2, self.w_block, self.rlk,
+                                 [self.gk_rounds[g] for g in self.g_block_rounds], out=self.context,
+                                 cache_stride_cts=self.stride)
+        c.kv_append(self.cache, self.stride, 2 * H, self.tau, self.rows, self.masks, self.d2)
+
+    def round_sizes(self, which):
+        """Rotations per round, by the rule the library states for its rounds (as even as possible,
+        longer rounds first); checked against the number of elements the library lists."""
+        n_bits = len(self.g_block) if which else len(self.g_fold)
+        w = self.w_block if which else self.w_fold
+        rounds = -(-n_bits // w)
+        lo, extra = divmod(n_bits, rounds)
+        sizes = [(1 << (lo + (1 if r < extra else 0))) - 1 for r in range(rounds)]
+        assert sum(sizes) == len(self.g_block_rounds if which else self.g_fold_rounds)
+        return sizes
+
     def step_serial(self):
         """The same work as three calls in sequence (used for per-kernel timing: a kernel's
         duration only describes the kernel when it has the device to itself)."""
@@ -130,12 +181,16 @@ class DecodeStep:
         c.kv_append(self.cache, self.stride, 2 * H, self.tau, self.rows, self.masks, self.d2)
 
     # per step: 96 mul, 60 relin, 372 rotations, 24 appends
-    def op_counts(self):
+    def op_counts(self, hoisted=False):
         H, C = self.heads, self.n_cts
+        if hoisted:
+            return {"mul": 2 * H * C, "relin": H * C + H,
+                    "rotation_sums": H * C * len(self.round_sizes(0)) + H * len(self.round_sizes(1)),
+                    "rotate": H * C * len(self.g_fold_rounds) + H * len(self.g_block_rounds), "append": 2 * H}
         return {"mul": 2 * H * C, "relin": H * C + H,
                 "rotate": H * C * len(self.g_fold) + H * len(self.g_block), "append": 2 * H}
 
-    def compulsory_bytes(self):
+    def compulsory_bytes(self, hoisted=False):
         """What one step has to move whatever the implementation: every input ciphertext (K and V
         caches, queries, weights, new rows), every key and block mask it uses, once each, and every
         output ciphertext (scores, contexts, the ciphertext each cache was appended to)."""
@@ -144,7 +199,8 @@ class DecodeStep:
         key = self.prm.dnum * 2 * (self.prm.k + self.prm.nsp) * self.n * 8
         cts_in = 2 * H * C + H + H * C + 2 * H
         cts_out = H * C + H + 2 * H
-        n_keys = 1 + len(self.g_fold) + len(self.g_block)
+        n_keys = 1 + (len(self.g_fold_rounds) + len(self.g_block_rounds) if hoisted
+                      else len(self.g_fold) + len(self.g_block))
         return (cts_in + cts_out) * ct + n_keys * key + self.n * 8
 
 
@@ -266,30 +322,43 @@ def cpvm_layer_us(torch, ws, reps=20):
             "value": round(ms * 1e3, 1), "unit": "us"}
 
 
-def cpu_baseline(ws: DecodeStep):
-    """Time the oracle on the whole step (same seeded inputs) and compare every output ciphertext
-    of the GPU step with it."""
+def cpu_baseline(ws: DecodeStep, hoisted: bool):
+    """Time the oracle on the whole step in the headline's form (same seeded inputs) and compare
+    every output ciphertext of the GPU step with it; then run the step once in the other family of
+    forms and compare that with the oracle's definition of it as well."""
     from oracle import Oracle, run_configs
+    torch = ws.torch
     orc = Oracle(ws.prm)
     H, C, S = ws.heads, ws.n_cts, ws.stride
-    gpu_scores = ws.P.to_host(ws.scores)
-    gpu_context = ws.P.to_host(ws.context)
-    gpu_cache = ws.P.to_host(ws.cache)
-    t0 = time.perf_counter()
-    want = run_configs.run_c4(orc, ws.st)
-    step_s = time.perf_counter() - t0
     idx = ws.tau // ws.B
-    ok = all(np.array_equal(gpu_scores[h, c], want[f"score{h}_{c}"]) for h in range(H) for c in range(C))
-    ok = ok and all(np.array_equal(gpu_context[h], want[f"context{h}"]) for h in range(H))
-    ok = ok and all(np.array_equal(gpu_cache[c * S + idx], want[f"cache{c}"]) for c in range(2 * H))
-    counts = ws.op_counts()
+
+    def check(form_hoisted):
+        (ws.step_hoisted if form_hoisted else ws.step)()
+        torch.cuda.synchronize()
+        gpu_scores, gpu_context, gpu_cache = (ws.P.to_host(t) for t in (ws.scores, ws.context, ws.cache))
+        t0 = time.perf_counter()
+        if form_hoisted:
+            want = run_configs.run_c4_hoisted(orc, ws.st, ws.w_fold, ws.w_block, ws.h_gk_rounds)
+        else:
+            want = run_configs.run_c4(orc, ws.st)
+        sec = time.perf_counter() - t0
+        ok = all(np.array_equal(gpu_scores[h, c], want[f"score{h}_{c}"]) for h in range(H) for c in range(C))
+        ok = ok and all(np.array_equal(gpu_context[h], want[f"context{h}"]) for h in range(H))
+        ok = ok and all(np.array_equal(gpu_cache[c * S + idx], want[f"cache{c}"]) for c in range(2 * H))
+        return sec, bool(ok)
+
+    step_s, ok = check(hoisted)
+    other_s, other_ok = check(not hoisted)
+    counts = ws.op_counts(hoisted)
+    work = ", ".join(f"{v} {k}" for k, v in counts.items())
     return {
         "value": round(step_s * 1e3, 1), "unit": "ms/token (one layer)",
         "cores": orc.threads, "kind": "oracle",
-        "sample": f"the whole step of the same seeded workload ({counts['mul']} products, {counts['relin']} "
-                  f"relinearisations, {counts['rotate']} rotations, {counts['append']} appends): "
+        "sample": f"the whole step of the same seeded workload in the timed form ({work}): "
                   f"{round(step_s * orc.threads, 1)} core-seconds",
-        "gpu_matches_oracle_on_every_output": bool(ok),
+        "gpu_matches_oracle_on_every_output": ok,
+        "other_form": {"form": "rotate-and-add chains" if hoisted else "folding sums in rounds of hoisted rotations",
+                       "oracle_ms": round(other_s * 1e3, 1), "gpu_matches_oracle_on_every_output": other_ok},
     }
 
 
@@ -314,7 +383,8 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="issue the step as three calls in sequence and nothing else: every kernel has the "
                          "device to itself (profiling runs)")
-    ap.add_argument("--one-call", choices=["plain", "ext"], default=None,
+    ap.add_argument("--hoisted", action="store_true", help="with --serial: the hoisted calls")
+    ap.add_argument("--one-call", choices=list(FORMS), default=None,
                     help="time only this form of the one-call step and nothing else (profiling runs)")
     ap.add_argument("--no-secondary", action="store_true",
                     help="skip the mult+relin/sec loops (used when profiling the step alone)")
@@ -329,27 +399,34 @@ def main():
         sys.exit(1)
 
     ws = DecodeStep()
+    fns = {"plain": ws.step_plain_cache, "ext": ws.step, "hoisted": ws.step_hoisted_plain_cache,
+           "hoisted_ext": ws.step_hoisted}
     profiling_run = args.serial or args.one_call is not None
-    ms_ext = ms_plain = ms_serial = None
+    per_form, ms_serial = {}, None
     if args.serial:
+        fn = ws.step_serial_hoisted if args.hoisted else ws.step_serial
         for _ in range(args.warmup):
-            ws.step_serial()
-        ms = ms_serial = timed(torch, ws.step_serial, args.steps)
-        form = "serial"
+            fn()
+        ms = ms_serial = timed(torch, fn, args.steps)
+        form = "serial_hoisted" if args.hoisted else "serial"
     elif args.one_call:
-        fn = ws.step if args.one_call == "ext" else ws.step_plain_cache
+        fn = fns[args.one_call]
         for _ in range(args.warmup):
             fn()
         ms = timed(torch, fn, args.steps)
         form = args.one_call
     else:
         for _ in range(args.warmup):
-            ws.step()
-            ws.step_plain_cache()
-        ms_ext = timed(torch, ws.step, args.steps)
-        ms_plain = timed(torch, ws.step_plain_cache, args.steps)
-        ms_serial = timed(torch, ws.step_serial, args.steps)
-        ms, form = (ms_ext, "ext") if ms_ext <= ms_plain else (ms_plain, "plain")
+            for fn in fns.values():
+                fn()
+        for name, fn in fns.items():
+            per_form[name] = timed(torch, fn, args.steps)
+        form = min(per_form, key=per_form.get)
+        ms = per_form[form]
+    hoisted = "hoisted" in form
+    serial_fn = ws.step_serial_hoisted if hoisted else ws.step_serial
+    if not profiling_run:
+        ms_serial = timed(torch, serial_fn, args.steps)
 
     kernels, roofline = [], None
     if args.one_call is None:
@@ -357,13 +434,21 @@ def main():
         # bracketing for per-kernel figures
         ws.ctx.profile_begin(200 * args.steps)
         for _ in range(args.steps):
-            ws.step_serial()
+            serial_fn()
         stats = ws.ctx.profile_end()
+        H, C, L2 = ws.heads, ws.n_cts, 2 * (ws.prm.k + ws.prm.nsp)
+        # rotation-rows and rotation-units of the summed kernels, per step
+        rot_rows = sum(H * C * L2 * r for r in ws.round_sizes(0)) + sum(H * L2 * r for r in ws.round_sizes(1))
+        rot_units = sum(H * C * r for r in ws.round_sizes(0)) + sum(H * r for r in ws.round_sizes(1))
         fp64_step = 0.0
         for s in stats:
             sec = s["total_ms"] * 1e-3
             gbs = s["algo_bytes"] / sec / 1e9
             fp64 = s["work_items"] * FP64_LANE_INSTR_PER_ITEM.get(s["name"], 0)
+            if s["name"] == "ntt_inv<ks_sum>":
+                fp64 += args.steps * rot_rows * FP64_LANE_INSTR_PER_ITEM["ntt_inv<ks_sum> per rotation"]
+            if s["name"] == "moddown<sum>":
+                fp64 += args.steps * rot_units * FP64_LANE_INSTR_PER_ITEM["moddown<sum> per rotation"]
             fp64_step += fp64 / args.steps
             kernels.append({"name": s["name"], "launches_per_step": s["launches"] / args.steps,
                             "avg_us": round(s["total_ms"] * 1e3 / s["launches"], 2),
@@ -375,8 +460,8 @@ def main():
         dom_stat = next(s for s in stats if s["name"] == dom["name"])
         traffic, traffic_note = stored_traffic(dom["name"])
         bound = "hbm" if dom["hbm_frac"] >= dom["fp64_valu_frac"] else "alu"
-        step_bytes = ws.compulsory_bytes()
-        if form == "ext":
+        step_bytes = ws.compulsory_bytes(hoisted)
+        if form.endswith("ext"):
             # the timed step read the cache's transformed copy: no lift and forward transform of the 2 H C
             # cache operands (2 polynomials each: k ciphertext-prime rows, k + 1 auxiliary rows), but
             # the same for the 2 H ciphertexts the step appended to
@@ -412,18 +497,26 @@ def main():
                      "ct_pt_projections": cpvm_layer_us(torch, ws),
                      "scaled_config": c5_curve(torch, ws.P)}
 
+    rounds = (f"both folding sums in rounds of hoisted rotation sums ({ws.w_fold} / {ws.w_block} bits per round: "
+              f"{len(ws.round_sizes(0))} + {len(ws.round_sizes(1))} dependent key switches after the relinearisations "
+              f"instead of {len(ws.g_fold)} + {len(ws.g_block)})")
     launch = {"serial": "three calls in sequence",
+              "serial_hoisted": "three calls in sequence, " + rounds,
               "ext": "cg_decode_step_ext: scores, context and append side by side on three streams; the products "
                      "read the cache's transformed copy and the step refreshes the copy of the 24 ciphertexts it "
                      "appends to",
-              "plain": "cg_decode_step: scores, context and append side by side on three streams"}[form]
+              "plain": "cg_decode_step: scores, context and append side by side on three streams",
+              "hoisted": "cg_decode_step_hoisted: three streams, " + rounds,
+              "hoisted_ext": "cg_decode_step_hoisted with the cache's transformed copy: three streams, " + rounds}[form]
     config = {"workload": "C4: decode step, 12 heads x d=64, 512-token encrypted KV cache, N=8192, "
-                          "3+1 primes < 2^50, t=65537", "ops_per_step": ws.op_counts(),
+                          "3+1 primes < 2^50, t=65537", "ops_per_step": ws.op_counts(hoisted),
               "arithmetic": "exact integer residues < 2^50 carried in FP64 registers; uint64 at the ABI",
-              "derived_12_layers_ms_per_token": round(12 * ms, 3), "launch": launch}
-    if ms_ext is not None:
-        config["ms_per_step_cg_decode_step_ext"] = round(ms_ext, 4)
-        config["ms_per_step_cg_decode_step"] = round(ms_plain, 4)
+              "derived_12_layers_ms_per_token": round(12 * ms, 3), "form": form, "launch": launch}
+    if per_form:
+        config["ms_per_step_cg_decode_step_ext"] = round(per_form["ext"], 4)
+        config["ms_per_step_cg_decode_step"] = round(per_form["plain"], 4)
+        config["ms_per_step_cg_decode_step_hoisted_ext"] = round(per_form["hoisted_ext"], 4)
+        config["ms_per_step_cg_decode_step_hoisted"] = round(per_form["hoisted"], 4)
     if ms_serial is not None:
         config["ms_per_step_three_calls_in_sequence"] = round(ms_serial, 4)
     result = {
@@ -439,7 +532,7 @@ def main():
         "kernels": kernels,
     }
     if not args.no_cpu_baseline and not profiling_run:
-        result["cpu_baseline"] = cpu_baseline(ws)
+        result["cpu_baseline"] = cpu_baseline(ws, hoisted)
     print(json.dumps(result))
 
 

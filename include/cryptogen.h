@@ -32,8 +32,8 @@
  *               Invalid arguments are rejected before any kernel is launched.
  *   aliasing    outputs must not overlap inputs unless stated.
  *   threads     a context may be used from several host threads as long as
- *               concurrent calls use distinct workspaces; cg_decode_step and
- *               cg_decode_step_ext use streams and events owned by the context,
+ *               concurrent calls use distinct workspaces; cg_decode_step,
+ *               cg_decode_step_ext and cg_decode_step_hoisted use streams and events owned by the context,
  *               and cg_ntt_forward / cg_ntt_inverse an index table owned by it,
  *               so a context runs one of each of these at a time.
  *
@@ -188,6 +188,21 @@ int cg_rotate_hoisted(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, uint32
                       const uint32_t *galois_elts_host, const void *const *gk_dev_host, uint64_t *out2_dev,
                       uint32_t batch, void *ws_dev);
 
+/* A ciphertext plus a series of its rotations, with one division by P for the whole series (the
+ * sums of rotated copies that section 4.3's products end in -- "rotations ... accumulated" --
+ * regrouped so that several rotations act on the same ciphertext):
+ *   digit_j and sigma_g on the digits as in cg_rotate_hoisted;
+ *   A_c = sum_i sum_j sigma_{g_i}(digit_j) * key^(g_i)_{j,c} mod P Q;
+ *   u_c = floor((A_c + floor(P/2)) / P) mod Q;
+ *   out2[b] = (c0 + sum_i sigma_{g_i}(c0) + u0, c1 + u1).
+ * It decrypts to the slot-wise sum of in2[b] and its n_rot rotations; it is not the sum of n_rot
+ * separately rotated ciphertexts (those round n_rot times).  1 <= n_rot <= 128; arrays as in
+ * cg_rotate_hoisted; out2 [batch] ciphertexts, must not overlap in2.
+ * ws_dev: cg_workspace_bytes(ctx, batch) bytes. */
+int cg_rotate_sum_hoisted(cg_ctx *ctx, void *stream, const uint64_t *in2_dev, uint32_t n_rot,
+                          const uint32_t *galois_elts_host, const void *const *gk_dev_host,
+                          uint64_t *out2_dev, uint32_t batch, void *ws_dev);
+
 /* out = a + b component-wise mod q_i ("accumulated", section 4.3); ncomp = 2 or 3;
  * out may alias a or b. */
 int cg_add(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *b_dev,
@@ -267,6 +282,43 @@ int cg_decode_step(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint6
                    const void *rlk_dev, const void *const *gk_fold_dev_host,
                    const void *const *gk_block_dev_host, uint64_t *scores_dev, uint64_t *context_dev,
                    void *ws_dev);
+
+/* The decode products with their folding sums taken in rounds (section 4.3 fixes what is summed --
+ * the d2 slots of a block for the scores, the N/d2 blocks for the context -- not the order).  The
+ * rotate-and-add chain applies generators g_0 .. g_{B-1} one after the other (scores: g_b =
+ * 3^(2^b), B = log2 d2; context: g_b = 3^(d2 2^b) for b < log2(N/(2 d2)), then 2N-1), each step on
+ * the previous step's result.  Here the B bits are cut into R = ceil(B / round_bits) chunks, as
+ * even as possible, the longer ones first; round r over bits [b0, b0 + c) is one
+ * cg_rotate_sum_hoisted of the previous round's result with the 2^c - 1 Galois elements
+ *   e_m = product of g_(b0+i) over the bits i set in m,  m = 1 .. 2^c - 1  (in this order),
+ * so R dependent key switches replace B.  Everything before the folding sum (products, the sum
+ * over cache ciphertexts, the relinearisation) is as in cg_decode_scores / cg_decode_context, and
+ * the results decrypt to the same slots; they are other ciphertexts.  1 <= round_bits <= 7.
+ * gk_rounds_dev_host: host array of device pointers to the prepared keys of all rounds, round 0's
+ * 2^c - 1 keys first.  kext_dev / vext_dev: the cache's transformed form (cg_cache_extend) or
+ * NULL; when given, kc_dev / vc_dev is not read and may be NULL.  cg_decode_step_hoisted is
+ * cg_decode_step (cache_ext_dev NULL) or cg_decode_step_ext with both folding sums in rounds.
+ * Workspaces as for the calls they replace. */
+/* The Galois elements of all rounds in the order of gk_rounds_dev_host, for the scores' folding
+ * sum (which = 0) or the context's (which = 1): writes min(cap, n) of them to elts_host and n to
+ * n_out (host memory; no device work). */
+int cg_round_galois(const cg_ctx *ctx, int which, uint32_t d2, uint32_t round_bits, uint32_t *elts_host,
+                    uint32_t cap, uint32_t *n_out);
+int cg_decode_scores_hoisted(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *kc_dev,
+                             const void *kext_dev, uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts,
+                             uint32_t d2, uint32_t round_bits, const void *rlk_dev,
+                             const void *const *gk_rounds_dev_host, uint64_t *out_dev, void *ws_dev);
+int cg_decode_context_hoisted(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *vc_dev,
+                              const void *vext_dev, uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts,
+                              uint32_t d2, uint32_t round_bits, const void *rlk_dev,
+                              const void *const *gk_rounds_dev_host, uint64_t *out_dev, void *ws_dev);
+int cg_decode_step_hoisted(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *a_dev,
+                           uint64_t *cache_dev, void *cache_ext_dev, uint32_t heads, uint32_t n_cts,
+                           uint32_t cache_stride_cts, uint32_t d2, uint32_t tau, const uint64_t *rows_dev,
+                           const void *masks_dev, const void *rlk_dev, uint32_t fold_round_bits,
+                           const void *const *gk_fold_rounds_dev_host, uint32_t block_round_bits,
+                           const void *const *gk_block_rounds_dev_host, uint64_t *scores_dev,
+                           uint64_t *context_dev, void *ws_dev);
 
 /* The cache kept in transformed form (an optimisation of the decode scan that leaves every
  * result bit-identical): a ciphertext that is multiplied in many steps -- every cache

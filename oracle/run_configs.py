@@ -58,6 +58,26 @@ def run_c4(orc, st):
     return out
 
 
+def run_c4_hoisted(orc, st, w_fold, w_block, gk_rounds):
+    """run_c4 with both folding sums taken in rounds of hoisted rotation sums (w_fold / w_block bits
+    per round); gk_rounds: switching keys by Galois element for attention.hoisted_fold_galois."""
+    out = {}
+    cache = st["cache"].copy()
+    H, S, C, d2 = st["heads"], st["stride"], st["n_cts"], st["d2"]
+    for h in range(H):
+        for c in range(C):
+            out[f"score{h}_{c}"] = attention.decode_scores_hoisted(orc, st["q"][h], cache[h * S + c], st["rlk"],
+                                                                   gk_rounds, d2, w_fold)
+        v0 = (H + h) * S
+        out[f"context{h}"] = attention.decode_context_hoisted(orc, list(st["a"][h * C:(h + 1) * C]),
+                                                              list(cache[v0:v0 + C]), st["rlk"], gk_rounds, d2, w_block)
+    idx, blk = divmod(st["tau"], st["B"])
+    for c in range(2 * H):
+        masked = orc.mul_plain(st["rows"][c], st["masks"][blk])
+        out[f"cache{c}"] = masked if blk == 0 else orc.add(cache[c * S + idx], masked)
+    return out
+
+
 def run_c3(orc, st, heads=None, progress=None):
     """Build every K and V cache ciphertext from its 128 row ciphertexts, then per head: Q K^T,
     the compaction of its score ciphertexts, and A V."""

@@ -23,7 +23,8 @@ _SYMBOLS = [
     "cg_bench_modmul", "cg_bench_exchange", "cg_profile_begin", "cg_profile_end", "cg_kernel_name",
     "cg_mul_relin_static", "cg_static_scratch_bytes",
     "cg_rotate_hoisted", "cg_prefill_qk_hoisted", "cg_prefill_av_hoisted", "cg_cpvm_hoisted",
-    "cg_rotate_sum_hoisted",
+    "cg_rotate_sum_hoisted", "cg_round_galois", "cg_decode_scores_hoisted", "cg_decode_context_hoisted",
+    "cg_decode_step_hoisted",
 ]
 
 
@@ -72,6 +73,11 @@ class Library:
         d.cg_mul_relin.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, vp]
         d.cg_rotate_hoisted.argtypes = [vp, vp, vp, u32, C.POINTER(u32), C.POINTER(vp), vp, u32, vp]
         d.cg_rotate_sum_hoisted.argtypes = d.cg_rotate_hoisted.argtypes
+        d.cg_round_galois.argtypes = [vp, i32, u32, u32, C.POINTER(u32), u32, C.POINTER(u32)]
+        d.cg_decode_scores_hoisted.argtypes = [vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
+        d.cg_decode_context_hoisted.argtypes = d.cg_decode_scores_hoisted.argtypes
+        d.cg_decode_step_hoisted.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp, vp, u32,
+                                             C.POINTER(vp), u32, C.POINTER(vp), vp, vp, vp]
         d.cg_prefill_qk_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
         d.cg_prefill_av_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
         d.cg_cpvm_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, u32, C.POINTER(vp), C.POINTER(vp), vp, vp]
@@ -466,6 +472,81 @@ class Context:
                 self.h, self.stream, _ptr(q), _ptr(a), _ptr(cache), _ptr(cache_ext), heads, n_cts, cache_stride_cts,
                 d2, tau, _ptr(rows), _ptr(masks), _ptr(rlk), self._keys(gk_fold), self._keys(gk_block),
                 _ptr(scores), _ptr(context), _ptr(self._ws_step)))
+        return scores, context
+
+    def round_galois(self, which, d2, round_bits):
+        """Galois elements of all rounds of a folding sum, in key order: which = 0 scores, 1 context."""
+        n = C.c_uint32(0)
+        self._check(self.lib.dll.cg_round_galois(self.h, which, d2, round_bits, None, 0, C.byref(n)))
+        buf = (C.c_uint32 * max(1, n.value))()
+        self._check(self.lib.dll.cg_round_galois(self.h, which, d2, round_bits, buf, n.value, C.byref(n)))
+        return [int(buf[i]) for i in range(n.value)]
+
+    def _need_round_keys(self, which, d2, round_bits, keys):
+        want = len(self.round_galois(which, d2, round_bits))
+        if len(keys) != want:
+            raise CgSizeError(f"{want} round keys needed, {len(keys)} given")
+
+    def decode_scores_hoisted(self, q, kcache, heads, n_cts, d2, round_bits, rlk, gk_rounds, out=None,
+                              cache_stride_cts=None, kext=None):
+        out = self.empty_ct(heads, n_cts) if out is None else out
+        ws = self.workspace(heads * n_cts)
+        stride = n_cts if cache_stride_cts is None else cache_stride_cts
+        self._need_round_keys(0, d2, round_bits, gk_rounds)
+        if kext is None:
+            self._need_products(q, heads, kcache, self._cts(1), heads, n_cts, stride, out, heads * n_cts, rlk, gk_rounds)
+        else:
+            self._need_products(q, heads, kext, int(self.sizes.ct_ext_bytes) // 8, heads, n_cts, stride, out,
+                                heads * n_cts, rlk, gk_rounds)
+        self._check(self.lib.dll.cg_decode_scores_hoisted(
+            self.h, self.stream, _ptr(q), _ptr(kcache), _ptr(kext), heads, n_cts, stride, d2, round_bits, _ptr(rlk),
+            self._keys(gk_rounds), _ptr(out), _ptr(ws)))
+        return out
+
+    def decode_context_hoisted(self, a, vcache, heads, n_cts, d2, round_bits, rlk, gk_rounds, out=None,
+                               cache_stride_cts=None, vext=None):
+        out = self.empty_ct(heads) if out is None else out
+        ws = self.workspace(heads * n_cts)
+        stride = n_cts if cache_stride_cts is None else cache_stride_cts
+        self._need_round_keys(1, d2, round_bits, gk_rounds)
+        if vext is None:
+            self._need_products(a, heads * n_cts, vcache, self._cts(1), heads, n_cts, stride, out, heads, rlk, gk_rounds)
+        else:
+            self._need_products(a, heads * n_cts, vext, int(self.sizes.ct_ext_bytes) // 8, heads, n_cts, stride, out,
+                                heads, rlk, gk_rounds)
+        self._check(self.lib.dll.cg_decode_context_hoisted(
+            self.h, self.stream, _ptr(a), _ptr(vcache), _ptr(vext), heads, n_cts, stride, d2, round_bits, _ptr(rlk),
+            self._keys(gk_rounds), _ptr(out), _ptr(ws)))
+        return out
+
+    def decode_step_hoisted(self, q, a, cache, heads, n_cts, cache_stride_cts, d2, tau, rows, masks, rlk,
+                            fold_round_bits, gk_fold_rounds, block_round_bits, gk_block_rounds, scores=None,
+                            context=None, cache_ext=None):
+        scores = self.empty_ct(heads, n_cts) if scores is None else scores
+        context = self.empty_ct(heads) if context is None else context
+        ct = 2 * self.k * self.n
+        self._check_append(cache, cache_stride_cts, 2 * heads, tau, rows, masks, d2)
+        _need(q, heads * ct, "q")
+        _need(a, heads * n_cts * ct, "a")
+        _need(scores, heads * n_cts * ct, "scores")
+        _need(context, heads * ct, "context")
+        self._need_key(rlk, "rlk")
+        self._need_round_keys(0, d2, fold_round_bits, gk_fold_rounds)
+        self._need_round_keys(1, d2, block_round_bits, gk_block_rounds)
+        for i, key in enumerate(list(gk_fold_rounds) + list(gk_block_rounds)):
+            self._need_key(key, f"Galois key {i}")
+        if cache_ext is not None:
+            _need(cache_ext, 2 * heads * cache_stride_cts * (int(self.sizes.ct_ext_bytes) // 8), "cache_ext")
+        need = int(self.lib.dll.cg_decode_step_workspace_bytes(self.h, heads, n_cts))
+        if need == 0:
+            raise CgError("cryptogen: invalid decode-step shape")
+        if self._ws_step is None or self._ws_step.numel() < need:
+            self._ws_step = None
+            self._ws_step = torch.empty(need, dtype=torch.uint8, device=self.device)
+        self._check(self.lib.dll.cg_decode_step_hoisted(
+            self.h, self.stream, _ptr(q), _ptr(a), _ptr(cache), _ptr(cache_ext), heads, n_cts, cache_stride_cts, d2,
+            tau, _ptr(rows), _ptr(masks), _ptr(rlk), fold_round_bits, self._keys(gk_fold_rounds), block_round_bits,
+            self._keys(gk_block_rounds), _ptr(scores), _ptr(context), _ptr(self._ws_step)))
         return scores, context
 
     def decode_scores_outer(self, q, kcols, heads, d2, masks, rlk, gk_fold, out=None):

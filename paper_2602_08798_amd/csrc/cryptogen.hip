@@ -143,12 +143,12 @@ struct cg_ctx {
 enum KernelId {
     KID_FWD_MULQ = 0, KID_FWD_MULB, KID_FWD_MODUP, KID_FWD_ROWS, KID_FWD_PLAIN,
     KID_INV_TENSOR, KID_INV_U64, KID_INV_MULPLAIN, KID_SCALE, KID_INV_KSINNER, KID_MODDOWN,
-    KID_ADD, KID_SUM_GROUPS, KID_COUNT
+    KID_ADD, KID_SUM_GROUPS, KID_INV_KSSUM, KID_MODDOWN_SUM, KID_COUNT
 };
 static const char *const kKernelNames[KID_COUNT] = {
     "ntt_fwd<mul,q-rows>", "ntt_fwd<mul,aux-rows>", "ntt_fwd<modup>", "ntt_fwd<rows>",
     "ntt_fwd<plain>", "ntt_inv<tensor>", "ntt_inv<u64>", "ntt_inv<mul_plain>", "scale",
-    "ntt_inv<ks_inner>", "moddown", "add", "sum_groups"};
+    "ntt_inv<ks_inner>", "moddown", "add", "sum_groups", "ntt_inv<ks_sum>", "moddown<sum>"};
 
 // Brackets one launch with two events when profiling is on.
 struct ProfScope {
@@ -781,7 +781,7 @@ static int do_rotate_sum(cg_ctx *c, hipStream_t s, const uint64_t *in2, size_t i
     const size_t irows = (size_t)batch * 2 * c->L;
     const double ibytes = LB * ((dig_rows + 2.0 * c->L) * B + 2.0 * dig_rows * n_rot);
     const StInvF64 ist{acc, c->logn};
-#define CG_KSS(D) rc = launch_inv(c, s, irows, LdInvKsInnerSum<D>{dig, T, (int)n_rot, c->logn}, ist, KID_INV_KSINNER, ibytes)
+#define CG_KSS(D) rc = launch_inv(c, s, irows, LdInvKsInnerSum<D>{dig, T, (int)n_rot, c->logn}, ist, KID_INV_KSSUM, ibytes)
     switch (c->dnum) {
     case 1: CG_KSS(1); break;
     case 2: CG_KSS(2); break;
@@ -793,7 +793,8 @@ static int do_rotate_sum(cg_ctx *c, hipStream_t s, const uint64_t *in2, size_t i
 #undef CG_KSS
     CG_TRY(rc);
     ModdownArgs A{acc, out2, out_stride, in2, in_stride, 1u, 1, (int)batch, in2, in_stride};
-    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + 4.0 * c->k) * B, B, moddown_kernel<2>, pw_blocks(c, (size_t)batch * 2) / 2,
+    // reads: the accumulators, the ciphertext, and its c0 once more per rotation (permuted)
+    CG_LAUNCH_PW(KID_MODDOWN_SUM, LB * (2.0 * c->L + (4.0 + n_rot) * c->k) * B, B, moddown_kernel<2>, pw_blocks(c, (size_t)batch * 2) / 2,
                  A, H, c->dc);
     return CG_OK;
 }
@@ -1034,21 +1035,106 @@ static int rotate_add_chain(cg_ctx *c, hipStream_t s, uint64_t *x0, uint64_t *x1
     return CG_OK;
 }
 
+// A folding sum over the subset products of the generators gens[0 .. n_bits) taken in rounds:
+// ceil(n_bits / w) rounds of as even a number of bits as possible, the longer ones first; a round
+// over bits [b0, b0 + c) adds to its input its rotations by the 2^c - 1 products of non-empty
+// subsets of gens[b0 .. b0 + c) (entry m - 1: the generators whose bit is set in m), hoisted, with
+// one mod-down.  keys: the prepared keys of all rounds in that order.
+struct FoldRounds {
+    int n_rounds = 0, n_keys = 0;
+    int first[16], count[16];
+    std::vector<uint32_t> g;
+};
+static bool fold_rounds(const cg_ctx *c, const uint32_t *gens, int n_bits, uint32_t w, FoldRounds &R)
+{
+    if (w < 1 || w > 7 || n_bits < 0 || n_bits > 16) return false;   // 2^7 - 1 rotations fit one launch
+    if (!n_bits) return true;
+    const int rounds = (n_bits + (int)w - 1) / (int)w, lo = n_bits / rounds, extra = n_bits % rounds;
+    int b0 = 0;
+    for (int r = 0; r < rounds; r++) {
+        const int cb = lo + (r < extra ? 1 : 0);
+        R.first[r] = R.n_keys;
+        R.count[r] = (1 << cb) - 1;
+        for (uint32_t m = 1; m < (1u << cb); m++) {
+            uint64_t e = 1;
+            for (int i = 0; i < cb; i++)
+                if ((m >> i) & 1) e = e * gens[b0 + i] % (2u * c->N);
+            R.g.push_back((uint32_t)e);
+        }
+        R.n_keys += R.count[r];
+        b0 += cb;
+    }
+    R.n_rounds = rounds;
+    return true;
+}
+static bool fold_keys_ok(const FoldRounds &R, const void *const *keys)
+{
+    if (R.n_keys && !keys) return false;
+    for (int i = 0; i < R.n_keys; i++)
+        if (!keys[i] || !aligned16(keys[i])) return false;
+    return true;
+}
+// x0 holds the start value; rounds ping-pong between x0 and x1, the last result lands in `out`
+static int fold_chain(cg_ctx *c, hipStream_t s, uint64_t *x0, uint64_t *x1, uint64_t *out, const FoldRounds &R,
+                      const void *const *keys, uint32_t batch, void *ws)
+{
+    uint64_t *cur = x0, *nxt = x1;
+    for (int r = 0; r < R.n_rounds; r++) {
+        uint64_t *dst = (r == R.n_rounds - 1) ? out : nxt;
+        CG_TRY(do_rotate_sum(c, s, cur, 0, (uint32_t)R.count[r], R.g.data() + R.first[r], keys + R.first[r], dst, 0,
+                             batch, ws));
+        nxt = cur;
+        cur = dst;
+    }
+    return CG_OK;
+}
+
+// generators of the two folding sums: the slots of a block (scores), the blocks and the two rows (context)
+static int fold_generators(const cg_ctx *c, uint32_t d2, uint32_t *gs)
+{
+    int n = 0;
+    for (uint32_t sh = 1; sh < d2; sh <<= 1) gs[n++] = pow3_mod(sh, 2u * c->N);
+    return n;
+}
+static int block_generators(const cg_ctx *c, uint32_t d2, uint32_t *gs)
+{
+    int n = 0;
+    for (uint32_t sh = d2; sh <= (uint32_t)c->N / 4; sh <<= 1) gs[n++] = pow3_mod(sh, 2u * c->N);
+    gs[n++] = 2u * c->N - 1;
+    return n;
+}
+
+extern "C" int cg_round_galois(const cg_ctx *c, int which, uint32_t d2, uint32_t round_bits, uint32_t *elts_host,
+                               uint32_t cap, uint32_t *n_out)
+{
+    CG_REQUIRE(c && n_out && (which == 0 || which == 1) && pow2_d(c, d2) && (elts_host || !cap));
+    uint32_t gs[20];
+    const int nb = which ? block_generators(c, d2, gs) : fold_generators(c, d2, gs);
+    FoldRounds R;
+    CG_REQUIRE(fold_rounds(c, gs, nb, round_bits, R));
+    for (uint32_t i = 0; i < cap && i < (uint32_t)R.n_keys; i++) elts_host[i] = R.g[i];
+    *n_out = (uint32_t)R.n_keys;
+    return CG_OK;
+}
+
 // kext != null: the cache in transformed form (kc is then not read)
+// w != 0: the folding sum in rounds of w bits (fold_rounds), gk_fold holding the rounds' keys
 static int scores_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kc, const double *kext,
                        uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
-                       const void *const *gk_fold, uint64_t *out, void *ws)
+                       const void *const *gk_fold, uint64_t *out, void *ws, uint32_t fold_w = 0)
 {
     CG_REQUIRE(c && ptrs_ok({q, kext ? (const void *)kext : (const void *)kc, rlk, out, ws}) && gk_fold &&
                heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
     CG_REQUIRE(cache_stride_cts >= n_cts);
     const uint32_t batch = heads * n_cts;
     CG_REQUIRE(batch_ok(batch));
-    int nrot = 0;
-    uint32_t gs[16];
-    for (uint32_t sh = 1; sh < d2; sh <<= 1) {
-        CG_REQUIRE(gk_fold[nrot] && aligned16(gk_fold[nrot]));
-        gs[nrot++] = pow3_mod(sh, 2u * c->N);
+    uint32_t gs[20];
+    const int nrot = fold_generators(c, d2, gs);
+    FoldRounds R;
+    if (fold_w) {
+        CG_REQUIRE(fold_rounds(c, gs, nrot, fold_w, R) && fold_keys_ok(R, gk_fold));
+    } else {
+        for (int i = 0; i < nrot; i++) CG_REQUIRE(gk_fold[i] && aligned16(gk_fold[i]));
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     Bump w = bump(c, ws);
@@ -1056,6 +1142,7 @@ static int scores_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_
     uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * batch), *xb = w.take<uint64_t>((size_t)2 * c->k * batch);
     CG_TRY(do_mul(c, s, q, kc, d3, batch, n_cts, w.p, 0, n_cts, cache_stride_cts, kext));
     CG_TRY(do_relin(c, s, d3, rlk, xa, batch, w.p));
+    if (fold_w) return fold_chain(c, s, xa, xb, out, R, gk_fold, batch, w.p);
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_fold, nrot, batch, w.p);
 }
 extern "C" int cg_decode_scores(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kc, uint32_t heads,
@@ -1075,18 +1162,21 @@ extern "C" int cg_decode_scores_ext(cg_ctx *c, void *stream, const uint64_t *q, 
 
 static int context_impl(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, const double *vext,
                         uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
-                        const void *const *gk_block, uint64_t *out, void *ws)
+                        const void *const *gk_block, uint64_t *out, void *ws, uint32_t fold_w = 0)
 {
     CG_REQUIRE(c && ptrs_ok({a, vext ? (const void *)vext : (const void *)vc, rlk, out, ws}) && gk_block &&
                heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
     CG_REQUIRE(cache_stride_cts >= n_cts);
     const uint32_t batch = heads * n_cts;
     CG_REQUIRE(batch_ok(batch));
-    int nrot = 0;
     uint32_t gs[20];
-    for (uint32_t sh = d2; sh <= (uint32_t)c->N / 4; sh <<= 1) gs[nrot++] = pow3_mod(sh, 2u * c->N);
-    gs[nrot++] = 2u * c->N - 1;
-    for (int i = 0; i < nrot; i++) CG_REQUIRE(gk_block[i] && aligned16(gk_block[i]));
+    const int nrot = block_generators(c, d2, gs);
+    FoldRounds R;
+    if (fold_w) {
+        CG_REQUIRE(fold_rounds(c, gs, nrot, fold_w, R) && fold_keys_ok(R, gk_block));
+    } else {
+        for (int i = 0; i < nrot; i++) CG_REQUIRE(gk_block[i] && aligned16(gk_block[i]));
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     Bump w = bump(c, ws);
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
@@ -1098,6 +1188,7 @@ static int context_impl(cg_ctx *c, void *stream, const uint64_t *a, const uint64
     CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), (double)batch, sum_groups_kernel,
                  pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)n_cts, rows, c->dc);
     CG_TRY(do_relin(c, s, y, rlk, xa, heads, w.p));
+    if (fold_w) return fold_chain(c, s, xa, xb, out, R, gk_block, heads, w.p);
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, heads, w.p);
 }
 extern "C" int cg_decode_context(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, uint32_t heads,
@@ -1113,6 +1204,25 @@ extern "C" int cg_decode_context_ext(cg_ctx *c, void *stream, const uint64_t *a,
     CG_REQUIRE(vext);
     return context_impl(c, stream, a, nullptr, static_cast<const double *>(vext), heads, n_cts, cache_stride_cts, d2,
                         rlk, gk_block, out, ws);
+}
+
+extern "C" int cg_decode_scores_hoisted(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kc, const void *kext,
+                                        uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2,
+                                        uint32_t round_bits, const void *rlk, const void *const *gk_rounds,
+                                        uint64_t *out, void *ws)
+{
+    CG_REQUIRE(round_bits >= 1);
+    return scores_impl(c, stream, q, kext ? nullptr : kc, static_cast<const double *>(kext), heads, n_cts,
+                       cache_stride_cts, d2, rlk, gk_rounds, out, ws, round_bits);
+}
+extern "C" int cg_decode_context_hoisted(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, const void *vext,
+                                         uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2,
+                                         uint32_t round_bits, const void *rlk, const void *const *gk_rounds,
+                                         uint64_t *out, void *ws)
+{
+    CG_REQUIRE(round_bits >= 1);
+    return context_impl(c, stream, a, vext ? nullptr : vc, static_cast<const double *>(vext), heads, n_cts,
+                        cache_stride_cts, d2, rlk, gk_rounds, out, ws, round_bits);
 }
 
 extern "C" int cg_cache_extend(cg_ctx *c, void *stream, const uint64_t *cts, uint32_t n_groups, uint32_t group_len,
@@ -1136,7 +1246,8 @@ extern "C" size_t cg_decode_step_workspace_bytes(const cg_ctx *c, uint32_t heads
 static int step_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *a, uint64_t *cache, double *ext,
                      uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, uint32_t tau,
                      const uint64_t *rows, const void *masks, const void *rlk, const void *const *gk_fold,
-                     const void *const *gk_block, uint64_t *scores, uint64_t *context, void *ws)
+                     const void *const *gk_block, uint64_t *scores, uint64_t *context, void *ws,
+                     uint32_t fold_w = 0, uint32_t block_w = 0)
 {
     CG_REQUIRE(c && ptrs_ok({q, a, cache, rows, masks, rlk, scores, context, ws}) && gk_fold && gk_block);
     CG_REQUIRE(heads >= 1 && n_cts >= 1 && batch_ok(heads * n_cts) && pow2_d(c, d2) && cache_stride_cts >= n_cts);
@@ -1166,9 +1277,10 @@ static int step_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t 
     if (!append_first) CG_HIP(hipStreamWaitEvent(c->side[1], c->ev_fork, 0));
     // Branches are always joined, also after a failed launch, so that the caller's stream never
     // runs ahead of work this call started.
-    int rc = scores_impl(c, s, q, cache, kext, heads, n_cts, cache_stride_cts, d2, rlk, gk_fold, scores, ws_scores);
+    int rc = scores_impl(c, s, q, cache, kext, heads, n_cts, cache_stride_cts, d2, rlk, gk_fold, scores, ws_scores,
+                         fold_w);
     const int rc1 = context_impl(c, c->side[0], a, vcache, vext, heads, n_cts, cache_stride_cts, d2, rlk, gk_block,
-                                 context, ws_context);
+                                 context, ws_context, block_w);
     if (rc == CG_OK) rc = rc1;
     if (!append_first) {
         const int rc2 = append(c->side[1]);
@@ -1198,6 +1310,19 @@ extern "C" int cg_decode_step_ext(cg_ctx *c, void *stream, const uint64_t *q, co
     CG_REQUIRE(cache_ext && aligned16(cache_ext));
     return step_impl(c, stream, q, a, cache, static_cast<double *>(cache_ext), heads, n_cts, cache_stride_cts, d2, tau,
                      rows, masks, rlk, gk_fold, gk_block, scores, context, ws);
+}
+
+extern "C" int cg_decode_step_hoisted(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *a, uint64_t *cache,
+                                      void *cache_ext, uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts,
+                                      uint32_t d2, uint32_t tau, const uint64_t *rows, const void *masks,
+                                      const void *rlk, uint32_t fold_round_bits, const void *const *gk_fold_rounds,
+                                      uint32_t block_round_bits, const void *const *gk_block_rounds, uint64_t *scores,
+                                      uint64_t *context, void *ws)
+{
+    CG_REQUIRE(fold_round_bits >= 1 && block_round_bits >= 1 && (!cache_ext || aligned16(cache_ext)));
+    return step_impl(c, stream, q, a, cache, static_cast<double *>(cache_ext), heads, n_cts, cache_stride_cts, d2, tau,
+                     rows, masks, rlk, gk_fold_rounds, gk_block_rounds, scores, context, ws, fold_round_bits,
+                     block_round_bits);
 }
 
 extern "C" int cg_decode_scores_outer(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kcols,
@@ -1499,6 +1624,7 @@ static int warm_launch_table(cg_ctx *c)
             const uint32_t gs1[1] = {3};
             const void *const keys1[1] = {f};
             CG_TRY(do_rotate_hoisted(c, s, u, 0, 1, gs1, keys1, u, 1, batch, f));
+            CG_TRY(do_rotate_sum(c, s, u, 0, 1, gs1, keys1, u, 0, batch, f));
         }
         const size_t rows = (size_t)batch * 2 * c->k;
         const LdRowsU64 ld{u, nullptr, c->k, c->logn};

@@ -105,6 +105,35 @@ def test_c4_full_decode_step_every_output():
     compare(got, want, "C4")
 
 
+def test_c4_full_decode_step_in_hoisted_form_every_output():
+    """The step as bench.py's headline runs it: one call, three streams, folding sums in rounds of
+    hoisted rotation sums, the products reading the cache's transformed copy."""
+    say("C4 hoisted")
+    st, want = configs.c4_inputs(), load("C4H")
+    g = Gpu(st["prm"])
+    d = _decode_state(g, st)
+    H, C, S, d2 = st["heads"], st["n_cts"], st["stride"], st["d2"]
+    wf, wb = configs.C4_ROUND_BITS
+    g_fold, g_block = g.ctx.round_galois(0, d2, wf), g.ctx.round_galois(1, d2, wb)
+    raw = configs.galois_keys("C4", sorted(set(g_fold + g_block)))
+    keys = {gal: g.key(k) for gal, k in raw.items()}
+    cache = g.dev(st["cache"])
+    ext = g.ctx.cache_extend(cache, 2 * H, C, S, g.ctx.empty_ext(2 * H * S))
+    scores, context = g.ctx.decode_step_hoisted(g.dev(st["q"]), g.dev(st["a"]), cache, H, C, S, d2, st["tau"],
+                                                g.dev(st["rows"]), d["masks"], d["rlk"], wf, [keys[x] for x in g_fold],
+                                                wb, [keys[x] for x in g_block], cache_ext=ext)
+    scores, context, cache_h = g.host(scores), g.host(context), g.host(cache)
+    got = {}
+    for h in range(H):
+        for c in range(C):
+            got[f"score{h}_{c}"] = digest(scores[h, c])
+        got[f"context{h}"] = digest(context[h])
+    idx = st["tau"] // st["B"]
+    for c in range(2 * H):
+        got[f"cache{c}"] = digest(cache_h[c * S + idx])
+    compare(got, want, "C4H")
+
+
 def test_c3_prefill_appends_diagonals_compaction_and_context():
     say("C3")
     st, want = configs.c3_inputs(), load("C3")

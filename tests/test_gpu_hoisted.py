@@ -116,3 +116,146 @@ def test_cpvm_with_hoisted_token_copies_matches_oracle(name, d1, d2, units):
     for u in range(units):
         want = attention.cpvm_hoisted(env.orc, x, list(polys[u * C:(u + 1) * C]), raw, d2)
         assert np.array_equal(got[u], want), (name, d1, d2, u)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C5"])
+def test_rotation_sum_matches_oracle(name):
+    """One, three and seven rotations summed under one mod-down; a batch that spans several
+    workgroups with a ragged tail; zero coefficients; the identity among the elements."""
+    env = _env(name)
+    n = env.n
+    gs = [pow(3, 1, 2 * n), pow(3, 64, 2 * n), 2 * n - 1, (2 * n - 1) * pow(3, 5, 2 * n) % (2 * n), 1, 2 * n - 3,
+          pow(3, 7, 2 * n)]
+    keys = [env.key(900 + i) for i in range(len(gs))]
+    batch = 5
+    x = env.cts(97, batch)
+    x[1, :, :, ::3] = 0
+    xd = env.dev(x)
+    for n_rot in (1, 3, 7):
+        say(f"rotate_sum_hoisted {name}: batch {batch}, {n_rot} rotations")
+        got = env.host(env.ctx.rotate_sum_hoisted(xd, gs[:n_rot], [k[1] for k in keys[:n_rot]], batch))
+        raws = {g: keys[i][0] for i, g in enumerate(gs[:n_rot])}
+        for b in range(batch):
+            assert np.array_equal(got[b], env.orc.rotate_sum_hoisted(x[b], gs[:n_rot], raws)), (name, n_rot, b)
+
+
+def test_rotation_sum_of_a_long_series_and_invalid_arguments():
+    from paper_2602_08798_amd.binding import CgError
+    env = _env("C1")
+    n = env.n
+    n_rot = 128                                                             # the most one call takes
+    gs = [pow(3, 1 + i, 2 * n) for i in range(n_rot)]
+    keys = [env.key(950 + i % 3) for i in range(n_rot)]
+    x = env.cts(98, 2)
+    xd = env.dev(x)
+    say(f"rotate_sum_hoisted C1: 2 x {n_rot} rotations")
+    got = env.host(env.ctx.rotate_sum_hoisted(xd, gs, [k[1] for k in keys], 2))
+    want = env.orc.rotate_sum_hoisted(x[1], gs, {g: keys[i][0] for i, g in enumerate(gs)})
+    assert np.array_equal(got[1], want)
+    with pytest.raises(CgError):
+        env.ctx.rotate_sum_hoisted(xd, gs + [3], [k[1] for k in keys] + [keys[0][1]], 2)   # 129 rotations
+    with pytest.raises(CgError):
+        env.ctx.rotate_sum_hoisted(xd, [2], [keys[0][1]], 2)                # even Galois element
+    with pytest.raises(CgError):
+        env.ctx.rotate_sum_hoisted(xd, [3], [keys[0][1]], 2, out=xd)        # output over the input
+    with pytest.raises(CgError):
+        env.ctx.rotate_sum_hoisted(xd, [], [], 2)                           # an empty series
+
+
+def _round_keys(env, which, d2, w, seed):
+    """Galois elements of all rounds as the library orders them, checked against the oracle's own
+    list; -> (elements, raw keys by element, prepared keys in order)."""
+    from oracle import attention
+    n = env.n
+    gens = attention.block_generators(n, d2) if which else attention.fold_generators(n, d2)
+    elts = env.ctx.round_galois(which, d2, w)
+    assert elts == [e for r in attention.round_galois(n, gens, w) for e in r], (which, d2, w)
+    keys = {g: env.key(seed + i % 5) for i, g in enumerate(sorted(set(elts)))}
+    return elts, {g: keys[g][0] for g in keys}, [keys[g][1] for g in elts]
+
+
+@pytest.mark.parametrize("name,w_fold,w_block", [("C1", 2, 3), ("C2", 3, 4), ("C5", 2, 2), ("C1", 1, 1), ("C1", 6, 7)])
+def test_decode_products_with_folding_sums_in_rounds_match_oracle(name, w_fold, w_block):
+    from oracle import attention
+    env = _env(name)
+    heads, n_cts, d2 = 2, 2, 64
+    say(f"decode_scores_hoisted / decode_context_hoisted {name}: rounds of {w_fold} / {w_block} bits")
+    raw_rlk, rlk = env.key(70)
+    _, raw_f, dev_f = _round_keys(env, 0, d2, w_fold, 1100)
+    _, raw_b, dev_b = _round_keys(env, 1, d2, w_block, 1200)
+    q, kc = env.cts(71, heads), env.cts(72, heads * n_cts)
+    got = env.host(env.ctx.decode_scores_hoisted(env.dev(q), env.dev(kc), heads, n_cts, d2, w_fold, rlk, dev_f))
+    ext = env.ctx.cache_extend(env.dev(kc), heads, n_cts, n_cts, env.ctx.empty_ext(heads * n_cts))
+    got_ext = env.host(env.ctx.decode_scores_hoisted(env.dev(q), None, heads, n_cts, d2, w_fold, rlk, dev_f, kext=ext))
+    for h in range(heads):
+        for c in range(n_cts):
+            want = attention.decode_scores_hoisted(env.orc, q[h], kc[h * n_cts + c], raw_rlk, raw_f, d2, w_fold)
+            assert np.array_equal(got[h, c], want), (name, h, c)
+            assert np.array_equal(got_ext[h, c], want), (name, h, c, "transformed cache")
+    a, vc = env.cts(81, heads * n_cts), env.cts(82, heads * n_cts)
+    got = env.host(env.ctx.decode_context_hoisted(env.dev(a), env.dev(vc), heads, n_cts, d2, w_block, rlk, dev_b))
+    ext = env.ctx.cache_extend(env.dev(vc), heads, n_cts, n_cts, env.ctx.empty_ext(heads * n_cts))
+    got_ext = env.host(env.ctx.decode_context_hoisted(env.dev(a), None, heads, n_cts, d2, w_block, rlk, dev_b, vext=ext))
+    for h in range(heads):
+        sl = slice(h * n_cts, (h + 1) * n_cts)
+        want = attention.decode_context_hoisted(env.orc, list(a[sl]), list(vc[sl]), raw_rlk, raw_b, d2, w_block)
+        assert np.array_equal(got[h], want), (name, h)
+        assert np.array_equal(got_ext[h], want), (name, h, "transformed cache")
+
+
+@pytest.mark.parametrize("name,with_copy", [("C1", False), ("C2", True)])
+def test_decode_step_with_folding_sums_in_rounds_matches_oracle(name, with_copy):
+    """The one-call step (three streams) in its hoisted form, with and without the cache's
+    transformed copy: the appended cache, every score ciphertext and the context."""
+    from oracle import attention
+    from paper_2602_08798_amd.binding import CgError, CgSizeError
+    env = _env(name)
+    n = env.n
+    heads, n_cts, stride, d2, w_fold, w_block = 3, 2, 3, 64, 2, 3
+    B = n // d2
+    raw_rlk, rlk = env.key(70)
+    _, raw_f, dev_f = _round_keys(env, 0, d2, w_fold, 1100)
+    _, raw_b, dev_b = _round_keys(env, 1, d2, w_block, 1200)
+    rng = np.random.default_rng(11)
+    taus = (B + 5, 2 * B + 1)                       # appended inside the products' range, then outside it
+    masks_pt = np.zeros((6, n), dtype=np.uint64)
+    for t in taus:
+        masks_pt[t % B] = rng.integers(0, env.prm.t, n, dtype=np.uint64)
+    masks = env.ctx.plain_prepare(env.dev(masks_pt))
+    cache = env.cts(640, 2 * heads * stride)
+    want_cache = cache.copy()
+    dcache = env.dev(cache)
+    ext = None
+    if with_copy:
+        ext = env.ctx.cache_extend(dcache, 2 * heads, stride, stride, env.ctx.empty_ext(2 * heads * stride))
+    for tau in taus:
+        idx, blk = divmod(tau, B)
+        say(f"decode_step_hoisted {name}: token {tau}, transformed copy {with_copy}")
+        q, a, rows = env.cts(650 + tau, heads), env.cts(660 + tau, heads * n_cts), env.cts(670 + tau, 2 * heads)
+        scores, context = env.ctx.decode_step_hoisted(env.dev(q), env.dev(a), dcache, heads, n_cts, stride, d2, tau,
+                                                      env.dev(rows), masks, rlk, w_fold, dev_f, w_block, dev_b,
+                                                      cache_ext=ext)
+        for c in range(2 * heads):
+            masked = env.orc.mul_plain(rows[c], masks_pt[blk])
+            want_cache[c * stride + idx] = env.orc.add(want_cache[c * stride + idx], masked)
+        assert np.array_equal(env.host(dcache), want_cache), tau
+        scores, context = env.host(scores), env.host(context)
+        for h in range(heads):
+            for c in range(n_cts):
+                w = attention.decode_scores_hoisted(env.orc, q[h], want_cache[h * stride + c], raw_rlk, raw_f, d2, w_fold)
+                assert np.array_equal(scores[h, c], w), (tau, h, c)
+            vs = want_cache[(heads + h) * stride:(heads + h) * stride + n_cts]
+            w = attention.decode_context_hoisted(env.orc, list(a[h * n_cts:(h + 1) * n_cts]), list(vs), raw_rlk, raw_b,
+                                                 d2, w_block)
+            assert np.array_equal(context[h], w), (tau, h)
+    # wrong key counts and round sizes are refused before any launch
+    q, a, rows = env.dev(env.cts(1, heads)), env.dev(env.cts(2, heads * n_cts)), env.dev(env.cts(3, 2 * heads))
+    with pytest.raises(CgSizeError):
+        env.ctx.decode_step_hoisted(q, a, dcache, heads, n_cts, stride, d2, 0, rows, masks, rlk, w_fold, dev_f[:-1],
+                                    w_block, dev_b, cache_ext=ext)
+    with pytest.raises(CgError):
+        env.ctx.decode_step_hoisted(q, a, dcache, heads, n_cts, stride, d2, 0, rows, masks, rlk, 8, dev_f, w_block, dev_b,
+                                    cache_ext=ext)
+    with pytest.raises(CgError):
+        env.ctx.round_galois(0, d2, 0)
+    assert np.array_equal(env.host(dcache), want_cache)

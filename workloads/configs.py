@@ -33,6 +33,15 @@ def _keys(prm, seed, label, gals):
     return {g: pseudo_switch_key(Stream(seed, label, i), qp, prm.n, prm.dnum) for i, g in enumerate(gals)}
 
 
+def galois_keys(name: str, gals, label: int = 9):
+    """Stand-in switching keys for arbitrary Galois elements of configuration `name`, one seeded draw
+    per element (the stream is labelled by the element itself, so whoever asks for element g gets
+    the same key whatever list it came in)."""
+    w, prm = WORKLOADS[name], PRESETS[name]
+    qp = list(prm.q) + list(prm.p)
+    return {int(g): pseudo_switch_key(Stream(w.seed, label, int(g)), qp, prm.n, prm.dnum) for g in gals}
+
+
 def _masks(prm, seed, count):
     rng = np.random.default_rng(seed)
     return rng.integers(0, prm.t, (count, prm.n), dtype=np.uint64)
@@ -71,6 +80,11 @@ def c2_inputs():
 def c4_inputs():
     """Full decode step at 512-token context, 12 heads, N = 8192."""
     return decode_inputs("C4", heads=12, context=512)
+
+
+# bits per round of the scores' and the context's folding sums when the C4 step is run in its
+# hoisted form (rounds of 3 rotations for the scores; of 7, 3 and 3 for the context)
+C4_ROUND_BITS = (2, 3)
 
 
 def c3_inputs(heads: int = 12, d2: int = 64):
