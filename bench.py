@@ -13,8 +13,8 @@ step is timed as one call in four forms, K steps each: cg_decode_step (plain
 cache), cg_decode_step_ext (the products read a transformed copy of the cache,
 which the step keeps up to date), and cg_decode_step_hoisted without and with
 that copy (the same products with both folding sums regrouped into rounds of
-hoisted rotation sums: 3 + 3 dependent key switches after the
-relinearisations instead of 6 + 7, for 9 + 13 rotation keys instead of 6 + 7;
+hoisted rotation sums: 2 + 3 dependent key switches after the
+relinearisations instead of 6 + 7, for 14 + 13 rotation keys instead of 6 + 7;
 the results decrypt to the same slots and each form is checked against the
 oracle's definition of that form).  The fastest is the headline `value`, the
 others are listed beside it.  --serial times three calls in sequence instead

@@ -548,6 +548,23 @@ static unsigned pw_blocks(const cg_ctx *c, size_t rows) { return (unsigned)((row
         CG_TRY(rc_pw_);                                                                                \
     } while (0)
 
+// mod-down of a summed series of rotations, one output row per workgroup
+static int launch_moddown_sum(cg_ctx *c, hipStream_t s, double bytes, size_t batch, const ModdownArgs &A,
+                              const ModdownHoist &H)
+{
+    if (c->dry) return CG_OK;
+    ProfScope ps(c, s, KID_MODDOWN_SUM, bytes, (double)batch);
+    const dim3 block(1024);
+    const size_t rows = batch * 2 * c->k;
+    const DevConst *dc = c->dc;
+    switch (c->logn) {
+    case 12: return launch_kernel(moddown_sum_kernel<12>, dim3((unsigned)(rows * moddown_sum_split<12>())), block, s, A, H, dc);
+    case 13: return launch_kernel(moddown_sum_kernel<13>, dim3((unsigned)(rows * moddown_sum_split<13>())), block, s, A, H, dc);
+    case 14: return launch_kernel(moddown_sum_kernel<14>, dim3((unsigned)(rows * moddown_sum_split<14>())), block, s, A, H, dc);
+    default: return CG_EINVAL;
+    }
+}
+
 // Every polynomial named by src -> its transform over the k ciphertext primes and the l auxiliary
 // primes (centred lift), rows dst[poly][k+l][N], lazy.
 static int transform_ext(cg_ctx *c, hipStream_t s, const MulSrc &src, size_t polys, double *dst)
@@ -650,7 +667,7 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     CG_TRY(rc);
     ModdownArgs A{acc, out2, out_stride, add, add_stride, galois_inv, accumulate, (int)batch, acc_add, acc_stride};
     const double add_rows = !add ? 0.0 : (galois_inv ? c->k + (accumulate ? 2.0 * c->k : 0.0) : 2.0 * c->k);
-    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, B, moddown_kernel<0>,
+    CG_LAUNCH_PW(KID_MODDOWN, LB * (2.0 * c->L + add_rows + 2.0 * c->k) * B, B, moddown_kernel<false>,
                  pw_blocks(c, (size_t)batch * 2) / 2, A, ModdownHoist{}, c->dc);
     return CG_OK;
 }
@@ -740,7 +757,7 @@ static int do_rotate_hoisted(cg_ctx *c, hipStream_t s, const uint64_t *in2, size
         // galois != 0 marks the rotation form; the element itself comes from the table
         ModdownArgs A{acc, out2 + (size_t)i0 * ct2, ct2, in2, in_stride, 1u, 0, (int)units, in2, in_stride};
         CG_LAUNCH_PW(KID_MODDOWN, LB * ((2.0 * c->L + 2.0 * c->k) * units + c->k * B), (double)units,
-                     moddown_kernel<1>, pw_blocks(c, units * 2) / 2, A, H, c->dc);
+                     moddown_kernel<true>, pw_blocks(c, units * 2) / 2, A, H, c->dc);
     }
     return CG_OK;
 }
@@ -793,10 +810,8 @@ static int do_rotate_sum(cg_ctx *c, hipStream_t s, const uint64_t *in2, size_t i
 #undef CG_KSS
     CG_TRY(rc);
     ModdownArgs A{acc, out2, out_stride, in2, in_stride, 1u, 1, (int)batch, in2, in_stride};
-    // reads: the accumulators, the ciphertext, and its c0 once more per rotation (permuted)
-    CG_LAUNCH_PW(KID_MODDOWN_SUM, LB * (2.0 * c->L + (4.0 + n_rot) * c->k) * B, B, moddown_kernel<2>, pw_blocks(c, (size_t)batch * 2) / 2,
-                 A, H, c->dc);
-    return CG_OK;
+    // reads: the accumulators and the ciphertext (the permuted reads of c0 come from LDS)
+    return launch_moddown_sum(c, s, LB * (2.0 * c->L + 4.0 * c->k) * B, batch, A, H);
 }
 
 static int do_add(cg_ctx *c, hipStream_t s, const uint64_t *a, const uint64_t *b, uint64_t *out, size_t rows)

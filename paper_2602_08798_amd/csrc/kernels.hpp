@@ -1161,13 +1161,13 @@ struct ModdownArgs {
 // HOIST: the units are the rotations of a series, unit u = i * rot_batch + b being rotation i of
 // ciphertext b: its Galois element comes from the table, its addend is ciphertext b and its output
 // ciphertext b * out_per_b + i.
-// HOIST == 2: the units are ciphertexts, acc holds the summed accumulators of n_sum rotations of
-// each, and the output is ciphertext b + sum_i (sigma_{g_i}(c0 of b), 0) + u.
+// n_sum: rotations whose accumulators were summed (moddown_sum_kernel).
+template <int LOGN> constexpr int moddown_sum_split() { return (1 << LOGN) / 2048 >= 4 ? 4 : (1 << LOGN) / 2048; }
 struct ModdownHoist {
     uint32_t ginv[MAXROT];
     int rot_batch, out_per_b, n_sum;
 };
-template <int HOIST>
+template <bool HOIST>
 __global__ void __launch_bounds__(PW_THREADS)
 moddown_kernel(ModdownArgs A, ModdownHoist H, const DevConst *__restrict__ C)
 {
@@ -1184,7 +1184,7 @@ moddown_kernel(ModdownArgs A, ModdownHoist H, const DevConst *__restrict__ C)
     if (bc >= A.batch * 2) return;
     const int c = bc & 1;
     int b = bc >> 1, bo = b;       // addend index, output index
-    if (HOIST == 1) {
+    if (HOIST) {
         const int i = b / H.rot_batch;
         b -= i * H.rot_batch;
         bo = b * H.out_per_b + i;
@@ -1228,24 +1228,7 @@ moddown_kernel(ModdownArgs A, ModdownHoist H, const DevConst *__restrict__ C)
                 const double ri = horner(C->p2q, C, dg[e2], i, false);
                 v[e2] = canon(mulmod(red(ai - ri, mq), C->Pinv_q[i], mq), mq);
             }
-            if constexpr (HOIST == 2) {
-                const uint64_t *ad = A.add + (size_t)b * A.add_stride;
-                if (c == 0)
-                    for (int r = 0; r < H.n_sum; r++) {
-                        const uint32_t gi = H.ginv[r];
-#pragma unroll
-                        for (int e2 = 0; e2 < 2; e2++) {
-                            const uint32_t e = ((uint32_t)(n + e2) * gi) & (2 * N - 1);
-                            const bool ng = e >= (uint32_t)N;
-                            double w = u64_to_f64(ad[((size_t)i << logn) + (ng ? e - N : e)]);
-                            if (ng) w = (w == 0.0) ? 0.0 : mq.p - w;
-                            v[e2] = addmod_canon(v[e2], w, mq);
-                        }
-                    }
-                const ulonglong2 w2 = *reinterpret_cast<const ulonglong2 *>(ad + ((size_t)(c * k + i) << logn) + n);
-                v[0] = addmod_canon(v[0], u64_to_f64(w2.x), mq);
-                v[1] = addmod_canon(v[1], u64_to_f64(w2.y), mq);
-            } else if (A.add) {
+            if (A.add) {
                 const uint64_t *ad = A.add + (size_t)b * A.add_stride;
                 if (A.galois) {
                     if (c == 0) {
@@ -1271,6 +1254,110 @@ moddown_kernel(ModdownArgs A, ModdownHoist H, const DevConst *__restrict__ C)
             }
             *reinterpret_cast<ulonglong2 *>(o + ((size_t)i << logn)) = make_ulonglong2(f64_to_u64(v[0]), f64_to_u64(v[1]));
         }
+}
+
+// Mod-down of a summed series of rotations (acc holds the summed accumulators of the H.n_sum
+// rotations of ciphertext b), one output row per workgroup: block -> (ciphertext b, component c,
+// ciphertext prime i), the prime running fastest.
+//   out[b][c][i] = in[b][c][i] + u_{c,i} + [c = 0] sum_r sigma_r(c0)_i
+// The Galois maps read c0 at the indices n g_r^-1 mod 2N, a different cache line for every lane;
+// the workgroup brings its input row into LDS with coalesced loads and takes the permuted
+// coefficients (and the un-permuted addend) from there.  Base conversion as in moddown_kernel,
+// for the one prime of the row; the special-prime rows are read by the k workgroups of a
+// (ciphertext, component), neighbours on one XCD.
+template <int LOGN>
+__global__ void __launch_bounds__(1024, (LOGN <= 13 ? 8 : 4))
+moddown_sum_kernel(ModdownArgs A, ModdownHoist H, const DevConst *__restrict__ C)
+{
+    // a row is shared by SPLIT workgroups: each parks the whole input row in LDS and produces
+    // N / SPLIT of the outputs (SPLIT x k workgroups per ciphertext and component)
+    constexpr int N = 1 << LOGN, SPLIT = moddown_sum_split<LOGN>(), ROWP = N / 2048, PAIRS = ROWP / SPLIT;
+    static_assert(PAIRS >= 1, "at least one pair of outputs per thread");
+    __shared__ double row[N];
+    const int k = C->k, nsp = C->nsp, L = C->L, tid = threadIdx.x;
+    const int blk = xcd_row((int)blockIdx.x, (int)gridDim.x, k * SPLIT);
+    const int part = blk % SPLIT, i = (blk / SPLIT) % k, bc = blk / (SPLIT * k), c = bc & 1, b = bc >> 1;
+    const ModD mq = C->mod[i];
+    const uint64_t *in = A.add + (size_t)b * A.add_stride + ((size_t)(c * k + i) << LOGN);   // row i of c_c
+    const double *acc = A.acc + (((size_t)bc * L) << LOGN);
+    uint64_t *o = A.out + (size_t)b * A.out_stride + ((size_t)(c * k + i) << LOGN);
+    // the input row (component 1: only the part this workgroup produces), and the accumulator
+    // operands of the thread's first pairs, are requested before anything waits
+    auto pair_index = [&](int j) { return 2 * (tid + 1024 * (part * PAIRS + j)); };
+    if (c == 0) {
+        ulonglong2 all[ROWP];
+#pragma unroll
+        for (int j = 0; j < ROWP; j++) all[j] = *reinterpret_cast<const ulonglong2 *>(in + 2 * (tid + 1024 * j));
+#pragma unroll
+        for (int j = 0; j < ROWP; j++)
+            *reinterpret_cast<double2 *>(row + 2 * (tid + 1024 * j)) =
+                make_double2(u64_to_f64(all[j].x), u64_to_f64(all[j].y));
+    } else {
+#pragma unroll
+        for (int j = 0; j < PAIRS; j++) {
+            const ulonglong2 w = *reinterpret_cast<const ulonglong2 *>(in + pair_index(j));
+            *reinterpret_cast<double2 *>(row + pair_index(j)) = make_double2(u64_to_f64(w.x), u64_to_f64(w.y));
+        }
+    }
+    constexpr int PB = PAIRS < 2 ? PAIRS : 2;
+    double2 xs[PB][2], as[PB];
+    auto request = [&](int j0) {
+#pragma unroll
+        for (int j = 0; j < PB; j++) {
+            const int n = pair_index(j0 + j);
+#pragma unroll
+            for (int s = 0; s < 2; s++)
+                if (s < nsp) xs[j][s] = *reinterpret_cast<const double2 *>(acc + ((size_t)(k + s) << LOGN) + n);
+            as[j] = *reinterpret_cast<const double2 *>(acc + ((size_t)i << LOGN) + n);
+        }
+    };
+    request(0);
+    if (c == 0) __syncthreads();     // component 1 reads back only its own elements
+#pragma unroll
+    for (int j0 = 0; j0 < PAIRS; j0 += PB) {
+        double v[PB][2];
+#pragma unroll
+        for (int j = 0; j < PB; j++) {
+            double xp[2][MAXS], dg[2][MAXS];
+#pragma unroll
+            for (int s = 0; s < 2; s++)
+                if (s < nsp) {
+                    const ModD mp = C->mod[k + s];
+                    xp[0][s] = addmod_canon(canon(xs[j][s].x, mp), C->halfP[k + s], mp);
+                    xp[1][s] = addmod_canon(canon(xs[j][s].y, mp), C->halfP[k + s], mp);
+                }
+            garner<false>(C->p2q, C, xp[0], dg[0]);
+            garner<false>(C->p2q, C, xp[1], dg[1]);
+            const double ain[2] = {as[j].x, as[j].y};
+#pragma unroll
+            for (int e2 = 0; e2 < 2; e2++) {
+                const double ai = addmod_canon(canon(ain[e2], mq), C->halfP[i], mq);
+                const double ri = horner(C->p2q, C, dg[e2], i, false);
+                v[j][e2] = canon(mulmod(red(ai - ri, mq), C->Pinv_q[i], mq), mq);
+            }
+        }
+        if (j0 + PB < PAIRS) request(j0 + PB);     // the next pairs' operands travel during the LDS reads
+#pragma unroll
+        for (int j = 0; j < PB; j++) {
+            const int n = pair_index(j0 + j);
+            if (c == 0)
+                for (int r = 0; r < H.n_sum; r++) {
+                    const uint32_t gi = H.ginv[r];
+#pragma unroll
+                    for (int e2 = 0; e2 < 2; e2++) {
+                        const uint32_t e = ((uint32_t)(n + e2) * gi) & (2 * N - 1);
+                        const bool ng = e >= (uint32_t)N;
+                        double w = row[ng ? e - N : e];
+                        if (ng) w = (w == 0.0) ? 0.0 : mq.p - w;
+                        v[j][e2] = addmod_canon(v[j][e2], w, mq);
+                    }
+                }
+            const double2 own = *reinterpret_cast<const double2 *>(row + n);
+            v[j][0] = addmod_canon(v[j][0], own.x, mq);
+            v[j][1] = addmod_canon(v[j][1], own.y, mq);
+            *reinterpret_cast<ulonglong2 *>(o + n) = make_ulonglong2(f64_to_u64(v[j][0]), f64_to_u64(v[j][1]));
+        }
+    }
 }
 
 // out = a + b over `rows` rows of N residues, row w modulo q_(w % k)

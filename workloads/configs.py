@@ -83,8 +83,8 @@ def c4_inputs():
 
 
 # bits per round of the scores' and the context's folding sums when the C4 step is run in its
-# hoisted form (rounds of 3 rotations for the scores; of 7, 3 and 3 for the context)
-C4_ROUND_BITS = (2, 3)
+# hoisted form (two rounds of 7 rotations for the scores; rounds of 7, 3 and 3 for the context)
+C4_ROUND_BITS = (3, 3)
 
 
 def c3_inputs(heads: int = 12, d2: int = 64):
