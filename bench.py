@@ -64,8 +64,10 @@ FP64_LANE_INSTR_PER_ITEM = {
     "ntt_inv<ks_sum> per rotation": 200 * 1024,
     "scale": 373 * 3 * 8192,
     "moddown": 320 * 8192,
-    "moddown<sum>": 320 * 8192,
-    "moddown<sum> per rotation": 18 * 8192,
+    # one thread per pair of coefficients and prime: about 100 outside the rotation loop, 10 per rotation
+    # on the c0 half
+    "moddown<sum>": 100 * 3 * 8192,
+    "moddown<sum> per rotation": 10 * 3 * 4096,
     "sum_groups": 16 * 9 * 8192,
     "add": 6 * 8192,
 }
@@ -296,11 +298,25 @@ def c5_curve(torch, P):
     per = []
     for i in range(st["steps"]):
         per.append(timed(torch, lambda: step(512 + i), 1))
+    # the same steps with the folding sums in rounds of hoisted rotation sums (stand-in keys per element)
+    wf, wb = configs.C4_ROUND_BITS
+    g_fold, g_block = ctx.round_galois(0, d2, wf), ctx.round_galois(1, d2, wb)
+    rk = {g: ctx.ksk_prepare(dev(k)) for g, k in configs.galois_keys("C5", sorted(set(g_fold + g_block))).items()}
+    kf, kb = [rk[g] for g in g_fold], [rk[g] for g in g_block]
+    hstep = lambda tau: ctx.decode_step_hoisted(q, a, cache, H, C, S, d2, tau, rows, masks, rlk, wf, kf, wb, kb,
+                                                scores=scores, context=context)
+    for _ in range(3):
+        hstep(512)
+    per_h = []
+    for i in range(st["steps"]):
+        per_h.append(timed(torch, lambda: hstep(512 + i), 1))
     ctx.close()
     return {"metric": "C5 scaled decode step ms/token (one layer: 16 heads, N=16384, 6+2 primes), "
                       "64 successive steps with cache growth",
             "value": round(float(np.mean(per)), 4), "unit": "ms", "min": round(min(per), 4),
-            "max": round(max(per), 4), "first": round(per[0], 4), "last": round(per[-1], 4)}
+            "max": round(max(per), 4), "first": round(per[0], 4), "last": round(per[-1], 4),
+            "hoisted_rounds": {"round_bits": [wf, wb], "value": round(float(np.mean(per_h)), 4),
+                               "min": round(min(per_h), 4), "max": round(max(per_h), 4)}}
 
 
 def cpvm_layer_us(torch, ws, reps=20):
