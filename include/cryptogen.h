@@ -407,9 +407,11 @@ int cg_prefill_av(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64
  * sigma = 0 and (2N-1) 3^(d2 r) mod 2N for sigma = 1; everything after the copies is unchanged.
  * The outputs decrypt to the same values as the unhoisted calls' but are other ciphertexts (each
  * copy has seen one key switch instead of up to m/2).  gk_copies_dev_host: host array of m - 1
- * device pointers, prepared keys of copies 1 .. m-1 in that order. */
+ * device pointers, prepared keys of copies 1 .. m-1 in that order.  fold_round_bits = 0: the
+ * folding sum as in cg_prefill_qk (gk_fold as there); >= 1: in rounds of that many bits as in
+ * cg_decode_scores_hoisted, gk_fold_dev_host then holding the rounds' keys in its order. */
 int cg_prefill_qk_hoisted(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *k_dev,
-                          uint32_t heads, uint32_t d2, const void *rlk_dev,
+                          uint32_t heads, uint32_t d2, uint32_t fold_round_bits, const void *rlk_dev,
                           const void *const *gk_fold_dev_host, const void *const *gk_copies_dev_host,
                           uint64_t *out_dev, void *ws_dev);
 int cg_prefill_av_hoisted(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *v_dev,
@@ -455,10 +457,14 @@ int cg_cpvm(cg_ctx *ctx, void *stream, const uint64_t *x_dev, const void *diags_
 /* cg_cpvm with the n_diag - 1 rotated copies of the token made as one series of hoisted rotations
  * of the token (copy c = rotate_hoisted(x, 3^c)) instead of the doubling tree: n_diag - 1 keys
  * instead of log2(n_diag), one decomposition instead of n_diag - 1.  gk_copies_dev_host: prepared
- * keys for 3^1, 3^2, ..., 3^(n_diag - 1) (may be NULL when n_diag is 1). */
+ * keys for 3^1, 3^2, ..., 3^(n_diag - 1) (may be NULL when n_diag is 1).  block_round_bits = 0:
+ * the sum over residue classes as in cg_cpvm (gk_block as there); >= 1: in rounds of that many
+ * bits as in cg_decode_context_hoisted, gk_block_dev_host then holding the rounds' keys in its
+ * order (cg_round_galois, which = 1). */
 int cg_cpvm_hoisted(cg_ctx *ctx, void *stream, const uint64_t *x_dev, const void *diags_dev, uint32_t units,
-                    uint32_t n_diag, uint32_t d2, const void *const *gk_copies_dev_host,
-                    const void *const *gk_block_dev_host, uint64_t *out_dev, void *ws_dev);
+                    uint32_t n_diag, uint32_t d2, uint32_t block_round_bits,
+                    const void *const *gk_copies_dev_host, const void *const *gk_block_dev_host,
+                    uint64_t *out_dev, void *ws_dev);
 
 #ifdef __cplusplus
 }

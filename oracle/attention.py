@@ -301,15 +301,19 @@ def rotated_copies_hoisted(orc, ct, gks, d: int):
     return [ct] + orc.rotate_many(ct, gs[1:], gks)
 
 
-def prefill_qk_hoisted(orc, q_ct, k_ct, rlk, gks, d: int):
-    """prefill_qk with the rotated copies of K made by hoisted rotations (same slots, other bits)."""
+def prefill_qk_hoisted(orc, q_ct, k_ct, rlk, gks, d: int, w: int = 0):
+    """prefill_qk with the rotated copies of K made by hoisted rotations (same slots, other bits);
+    w >= 1: the folding sum of every product in rounds of w bits (fold_by_rounds)."""
     n = orc.n
     out = []
     for kk in rotated_copies_hoisted(orc, k_ct, gks, d):
         x = orc.relin(orc.mul(q_ct, kk), rlk)
-        for sh in fold_shifts(d):
-            g = galois_rot(n, sh)
-            x = orc.add(x, orc.rotate(x, g, gks[g]))
+        if w:
+            x = fold_by_rounds(orc, x, fold_generators(n, d), gks, w)
+        else:
+            for sh in fold_shifts(d):
+                g = galois_rot(n, sh)
+                x = orc.add(x, orc.rotate(x, g, gks[g]))
         out.append(x)
     return out
 
@@ -437,18 +441,22 @@ def cpvm(orc, x_ct, diag_polys, gks, d2: int, counts=None):
     return y
 
 
-def cpvm_hoisted(orc, x_ct, diag_polys, gks, d2: int, counts=None):
+def cpvm_hoisted(orc, x_ct, diag_polys, gks, d2: int, counts=None, w: int = 0):
     """cpvm with the C - 1 rotated copies of the token made as one series of hoisted rotations of the
-    token itself (copy c = token rotated by c, key for 3^c) instead of a doubling tree."""
+    token itself (copy c = token rotated by c, key for 3^c) instead of a doubling tree; w >= 1: the
+    sum over residue classes in rounds of w bits (fold_by_rounds)."""
     n = orc.n
     C = len(diag_polys)
     copies = [x_ct] + orc.rotate_many(x_ct, [galois_rot(n, c) for c in range(1, C)], gks)
     y = orc.mul_plain(copies[0], diag_polys[0])
     for c in range(1, C):
         y = orc.add(y, orc.mul_plain(copies[c], diag_polys[c]))
-    gs = [galois_rot(n, sh) for sh in block_shifts(n, d2)] + [galois_swap(n)]
-    for g in gs:
-        y = orc.add(y, orc.rotate(y, g, gks[g]))
+    gs = block_generators(n, d2)
+    if w:
+        y = fold_by_rounds(orc, y, gs, gks, w)
+    else:
+        for g in gs:
+            y = orc.add(y, orc.rotate(y, g, gks[g]))
     if counts is not None:
         counts.update(mul_plain=C, rotate_shared=C - 1, rotate=len(gs))
     return y

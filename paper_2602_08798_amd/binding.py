@@ -78,9 +78,9 @@ class Library:
         d.cg_decode_context_hoisted.argtypes = d.cg_decode_scores_hoisted.argtypes
         d.cg_decode_step_hoisted.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp, vp, u32,
                                              C.POINTER(vp), u32, C.POINTER(vp), vp, vp, vp]
-        d.cg_prefill_qk_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
+        d.cg_prefill_qk_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
         d.cg_prefill_av_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
-        d.cg_cpvm_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, u32, C.POINTER(vp), C.POINTER(vp), vp, vp]
+        d.cg_cpvm_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, C.POINTER(vp), C.POINTER(vp), vp, vp]
         d.cg_mul_relin_static.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32]
         d.cg_static_scratch_bytes.argtypes = []
         d.cg_static_scratch_bytes.restype = C.c_size_t
@@ -580,15 +580,25 @@ class Context:
                                                _ptr(gk_blk), _ptr(gk_swap), _ptr(out), _ptr(ws)))
         return out
 
-    def prefill_qk_hoisted(self, q, k, heads, d2, rlk, gk_fold, gk_copies, out=None):
+    def _need_fold_keys(self, which, d2, round_bits, keys):
+        """Key count of a folding sum: the rounds' keys, or (round_bits = 0) one per generator."""
+        if round_bits:
+            self._need_round_keys(which, d2, round_bits, keys)
+        else:
+            want = len(self.round_galois(which, d2, 1))
+            if len(keys) != want:
+                raise CgSizeError(f"{want} rotation keys needed, {len(keys)} given")
+
+    def prefill_qk_hoisted(self, q, k, heads, d2, rlk, gk_fold, gk_copies, out=None, fold_round_bits=0):
         m = self.n // d2
         out = self.empty_ct(heads, m) if out is None else out
         if len(gk_copies) != m - 1:
             raise CgSizeError(f"{m - 1} copy keys needed, {len(gk_copies)} given")
+        self._need_fold_keys(0, d2, fold_round_bits, gk_fold)
         ws = self.workspace(heads * m)
-        self._check(self.lib.dll.cg_prefill_qk_hoisted(self.h, self.stream, _ptr(q), _ptr(k), heads, d2, _ptr(rlk),
-                                                       self._keys(gk_fold), self._keys(gk_copies), _ptr(out),
-                                                       _ptr(ws)))
+        self._check(self.lib.dll.cg_prefill_qk_hoisted(self.h, self.stream, _ptr(q), _ptr(k), heads, d2,
+                                                       fold_round_bits, _ptr(rlk), self._keys(gk_fold),
+                                                       self._keys(gk_copies), _ptr(out), _ptr(ws)))
         return out
 
     def prefill_av_hoisted(self, a, v, heads, d2, rlk, gk_copies, out=None):
@@ -624,18 +634,22 @@ class Context:
                                          self._keys(gk_block), _ptr(out), _ptr(ws)))
         return out
 
-    def cpvm_hoisted(self, x, diags, units, n_diag, d2, gk_copies, gk_block, out=None):
-        """cpvm with the token's copies made by one series of hoisted rotations (keys for 3^1 .. 3^(n_diag-1))."""
+    def cpvm_hoisted(self, x, diags, units, n_diag, d2, gk_copies, gk_block, out=None, block_round_bits=0):
+        """cpvm with the token's copies made by one series of hoisted rotations (keys for 3^1 .. 3^(n_diag-1));
+        block_round_bits >= 1: the sum over residue classes in rounds (gk_block: the rounds' keys)."""
         out = self.empty_ct(units) if out is None else out
         _need(x, self._cts(1), "x")
         _need(diags, max(0, int(units)) * max(0, int(n_diag)) * self.k * self.n, "diags (prepared)")
         _need(out, self._cts(units), "out")
         for i, key in enumerate(list(gk_copies) + list(gk_block)):
             self._need_key(key, f"Galois key {i}")
+        if len(gk_copies) != max(0, int(n_diag) - 1):
+            raise CgSizeError(f"{int(n_diag) - 1} copy keys needed, {len(gk_copies)} given")
+        self._need_fold_keys(1, d2, block_round_bits, gk_block)
         ws = self.workspace(units + n_diag)
         copies = self._keys(gk_copies) if len(gk_copies) else None
-        self._check(self.lib.dll.cg_cpvm_hoisted(self.h, self.stream, _ptr(x), _ptr(diags), units, n_diag, d2, copies,
-                                                 self._keys(gk_block), _ptr(out), _ptr(ws)))
+        self._check(self.lib.dll.cg_cpvm_hoisted(self.h, self.stream, _ptr(x), _ptr(diags), units, n_diag, d2,
+                                                 block_round_bits, copies, self._keys(gk_block), _ptr(out), _ptr(ws)))
         return out
 
     def profile_begin(self, max_launches=65536):

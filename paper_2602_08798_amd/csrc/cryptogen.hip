@@ -1437,7 +1437,7 @@ static int rotated_copies_hoisted(cg_ctx *c, hipStream_t s, const uint64_t *src,
 // gk_copies != null: the copies of K come from hoisted rotations (gk_blk / gk_swap are then not used)
 static int prefill_qk_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads, uint32_t d2,
                            const void *rlk, const void *const *gk_fold, const void *gk_blk, const void *gk_swap,
-                           const void *const *gk_copies, uint64_t *out, void *ws)
+                           const void *const *gk_copies, uint64_t *out, void *ws, uint32_t fold_w = 0)
 {
     CG_REQUIRE(c && ptrs_ok({q, kk, rlk, out, ws}) && gk_fold && heads >= 1 && pow2_d(c, d2));
     const uint32_t m = (uint32_t)c->N / d2, batch = heads * m;
@@ -1447,11 +1447,13 @@ static int prefill_qk_impl(cg_ctx *c, void *stream, const uint64_t *q, const uin
     } else {
         CG_REQUIRE(ptrs_ok({gk_blk, gk_swap}));
     }
-    int nrot = 0;
-    uint32_t gs[16];
-    for (uint32_t sh = 1; sh < d2; sh <<= 1) {
-        CG_REQUIRE(gk_fold[nrot] && aligned16(gk_fold[nrot]));
-        gs[nrot++] = pow3_mod(sh, 2u * c->N);
+    uint32_t gs[20];
+    const int nrot = fold_generators(c, d2, gs);
+    FoldRounds R;
+    if (fold_w) {
+        CG_REQUIRE(fold_rounds(c, gs, nrot, fold_w, R) && fold_keys_ok(R, gk_fold));
+    } else {
+        for (int i = 0; i < nrot; i++) CG_REQUIRE(gk_fold[i] && aligned16(gk_fold[i]));
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     // kp[h][sigma*H + r]: rotated copies of K, one ciphertext per output unit
@@ -1464,6 +1466,7 @@ static int prefill_qk_impl(cg_ctx *c, void *stream, const uint64_t *q, const uin
     // all heads x m products at once
     CG_TRY(do_mul(c, s, q, kp, d3, batch, m, w.p, 0));
     CG_TRY(do_relin(c, s, d3, rlk, kp, batch, w.p));   // the rotated keys are consumed: reuse as x0
+    if (fold_w) return fold_chain(c, s, kp, xb, out, R, gk_fold, batch, w.p);
     return rotate_add_chain(c, s, kp, xb, out, gs, gk_fold, nrot, batch, w.p);
 }
 extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads,
@@ -1473,11 +1476,12 @@ extern "C" int cg_prefill_qk(cg_ctx *c, void *stream, const uint64_t *q, const u
     return prefill_qk_impl(c, stream, q, kk, heads, d2, rlk, gk_fold, gk_blk, gk_swap, nullptr, out, ws);
 }
 extern "C" int cg_prefill_qk_hoisted(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kk, uint32_t heads,
-                                     uint32_t d2, const void *rlk, const void *const *gk_fold,
-                                     const void *const *gk_copies, uint64_t *out, void *ws)
+                                     uint32_t d2, uint32_t fold_round_bits, const void *rlk,
+                                     const void *const *gk_fold, const void *const *gk_copies, uint64_t *out, void *ws)
 {
     CG_REQUIRE(gk_copies);
-    return prefill_qk_impl(c, stream, q, kk, heads, d2, rlk, gk_fold, nullptr, nullptr, gk_copies, out, ws);
+    return prefill_qk_impl(c, stream, q, kk, heads, d2, rlk, gk_fold, nullptr, nullptr, gk_copies, out, ws,
+                           fold_round_bits);
 }
 
 static int prefill_av_impl(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *v, uint32_t heads, uint32_t d2,
@@ -1565,7 +1569,7 @@ extern "C" int cg_prefill_repack(cg_ctx *c, void *stream, const uint64_t *x, uin
 // itself (copy c by 3^c, key gk_copies[c - 1]) instead of the doubling tree over gk_shift
 static int cpvm_impl(cg_ctx *c, void *stream, const uint64_t *x, const void *diags, uint32_t units, uint32_t n_diag,
                      uint32_t d2, const void *const *gk_shift, const void *const *gk_copies,
-                     const void *const *gk_block, uint64_t *out, void *ws)
+                     const void *const *gk_block, uint64_t *out, void *ws, uint32_t block_w = 0)
 {
     CG_REQUIRE(c && ptrs_ok({x, diags, out, ws}) && gk_block && batch_ok(units) && pow2_d(c, d2));
     CG_REQUIRE(n_diag >= 1 && n_diag <= 64 && (n_diag & (n_diag - 1)) == 0 && n_diag <= d2);
@@ -1577,11 +1581,14 @@ static int cpvm_impl(cg_ctx *c, void *stream, const uint64_t *x, const void *dia
         int levels = 0;
         for (uint32_t sh = 1; sh < n_diag; sh <<= 1, levels++) CG_REQUIRE(gk_shift[levels] && aligned16(gk_shift[levels]));
     }
-    int nrot = 0;
     uint32_t gs[20];
-    for (uint32_t sh = d2; sh <= (uint32_t)c->N / 4; sh <<= 1) gs[nrot++] = pow3_mod(sh, 2u * c->N);
-    gs[nrot++] = 2u * c->N - 1;
-    for (int i = 0; i < nrot; i++) CG_REQUIRE(gk_block[i] && aligned16(gk_block[i]));
+    const int nrot = block_generators(c, d2, gs);
+    FoldRounds R;
+    if (block_w) {
+        CG_REQUIRE(fold_rounds(c, gs, nrot, block_w, R) && fold_keys_ok(R, gk_block));
+    } else {
+        for (int i = 0; i < nrot; i++) CG_REQUIRE(gk_block[i] && aligned16(gk_block[i]));
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t ct2 = (size_t)2 * c->k * c->N;
     const double LB = (double)limb_bytes(c);
@@ -1605,6 +1612,7 @@ static int cpvm_impl(cg_ctx *c, void *stream, const uint64_t *x, const void *dia
     CG_TRY(launch_inv(c, s, rows, LdInvPlainSum{f, static_cast<const double *>(diags), (int)n_diag, c->logn},
                       StInvU64{xa, c->logn}, KID_INV_MULPLAIN,
                       LB * (crows + (double)units * n_diag * c->k + rows)));
+    if (block_w) return fold_chain(c, s, xa, xb, out, R, gk_block, units, w.p);
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, units, w.p);
 }
 extern "C" int cg_cpvm(cg_ctx *c, void *stream, const uint64_t *x, const void *diags, uint32_t units,
@@ -1614,11 +1622,11 @@ extern "C" int cg_cpvm(cg_ctx *c, void *stream, const uint64_t *x, const void *d
     return cpvm_impl(c, stream, x, diags, units, n_diag, d2, gk_shift, nullptr, gk_block, out, ws);
 }
 extern "C" int cg_cpvm_hoisted(cg_ctx *c, void *stream, const uint64_t *x, const void *diags, uint32_t units,
-                               uint32_t n_diag, uint32_t d2, const void *const *gk_copies,
-                               const void *const *gk_block, uint64_t *out, void *ws)
+                               uint32_t n_diag, uint32_t d2, uint32_t block_round_bits,
+                               const void *const *gk_copies, const void *const *gk_block, uint64_t *out, void *ws)
 {
     CG_REQUIRE(n_diag == 1 || gk_copies);
-    return cpvm_impl(c, stream, x, diags, units, n_diag, d2, nullptr, gk_copies, gk_block, out, ws);
+    return cpvm_impl(c, stream, x, diags, units, n_diag, d2, nullptr, gk_copies, gk_block, out, ws, block_round_bits);
 }
 
 // Every transform-kernel instantiation this context can launch, at a batch below and one above the

@@ -185,6 +185,12 @@ def prefill():
     print(f"{'Q K^T with hoisted copies of K':58s} {qk_h:8.2f} ms", flush=True)
     print(f"{'A V with hoisted copies of V':58s} {av_h:8.2f} ms", flush=True)
     print(f"{'prompt attention of one layer, hoisted copies':58s} {part_ms[0] + qk_h + part_ms[2] + av_h:8.2f} ms")
+    # and with the folding sum of every product in rounds of hoisted rotation sums
+    for w in (2, 3):
+        rk = [copies[i % len(copies)] for i in range(len(ctx.round_galois(0, d2, w)))]
+        qk_r = timed(lambda: ctx.prefill_qk_hoisted(q, cache[:H], H, d2, rlk, rk, copies, out=out, fold_round_bits=w))
+        print(f"{'Q K^T, hoisted copies, folding sums in rounds of %d bits' % w:58s} {qk_r:8.2f} ms", flush=True)
+        print(f"{'prompt attention of one layer, that form':58s} {part_ms[0] + qk_r + part_ms[2] + av_h:8.2f} ms")
 
 
 def mulrelin(preset="C2", batches=(12, 24, 48, 96, 192, 384, 768), chunks=(24, 48, 96, 192)):
@@ -255,6 +261,10 @@ def cpvm(preset="C2", d2=64, n_diag=8, heads=12):
     copies = [key() for _ in range(n_diag - 1)]
     us_h = _time(lambda: ctx.cpvm_hoisted(x, diags, units, n_diag, d2, copies, block, out=out), 20)
     print(f"{preset}: the same with the token's {n_diag - 1} copies as one hoisted rotation series: {us_h:8.1f} us", flush=True)
+    for w in (2, 3, 4):
+        rk = [key() for _ in range(len(ctx.round_galois(1, d2, w)))]
+        us_r = _time(lambda: ctx.cpvm_hoisted(x, diags, units, n_diag, d2, copies, rk, out=out, block_round_bits=w), 20)
+        print(f"{preset}: hoisted copies and the sum over residue classes in rounds of {w} bits: {us_r:8.1f} us", flush=True)
 
 
 if __name__ == "__main__":

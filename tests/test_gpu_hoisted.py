@@ -87,6 +87,18 @@ def test_prompt_products_with_hoisted_copies_match_oracle(name, heads, d2):
         want = attention.prefill_qk_hoisted(env.orc, q[h], kk[h], raw_rlk, raws, d2)
         for i, w in enumerate(want):
             assert np.array_equal(got[h, i], w), ("qk", name, h, i)
+    # the folding sums in rounds of 3 bits on top of the hoisted copies (sampled units); the rounds'
+    # elements are 3^e with e < d2, the copies' are 3^(d2 r) or row-swapped: the key tables are disjoint
+    _, raw_f, dev_f = _round_keys(env, 0, d2, 3, 1100)
+    assert not set(copies) & set(raw_f)
+    got = env.host(env.ctx.prefill_qk_hoisted(env.dev(q), env.dev(kk), heads, d2, rlk, dev_f,
+                                              [ckeys[g][1] for g in copies], fold_round_bits=3))
+    rr = {g: ckeys[g][0] for g in copies}
+    rr.update(raw_f)
+    for h in range(heads):
+        want = attention.prefill_qk_hoisted(env.orc, q[h], kk[h], raw_rlk, rr, d2, w=3)
+        for i in (0, 1, m // 2, m - 1):
+            assert np.array_equal(got[h, i], want[i]), ("qk rounds", name, h, i)
     a, v = env.cts(93, heads * m), env.cts(94, heads)
     got = env.host(env.ctx.prefill_av_hoisted(env.dev(a), env.dev(v), heads, d2, rlk, [ckeys[g][1] for g in copies]))
     for h in range(heads):
@@ -116,6 +128,17 @@ def test_cpvm_with_hoisted_token_copies_matches_oracle(name, d1, d2, units):
     for u in range(units):
         want = attention.cpvm_hoisted(env.orc, x, list(polys[u * C:(u + 1) * C]), raw, d2)
         assert np.array_equal(got[u], want), (name, d1, d2, u)
+    # the sum over residue classes in rounds of 3 bits (elements 3^(d2 j) and the row swap: disjoint
+    # from the copies' 3^c, c < C <= d2)
+    _, raw_b, dev_b = _round_keys(env, 1, d2, 3, 1300)
+    assert not set(g_copies) & set(raw_b)
+    got = env.host(env.ctx.cpvm_hoisted(env.dev(x[None]), env.ctx.plain_prepare(env.dev(polys)), units, C, d2,
+                                        [keys[gal][1] for gal in g_copies], dev_b, block_round_bits=3))
+    rr = {gal: keys[gal][0] for gal in g_copies}
+    rr.update(raw_b)
+    for u in range(units):
+        want = attention.cpvm_hoisted(env.orc, x, list(polys[u * C:(u + 1) * C]), rr, d2, w=3)
+        assert np.array_equal(got[u], want), ("rounds", name, d1, d2, u)
 
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C5"])

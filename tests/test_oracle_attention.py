@@ -149,9 +149,10 @@ def test_decode_context_by_rounds_of_hoisted_rotations_is_the_same_weighted_sum(
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
 
 
-@pytest.mark.parametrize("hoisted", [False, True])
+@pytest.mark.parametrize("hoisted", [False, True, 2])
 def test_prefill_generalised_diagonals_on_a_small_ring(hoisted):
-    """Also with the copies of K made by hoisted rotations of K itself: other ciphertexts, same slots."""
+    """Also with the copies of K made by hoisted rotations of K itself, and (2) with the folding sum
+    of every product in rounds of two bits on top: other ciphertexts, same slots."""
     prm = toy_params(8, 3, 1, 1)
     orc = Oracle(prm)
     cl = Client(prm, 64, orc)
@@ -165,8 +166,13 @@ def test_prefill_generalised_diagonals_on_a_small_ring(hoisted):
     if hoisted:
         assert len(set(attention.copy_galois(n, d))) == m and attention.copy_galois(n, d)[0] == 1
         gks.update({g: cl.galois_key(g) for g in attention.copy_galois(n, d)[1:]})
-    fn = attention.prefill_qk_hoisted if hoisted else attention.prefill_qk
-    outs = fn(orc, cl.encrypt_slots(Qm.reshape(-1)), cl.encrypt_slots(Km.reshape(-1)), rlk, gks, d)
+    q_ct, k_ct = cl.encrypt_slots(Qm.reshape(-1)), cl.encrypt_slots(Km.reshape(-1))
+    if hoisted == 2:
+        gks.update({g: cl.galois_key(g) for g in attention.hoisted_fold_galois(n, d, 2, 1) if g not in gks})
+        outs = attention.prefill_qk_hoisted(orc, q_ct, k_ct, rlk, gks, d, w=2)
+        assert not np.array_equal(outs[1], attention.prefill_qk_hoisted(orc, q_ct, k_ct, rlk, gks, d)[1])
+    else:
+        outs = (attention.prefill_qk_hoisted if hoisted else attention.prefill_qk)(orc, q_ct, k_ct, rlk, gks, d)
     assert len(outs) == m
     S = (Qm @ Km.T) % t
     seen = np.zeros((m, m), dtype=bool)
@@ -428,7 +434,7 @@ def test_a_full_cache_ciphertext_stays_far_from_the_refresh_threshold():
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
 
 
-def _cpvm_case(prm, d1, d2, seed, want_shape, hoisted=False):
+def _cpvm_case(prm, d1, d2, seed, want_shape, hoisted=False, rounds=0):
     """Decrypts to x W mod t, tiled with period d2 (the layout the decode scores take a query in)."""
     orc = Oracle(prm)
     cl = Client(prm, seed, orc)
@@ -439,11 +445,16 @@ def _cpvm_case(prm, d1, d2, seed, want_shape, hoisted=False):
     x = attention_activations(g, 1, 1, d1)[0, 0]
     W = attention_activations(g, 1, d1, d2)[0]
     need = attention.cpvm_hoisted_galois(n, C, d2) if hoisted else attention.cpvm_galois(n, C, d2)
+    if rounds:
+        need = sorted(set(need) | set(attention.hoisted_fold_galois(n, d2, 1, rounds)))
     gks = {gal: cl.galois_key(gal) for gal in need}
     diags = [cl.codec.encode(attention.cpvm_weight_values(n, d1, d2, W, c)) for c in range(C)]
     x_ct = cl.encrypt_slots(attention.cpvm_token_values(n, d1, d2, x))
     counts = {}
-    y = (attention.cpvm_hoisted if hoisted else attention.cpvm)(orc, x_ct, diags, gks, d2, counts)
+    if rounds:
+        y = attention.cpvm_hoisted(orc, x_ct, diags, gks, d2, counts, w=rounds)
+    else:
+        y = (attention.cpvm_hoisted if hoisted else attention.cpvm)(orc, x_ct, diags, gks, d2, counts)
     levels = (n // d2).bit_length() - 1
     assert counts == {"mul_plain": C, "rotate_shared": C - 1, "rotate": levels}
     want = (x.astype(object) @ W.astype(object)) % t
@@ -481,6 +492,9 @@ def test_cpvm_with_hoisted_token_copies_on_small_rings():
     """The token's copies as one series of hoisted rotations of the token: same plaintext result."""
     _cpvm_case(toy_params(7, 3, 1, 1), 20, 8, 76, (32, 4, 2), hoisted=True)
     _cpvm_case(toy_params(8, 3, 1, 1), 100, 16, 77, (128, 2, 8), hoisted=True)
+    # and the sum over residue classes in rounds of 2 and 3 bits
+    _cpvm_case(toy_params(7, 3, 1, 1), 20, 8, 76, (32, 4, 2), hoisted=True, rounds=2)
+    _cpvm_case(toy_params(8, 3, 1, 1), 100, 16, 77, (128, 2, 8), hoisted=True, rounds=3)
 
 
 def test_cpvm_at_the_paper_sizes_takes_eight_products_and_seven_rotations_per_matrix():
