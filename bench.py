@@ -334,8 +334,16 @@ def cpvm_layer_us(torch, ws, reps=20):
     fn = lambda: ctx.cpvm(x, diags, units, n_diag, d2, shift, block, out=out)
     fn()
     ms = timed(torch, fn, reps)
+    # the token's copies as one hoisted series and the final sums in rounds of 3 bits (stand-in keys)
+    key = lambda: ctx.ksk_prepare(rnd(lim, ctx.dnum, 2, ctx.L, prm.n))
+    copies = [key() for _ in range(n_diag - 1)]
+    rounds = [key() for _ in range(len(ctx.round_galois(1, d2, 3)))]
+    fh = lambda: ctx.cpvm_hoisted(x, diags, units, n_diag, d2, copies, rounds, out=out, block_round_bits=3)
+    fh()
+    ms_h = timed(torch, fh, reps)
     return {"metric": "decode-step CT x PT projections of one layer (one token x 36 matrices of 768 x 64)",
-            "value": round(ms * 1e3, 1), "unit": "us"}
+            "value": round(ms * 1e3, 1), "unit": "us",
+            "hoisted_copies_and_rounds_of_3_bits": round(ms_h * 1e3, 1)}
 
 
 def cpu_baseline(ws: DecodeStep, hoisted: bool):

@@ -16,7 +16,8 @@ def say(msg):
     sys.stdout.flush()
 
 
-def test_captured_decode_step_replays_to_the_eager_result():
+@pytest.mark.parametrize("hoisted", [False, True], ids=["chains", "rounds"])
+def test_captured_decode_step_replays_to_the_eager_result(hoisted):
     import torch
     import paper_2602_08798_amd as P
     prm = PRESETS["C1"]
@@ -41,6 +42,11 @@ def test_captured_decode_step_replays_to_the_eager_result():
     scores, context = ctx.empty_ct(heads, n_cts), ctx.empty_ct(heads)
     step = lambda: ctx.decode_step(q, a, cache, heads, n_cts, stride, d2, tau, rows, masks, rlk, fold, block,
                                    scores=scores, context=context)
+    if hoisted:                                           # folding sums in rounds of hoisted rotation sums
+        rf = [key(60 + i % 4) for i in range(len(ctx.round_galois(0, d2, 3)))]
+        rb = [key(70 + i % 4) for i in range(len(ctx.round_galois(1, d2, 2)))]
+        step = lambda: ctx.decode_step_hoisted(q, a, cache, heads, n_cts, stride, d2, tau, rows, masks, rlk, 3, rf,
+                                               2, rb, scores=scores, context=context)
     say("eager step")
     step()
     torch.cuda.synchronize()
