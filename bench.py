@@ -15,8 +15,9 @@ which the step keeps up to date), and cg_decode_step_hoisted without and with
 that copy (the same products with both folding sums regrouped into rounds of
 hoisted rotation sums: 2 + 3 dependent key switches after the
 relinearisations instead of 6 + 7, for 14 + 13 rotation keys instead of 6 + 7;
-the results decrypt to the same slots and each form is checked against the
-oracle's definition of that form).  The fastest is the headline `value`, the
+the context's 4 products per head are summed as tensor products and scaled
+once; the results decrypt to the same slots and each form is checked against
+the oracle's definition of that form).  The fastest is the headline `value`, the
 others are listed beside it.  --serial times three calls in sequence instead
 and nothing else (profiling runs; with --hoisted the hoisted calls).
 
@@ -56,6 +57,10 @@ FP64_LANE_INSTR_PER_ITEM = {
     "ntt_fwd<rows>": 472 * 1024,
     "ntt_fwd<plain>": 514 * 1024,
     "ntt_inv<tensor>": 760 * 1024,
+    # tensor products of the n units of a group summed on the way in: 560 outside the loop over the units,
+    # per unit 136 (components 0 and 2) or 232 (component 1), 168 on average
+    "ntt_inv<tensor_sum>": 560 * 1024,
+    "ntt_inv<tensor_sum> per unit": 168 * 1024,
     "ntt_inv<u64>": 616 * 1024,
     "ntt_inv<mul_plain>": 688 * 1024,
     "ntt_inv<ks_inner>": 728 * 1024,
@@ -116,6 +121,7 @@ class DecodeStep:
         # the folding sums in rounds: elements in the library's key order, stand-in keys drawn per element
         # bits per round (scores: 6 bits, context: 7): the measured optimum on MI355X
         self.w_fold, self.w_block = configs.C4_ROUND_BITS
+        self.sum_first = configs.C4_SUM_BEFORE_SCALING
         self.g_fold_rounds = ctx.round_galois(0, self.d2, self.w_fold)
         self.g_block_rounds = ctx.round_galois(1, self.d2, self.w_block)
         self.h_gk_rounds = configs.galois_keys("C4", sorted(set(self.g_fold_rounds + self.g_block_rounds)))
@@ -146,7 +152,8 @@ class DecodeStep:
                                      self.tau, self.rows, self.masks, self.rlk, self.w_fold,
                                      [self.gk_rounds[g] for g in self.g_fold_rounds], self.w_block,
                                      [self.gk_rounds[g] for g in self.g_block_rounds], scores=self.scores,
-                                     context=self.context, cache_ext=self.ext if transformed_cache else None)
+                                     context=self.context, cache_ext=self.ext if transformed_cache else None,
+                                     sum_before_scaling=self.sum_first)
 
     def step_hoisted_plain_cache(self):
         self.step_hoisted(transformed_cache=False)
@@ -158,7 +165,7 @@ class DecodeStep:
                                 cache_stride_cts=self.stride)
         c.decode_context_hoisted(self.a, self.vcache, H, C, self.d2, self.w_block, self.rlk,
                                  [self.gk_rounds[g] for g in self.g_block_rounds], out=self.context,
-                                 cache_stride_cts=self.stride)
+                                 cache_stride_cts=self.stride, sum_before_scaling=self.sum_first)
         c.kv_append(self.cache, self.stride, 2 * H, self.tau, self.rows, self.masks, self.d2)
 
     def round_sizes(self, which):
@@ -186,7 +193,8 @@ class DecodeStep:
     def op_counts(self, hoisted=False):
         H, C = self.heads, self.n_cts
         if hoisted:
-            return {"mul": 2 * H * C, "relin": H * C + H,
+            mul = {"mul": H * C, "tensor_products_summed_before_one_scaling": H * C} if self.sum_first else {"mul": 2 * H * C}
+            return {**mul, "relin": H * C + H,
                     "rotation_sums": H * C * len(self.round_sizes(0)) + H * len(self.round_sizes(1)),
                     "rotate": H * C * len(self.g_fold_rounds) + H * len(self.g_block_rounds), "append": 2 * H}
         return {"mul": 2 * H * C, "relin": H * C + H,
@@ -362,7 +370,7 @@ def cpu_baseline(ws: DecodeStep, hoisted: bool):
         gpu_scores, gpu_context, gpu_cache = (ws.P.to_host(t) for t in (ws.scores, ws.context, ws.cache))
         t0 = time.perf_counter()
         if form_hoisted:
-            want = run_configs.run_c4_hoisted(orc, ws.st, ws.w_fold, ws.w_block, ws.h_gk_rounds)
+            want = run_configs.run_c4_hoisted(orc, ws.st, ws.w_fold, ws.w_block, ws.h_gk_rounds, sum_first=ws.sum_first)
         else:
             want = run_configs.run_c4(orc, ws.st)
         sec = time.perf_counter() - t0
@@ -471,6 +479,8 @@ def main():
             fp64 = s["work_items"] * FP64_LANE_INSTR_PER_ITEM.get(s["name"], 0)
             if s["name"] == "ntt_inv<ks_sum>":
                 fp64 += args.steps * rot_rows * FP64_LANE_INSTR_PER_ITEM["ntt_inv<ks_sum> per rotation"]
+            if s["name"] == "ntt_inv<tensor_sum>":     # its rows each take in the n_cts units of a head
+                fp64 += s["work_items"] * C * FP64_LANE_INSTR_PER_ITEM["ntt_inv<tensor_sum> per unit"]
             if s["name"] == "moddown<sum>":
                 fp64 += args.steps * rot_units * FP64_LANE_INSTR_PER_ITEM["moddown<sum> per rotation"]
             fp64_step += fp64 / args.steps
@@ -523,7 +533,8 @@ def main():
 
     rounds = (f"both folding sums in rounds of hoisted rotation sums ({ws.w_fold} / {ws.w_block} bits per round: "
               f"{len(ws.round_sizes(0))} + {len(ws.round_sizes(1))} dependent key switches after the relinearisations "
-              f"instead of {len(ws.g_fold)} + {len(ws.g_block)})")
+              f"instead of {len(ws.g_fold)} + {len(ws.g_block)})"
+              + ("; the context's products over the cache ciphertexts summed before one scaling" if ws.sum_first else ""))
     launch = {"serial": "three calls in sequence",
               "serial_hoisted": "three calls in sequence, " + rounds,
               "ext": "cg_decode_step_ext: scores, context and append side by side on three streams; the products "

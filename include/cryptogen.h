@@ -131,6 +131,15 @@ int cg_plain_prepare(cg_ctx *ctx, void *stream, const uint64_t *pt_dev, void *pl
 int cg_mul(cg_ctx *ctx, void *stream, const uint64_t *a2_dev, const uint64_t *b2_dev,
            uint64_t *out3_dev, uint32_t batch, uint32_t a_group, void *ws_dev);
 
+/* Sum of products with one scaling (the "accumulated" products of section 4.3 with the rounding
+ * moved behind the sum): out3[g] = round(t/Q * sum_{i < group_len} a[g*group_len+i] (x) b[g*group_len+i])
+ * mod Q, the tensor products (centred lifts, three components) summed over the integers before
+ * the division.  a2_dev, b2_dev: n_groups * group_len ciphertexts each; out3_dev: n_groups
+ * three-component results.  n_groups * group_len <= 65536.
+ * ws_dev: cg_workspace_bytes(ctx, n_groups * group_len) bytes. */
+int cg_mul_sum(cg_ctx *ctx, void *stream, const uint64_t *a2_dev, const uint64_t *b2_dev,
+               uint64_t *out3_dev, uint32_t n_groups, uint32_t group_len, void *ws_dev);
+
 /* Relinearisation: out2 = (d0 + u0, d1 + u1) with u = KeySwitch(d2, rlk):
  *   digit_j = d2 mod Q_j as the integer polynomial with coefficients in [0,Q_j);
  *   A_c = sum_j digit_j * key_{j,c}  mod P Q, coefficients taken in [0,PQ);
@@ -296,7 +305,10 @@ int cg_decode_step(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint6
  * the results decrypt to the same slots; they are other ciphertexts.  1 <= round_bits <= 7.
  * gk_rounds_dev_host: host array of device pointers to the prepared keys of all rounds, round 0's
  * 2^c - 1 keys first.  kext_dev / vext_dev: the cache's transformed form (cg_cache_extend) or
- * NULL; when given, kc_dev / vc_dev is not read and may be NULL.  cg_decode_step_hoisted is
+ * NULL; when given, kc_dev / vc_dev is not read and may be NULL.  sum_before_scaling (0 or 1,
+ * context only): 1 = the n_cts products of a head are summed as tensor products over the integers
+ * and scaled by t/Q once (cg_mul_sum) instead of scaled one by one and added -- one rounding
+ * instead of n_cts, again other bits for the same slots.  cg_decode_step_hoisted is
  * cg_decode_step (cache_ext_dev NULL) or cg_decode_step_ext with both folding sums in rounds.
  * Workspaces as for the calls they replace. */
 /* The Galois elements of all rounds in the order of gk_rounds_dev_host, for the scores' folding
@@ -310,15 +322,15 @@ int cg_decode_scores_hoisted(cg_ctx *ctx, void *stream, const uint64_t *q_dev, c
                              const void *const *gk_rounds_dev_host, uint64_t *out_dev, void *ws_dev);
 int cg_decode_context_hoisted(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *vc_dev,
                               const void *vext_dev, uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts,
-                              uint32_t d2, uint32_t round_bits, const void *rlk_dev,
+                              uint32_t d2, uint32_t round_bits, int sum_before_scaling, const void *rlk_dev,
                               const void *const *gk_rounds_dev_host, uint64_t *out_dev, void *ws_dev);
 int cg_decode_step_hoisted(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *a_dev,
                            uint64_t *cache_dev, void *cache_ext_dev, uint32_t heads, uint32_t n_cts,
                            uint32_t cache_stride_cts, uint32_t d2, uint32_t tau, const uint64_t *rows_dev,
                            const void *masks_dev, const void *rlk_dev, uint32_t fold_round_bits,
                            const void *const *gk_fold_rounds_dev_host, uint32_t block_round_bits,
-                           const void *const *gk_block_rounds_dev_host, uint64_t *scores_dev,
-                           uint64_t *context_dev, void *ws_dev);
+                           int sum_before_scaling, const void *const *gk_block_rounds_dev_host,
+                           uint64_t *scores_dev, uint64_t *context_dev, void *ws_dev);
 
 /* The cache kept in transformed form (an optimisation of the decode scan that leaves every
  * result bit-identical): a ciphertext that is multiplied in many steps -- every cache
@@ -409,13 +421,15 @@ int cg_prefill_av(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64
  * copy has seen one key switch instead of up to m/2).  gk_copies_dev_host: host array of m - 1
  * device pointers, prepared keys of copies 1 .. m-1 in that order.  fold_round_bits = 0: the
  * folding sum as in cg_prefill_qk (gk_fold as there); >= 1: in rounds of that many bits as in
- * cg_decode_scores_hoisted, gk_fold_dev_host then holding the rounds' keys in its order. */
+ * cg_decode_scores_hoisted, gk_fold_dev_host then holding the rounds' keys in its order.
+ * sum_before_scaling (cg_prefill_av_hoisted, 0 or 1): 1 = the m products of a head summed as
+ * tensor products and scaled once (cg_mul_sum) instead of scaled one by one and added. */
 int cg_prefill_qk_hoisted(cg_ctx *ctx, void *stream, const uint64_t *q_dev, const uint64_t *k_dev,
                           uint32_t heads, uint32_t d2, uint32_t fold_round_bits, const void *rlk_dev,
                           const void *const *gk_fold_dev_host, const void *const *gk_copies_dev_host,
                           uint64_t *out_dev, void *ws_dev);
 int cg_prefill_av_hoisted(cg_ctx *ctx, void *stream, const uint64_t *a_dev, const uint64_t *v_dev,
-                          uint32_t heads, uint32_t d2, const void *rlk_dev,
+                          uint32_t heads, uint32_t d2, int sum_before_scaling, const void *rlk_dev,
                           const void *const *gk_copies_dev_host, uint64_t *out_dev, void *ws_dev);
 
 /* Compaction of the m score ciphertexts of cg_prefill_qk, whose useful values sit in slot 0 of

@@ -169,12 +169,17 @@ def decode_scores_hoisted(orc, q_ct, k_ct, rlk, gks, d: int, w: int, counts=None
     return fold_by_rounds(orc, x, fold_generators(orc.n, d), gks, w, counts)
 
 
-def decode_context_hoisted(orc, a_cts, v_cts, rlk, gks, d: int, w: int, counts=None):
-    """decode_context with the sum over blocks (and the two slot rows) taken in rounds of w bits."""
-    y = None
-    for a_ct, v_ct in zip(a_cts, v_cts):
-        prod3 = orc.mul(a_ct, v_ct)
-        y = prod3 if y is None else orc.add(y, prod3)
+def decode_context_hoisted(orc, a_cts, v_cts, rlk, gks, d: int, w: int, counts=None, sum_first: bool = False):
+    """decode_context with the sum over blocks (and the two slot rows) taken in rounds of w bits.
+    sum_first: the products over the cache ciphertexts are summed as tensor products over the
+    integers and scaled by t/Q once (Oracle.mul_sum) instead of scaled one by one and added."""
+    if sum_first:
+        y = orc.mul_sum(list(a_cts), list(v_cts))
+    else:
+        y = None
+        for a_ct, v_ct in zip(a_cts, v_cts):
+            prod3 = orc.mul(a_ct, v_ct)
+            y = prod3 if y is None else orc.add(y, prod3)
     x = orc.relin(y, rlk)
     return fold_by_rounds(orc, x, block_generators(orc.n, d), gks, w, counts)
 
@@ -318,9 +323,12 @@ def prefill_qk_hoisted(orc, q_ct, k_ct, rlk, gks, d: int, w: int = 0):
     return out
 
 
-def prefill_av_hoisted(orc, a_cts, v_ct, rlk, gks, d: int):
-    """prefill_av with the rotated copies of V made by hoisted rotations."""
+def prefill_av_hoisted(orc, a_cts, v_ct, rlk, gks, d: int, sum_first: bool = False):
+    """prefill_av with the rotated copies of V made by hoisted rotations; sum_first: the m products
+    summed as tensor products and scaled once (Oracle.mul_sum)."""
     vs = rotated_copies_hoisted(orc, v_ct, gks, d)
+    if sum_first:
+        return orc.relin(orc.mul_sum(list(a_cts), vs), rlk)
     y = orc.mul(a_cts[0], vs[0])
     for u in range(1, len(vs)):
         y = orc.add(y, orc.mul(a_cts[u], vs[u]))

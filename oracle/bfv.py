@@ -38,6 +38,8 @@ def load_library():
     lib.orc_set_threads.argtypes = [C.c_int]
     lib.orc_add.argtypes = [C.c_void_p, _U64P, _U64P, _U64P, C.c_int]
     lib.orc_mul.argtypes = [C.c_void_p, _U64P, _U64P, _U64P]
+    lib.orc_mul_sum.argtypes = [C.c_void_p, _U64P, _U64P, C.c_int, _U64P]
+    lib.orc_mul_sum.restype = C.c_int
     lib.orc_keyswitch.argtypes = [C.c_void_p, _U64P, _U64P, _U64P]
     lib.orc_relin.argtypes = [C.c_void_p, _U64P, _U64P, _U64P]
     lib.orc_galois_poly.argtypes = [C.c_void_p, _U64P, C.c_uint64, _U64P]
@@ -199,6 +201,17 @@ class Oracle:
         a2, b2 = self._ct(a2, 2), self._ct(b2, 2)
         out = np.empty((3, self.k, self.n), dtype=np.uint64)
         self.lib.orc_mul(self.ctx, _p(a2), _p(b2), _p(out))
+        return out
+
+    def mul_sum(self, a2s, b2s):
+        """round(t/Q * sum_u a_u (x) b_u): the tensor products of the pairs summed over the integers
+        before the one scaling (three components)."""
+        a = np.ascontiguousarray(np.stack([self._ct(x, 2) for x in a2s]))
+        b = np.ascontiguousarray(np.stack([self._ct(x, 2) for x in b2s]))
+        assert len(a) == len(b) >= 1
+        out = np.empty((3, self.k, self.n), dtype=np.uint64)
+        if self.lib.orc_mul_sum(self.ctx, _p(a), _p(b), len(a), _p(out)):
+            raise ValueError("too many products for the oracle's private basis")
         return out
 
     def _key(self, ksk):

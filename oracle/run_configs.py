@@ -58,9 +58,10 @@ def run_c4(orc, st):
     return out
 
 
-def run_c4_hoisted(orc, st, w_fold, w_block, gk_rounds):
+def run_c4_hoisted(orc, st, w_fold, w_block, gk_rounds, sum_first=False):
     """run_c4 with both folding sums taken in rounds of hoisted rotation sums (w_fold / w_block bits
-    per round); gk_rounds: switching keys by Galois element for attention.hoisted_fold_galois."""
+    per round); gk_rounds: switching keys by Galois element for attention.hoisted_fold_galois.
+    sum_first: the context's products over the cache ciphertexts summed before the one scaling."""
     out = {}
     cache = st["cache"].copy()
     H, S, C, d2 = st["heads"], st["stride"], st["n_cts"], st["d2"]
@@ -70,7 +71,8 @@ def run_c4_hoisted(orc, st, w_fold, w_block, gk_rounds):
                                                                    gk_rounds, d2, w_fold)
         v0 = (H + h) * S
         out[f"context{h}"] = attention.decode_context_hoisted(orc, list(st["a"][h * C:(h + 1) * C]),
-                                                              list(cache[v0:v0 + C]), st["rlk"], gk_rounds, d2, w_block)
+                                                              list(cache[v0:v0 + C]), st["rlk"], gk_rounds, d2, w_block,
+                                                              sum_first=sum_first)
     idx, blk = divmod(st["tau"], st["B"])
     for c in range(2 * H):
         masked = orc.mul_plain(st["rows"][c], st["masks"][blk])

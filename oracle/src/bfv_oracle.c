@@ -544,13 +544,13 @@ void orc_add(const orc_ctx *c, const u64 *a, const u64 *b, u64 *out, int ncomp)
             }
 }
 
-/* BFV multiplication without relinearisation: out3 = round(t/Q * (a (x) b)) mod Q */
-void orc_mul(const orc_ctx *c, const u64 *a2, const u64 *b2, u64 *out3)
+/* prod_c += (a (x) b)_c over Z, in the private basis (prod = uint64[3][nm][N]):
+ * e0 = a0 b0, e1 = a0 b1 + a1 b0, e2 = a1 b1, every operand lifted to its centred representative */
+static void add_tensor(const orc_ctx *c, const u64 *a2, const u64 *b2, u64 *prod)
 {
     const int N = c->N, k = c->k, nm = c->cM.n;
     const u64 *polys[4] = {a2, a2 + (size_t)k * N, b2, b2 + (size_t)k * N};
     u64 *lift = (u64 *)malloc(sizeof(u64) * (size_t)4 * nm * N);
-    u64 *prod = (u64 *)malloc(sizeof(u64) * (size_t)3 * nm * N);
     /* centred integer lift of every coefficient, reduced into the private basis */
 #pragma omp parallel for collapse(2) schedule(static)
     for (int pi = 0; pi < 4; pi++)
@@ -563,23 +563,30 @@ void orc_mul(const orc_ctx *c, const u64 *a2, const u64 *b2, u64 *out3)
             for (int j = 0; j < nm; j++)
                 lift[((size_t)pi * nm + j) * N + n] = signed_mod(&mag, neg, c->cM.m[j]);
         }
-    /* e0 = a0 b0, e1 = a0 b1 + a1 b0, e2 = a1 b1 over Z (via the private basis) */
 #pragma omp parallel for schedule(static)
     for (int j = 0; j < nm; j++) {
         u64 m = c->cM.m[j], psi = c->psi_m[j];
         const u64 *a0 = lift + ((size_t)0 * nm + j) * N, *a1 = lift + ((size_t)1 * nm + j) * N;
         const u64 *b0 = lift + ((size_t)2 * nm + j) * N, *b1 = lift + ((size_t)3 * nm + j) * N;
-        u64 *e0 = prod + ((size_t)0 * nm + j) * N, *e1 = prod + ((size_t)1 * nm + j) * N;
-        u64 *e2 = prod + ((size_t)2 * nm + j) * N;
+        u64 *e[3] = {prod + ((size_t)0 * nm + j) * N, prod + ((size_t)1 * nm + j) * N, prod + ((size_t)2 * nm + j) * N};
         u64 *tmp = (u64 *)malloc(sizeof(u64) * (size_t)N);
-        polymul_psi(a0, b0, e0, N, m, psi);
-        polymul_psi(a0, b1, e1, N, m, psi);
+        polymul_psi(a0, b0, tmp, N, m, psi);
+        for (int n = 0; n < N; n++) e[0][n] = addmod(e[0][n], tmp[n], m);
+        polymul_psi(a0, b1, tmp, N, m, psi);
+        for (int n = 0; n < N; n++) e[1][n] = addmod(e[1][n], tmp[n], m);
         polymul_psi(a1, b0, tmp, N, m, psi);
-        for (int n = 0; n < N; n++) e1[n] = addmod(e1[n], tmp[n], m);
-        polymul_psi(a1, b1, e2, N, m, psi);
+        for (int n = 0; n < N; n++) e[1][n] = addmod(e[1][n], tmp[n], m);
+        polymul_psi(a1, b1, tmp, N, m, psi);
+        for (int n = 0; n < N; n++) e[2][n] = addmod(e[2][n], tmp[n], m);
         free(tmp);
     }
-    /* d = round(t * e / Q) mod Q, exactly */
+    free(lift);
+}
+
+/* d = round(t * e / Q) mod Q, exactly, for the three components held in the private basis */
+static void scale_tensor(const orc_ctx *c, const u64 *prod, u64 *out3)
+{
+    const int N = c->N, k = c->k, nm = c->cM.n;
     bn twoQ = c->cQ.M;
     bn_shl1(&twoQ);
 #pragma omp parallel for collapse(2) schedule(static)
@@ -596,8 +603,34 @@ void orc_mul(const orc_ctx *c, const u64 *a2, const u64 *b2, u64 *out3)
             for (int i = 0; i < k; i++)
                 out3[((size_t)cc * k + i) * N + n] = signed_mod(&quo, neg, c->q[i]);
         }
-    free(lift);
+}
+
+/* BFV multiplication without relinearisation: out3 = round(t/Q * (a (x) b)) mod Q */
+void orc_mul(const orc_ctx *c, const u64 *a2, const u64 *b2, u64 *out3)
+{
+    u64 *prod = (u64 *)calloc((size_t)3 * c->cM.n * c->N, sizeof(u64));
+    add_tensor(c, a2, b2, prod);
+    scale_tensor(c, prod, out3);
     free(prod);
+}
+
+/* Sum of n products with ONE scaling: out3 = round(t/Q * sum_u (a_u (x) b_u)) mod Q, the tensor
+ * products summed over Z before the rounding division (a2s, b2s: n ciphertexts back to back).
+ * It decrypts to the sum of the n slot-wise products like the sum of n separately scaled ones, from
+ * which it differs by less than n/2 + 1 per coefficient (one rounding instead of n).  Returns
+ * nonzero when the private basis cannot hold the sum (n N Q^2 must stay below its modulus). */
+int orc_mul_sum(const orc_ctx *c, const u64 *a2s, const u64 *b2s, int n, u64 *out3)
+{
+    const size_t ct = (size_t)2 * c->k * c->N;
+    bn need, tmp;
+    bn_mul(&tmp, &c->cQ.M, &c->cQ.M);
+    bn_mul_u64(&need, &tmp, (u64)c->N * (u64)(n > 0 ? n : 1));
+    if (n < 1 || bn_cmp(&need, &c->cM.M) >= 0) return 1;
+    u64 *prod = (u64 *)calloc((size_t)3 * c->cM.n * c->N, sizeof(u64));
+    for (int u = 0; u < n; u++) add_tensor(c, a2s + u * ct, b2s + u * ct, prod);
+    scale_tensor(c, prod, out3);
+    free(prod);
+    return 0;
 }
 
 /* acc_c += sum_j digit_j * ksk_{j,c} in Z_{PQ}[X]/(X^N+1), residue by residue

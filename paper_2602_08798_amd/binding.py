@@ -24,7 +24,7 @@ _SYMBOLS = [
     "cg_mul_relin_static", "cg_static_scratch_bytes",
     "cg_rotate_hoisted", "cg_prefill_qk_hoisted", "cg_prefill_av_hoisted", "cg_cpvm_hoisted",
     "cg_rotate_sum_hoisted", "cg_round_galois", "cg_decode_scores_hoisted", "cg_decode_context_hoisted",
-    "cg_decode_step_hoisted",
+    "cg_decode_step_hoisted", "cg_mul_sum",
 ]
 
 
@@ -75,11 +75,13 @@ class Library:
         d.cg_rotate_sum_hoisted.argtypes = d.cg_rotate_hoisted.argtypes
         d.cg_round_galois.argtypes = [vp, i32, u32, u32, C.POINTER(u32), u32, C.POINTER(u32)]
         d.cg_decode_scores_hoisted.argtypes = [vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, C.POINTER(vp), vp, vp]
-        d.cg_decode_context_hoisted.argtypes = d.cg_decode_scores_hoisted.argtypes
+        d.cg_decode_context_hoisted.argtypes = [vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, i32, vp, C.POINTER(vp),
+                                                vp, vp]
         d.cg_decode_step_hoisted.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp, vp, u32,
-                                             C.POINTER(vp), u32, C.POINTER(vp), vp, vp, vp]
+                                             C.POINTER(vp), u32, i32, C.POINTER(vp), vp, vp, vp]
+        d.cg_mul_sum.argtypes = [vp, vp, vp, vp, vp, u32, u32, vp]
         d.cg_prefill_qk_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
-        d.cg_prefill_av_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, vp, C.POINTER(vp), vp, vp]
+        d.cg_prefill_av_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, i32, vp, C.POINTER(vp), vp, vp]
         d.cg_cpvm_hoisted.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, C.POINTER(vp), C.POINTER(vp), vp, vp]
         d.cg_mul_relin_static.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32]
         d.cg_static_scratch_bytes.argtypes = []
@@ -260,6 +262,18 @@ class Context:
         ws = self.workspace(batch)
         self._check(self.lib.dll.cg_mul(self.h, self.stream, _ptr(a2), _ptr(b2), _ptr(out), batch,
                                         a_group, _ptr(ws)))
+        return out
+
+    def mul_sum(self, a2, b2, n_groups, group_len, out=None):
+        """out[g] = one scaling of the sum of the group's tensor products (three components)."""
+        batch = max(0, int(n_groups)) * max(0, int(group_len))
+        out = self.empty_ct(n_groups, ncomp=3) if out is None else out
+        _need(a2, self._cts(batch), "a")
+        _need(b2, self._cts(batch), "b")
+        _need(out, self._cts(n_groups, 3), "out")
+        ws = self.workspace(batch)
+        self._check(self.lib.dll.cg_mul_sum(self.h, self.stream, _ptr(a2), _ptr(b2), _ptr(out), n_groups, group_len,
+                                            _ptr(ws)))
         return out
 
     def _need_mul(self, a2, b2, batch, a_group):
@@ -504,7 +518,7 @@ class Context:
         return out
 
     def decode_context_hoisted(self, a, vcache, heads, n_cts, d2, round_bits, rlk, gk_rounds, out=None,
-                               cache_stride_cts=None, vext=None):
+                               cache_stride_cts=None, vext=None, sum_before_scaling=False):
         out = self.empty_ct(heads) if out is None else out
         ws = self.workspace(heads * n_cts)
         stride = n_cts if cache_stride_cts is None else cache_stride_cts
@@ -515,13 +529,13 @@ class Context:
             self._need_products(a, heads * n_cts, vext, int(self.sizes.ct_ext_bytes) // 8, heads, n_cts, stride, out,
                                 heads, rlk, gk_rounds)
         self._check(self.lib.dll.cg_decode_context_hoisted(
-            self.h, self.stream, _ptr(a), _ptr(vcache), _ptr(vext), heads, n_cts, stride, d2, round_bits, _ptr(rlk),
-            self._keys(gk_rounds), _ptr(out), _ptr(ws)))
+            self.h, self.stream, _ptr(a), _ptr(vcache), _ptr(vext), heads, n_cts, stride, d2, round_bits,
+            1 if sum_before_scaling else 0, _ptr(rlk), self._keys(gk_rounds), _ptr(out), _ptr(ws)))
         return out
 
     def decode_step_hoisted(self, q, a, cache, heads, n_cts, cache_stride_cts, d2, tau, rows, masks, rlk,
                             fold_round_bits, gk_fold_rounds, block_round_bits, gk_block_rounds, scores=None,
-                            context=None, cache_ext=None):
+                            context=None, cache_ext=None, sum_before_scaling=False):
         scores = self.empty_ct(heads, n_cts) if scores is None else scores
         context = self.empty_ct(heads) if context is None else context
         ct = 2 * self.k * self.n
@@ -546,7 +560,8 @@ class Context:
         self._check(self.lib.dll.cg_decode_step_hoisted(
             self.h, self.stream, _ptr(q), _ptr(a), _ptr(cache), _ptr(cache_ext), heads, n_cts, cache_stride_cts, d2,
             tau, _ptr(rows), _ptr(masks), _ptr(rlk), fold_round_bits, self._keys(gk_fold_rounds), block_round_bits,
-            self._keys(gk_block_rounds), _ptr(scores), _ptr(context), _ptr(self._ws_step)))
+            1 if sum_before_scaling else 0, self._keys(gk_block_rounds), _ptr(scores), _ptr(context),
+            _ptr(self._ws_step)))
         return scores, context
 
     def decode_scores_outer(self, q, kcols, heads, d2, masks, rlk, gk_fold, out=None):
@@ -601,13 +616,14 @@ class Context:
                                                        self._keys(gk_copies), _ptr(out), _ptr(ws)))
         return out
 
-    def prefill_av_hoisted(self, a, v, heads, d2, rlk, gk_copies, out=None):
+    def prefill_av_hoisted(self, a, v, heads, d2, rlk, gk_copies, out=None, sum_before_scaling=False):
         m = self.n // d2
         out = self.empty_ct(heads) if out is None else out
         if len(gk_copies) != m - 1:
             raise CgSizeError(f"{m - 1} copy keys needed, {len(gk_copies)} given")
         ws = self.workspace(heads * m)
-        self._check(self.lib.dll.cg_prefill_av_hoisted(self.h, self.stream, _ptr(a), _ptr(v), heads, d2, _ptr(rlk),
+        self._check(self.lib.dll.cg_prefill_av_hoisted(self.h, self.stream, _ptr(a), _ptr(v), heads, d2,
+                                                       1 if sum_before_scaling else 0, _ptr(rlk),
                                                        self._keys(gk_copies), _ptr(out), _ptr(ws)))
         return out
 

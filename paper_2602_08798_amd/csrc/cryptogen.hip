@@ -143,12 +143,13 @@ struct cg_ctx {
 enum KernelId {
     KID_FWD_MULQ = 0, KID_FWD_MULB, KID_FWD_MODUP, KID_FWD_ROWS, KID_FWD_PLAIN,
     KID_INV_TENSOR, KID_INV_U64, KID_INV_MULPLAIN, KID_SCALE, KID_INV_KSINNER, KID_MODDOWN,
-    KID_ADD, KID_SUM_GROUPS, KID_INV_KSSUM, KID_MODDOWN_SUM, KID_COUNT
+    KID_ADD, KID_SUM_GROUPS, KID_INV_KSSUM, KID_MODDOWN_SUM, KID_INV_TENSORSUM, KID_COUNT
 };
 static const char *const kKernelNames[KID_COUNT] = {
     "ntt_fwd<mul,q-rows>", "ntt_fwd<mul,aux-rows>", "ntt_fwd<modup>", "ntt_fwd<rows>",
     "ntt_fwd<plain>", "ntt_inv<tensor>", "ntt_inv<u64>", "ntt_inv<mul_plain>", "scale",
-    "ntt_inv<ks_inner>", "moddown", "add", "sum_groups", "ntt_inv<ks_sum>", "moddown<sum>"};
+    "ntt_inv<ks_inner>", "moddown", "add", "sum_groups", "ntt_inv<ks_sum>", "moddown<sum>",
+    "ntt_inv<tensor_sum>"};
 
 // Brackets one launch with two events when profiling is on.
 struct ProfScope {
@@ -589,10 +590,12 @@ static int transform_ext(cg_ctx *c, hipStream_t s, const MulSrc &src, size_t pol
 // b ciphertext of unit u sits at index (u / b_group) * b_stride + u % b_group (b_group = 0: dense)
 static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *b2, uint64_t *out3,
                   uint32_t batch, uint32_t a_group, void *ws, int accumulate, uint32_t b_group = 0,
-                  uint32_t b_stride = 0, const double *b_ext = nullptr)
+                  uint32_t b_stride = 0, const double *b_ext = nullptr, uint32_t sum_group = 0)
 {
     // b_ext: the b operands are already in transformed extended-basis form (cg_cache_extend);
     // only the a operands are transformed here
+    // sum_group: the tensor products of every sum_group consecutive units are summed before the
+    // inverse transform and the scaling; out3 then holds batch / sum_group results
     if (!b_group) { b_group = batch; b_stride = batch; }
     const uint32_t n_a = (batch + a_group - 1) / a_group;
     const size_t polys = 2 * ((size_t)n_a + (b_ext ? 0 : batch));
@@ -603,14 +606,16 @@ static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *
     const MulSrc src{a2, b2, (int)n_a, (int)b_group, (int)b_stride, c->logn, 0};
     CG_TRY(transform_ext(c, s, src, polys, ntt));
     // tensor product fused into the inverse transform's load
-    const size_t rows = (size_t)batch * 3 * c->KL;
-    CG_TRY(launch_inv(c, s, rows,
-                      LdInvTensor{ntt, b_ext, (int)a_group, (int)n_a, (int)b_group, (int)b_stride, c->logn},
-                      StInvF64{tens, c->logn}, KID_INV_TENSOR,
-                      LB * c->KL * (2.0 * ((double)n_a + B) + 3.0 * B)));
-    const double sbytes = LB * (3.0 * c->KL + 3.0 * c->k * (accumulate ? 2 : 1)) * B;
-    const unsigned sblocks = pw_blocks(c, (size_t)batch * 3);
-#define CG_SCALE(K) CG_LAUNCH_PW(KID_SCALE, sbytes, (double)batch, scale_kernel<K>, sblocks, tens, out3, (int)batch * 3, accumulate, c->dc)
+    const LdInvTensor ld{ntt, b_ext, (int)a_group, (int)n_a, (int)b_group, (int)b_stride, c->logn};
+    const uint32_t n_out = sum_group ? batch / sum_group : batch;
+    const size_t rows = (size_t)n_out * 3 * c->KL;
+    const double tbytes = LB * c->KL * (2.0 * ((double)n_a + B) + 3.0 * n_out);
+    if (sum_group) CG_TRY(launch_inv(c, s, rows, LdInvTensorSum{ld, (int)sum_group}, StInvF64{tens, c->logn},
+                                     KID_INV_TENSORSUM, tbytes));
+    else CG_TRY(launch_inv(c, s, rows, ld, StInvF64{tens, c->logn}, KID_INV_TENSOR, tbytes));
+    const double sbytes = LB * (3.0 * c->KL + 3.0 * c->k * (accumulate ? 2 : 1)) * n_out;
+    const unsigned sblocks = pw_blocks(c, (size_t)n_out * 3);
+#define CG_SCALE(K) CG_LAUNCH_PW(KID_SCALE, sbytes, (double)n_out, scale_kernel<K>, sblocks, tens, out3, (int)n_out * 3, accumulate, c->dc)
     switch (c->k) {
     case 1: CG_SCALE(1); break;
     case 2: CG_SCALE(2); break;
@@ -902,6 +907,15 @@ extern "C" int cg_mul(cg_ctx *c, void *stream, const uint64_t *a2, const uint64_
     return do_mul(c, static_cast<hipStream_t>(stream), a2, b2, out3, batch, a_group, ws, 0);
 }
 
+extern "C" int cg_mul_sum(cg_ctx *c, void *stream, const uint64_t *a2, const uint64_t *b2, uint64_t *out3,
+                          uint32_t n_groups, uint32_t group_len, void *ws)
+{
+    CG_REQUIRE(c && ptrs_ok({a2, b2, out3, ws}) && n_groups >= 1 && group_len >= 1);
+    CG_REQUIRE((uint64_t)n_groups * group_len <= (1u << 16));
+    return do_mul(c, static_cast<hipStream_t>(stream), a2, b2, out3, n_groups * group_len, 1, ws, 0, 0, 0, nullptr,
+                  group_len);
+}
+
 extern "C" int cg_relin(cg_ctx *c, void *stream, const uint64_t *in3, const void *rlk, uint64_t *out2,
                         uint32_t batch, void *ws)
 {
@@ -1177,7 +1191,8 @@ extern "C" int cg_decode_scores_ext(cg_ctx *c, void *stream, const uint64_t *q, 
 
 static int context_impl(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, const double *vext,
                         uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, const void *rlk,
-                        const void *const *gk_block, uint64_t *out, void *ws, uint32_t fold_w = 0)
+                        const void *const *gk_block, uint64_t *out, void *ws, uint32_t fold_w = 0,
+                        bool sum_first = false)
 {
     CG_REQUIRE(c && ptrs_ok({a, vext ? (const void *)vext : (const void *)vc, rlk, out, ws}) && gk_block &&
                heads >= 1 && n_cts >= 1 && pow2_d(c, d2));
@@ -1197,11 +1212,16 @@ static int context_impl(cg_ctx *c, void *stream, const uint64_t *a, const uint64
     uint64_t *d3 = w.take<uint64_t>((size_t)3 * c->k * batch);
     uint64_t *y = w.take<uint64_t>((size_t)3 * c->k * heads);
     uint64_t *xa = w.take<uint64_t>((size_t)2 * c->k * heads), *xb = w.take<uint64_t>((size_t)2 * c->k * heads);
-    CG_TRY(do_mul(c, s, a, vc, d3, batch, 1, w.p, 0, n_cts, cache_stride_cts, vext));
-    // y[h] = sum_c d3[h][c]  (three components)
-    const int rows = 3 * c->k;
-    CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), (double)batch, sum_groups_kernel,
-                 pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)n_cts, rows, c->dc);
+    if (sum_first) {
+        // y[h] = one scaling of the sum over c of the tensor products
+        CG_TRY(do_mul(c, s, a, vc, y, batch, 1, w.p, 0, n_cts, cache_stride_cts, vext, n_cts));
+    } else {
+        CG_TRY(do_mul(c, s, a, vc, d3, batch, 1, w.p, 0, n_cts, cache_stride_cts, vext));
+        // y[h] = sum_c d3[h][c]  (three components)
+        const int rows = 3 * c->k;
+        CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), (double)batch, sum_groups_kernel,
+                     pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)n_cts, rows, c->dc);
+    }
     CG_TRY(do_relin(c, s, y, rlk, xa, heads, w.p));
     if (fold_w) return fold_chain(c, s, xa, xb, out, R, gk_block, heads, w.p);
     return rotate_add_chain(c, s, xa, xb, out, gs, gk_block, nrot, heads, w.p);
@@ -1232,12 +1252,12 @@ extern "C" int cg_decode_scores_hoisted(cg_ctx *c, void *stream, const uint64_t 
 }
 extern "C" int cg_decode_context_hoisted(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *vc, const void *vext,
                                          uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2,
-                                         uint32_t round_bits, const void *rlk, const void *const *gk_rounds,
-                                         uint64_t *out, void *ws)
+                                         uint32_t round_bits, int sum_before_scaling, const void *rlk,
+                                         const void *const *gk_rounds, uint64_t *out, void *ws)
 {
-    CG_REQUIRE(round_bits >= 1);
+    CG_REQUIRE(round_bits >= 1 && (sum_before_scaling == 0 || sum_before_scaling == 1));
     return context_impl(c, stream, a, vext ? nullptr : vc, static_cast<const double *>(vext), heads, n_cts,
-                        cache_stride_cts, d2, rlk, gk_rounds, out, ws, round_bits);
+                        cache_stride_cts, d2, rlk, gk_rounds, out, ws, round_bits, sum_before_scaling != 0);
 }
 
 extern "C" int cg_cache_extend(cg_ctx *c, void *stream, const uint64_t *cts, uint32_t n_groups, uint32_t group_len,
@@ -1262,7 +1282,7 @@ static int step_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t 
                      uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts, uint32_t d2, uint32_t tau,
                      const uint64_t *rows, const void *masks, const void *rlk, const void *const *gk_fold,
                      const void *const *gk_block, uint64_t *scores, uint64_t *context, void *ws,
-                     uint32_t fold_w = 0, uint32_t block_w = 0)
+                     uint32_t fold_w = 0, uint32_t block_w = 0, bool sum_first = false)
 {
     CG_REQUIRE(c && ptrs_ok({q, a, cache, rows, masks, rlk, scores, context, ws}) && gk_fold && gk_block);
     CG_REQUIRE(heads >= 1 && n_cts >= 1 && batch_ok(heads * n_cts) && pow2_d(c, d2) && cache_stride_cts >= n_cts);
@@ -1295,7 +1315,7 @@ static int step_impl(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t 
     int rc = scores_impl(c, s, q, cache, kext, heads, n_cts, cache_stride_cts, d2, rlk, gk_fold, scores, ws_scores,
                          fold_w);
     const int rc1 = context_impl(c, c->side[0], a, vcache, vext, heads, n_cts, cache_stride_cts, d2, rlk, gk_block,
-                                 context, ws_context, block_w);
+                                 context, ws_context, block_w, sum_first);
     if (rc == CG_OK) rc = rc1;
     if (!append_first) {
         const int rc2 = append(c->side[1]);
@@ -1331,13 +1351,14 @@ extern "C" int cg_decode_step_hoisted(cg_ctx *c, void *stream, const uint64_t *q
                                       void *cache_ext, uint32_t heads, uint32_t n_cts, uint32_t cache_stride_cts,
                                       uint32_t d2, uint32_t tau, const uint64_t *rows, const void *masks,
                                       const void *rlk, uint32_t fold_round_bits, const void *const *gk_fold_rounds,
-                                      uint32_t block_round_bits, const void *const *gk_block_rounds, uint64_t *scores,
-                                      uint64_t *context, void *ws)
+                                      uint32_t block_round_bits, int sum_before_scaling,
+                                      const void *const *gk_block_rounds, uint64_t *scores, uint64_t *context, void *ws)
 {
     CG_REQUIRE(fold_round_bits >= 1 && block_round_bits >= 1 && (!cache_ext || aligned16(cache_ext)));
+    CG_REQUIRE(sum_before_scaling == 0 || sum_before_scaling == 1);
     return step_impl(c, stream, q, a, cache, static_cast<double *>(cache_ext), heads, n_cts, cache_stride_cts, d2, tau,
                      rows, masks, rlk, gk_fold_rounds, gk_block_rounds, scores, context, ws, fold_round_bits,
-                     block_round_bits);
+                     block_round_bits, sum_before_scaling != 0);
 }
 
 extern "C" int cg_decode_scores_outer(cg_ctx *c, void *stream, const uint64_t *q, const uint64_t *kcols,
@@ -1486,7 +1507,7 @@ extern "C" int cg_prefill_qk_hoisted(cg_ctx *c, void *stream, const uint64_t *q,
 
 static int prefill_av_impl(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *v, uint32_t heads, uint32_t d2,
                            const void *rlk, const void *gk_blk, const void *gk_swap, const void *const *gk_copies,
-                           uint64_t *out, void *ws)
+                           uint64_t *out, void *ws, bool sum_first = false)
 {
     CG_REQUIRE(c && ptrs_ok({a, v, rlk, out, ws}) && heads >= 1 && pow2_d(c, d2));
     const uint32_t m = (uint32_t)c->N / d2, batch = heads * m;
@@ -1503,10 +1524,14 @@ static int prefill_av_impl(cg_ctx *c, void *stream, const uint64_t *a, const uin
     uint64_t *y = w.take<uint64_t>((size_t)3 * c->k * heads);
     if (gk_copies) CG_TRY(rotated_copies_hoisted(c, s, v, heads, d2, gk_copies, vp, w.p));
     else CG_TRY(rotated_copies(c, s, v, heads, d2, gk_blk, gk_swap, vp, w.p));
-    CG_TRY(do_mul(c, s, a, vp, d3, batch, 1, w.p, 0));
-    const int rows = 3 * c->k;
-    CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), (double)batch, sum_groups_kernel,
-                 pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)m, rows, c->dc);
+    if (sum_first) {
+        CG_TRY(do_mul(c, s, a, vp, y, batch, 1, w.p, 0, 0, 0, nullptr, m));
+    } else {
+        CG_TRY(do_mul(c, s, a, vp, d3, batch, 1, w.p, 0));
+        const int rows = 3 * c->k;
+        CG_LAUNCH_PW(KID_SUM_GROUPS, (double)limb_bytes(c) * rows * (batch + heads), (double)batch, sum_groups_kernel,
+                     pw_blocks(c, (size_t)heads * rows), d3, y, (int)heads, (int)m, rows, c->dc);
+    }
     return do_relin(c, s, y, rlk, out, heads, w.p);
 }
 extern "C" int cg_prefill_av(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *v, uint32_t heads,
@@ -1516,11 +1541,12 @@ extern "C" int cg_prefill_av(cg_ctx *c, void *stream, const uint64_t *a, const u
     return prefill_av_impl(c, stream, a, v, heads, d2, rlk, gk_blk, gk_swap, nullptr, out, ws);
 }
 extern "C" int cg_prefill_av_hoisted(cg_ctx *c, void *stream, const uint64_t *a, const uint64_t *v, uint32_t heads,
-                                     uint32_t d2, const void *rlk, const void *const *gk_copies, uint64_t *out,
-                                     void *ws)
+                                     uint32_t d2, int sum_before_scaling, const void *rlk,
+                                     const void *const *gk_copies, uint64_t *out, void *ws)
 {
-    CG_REQUIRE(gk_copies);
-    return prefill_av_impl(c, stream, a, v, heads, d2, rlk, nullptr, nullptr, gk_copies, out, ws);
+    CG_REQUIRE(gk_copies && (sum_before_scaling == 0 || sum_before_scaling == 1));
+    return prefill_av_impl(c, stream, a, v, heads, d2, rlk, nullptr, nullptr, gk_copies, out, ws,
+                           sum_before_scaling != 0);
 }
 
 extern "C" int cg_prefill_repack(cg_ctx *c, void *stream, const uint64_t *x, uint32_t heads, uint32_t d2,
@@ -1641,6 +1667,7 @@ static int warm_launch_table(cg_ctx *c)
     const double LB = 0.0;
     for (uint32_t batch : {1u, 4096u}) {
         CG_TRY(do_mul(c, s, u, u, u, batch, 1, f, 0));
+        CG_TRY(do_mul(c, s, u, u, u, batch, 1, f, 0, 0, 0, nullptr, 1));
         CG_TRY(do_keyswitch(c, s, u, 0, 0, f, u, 0, u, 0, 0, 0, batch, f));
         CG_TRY(do_keyswitch(c, s, u, 0, 3, f, u, 0, u, 0, 3, 1, batch, f));
         {

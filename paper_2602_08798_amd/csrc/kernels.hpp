@@ -1009,6 +1009,34 @@ struct LdInvTensor {
     }
 };
 
+// The tensor products of a group of consecutive units summed before the inverse transform (and so
+// before the one scaling that follows): workgroup -> (group g, prime r, component c); element =
+// sum over the group's units u = g * group + i of the element LdInvTensor forms for u; result row
+// [g][c][r].  Operand addressing as in LdInvTensor.
+struct LdInvTensorSum {
+    static constexpr int kRaw = 4;
+    static constexpr bool kPrefetch = false;
+    LdInvTensor one;
+    int group;
+    __device__ __forceinline__ int prime(int wg, const DevConst *C) const { return (wg / 3) % C->KL; }
+    __device__ __forceinline__ int share(const DevConst *) const { return 3; }
+    __device__ __forceinline__ int out_row(int wg, const DevConst *C) const { return one.out_row(wg, C); }
+    __device__ __forceinline__ int rounds() const { return group; }
+    __device__ __forceinline__ void fetch_round(int wg, int idx, int i, const DevConst *C, uint64_t *raw) const
+    {
+        const int per = 3 * C->KL, g = wg / per;
+        one.fetch((g * group + i) * per + wg % per, idx, C, raw);
+    }
+    __device__ __forceinline__ void fetch(int, int, const DevConst *, uint64_t *) const {}
+    __device__ __forceinline__ double finish(const uint64_t *raw, int wg, int idx, const ModD m, const DevConst *C) const
+    {
+        return one.finish(raw, wg, idx, m, C);     // only wg % 3 matters there
+    }
+    // a unit's term is below 1.2 p (two products of operands reduced to p/2)
+    __device__ __forceinline__ double join(double sum, double term, const ModD m) const { return red(sum, m) + term; }
+};
+template <> struct ld_rounds<LdInvTensorSum> { static constexpr bool value = true; };
+
 // transformed ciphertext row times prepared plaintext row (ct x pt fused into the load):
 // workgroup -> (unit b, comp c, prime i); ciphertext = ctf[b / ct_group], plaintext =
 // plain[(b % p_mod) * pstride + pofs]

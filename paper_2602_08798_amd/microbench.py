@@ -185,6 +185,9 @@ def prefill():
     print(f"{'Q K^T with hoisted copies of K':58s} {qk_h:8.2f} ms", flush=True)
     print(f"{'A V with hoisted copies of V':58s} {av_h:8.2f} ms", flush=True)
     print(f"{'prompt attention of one layer, hoisted copies':58s} {part_ms[0] + qk_h + part_ms[2] + av_h:8.2f} ms")
+    av_s = timed(lambda: ctx.prefill_av_hoisted(a, cache[H:], H, d2, rlk, copies, sum_before_scaling=True))
+    print(f"{'A V, hoisted copies, products summed before one scaling':58s} {av_s:8.2f} ms", flush=True)
+    av_h = av_s
     # and with the folding sum of every product in rounds of hoisted rotation sums
     for w in (2, 3):
         rk = [copies[i % len(copies)] for i in range(len(ctx.round_galois(0, d2, w)))]

@@ -78,6 +78,23 @@ def bf_mul(a2, b2, q, t):
     return out
 
 
+def bf_mul_sum(pairs, q, t):
+    """Sum over the pairs (a2, b2) of the tensor products over the integers, then ONE scaling by t/Q
+    with rounding; returns [3][k][n] residues."""
+    Q = prod(q)
+    n = len(pairs[0][0][0][0])
+    e = [[0] * n for _ in range(3)]
+    for a2, b2 in pairs:
+        a = [[centre(x, Q) for x in ring_from_rns(c, q)] for c in a2]
+        b = [[centre(x, Q) for x in ring_from_rns(c, q)] for c in b2]
+        terms = (negacyclic(a[0], b[0]),
+                 [x + y for x, y in zip(negacyclic(a[0], b[1]), negacyclic(a[1], b[0]))],
+                 negacyclic(a[1], b[1]))
+        for cc in range(3):
+            e[cc] = [x + y for x, y in zip(e[cc], terms[cc])]
+    return [[[round_div(t * x, Q) % m for x in e[cc]] for m in q] for cc in range(3)]
+
+
 def bf_keyswitch(d, ksk, q, p, alpha):
     """Hybrid key switch of d ([k][n]) with ksk ([dnum][2][k+nsp][n]); returns [2][k][n]."""
     k, n = len(q), len(d[0])

@@ -1,7 +1,7 @@
 """Writes tests/golden/digests_<config>.json: SHA-256 of every output ciphertext of the five
 benchmark configurations as computed by the CPU oracle (and by nothing else).
 
-    python -m tests.golden.make_digests C1 C2 C4 C4H    (about a minute)
+    python -m tests.golden.make_digests C1 C2 C4 C4H C4HS    (about a minute)
     python -m tests.golden.make_digests C3              (all 12 heads: tens of minutes)
     python -m tests.golden.make_digests C5              (all 64 steps: about 40 minutes on 8 cores)
 
@@ -36,13 +36,15 @@ def main(names):
             inp = configs.c2_inputs(); out = run_configs.run_c2(Oracle(inp["prm"]), inp); note = "decode scores, 1 head x 1 ciphertext"
         elif name == "C4":
             inp = configs.c4_inputs(); out = run_configs.run_c4(Oracle(inp["prm"]), inp); note = "full decode step, 12 heads, 512-token cache"
-        elif name == "C4H":
+        elif name in ("C4H", "C4HS"):
             from oracle import attention
             inp = configs.c4_inputs()
             wf, wb = configs.C4_ROUND_BITS
             keys = configs.galois_keys("C4", attention.hoisted_fold_galois(inp["prm"].n, inp["d2"], wf, wb))
-            out = run_configs.run_c4_hoisted(Oracle(inp["prm"]), inp, wf, wb, keys)
+            out = run_configs.run_c4_hoisted(Oracle(inp["prm"]), inp, wf, wb, keys, sum_first=name == "C4HS")
             note = f"full decode step, 12 heads, 512-token cache, folding sums in rounds of {wf} / {wb} bits (hoisted rotation sums)"
+            if name == "C4HS":
+                note += ", the context's products over the cache ciphertexts summed before the one scaling"
         elif name == "C3":
             inp = configs.c3_inputs()
             out = run_configs.run_c3(Oracle(inp["prm"]), inp, progress=lambda m: print(m, f"{time.time() - t0:.0f}s", flush=True))
@@ -62,4 +64,4 @@ def main(names):
 
 
 if __name__ == "__main__":
-    main(sys.argv[1:] or ["C1", "C2", "C4", "C4H"])
+    main(sys.argv[1:] or ["C1", "C2", "C4", "C4H", "C4HS"])

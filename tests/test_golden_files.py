@@ -22,9 +22,12 @@ def test_digest_files_cover_every_output_unit():
     assert len(_load("C4H")["digests"]) == 48 + 12 + 24
     assert _load("C4H")["digests"] != _load("C4")["digests"]          # other ciphertexts, same append
     assert all(_load("C4H")["digests"][f"cache{c}"] == _load("C4")["digests"][f"cache{c}"] for c in range(24))
+    # summing the context's products before the scaling changes the contexts and nothing else
+    h, hs = _load("C4H")["digests"], _load("C4HS")["digests"]
+    assert set(h) == set(hs) and all((h[k] != hs[k]) == k.startswith("context") for k in h)
     assert len(_load("C3")["digests"]) == 24 + 12 * (128 + 2 + 1)
     assert len(_load("C5")["digests"]) == 64 * (32 + 16 * 3 + 16)     # all 64 steps
-    for name in ("C1", "C2", "C3", "C4", "C4H", "C5"):
+    for name in ("C1", "C2", "C3", "C4", "C4H", "C4HS", "C5"):
         assert _load(name)["source"].startswith("oracle/ only")
 
 

@@ -105,11 +105,14 @@ def test_c4_full_decode_step_every_output():
     compare(got, want, "C4")
 
 
-def test_c4_full_decode_step_in_hoisted_form_every_output():
+@pytest.mark.parametrize("sum_first", [False, True], ids=["C4H", "C4HS"])
+def test_c4_full_decode_step_in_hoisted_form_every_output(sum_first):
     """The step as bench.py's headline runs it: one call, three streams, folding sums in rounds of
-    hoisted rotation sums, the products reading the cache's transformed copy."""
-    say("C4 hoisted")
-    st, want = configs.c4_inputs(), load("C4H")
+    hoisted rotation sums, the products reading the cache's transformed copy; without and with the
+    context's products summed before their scaling (the headline has them summed)."""
+    name = "C4HS" if sum_first else "C4H"
+    say(name)
+    st, want = configs.c4_inputs(), load(name)
     g = Gpu(st["prm"])
     d = _decode_state(g, st)
     H, C, S, d2 = st["heads"], st["n_cts"], st["stride"], st["d2"]
@@ -121,7 +124,8 @@ def test_c4_full_decode_step_in_hoisted_form_every_output():
     ext = g.ctx.cache_extend(cache, 2 * H, C, S, g.ctx.empty_ext(2 * H * S))
     scores, context = g.ctx.decode_step_hoisted(g.dev(st["q"]), g.dev(st["a"]), cache, H, C, S, d2, st["tau"],
                                                 g.dev(st["rows"]), d["masks"], d["rlk"], wf, [keys[x] for x in g_fold],
-                                                wb, [keys[x] for x in g_block], cache_ext=ext)
+                                                wb, [keys[x] for x in g_block], cache_ext=ext,
+                                                sum_before_scaling=sum_first)
     scores, context, cache_h = g.host(scores), g.host(context), g.host(cache)
     got = {}
     for h in range(H):
@@ -131,7 +135,7 @@ def test_c4_full_decode_step_in_hoisted_form_every_output():
     idx = st["tau"] // st["B"]
     for c in range(2 * H):
         got[f"cache{c}"] = digest(cache_h[c * S + idx])
-    compare(got, want, "C4H")
+    compare(got, want, name)
 
 
 def test_c3_prefill_appends_diagonals_compaction_and_context():

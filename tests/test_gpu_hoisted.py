@@ -104,6 +104,11 @@ def test_prompt_products_with_hoisted_copies_match_oracle(name, heads, d2):
     for h in range(heads):
         want = attention.prefill_av_hoisted(env.orc, list(a[h * m:(h + 1) * m]), v[h], raw_rlk, raws, d2)
         assert np.array_equal(got[h], want), ("av", name, h)
+    got = env.host(env.ctx.prefill_av_hoisted(env.dev(a), env.dev(v), heads, d2, rlk, [ckeys[g][1] for g in copies],
+                                              sum_before_scaling=True))
+    for h in range(heads):
+        want = attention.prefill_av_hoisted(env.orc, list(a[h * m:(h + 1) * m]), v[h], raw_rlk, raws, d2, sum_first=True)
+        assert np.array_equal(got[h], want), ("av, products summed before scaling", name, h)
 
 
 @pytest.mark.parametrize("name,d1,d2,units", [("C1", 1000, 64, 2), ("C2", 768, 64, 3), ("C5", 768, 64, 1)])
@@ -282,3 +287,78 @@ def test_decode_step_with_folding_sums_in_rounds_matches_oracle(name, with_copy)
     with pytest.raises(CgError):
         env.ctx.round_galois(0, d2, 0)
     assert np.array_equal(env.host(dcache), want_cache)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C5"])
+def test_sum_of_products_with_one_scaling_matches_oracle(name):
+    """Groups of 1, 3 and 5 pairs (ragged against the kernel's slices), several groups per launch;
+    extreme residues in one pair; rejected sizes."""
+    from paper_2602_08798_amd.binding import CgError
+    env = _env(name)
+    for n_groups, group_len in ((1, 1), (2, 3), (3, 5)):
+        say(f"mul_sum {name}: {n_groups} groups of {group_len}")
+        batch = n_groups * group_len
+        a, b = env.cts(1400 + batch, batch), env.cts(1500 + batch, batch)
+        for i, m in enumerate(env.prm.q):                      # one pair at the largest residues
+            a[batch - 1, :, i, :] = m - 1
+            b[batch - 1, :, i, :] = m - 1
+        got = env.host(env.ctx.mul_sum(env.dev(a), env.dev(b), n_groups, group_len))
+        for g in range(n_groups):
+            sl = slice(g * group_len, (g + 1) * group_len)
+            assert np.array_equal(got[g], env.orc.mul_sum(list(a[sl]), list(b[sl]))), (name, n_groups, group_len, g)
+    with pytest.raises(CgError):
+        env.ctx.mul_sum(env.dev(a), env.dev(b), 0, 3)
+    with pytest.raises(CgError):
+        env.ctx.mul_sum(env.dev(a), env.dev(b), 3, 0)
+
+
+@pytest.mark.parametrize("name,with_copy", [("C1", True), ("C2", False), ("C5", False)])
+def test_decode_context_and_step_with_products_summed_before_scaling_match_oracle(name, with_copy):
+    from oracle import attention
+    env = _env(name)
+    n = env.n
+    heads, n_cts, stride, d2, w_fold, w_block = 2, 3, 3, 64, 3, 3
+    B = n // d2
+    raw_rlk, rlk = env.key(70)
+    _, raw_f, dev_f = _round_keys(env, 0, d2, w_fold, 1100)
+    _, raw_b, dev_b = _round_keys(env, 1, d2, w_block, 1200)
+    say(f"decode_context_hoisted, products summed before scaling, {name}")
+    a, vc = env.cts(83, heads * n_cts), env.cts(84, heads * n_cts)
+    got = env.host(env.ctx.decode_context_hoisted(env.dev(a), env.dev(vc), heads, n_cts, d2, w_block, rlk, dev_b,
+                                                  sum_before_scaling=True))
+    ext = env.ctx.cache_extend(env.dev(vc), heads, n_cts, n_cts, env.ctx.empty_ext(heads * n_cts))
+    got_ext = env.host(env.ctx.decode_context_hoisted(env.dev(a), None, heads, n_cts, d2, w_block, rlk, dev_b, vext=ext,
+                                                      sum_before_scaling=True))
+    for h in range(heads):
+        sl = slice(h * n_cts, (h + 1) * n_cts)
+        want = attention.decode_context_hoisted(env.orc, list(a[sl]), list(vc[sl]), raw_rlk, raw_b, d2, w_block,
+                                                sum_first=True)
+        assert np.array_equal(got[h], want), (name, h)
+        assert np.array_equal(got_ext[h], want), (name, h, "transformed cache")
+    say(f"decode_step_hoisted, products summed before scaling, {name}, transformed copy {with_copy}")
+    rng = np.random.default_rng(12)
+    tau = 2 * B + 7                                  # appended into the third ciphertext, which the products read
+    masks_pt = np.zeros((8, n), dtype=np.uint64)
+    masks_pt[tau % B] = rng.integers(0, env.prm.t, n, dtype=np.uint64)
+    masks = env.ctx.plain_prepare(env.dev(masks_pt))
+    cache = env.cts(680, 2 * heads * stride)
+    want_cache = cache.copy()
+    dcache = env.dev(cache)
+    cext = env.ctx.cache_extend(dcache, 2 * heads, stride, stride, env.ctx.empty_ext(2 * heads * stride)) if with_copy else None
+    q, rows = env.cts(681, heads), env.cts(682, 2 * heads)
+    scores, context = env.ctx.decode_step_hoisted(env.dev(q), env.dev(a), dcache, heads, n_cts, stride, d2, tau,
+                                                  env.dev(rows), masks, rlk, w_fold, dev_f, w_block, dev_b,
+                                                  cache_ext=cext, sum_before_scaling=True)
+    idx, blk = divmod(tau, B)
+    for c in range(2 * heads):
+        want_cache[c * stride + idx] = env.orc.add(want_cache[c * stride + idx], env.orc.mul_plain(rows[c], masks_pt[blk]))
+    assert np.array_equal(env.host(dcache), want_cache)
+    scores, context = env.host(scores), env.host(context)
+    for h in range(heads):
+        for c in (0, n_cts - 1):
+            w = attention.decode_scores_hoisted(env.orc, q[h], want_cache[h * stride + c], raw_rlk, raw_f, d2, w_fold)
+            assert np.array_equal(scores[h, c], w), (h, c)
+        vs = want_cache[(heads + h) * stride:(heads + h) * stride + n_cts]
+        w = attention.decode_context_hoisted(env.orc, list(a[h * n_cts:(h + 1) * n_cts]), list(vs), raw_rlk, raw_b, d2,
+                                             w_block, sum_first=True)
+        assert np.array_equal(context[h], w), h

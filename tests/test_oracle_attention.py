@@ -127,8 +127,10 @@ def test_decode_scores_by_rounds_of_hoisted_rotations_are_the_same_dot_products(
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
 
 
-@pytest.mark.parametrize("w", [2, 3, 4])
+@pytest.mark.parametrize("w", [2, 3, 4, -3])
 def test_decode_context_by_rounds_of_hoisted_rotations_is_the_same_weighted_sum(w):
+    """w < 0: rounds of -w bits and the cache ciphertexts' products summed before the one scaling."""
+    sum_first, w = w < 0, abs(w)
     prm = PRESETS["C2"]
     orc = Oracle(prm)
     cl = Client(prm, 63, orc)
@@ -142,11 +144,16 @@ def test_decode_context_by_rounds_of_hoisted_rotations_is_the_same_weighted_sum(
     a_cts = [cl.encrypt_slots(np.repeat(a[c * B:(c + 1) * B], d)) for c in range(2)]
     v_cts = [cl.encrypt_slots(V[c * B:(c + 1) * B].reshape(-1)) for c in range(2)]
     counts = {}
-    out = attention.decode_context_hoisted(orc, a_cts, v_cts, rlk, gks, d, w, counts)
+    out = attention.decode_context_hoisted(orc, a_cts, v_cts, rlk, gks, d, w, counts, sum_first=sum_first)
     assert counts == {2: {"rounds": 4, "rotate": 3 + 3 + 3 + 1}, 3: {"rounds": 3, "rotate": 7 + 3 + 3},
                       4: {"rounds": 2, "rotate": 15 + 7}}[w]
     assert np.array_equal(cl.decrypt_slots(out), np.tile((a @ V) % t, B))
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
+    if sum_first:
+        other = attention.decode_context_hoisted(orc, a_cts, v_cts, rlk, gks, d, w)
+        assert not np.array_equal(out, other)
+        # one rounding instead of two: never a smaller budget
+        assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) >= cl.noise_budget_bits(other, cl.decrypt_poly(other)) - 1
 
 
 @pytest.mark.parametrize("hoisted", [False, True, 2])
@@ -273,9 +280,14 @@ def test_prefill_context_is_the_matrix_product_on_a_small_ring(hoisted):
     if hoisted:
         gks.update({g: cl.galois_key(g) for g in attention.copy_galois(n, d)[1:]})
     fn = attention.prefill_av_hoisted if hoisted else attention.prefill_av
-    out = fn(orc, a_cts, cl.encrypt_slots(Vm.reshape(-1)), rlk, gks, d)
+    v_ct = cl.encrypt_slots(Vm.reshape(-1))
+    out = fn(orc, a_cts, v_ct, rlk, gks, d)
     dec = cl.decrypt_slots(out).reshape(m, d)
     assert np.array_equal(dec, (Am @ Vm) % t)
+    if hoisted:     # and with the m products summed before their one scaling: other bits, same rows
+        out2 = attention.prefill_av_hoisted(orc, a_cts, v_ct, rlk, gks, d, sum_first=True)
+        assert not np.array_equal(out2, out)
+        assert np.array_equal(cl.decrypt_slots(out2).reshape(m, d), (Am @ Vm) % t)
 
 
 def _repack_case(log2n, d, seed):

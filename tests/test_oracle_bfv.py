@@ -43,6 +43,38 @@ def test_mul_matches_brute_force(prm):
 
 
 @pytest.mark.parametrize("prm", TOYS, ids=lambda p: f"{p.name}_a{p.alpha}")
+def test_sum_of_products_with_one_scaling_matches_brute_force(prm):
+    """Tensor products summed over the integers before the rounding division: brute force for one,
+    two and five pairs (one of them at the extreme residues); a single pair is the ordinary product;
+    several pairs are NOT the sum of separately scaled products, from which they differ by at most
+    (number of pairs + 1) / 2 per coefficient."""
+    rnd = random.Random(17)
+    orc = Oracle(prm)
+    q, n = list(prm.q), prm.n
+    Q = prod(q)
+    ext = [[[(Q // 2 + s) % m for _ in range(n)] for m in q] for s in (0, 1)]
+    pairs = [([_rand_ring(rnd, q, n) for _ in range(2)], [_rand_ring(rnd, q, n) for _ in range(2)]) for _ in range(4)]
+    pairs.append((ext, ext))
+    arr = lambda x: np.array(x, dtype=np.uint64)
+    for cnt in (1, 2, 5):
+        sel = pairs[-cnt:]
+        got = orc.mul_sum([arr(a) for a, _ in sel], [arr(b) for _, b in sel])
+        assert got.tolist() == bf.bf_mul_sum(sel, q, prm.t)
+        apart = None
+        for a, b in sel:
+            m3 = orc.mul(arr(a), arr(b))
+            apart = m3 if apart is None else orc.add(apart, m3)
+        if cnt == 1:
+            assert np.array_equal(got, apart)
+        else:
+            assert not np.array_equal(got, apart)
+            for c in range(3):
+                x = bf.ring_from_rns(got[c].tolist(), q)
+                y = bf.ring_from_rns(apart[c].tolist(), q)
+                assert max(min((u - v) % Q, (v - u) % Q) for u, v in zip(x, y)) <= (cnt + 1) // 2
+
+
+@pytest.mark.parametrize("prm", TOYS, ids=lambda p: f"{p.name}_a{p.alpha}")
 def test_keyswitch_matches_brute_force(prm):
     rnd = random.Random(12)
     orc = Oracle(prm)

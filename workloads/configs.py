@@ -85,6 +85,8 @@ def c4_inputs():
 # bits per round of the scores' and the context's folding sums when the C4 step is run in its
 # hoisted form (two rounds of 7 rotations for the scores; rounds of 7, 3 and 3 for the context)
 C4_ROUND_BITS = (3, 3)
+# ... and whether the context's products over the cache ciphertexts are summed before the one scaling
+C4_SUM_BEFORE_SCALING = True
 
 
 def c3_inputs(heads: int = 12, d2: int = 64):
