@@ -312,7 +312,8 @@ def c5_curve(torch, P):
     rk = {g: ctx.ksk_prepare(dev(k)) for g, k in configs.galois_keys("C5", sorted(set(g_fold + g_block))).items()}
     kf, kb = [rk[g] for g in g_fold], [rk[g] for g in g_block]
     hstep = lambda tau: ctx.decode_step_hoisted(q, a, cache, H, C, S, d2, tau, rows, masks, rlk, wf, kf, wb, kb,
-                                                scores=scores, context=context)
+                                                scores=scores, context=context,
+                                                sum_before_scaling=configs.C4_SUM_BEFORE_SCALING)
     for _ in range(3):
         hstep(512)
     per_h = []
