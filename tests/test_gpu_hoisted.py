@@ -362,3 +362,42 @@ def test_decode_context_and_step_with_products_summed_before_scaling_match_oracl
         w = attention.decode_context_hoisted(env.orc, list(a[h * n_cts:(h + 1) * n_cts]), list(vs), raw_rlk, raw_b, d2,
                                              w_block, sum_first=True)
         assert np.array_equal(context[h], w), h
+
+
+def test_decode_step_in_rounds_at_the_smallest_and_largest_head_dimension():
+    """d2 = 2 (one fold bit, eleven block bits: rounds of 6 and 5 bits at the widest setting) and
+    d2 = N/4 (ten fold bits, two block bits), one head, tokens at the first and last block."""
+    from oracle import attention
+    env = _env("C1")
+    n = env.n
+    raw_rlk, rlk = env.key(70)
+    for d2, tau, w_fold, w_block in ((2, n // 2 - 1, 1, 7), (n // 4, 3, 7, 2), (n // 4, 4, 4, 1)):
+        B = n // d2
+        say(f"decode_step_hoisted C1: d2 = {d2}, token {tau}, rounds of {w_fold} / {w_block} bits")
+        _, raw_f, dev_f = _round_keys(env, 0, d2, w_fold, 1100)
+        _, raw_b, dev_b = _round_keys(env, 1, d2, w_block, 1200)
+        rng = np.random.default_rng(13 + d2)
+        masks_pt = np.zeros((tau % B + 1, n), dtype=np.uint64)
+        masks_pt[tau % B] = rng.integers(0, env.prm.t, n, dtype=np.uint64)
+        masks = env.ctx.plain_prepare(env.dev(masks_pt))
+        heads, stride = 1, 2
+        idx, blk = divmod(tau, B)
+        n_cts = idx + 1
+        cache = env.cts(690 + d2 + tau, 2 * heads * stride)
+        want_cache = cache.copy()
+        dcache = env.dev(cache)
+        q, a, rows = env.cts(691 + tau, heads), env.cts(692 + tau, heads * n_cts), env.cts(693 + tau, 2 * heads)
+        scores, context = env.ctx.decode_step_hoisted(env.dev(q), env.dev(a), dcache, heads, n_cts, stride, d2, tau,
+                                                      env.dev(rows), masks, rlk, w_fold, dev_f, w_block, dev_b,
+                                                      sum_before_scaling=(n_cts > 1))
+        for c in range(2 * heads):               # the first token of a ciphertext is stored, later ones are added
+            masked = env.orc.mul_plain(rows[c], masks_pt[blk])
+            want_cache[c * stride + idx] = masked if blk == 0 else env.orc.add(want_cache[c * stride + idx], masked)
+        assert np.array_equal(env.host(dcache), want_cache), (d2, tau)
+        scores, context = env.host(scores), env.host(context)
+        for c in range(n_cts):
+            w = attention.decode_scores_hoisted(env.orc, q[0], want_cache[c], raw_rlk, raw_f, d2, w_fold)
+            assert np.array_equal(scores[0, c], w), (d2, tau, c)
+        w = attention.decode_context_hoisted(env.orc, list(a), list(want_cache[stride:stride + n_cts]), raw_rlk, raw_b,
+                                             d2, w_block, sum_first=(n_cts > 1))
+        assert np.array_equal(context[0], w), (d2, tau)
