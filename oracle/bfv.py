@@ -264,8 +264,9 @@ class Oracle:
         """in2 + the sum of its hoisted rotations by every g of gs (keys gks[g]), the key-switch
         accumulators of the series summed before the one division by P."""
         in2 = self._ct(in2, 2)
-        keys = [self._key(gks[g]) for g in gs]
-        assert all(g % 2 == 1 and 0 < g < 2 * self.n for g in gs)
+        # gks: keys by Galois element, or a list with one key per position of gs
+        keys = [self._key(k) for k in gks] if isinstance(gks, (list, tuple)) else [self._key(gks[g]) for g in gs]
+        assert len(keys) == len(gs) and all(g % 2 == 1 and 0 < g < 2 * self.n for g in gs)
         garr = np.asarray(list(gs), dtype=np.uint64)
         kptr = (_U64P * max(1, len(keys)))(*[_p(k) for k in keys])
         out = np.empty_like(in2)

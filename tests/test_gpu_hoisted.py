@@ -401,3 +401,22 @@ def test_decode_step_in_rounds_at_the_smallest_and_largest_head_dimension():
         w = attention.decode_context_hoisted(env.orc, list(a), list(want_cache[stride:stride + n_cts]), raw_rlk, raw_b,
                                              d2, w_block, sum_first=(n_cts > 1))
         assert np.array_equal(context[0], w), (d2, tau)
+
+
+def test_rotation_sums_with_random_series_match_oracle():
+    """Seeded random series: 1 to 20 Galois elements drawn from all odd residues (repeats allowed: the
+    same rotation may enter a sum twice), batches of 1 to 7."""
+    env = _env("C1")
+    n = env.n
+    rng = np.random.default_rng(20260208)
+    pool = [env.key(1000 + i) for i in range(5)]
+    for case in range(6):
+        n_rot, batch = int(rng.integers(1, 21)), int(rng.integers(1, 8))
+        gs = [int(2 * rng.integers(0, n) + 1) for _ in range(n_rot)]
+        which = [int(rng.integers(0, len(pool))) for _ in range(n_rot)]
+        say(f"rotate_sum_hoisted C1 random case {case}: batch {batch}, {n_rot} rotations")
+        x = env.cts(2000 + case, batch)
+        got = env.host(env.ctx.rotate_sum_hoisted(env.dev(x), gs, [pool[w][1] for w in which], batch))
+        for b in (0, batch - 1):
+            want = env.orc.rotate_sum_hoisted(x[b], gs, [pool[w][0] for w in which])
+            assert np.array_equal(got[b], want), (case, b)
