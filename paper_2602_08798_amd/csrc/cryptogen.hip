@@ -628,6 +628,26 @@ static int do_mul(cg_ctx *c, hipStream_t s, const uint64_t *a2, const uint64_t *
     return CG_OK;
 }
 
+// Mod-up of one ring element per unit (src + b*src_stride, Galois map first when galois != 0): the
+// dnum digits extended to the k+nsp primes and transformed, rows dig[b][dnum][k+nsp][N]
+static int launch_modup(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t src_stride, uint32_t galois,
+                        uint32_t batch, double *dig)
+{
+    const size_t nrows = (size_t)batch * c->dnum * c->L;
+    const double mbytes = (double)limb_bytes(c) * (c->k + (double)c->dnum * c->L) * batch;
+    const StF64 st{dig, c->logn};
+#define CG_MODUP(G, A) return launch_fwd(c, s, nrows, LdModup<G, A>{src, src_stride, galois, c->logn}, st, KID_FWD_MODUP, mbytes)
+    switch (c->alpha * 2 + (galois ? 1 : 0)) {
+    case 2: CG_MODUP(false, 1);
+    case 3: CG_MODUP(true, 1);
+    case 4: CG_MODUP(false, 2);
+    case 5: CG_MODUP(true, 2);
+    case 6: CG_MODUP(false, 3);
+    default: CG_MODUP(true, 3);
+    }
+#undef CG_MODUP
+}
+
 // key switch of one ring element per unit (src + b*src_stride), then the final additions
 static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t src_stride, uint32_t galois,
                         const double *key, uint64_t *out2, size_t out_stride, const uint64_t *add, size_t add_stride,
@@ -640,21 +660,8 @@ static int do_keyswitch(cg_ctx *c, hipStream_t s, const uint64_t *src, size_t sr
     double *acc = w.take<double>((size_t)2 * c->L * batch);
     const double LB = (double)limb_bytes(c), B = batch;
     const double dig_rows = (double)c->dnum * c->L;
-    const size_t nrows = (size_t)batch * c->dnum * c->L;
-    const double mbytes = LB * (c->k + dig_rows) * B;
-    const StF64 st{dig, c->logn};
-#define CG_MODUP(G, A) launch_fwd(c, s, nrows, LdModup<G, A>{src, src_stride, galois, c->logn}, st, KID_FWD_MODUP, mbytes)
     int rc;
-    switch (c->alpha * 2 + (galois ? 1 : 0)) {
-    case 2: rc = CG_MODUP(false, 1); break;
-    case 3: rc = CG_MODUP(true, 1); break;
-    case 4: rc = CG_MODUP(false, 2); break;
-    case 5: rc = CG_MODUP(true, 2); break;
-    case 6: rc = CG_MODUP(false, 3); break;
-    default: rc = CG_MODUP(true, 3); break;
-    }
-#undef CG_MODUP
-    CG_TRY(rc);
+    CG_TRY(launch_modup(c, s, src, src_stride, galois, batch, dig));
     // inner product with the key fused into the inverse transform's load
     const size_t irows = (size_t)batch * 2 * c->L;
     const double ibytes = LB * ((dig_rows + 2.0 * c->L) * B + 2.0 * dig_rows);
@@ -724,16 +731,8 @@ static int do_rotate_hoisted(cg_ctx *c, hipStream_t s, const uint64_t *in2, size
     Bump w = bump(c, ws);
     double *dig = w.take<double>((size_t)c->dnum * c->L * batch);
     double *acc = w.take<double>((size_t)2 * c->L * batch * round_max);
-    const size_t nrows = (size_t)batch * c->dnum * c->L;
-    const StF64 st{dig, c->logn};
-    const uint64_t *src = in2 + (size_t)c->k * c->N;
     int rc;
-    switch (c->alpha) {
-    case 1: rc = launch_fwd(c, s, nrows, LdModup<false, 1>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
-    case 2: rc = launch_fwd(c, s, nrows, LdModup<false, 2>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
-    default: rc = launch_fwd(c, s, nrows, LdModup<false, 3>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
-    }
-    CG_TRY(rc);
+    CG_TRY(launch_modup(c, s, in2 + (size_t)c->k * c->N, in_stride, 0, batch, dig));
     for (uint32_t i0 = 0; i0 < n_rot; i0 += MAXROT) {
         const uint32_t nr = n_rot - i0 < (uint32_t)MAXROT ? n_rot - i0 : (uint32_t)MAXROT;
         HoistTab T{};
@@ -782,16 +781,8 @@ static int do_rotate_sum(cg_ctx *c, hipStream_t s, const uint64_t *in2, size_t i
     Bump w = bump(c, ws);
     double *dig = w.take<double>((size_t)c->dnum * c->L * batch);
     double *acc = w.take<double>((size_t)2 * c->L * batch);
-    const size_t nrows = (size_t)batch * c->dnum * c->L;
-    const StF64 st{dig, c->logn};
-    const uint64_t *src = in2 + (size_t)c->k * c->N;
     int rc;
-    switch (c->alpha) {
-    case 1: rc = launch_fwd(c, s, nrows, LdModup<false, 1>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
-    case 2: rc = launch_fwd(c, s, nrows, LdModup<false, 2>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
-    default: rc = launch_fwd(c, s, nrows, LdModup<false, 3>{src, in_stride, 0, c->logn}, st, KID_FWD_MODUP, LB * (c->k + dig_rows) * B); break;
-    }
-    CG_TRY(rc);
+    CG_TRY(launch_modup(c, s, in2 + (size_t)c->k * c->N, in_stride, 0, batch, dig));
     HoistTab T{};
     ModdownHoist H{};
     for (uint32_t i = 0; i < n_rot; i++) {
