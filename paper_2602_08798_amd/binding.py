@@ -185,6 +185,7 @@ class Context:
         with torch.cuda.device(self.device):
             self._check(self.lib.dll.cg_create(C.byref(h), C.byref(prm)))
         self.h = h
+        self._rounds = {}
         s = _Sizes()
         self._check(self.lib.dll.cg_get_sizes(self.h, C.byref(s)))
         self.sizes = s
@@ -490,11 +491,14 @@ class Context:
 
     def round_galois(self, which, d2, round_bits):
         """Galois elements of all rounds of a folding sum, in key order: which = 0 scores, 1 context."""
-        n = C.c_uint32(0)
-        self._check(self.lib.dll.cg_round_galois(self.h, which, d2, round_bits, None, 0, C.byref(n)))
-        buf = (C.c_uint32 * max(1, n.value))()
-        self._check(self.lib.dll.cg_round_galois(self.h, which, d2, round_bits, buf, n.value, C.byref(n)))
-        return [int(buf[i]) for i in range(n.value)]
+        key = (int(which), int(d2), int(round_bits))
+        if key not in self._rounds:                       # the answer depends on the arguments only
+            n = C.c_uint32(0)
+            self._check(self.lib.dll.cg_round_galois(self.h, which, d2, round_bits, None, 0, C.byref(n)))
+            buf = (C.c_uint32 * max(1, n.value))()
+            self._check(self.lib.dll.cg_round_galois(self.h, which, d2, round_bits, buf, n.value, C.byref(n)))
+            self._rounds[key] = [int(buf[i]) for i in range(n.value)]
+        return list(self._rounds[key])
 
     def _need_round_keys(self, which, d2, round_bits, keys):
         want = len(self.round_galois(which, d2, round_bits))
