@@ -127,6 +127,26 @@ def test_decode_scores_by_rounds_of_hoisted_rotations_are_the_same_dot_products(
     assert cl.noise_budget_bits(out, cl.decrypt_poly(out)) > 20
 
 
+def test_rounds_of_hoisted_rotation_sums_leave_the_noise_budget_of_the_chain():
+    """Same noise growth law either way (the sum of 64 rotated copies of the input's noise plus 63
+    key switches' worth): the budgets of the chain form and of the rounds differ by about a bit."""
+    prm = PRESETS["C2"]
+    orc = Oracle(prm)
+    cl = Client(prm, 65, orc)
+    n, d = prm.n, 64
+    B = n // d
+    act = attention_activations(Stream(65, 1), 1, B + 1, d)[0]
+    q_ct, k_ct = cl.encrypt_slots(np.tile(act[0], B)), cl.encrypt_slots(act[1:].reshape(-1))
+    rlk = cl.relin_key()
+    gks = {g: cl.galois_key(g) for g in set(attention.required_galois(n, d)) | set(attention.hoisted_fold_galois(n, d, 3, 1))}
+    chain = attention.decode_scores(orc, q_ct, k_ct, rlk, gks, d)
+    rounds = attention.decode_scores_hoisted(orc, q_ct, k_ct, rlk, gks, d, 3)
+    assert np.array_equal(cl.decrypt_slots(chain), cl.decrypt_slots(rounds))
+    b_chain = cl.noise_budget_bits(chain, cl.decrypt_poly(chain))
+    b_rounds = cl.noise_budget_bits(rounds, cl.decrypt_poly(rounds))
+    assert abs(b_chain - b_rounds) <= 2 and min(b_chain, b_rounds) > 20
+
+
 @pytest.mark.parametrize("w", [2, 3, 4, -3])
 def test_decode_context_by_rounds_of_hoisted_rotations_is_the_same_weighted_sum(w):
     """w < 0: rounds of -w bits and the cache ciphertexts' products summed before the one scaling."""
