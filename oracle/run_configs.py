@@ -11,9 +11,10 @@ def run_c1(orc, inp):
     return {f"pair{u}": orc.relin(orc.mul(inp["a"][u], inp["b"][u]), inp["rlk"]) for u in range(len(inp["a"]))}
 
 
-def _decode_step(orc, st, q, a, cache, rows, tau, n_cts, out, tag=""):
+def _decode_step(orc, st, q, a, cache, rows, tau, n_cts, out, tag="", rounds=None):
     """Append at token tau, then scores and context over n_cts cache ciphertexts per head.
-    `cache` is modified in place (numpy array [2*heads*stride] of ciphertexts)."""
+    `cache` is modified in place (numpy array [2*heads*stride] of ciphertexts).
+    rounds = (w_fold, w_block, keys by Galois element, sum_first): the hoisted forms of the products."""
     H, S, B, d2 = st["heads"], st["stride"], st["B"], st["d2"]
     idx, blk = divmod(tau, B)
     for c in range(2 * H):
@@ -24,11 +25,19 @@ def _decode_step(orc, st, q, a, cache, rows, tau, n_cts, out, tag=""):
     fold = {g: st["gk"][g] for g in st["fold"]}
     block = {g: st["gk"][g] for g in st["block"]}
     for h in range(H):
-        for c in range(n_cts):
-            out[f"{tag}score{h}_{c}"] = attention.decode_scores(orc, q[h], cache[h * S + c], st["rlk"], fold, d2)
         v0 = (H + h) * S
-        out[f"{tag}context{h}"] = attention.decode_context(orc, list(a[h * n_cts:(h + 1) * n_cts]),
-                                                          list(cache[v0:v0 + n_cts]), st["rlk"], block, d2)
+        a_h, v_h = list(a[h * n_cts:(h + 1) * n_cts]), list(cache[v0:v0 + n_cts])
+        if rounds is None:
+            for c in range(n_cts):
+                out[f"{tag}score{h}_{c}"] = attention.decode_scores(orc, q[h], cache[h * S + c], st["rlk"], fold, d2)
+            out[f"{tag}context{h}"] = attention.decode_context(orc, a_h, v_h, st["rlk"], block, d2)
+        else:
+            wf, wb, keys, sum_first = rounds
+            for c in range(n_cts):
+                out[f"{tag}score{h}_{c}"] = attention.decode_scores_hoisted(orc, q[h], cache[h * S + c], st["rlk"],
+                                                                            keys, d2, wf)
+            out[f"{tag}context{h}"] = attention.decode_context_hoisted(orc, a_h, v_h, st["rlk"], keys, d2, wb,
+                                                                       sum_first=sum_first)
 
 
 def run_c2(orc, st):
@@ -109,12 +118,13 @@ def run_c3(orc, st, heads=None, progress=None):
     return out
 
 
-def run_c5(orc, st, steps):
+def run_c5(orc, st, steps, rounds=None):
     """`steps` successive decode steps with cache growth (append first, then attend over the cache
-    including the new token's ciphertext)."""
+    including the new token's ciphertext); rounds as in _decode_step."""
     out = {}
     cache = st["cache"].copy()
     for i in range(steps):
         si = st["step_inputs"](i)
-        _decode_step(orc, st, si["q"], si["a"], cache, si["rows"], 512 + i, si["n_cts"], out, tag=f"s{i}_")
+        _decode_step(orc, st, si["q"], si["a"], cache, si["rows"], 512 + i, si["n_cts"], out, tag=f"s{i}_",
+                     rounds=rounds)
     return out

@@ -4,6 +4,7 @@ benchmark configurations as computed by the CPU oracle (and by nothing else).
     python -m tests.golden.make_digests C1 C2 C4 C4H C4HS    (about a minute)
     python -m tests.golden.make_digests C3              (all 12 heads: tens of minutes)
     python -m tests.golden.make_digests C5              (all 64 steps: about 40 minutes on 8 cores)
+    python -m tests.golden.make_digests C5H             (6 steps in the hoisted form: about 7 minutes)
 
 The GPU tests recompute the same units with the HIP library from the same seeded inputs
 (workloads.configs) and compare digests, i.e. every residue of every output, bit for bit.
@@ -21,6 +22,7 @@ from workloads import configs
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 C5_STEPS = 64
+C5H_STEPS = 6          # the scaled configuration in its hoisted form: the first steps only
 
 
 def digest(arr) -> str:
@@ -52,6 +54,14 @@ def main(names):
         elif name == "C5":
             inp = configs.c5_inputs(); out = run_configs.run_c5(Oracle(inp["prm"]), inp, C5_STEPS)
             note = f"{C5_STEPS} successive decode steps with cache growth, 16 heads, N = 16384"
+        elif name == "C5H":
+            from oracle import attention
+            inp = configs.c5_inputs()
+            wf, wb = configs.C4_ROUND_BITS
+            keys = configs.galois_keys("C5", attention.hoisted_fold_galois(inp["prm"].n, inp["d2"], wf, wb))
+            out = run_configs.run_c5(Oracle(inp["prm"]), inp, C5H_STEPS, rounds=(wf, wb, keys, configs.C4_SUM_BEFORE_SCALING))
+            note = (f"{C5H_STEPS} successive decode steps with cache growth, 16 heads, N = 16384, folding sums in rounds of "
+                    f"{wf} / {wb} bits, the context's products summed before one scaling")
         else:
             raise SystemExit(f"unknown configuration {name}")
         doc = {"config": name, "what": note, "source": "oracle/ only (tests/golden/make_digests.py)",

@@ -259,3 +259,40 @@ def test_c5_decode_step_entry_point_append_feeds_products(transformed_cache):
                 got[f"s{i}_score{h}_{c}"] = digest(scores[h, c])
             got[f"s{i}_context{h}"] = digest(context[h])
     compare(got, want, "C5 decode_step")
+
+
+def test_c5_first_steps_in_hoisted_form_with_cache_growth():
+    """The scaled configuration through cg_decode_step_hoisted (rounds of hoisted rotation sums, the
+    context's products summed before one scaling, the cache's transformed copy refreshed per step):
+    the appended ciphertext is read by the same step's products."""
+    from tests.golden.make_digests import C5H_STEPS
+    say("C5 hoisted")
+    st, want = configs.c5_inputs(), load("C5H")
+    g = Gpu(st["prm"])
+    d = _decode_state(g, st)
+    H, S, d2, B = st["heads"], st["stride"], st["d2"], st["B"]
+    wf, wb = configs.C4_ROUND_BITS
+    g_fold, g_block = g.ctx.round_galois(0, d2, wf), g.ctx.round_galois(1, d2, wb)
+    raw = configs.galois_keys("C5", sorted(set(g_fold + g_block)))
+    keys = {gal: g.key(k) for gal, k in raw.items()}
+    kf, kb = [keys[x] for x in g_fold], [keys[x] for x in g_block]
+    cache = g.dev(st["cache"])
+    ext = g.ctx.empty_ext(2 * H * S)
+    ext.fill_(float("nan"))
+    g.ctx.cache_extend(cache, 2 * H, 512 // B, S, ext)
+    got = {}
+    for i in range(C5H_STEPS):
+        si = st["step_inputs"](i)
+        tau, C = 512 + i, si["n_cts"]
+        scores, context = g.ctx.decode_step_hoisted(g.dev(si["q"]), g.dev(si["a"]), cache, H, C, S, d2, tau,
+                                                    g.dev(si["rows"]), d["masks"], d["rlk"], wf, kf, wb, kb,
+                                                    cache_ext=ext, sum_before_scaling=configs.C4_SUM_BEFORE_SCALING)
+        scores, context, cache_h = g.host(scores), g.host(context), g.host(cache)
+        idx = tau // B
+        for c in range(2 * H):
+            got[f"s{i}_cache{c}"] = digest(cache_h[c * S + idx])
+        for h in range(H):
+            for c in range(C):
+                got[f"s{i}_score{h}_{c}"] = digest(scores[h, c])
+            got[f"s{i}_context{h}"] = digest(context[h])
+    compare(got, want, "C5H")
