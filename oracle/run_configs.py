@@ -118,6 +118,28 @@ def run_c3(orc, st, heads=None, progress=None):
     return out
 
 
+def run_c3_hoisted(orc, st, heads, keys, w_fold, sum_first):
+    """The prompt's Q K^T and A V of the given heads in their hoisted forms: the rotated copies of K
+    and V as one series of hoisted rotations each, the folding sums in rounds of w_fold bits, the m
+    products of A V summed before one scaling (sum_first).  keys: switching keys by Galois element
+    for attention.copy_galois and the rounds' elements.  The caches are built as in run_c3."""
+    H, m, d2 = st["heads"], st["m"], st["d2"]
+    out = {}
+    for h in heads:
+        caches = {}
+        for c in (h, H + h):
+            acc = None
+            for tau in range(m):
+                masked = orc.mul_plain(st["rows"][tau][c], st["masks"][tau])
+                acc = masked if acc is None else orc.add(acc, masked)
+            caches[c] = acc
+        for i, x in enumerate(attention.prefill_qk_hoisted(orc, st["q"][h], caches[h], st["rlk"], keys, d2, w=w_fold)):
+            out[f"qk{h}_{i}"] = x
+        out[f"av{h}"] = attention.prefill_av_hoisted(orc, list(st["a"][h * m:(h + 1) * m]), caches[H + h], st["rlk"],
+                                                     keys, d2, sum_first=sum_first)
+    return out
+
+
 def run_c5(orc, st, steps, rounds=None):
     """`steps` successive decode steps with cache growth (append first, then attend over the cache
     including the new token's ciphertext); rounds as in _decode_step."""

@@ -5,6 +5,7 @@ benchmark configurations as computed by the CPU oracle (and by nothing else).
     python -m tests.golden.make_digests C3              (all 12 heads: tens of minutes)
     python -m tests.golden.make_digests C5              (all 64 steps: about 40 minutes on 8 cores)
     python -m tests.golden.make_digests C5H             (6 steps in the hoisted form: about 7 minutes)
+    python -m tests.golden.make_digests C3H             (all heads in the hoisted forms: about 7 minutes)
 
 The GPU tests recompute the same units with the HIP library from the same seeded inputs
 (workloads.configs) and compare digests, i.e. every residue of every output, bit for bit.
@@ -23,6 +24,7 @@ from workloads import configs
 HERE = os.path.dirname(os.path.abspath(__file__))
 C5_STEPS = 64
 C5H_STEPS = 6          # the scaled configuration in its hoisted form: the first steps only
+C3H_HEADS = tuple(range(12))   # the prompt configuration in its hoisted forms: all heads
 
 
 def digest(arr) -> str:
@@ -54,6 +56,17 @@ def main(names):
         elif name == "C5":
             inp = configs.c5_inputs(); out = run_configs.run_c5(Oracle(inp["prm"]), inp, C5_STEPS)
             note = f"{C5_STEPS} successive decode steps with cache growth, 16 heads, N = 16384"
+        elif name == "C3H":
+            from oracle import attention
+            inp = configs.c3_inputs()
+            n, d2 = inp["prm"].n, inp["d2"]
+            wf = configs.C4_ROUND_BITS[0]
+            gals = sorted(set(attention.copy_galois(n, d2)[1:]) | set(attention.hoisted_fold_galois(n, d2, wf, 1)))
+            keys = configs.galois_keys("C3", gals)
+            out = run_configs.run_c3_hoisted(Oracle(inp["prm"]), inp, C3H_HEADS, keys, wf, configs.C4_SUM_BEFORE_SCALING)
+            note = (f"prefill of head(s) {list(C3H_HEADS)} in the hoisted forms: 128 generalised diagonals of Q K^T with hoisted "
+                    f"copies of K and folding sums in rounds of {wf} bits, A V with hoisted copies of V and its products "
+                    f"summed before one scaling")
         elif name == "C5H":
             from oracle import attention
             inp = configs.c5_inputs()

@@ -296,3 +296,35 @@ def test_c5_first_steps_in_hoisted_form_with_cache_growth():
                 got[f"s{i}_score{h}_{c}"] = digest(scores[h, c])
             got[f"s{i}_context{h}"] = digest(context[h])
     compare(got, want, "C5H")
+
+
+def test_c3_prompt_products_in_hoisted_forms_every_output():
+    """The prompt configuration at full size through the hoisted calls: 12 x 128 diagonals of Q K^T
+    (hoisted copies of K, folding sums in rounds) and 12 contexts A V (hoisted copies of V, the 128
+    products of a head summed before one scaling)."""
+    from oracle import attention
+    say("C3 hoisted")
+    st, want = configs.c3_inputs(), load("C3H")
+    g = Gpu(st["prm"])
+    H, m, d2, n = st["heads"], st["m"], st["d2"], st["prm"].n
+    wf = configs.C4_ROUND_BITS[0]
+    masks = g.ctx.plain_prepare(g.dev(st["masks"]))
+    cache = g.ctx.empty_ct(2 * H)
+    for tau in range(m):
+        g.ctx.kv_append(cache, 1, 2 * H, tau, g.dev(st["rows"][tau]), masks, d2)
+    copies = attention.copy_galois(n, d2)[1:]
+    g_fold = g.ctx.round_galois(0, d2, wf)
+    raw = configs.galois_keys("C3", sorted(set(copies) | set(g_fold)))
+    keys = {gal: g.key(k) for gal, k in raw.items()}
+    rlk = g.key(st["rlk"])
+    out = g.ctx.prefill_qk_hoisted(g.dev(st["q"]), cache[:H], H, d2, rlk, [keys[x] for x in g_fold],
+                                   [keys[x] for x in copies], fold_round_bits=wf)
+    av = g.ctx.prefill_av_hoisted(g.dev(st["a"]), cache[H:], H, d2, rlk, [keys[x] for x in copies],
+                                  sum_before_scaling=configs.C4_SUM_BEFORE_SCALING)
+    out, av = g.host(out), g.host(av)
+    got = {}
+    for h in range(H):
+        for i in range(m):
+            got[f"qk{h}_{i}"] = digest(out[h, i])
+        got[f"av{h}"] = digest(av[h])
+    compare(got, want, "C3H")
