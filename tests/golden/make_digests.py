@@ -4,7 +4,7 @@ benchmark configurations as computed by the CPU oracle (and by nothing else).
     python -m tests.golden.make_digests C1 C2 C4 C4H C4HS    (about a minute)
     python -m tests.golden.make_digests C3              (all 12 heads: tens of minutes)
     python -m tests.golden.make_digests C5              (all 64 steps: about 40 minutes on 8 cores)
-    python -m tests.golden.make_digests C5H             (6 steps in the hoisted form: about 7 minutes)
+    python -m tests.golden.make_digests C5H             (16 steps in the hoisted form: about 13 minutes)
     python -m tests.golden.make_digests C3H             (all heads in the hoisted forms: about 7 minutes)
 
 The GPU tests recompute the same units with the HIP library from the same seeded inputs
@@ -23,7 +23,7 @@ from workloads import configs
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 C5_STEPS = 64
-C5H_STEPS = 6          # the scaled configuration in its hoisted form: the first steps only
+C5H_STEPS = 16         # the scaled configuration in its hoisted form: the first steps only
 C3H_HEADS = tuple(range(12))   # the prompt configuration in its hoisted forms: all heads
 
 

@@ -27,7 +27,7 @@ def test_digest_files_cover_every_output_unit():
     assert set(h) == set(hs) and all((h[k] != hs[k]) == k.startswith("context") for k in h)
     assert len(_load("C3")["digests"]) == 24 + 12 * (128 + 2 + 1)
     assert len(_load("C5")["digests"]) == 64 * (32 + 16 * 3 + 16)     # all 64 steps
-    assert len(_load("C5H")["digests"]) == 6 * (32 + 16 * 3 + 16)
+    assert len(_load("C5H")["digests"]) == 16 * (32 + 16 * 3 + 16)
     assert len(_load("C3H")["digests"]) == 12 * (128 + 1)
     for name in ("C1", "C2", "C3", "C3H", "C4", "C4H", "C4HS", "C5", "C5H"):
         assert _load(name)["source"].startswith("oracle/ only")
